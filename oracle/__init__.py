@@ -1,0 +1,115 @@
+"""CPU oracle for the memory-bound CNN layers: numpy front end.
+
+TEST INFRASTRUCTURE ONLY.  This package wraps ``cnnmem_ref.c`` (plain C, host
+pointers) with ctypes so that tests, the smoke check and the benchmark's
+``cpu_baseline`` leg can call it on numpy arrays.  It imports nothing from the
+GPU package and the GPU package imports nothing from here.
+
+Functions mirror the C ones: ``transform`` (Section IV.C), ``pool``
+(Equation 2 / Section II.A) and ``softmax`` (Section II.A, steps 1-5).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+NCHW, CHWN = 0, 1
+POOL_MAX, POOL_AVG = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "cnnmem_ref.c")
+_LIB = os.path.join(_HERE, "libcnnmem_ref.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc into ``oracle/libcnnmem_ref.so``."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        fp = ctypes.c_void_p
+        i = ctypes.c_int
+        lib.cnnmem_ref_transform.argtypes = [fp, fp, i, i, i, i, i, i]
+        lib.cnnmem_ref_pool_out_dims.argtypes = [i] * 8 + [ctypes.POINTER(i)] * 2
+        lib.cnnmem_ref_pool.argtypes = [fp, fp] + [i] * 12
+        lib.cnnmem_ref_softmax.argtypes = [fp, fp, i, i]
+        lib.cnnmem_ref_naive_pool_loads_1d.argtypes = [i, i, i]
+        for name in ("cnnmem_ref_transform", "cnnmem_ref_pool_out_dims", "cnnmem_ref_pool",
+                     "cnnmem_ref_softmax", "cnnmem_ref_naive_pool_loads_1d", "cnnmem_ref_threads"):
+            getattr(lib, name).restype = i
+        _lib = lib
+    return _lib
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise ValueError(f"oracle {what} failed with status {status}")
+
+
+def _f32(a: np.ndarray) -> np.ndarray:
+    if a.dtype != np.float32 or not a.flags["C_CONTIGUOUS"]:
+        raise TypeError("oracle takes C-contiguous float32 arrays")
+    return a
+
+
+def threads() -> int:
+    """Threads the oracle's OpenMP loops will use."""
+    return int(_load().cnnmem_ref_threads())
+
+
+def shape_of(layout: int, N: int, C: int, H: int, W: int):
+    """numpy shape of an N x C x H x W tensor stored in ``layout``."""
+    return (N, C, H, W) if layout == NCHW else (C, H, W, N)
+
+
+def transform(src: np.ndarray, N: int, C: int, H: int, W: int,
+              src_layout: int, dst_layout: int) -> np.ndarray:
+    src = _f32(src)
+    assert src.size == N * C * H * W
+    dst = np.empty(shape_of(dst_layout, N, C, H, W), dtype=np.float32)
+    _check(_load().cnnmem_ref_transform(src.ctypes.data, dst.ctypes.data, N, C, H, W,
+                                        src_layout, dst_layout), "transform")
+    return dst
+
+
+def pool_out_dims(H, W, kh, kw, sh, sw, ph, pw):
+    ho, wo = ctypes.c_int(), ctypes.c_int()
+    _check(_load().cnnmem_ref_pool_out_dims(H, W, kh, kw, sh, sw, ph, pw,
+                                            ctypes.byref(ho), ctypes.byref(wo)), "pool_out_dims")
+    return ho.value, wo.value
+
+
+def pool(src: np.ndarray, N: int, C: int, H: int, W: int, layout: int, mode: int,
+         kh: int, kw: int, sh: int, sw: int, ph: int = 0, pw: int = 0) -> np.ndarray:
+    src = _f32(src)
+    assert src.size == N * C * H * W
+    Ho, Wo = pool_out_dims(H, W, kh, kw, sh, sw, ph, pw)
+    dst = np.empty(shape_of(layout, N, C, Ho, Wo), dtype=np.float32)
+    _check(_load().cnnmem_ref_pool(src.ctypes.data, dst.ctypes.data, N, C, H, W, layout, mode,
+                                   kh, kw, sh, sw, ph, pw), "pool")
+    return dst
+
+
+def softmax(logits: np.ndarray) -> np.ndarray:
+    logits = _f32(logits)
+    assert logits.ndim == 2
+    N, classes = logits.shape
+    probs = np.empty_like(logits)
+    _check(_load().cnnmem_ref_softmax(logits.ctypes.data, probs.ctypes.data, N, classes), "softmax")
+    return probs
+
+
+def naive_pool_loads_1d(L: int, k: int, s: int) -> int:
+    return int(_load().cnnmem_ref_naive_pool_loads_1d(L, k, s))

@@ -1,0 +1,202 @@
+/*
+ * cnnmem_ref.c -- CPU oracle for the memory-bound CNN layers.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow,
+ * obviously-correct host implementation of what the GPU library computes.
+ * Only the tests, the smoke check and the benchmark's "cpu_baseline" leg may
+ * call it.  It shares no code with the HIP path and includes none of its
+ * headers.  All pointers are HOST pointers.
+ *
+ * What follows the paper:
+ *   - layouts: Section II.A (NCHW: W contiguous, H strides by W, C by H*W, N by
+ *     C*H*W) and Section IV.C (CHWN: N contiguous; NCHW == [N][C*H*W],
+ *     CHWN == [C*H*W][N], so the layout change is a 2-D transpose).
+ *   - pooling: Equation 2 (average) and the prose of Section II.A (max).
+ *   - softmax: the five steps of Section II.A, in the paper's order.
+ *
+ * Readings taken where the paper is silent or garbled (each is pinned or
+ * listed as a reading in the design notes):
+ *   - pooled extent = floor((L + 2*pad - k) / stride) + 1  (Fig. 8: 12 inputs,
+ *     window 4, stride 2 -> 5 outputs);
+ *   - Eq. 2's sums run over X*Y taps (upper bounds exclusive: the divisor is
+ *     /Y/X);
+ *   - padding is not in Eq. 2: a tap outside the image is skipped by max and
+ *     adds 0 to the average, whose divisor stays kh*kw;
+ *   - the doubled summation signs printed in front of each softmax step are
+ *     typesetting debris: step 1 is a max over categories of one image, step 4
+ *     a sum over categories of one image.
+ *
+ * Precision: transforms move 32-bit words untouched; max-pool compares fp32
+ * values; average pooling and softmax accumulate in fp64 and round once to
+ * fp32.
+ *
+ * Parity pins: every function here is pinned by tests that do not go through
+ * it (worked examples, closed forms, invariants, library routines).  The only
+ * unpinned behaviour is pooling with pad > 0, which the paper does not define:
+ * it is pinned to the common library routine's convention only.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { REF_OK = 0, REF_ERR_INVALID_ARG = 1, REF_ERR_NOMEM = 3 };
+enum { REF_NCHW = 0, REF_CHWN = 1 };
+enum { REF_POOL_MAX = 0, REF_POOL_AVG = 1 };
+
+/* Linear index of element (n, c, h, w) of an N x C x H x W tensor.
+ * Section II.A gives the NCHW strides; CHWN moves N to the fastest position. */
+static size_t at(int layout, int N, int C, int H, int W, int n, int c, int h, int w)
+{
+    if (layout == REF_NCHW)
+        return (((size_t)n * C + c) * H + h) * W + w;
+    return (((size_t)c * H + h) * W + w) * N + n;
+}
+
+int cnnmem_ref_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Layout change (Section IV.C): the same (n, c, h, w) element is read at its
+ * source index and written at its destination index.  Words are moved as
+ * 32-bit integers so every bit pattern survives. */
+int cnnmem_ref_transform(const float *src, float *dst, int N, int C, int H, int W,
+                         int src_layout, int dst_layout)
+{
+    if (!src || !dst || N <= 0 || C <= 0 || H <= 0 || W <= 0)
+        return REF_ERR_INVALID_ARG;
+    if ((src_layout != REF_NCHW && src_layout != REF_CHWN) ||
+        (dst_layout != REF_NCHW && dst_layout != REF_CHWN))
+        return REF_ERR_INVALID_ARG;
+    const uint32_t *s = (const uint32_t *)src;
+    uint32_t *d = (uint32_t *)dst;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c)
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w)
+                    d[at(dst_layout, N, C, H, W, n, c, h, w)] =
+                        s[at(src_layout, N, C, H, W, n, c, h, w)];
+    return REF_OK;
+}
+
+/* Pooled extent along one axis: number of window positions i with
+ * i*stride - pad + k <= L + pad, i.e. floor((L + 2*pad - k)/stride) + 1. */
+static int pooled_extent(int L, int k, int s, int p)
+{
+    return (L + 2 * p - k) / s + 1;
+}
+
+static int pool_args_ok(int N, int C, int H, int W, int layout, int mode,
+                        int kh, int kw, int sh, int sw, int ph, int pw)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0) return 0;
+    if (layout != REF_NCHW && layout != REF_CHWN) return 0;
+    if (mode != REF_POOL_MAX && mode != REF_POOL_AVG) return 0;
+    if (kh <= 0 || kw <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0) return 0;
+    if (ph > kh / 2 || pw > kw / 2) return 0;       /* every window keeps a tap */
+    if (H + 2 * ph < kh || W + 2 * pw < kw) return 0;
+    return 1;
+}
+
+int cnnmem_ref_pool_out_dims(int H, int W, int kh, int kw, int sh, int sw, int ph, int pw,
+                             int *Ho, int *Wo)
+{
+    if (!Ho || !Wo || !pool_args_ok(1, 1, H, W, REF_NCHW, REF_POOL_MAX, kh, kw, sh, sw, ph, pw))
+        return REF_ERR_INVALID_ARG;
+    *Ho = pooled_extent(H, kh, sh, ph);
+    *Wo = pooled_extent(W, kw, sw, pw);
+    return REF_OK;
+}
+
+/* Pooling (Equation 2 for the average; "max" replaces the sum by a maximum).
+ * Output element (n, c, i, j) looks at input rows i*sh - ph + y, y < kh, and
+ * columns j*sw - pw + x, x < kw.  The output has the layout of the input. */
+int cnnmem_ref_pool(const float *src, float *dst, int N, int C, int H, int W, int layout,
+                    int mode, int kh, int kw, int sh, int sw, int ph, int pw)
+{
+    if (!src || !dst || !pool_args_ok(N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw))
+        return REF_ERR_INVALID_ARG;
+    const int Ho = pooled_extent(H, kh, sh, ph);
+    const int Wo = pooled_extent(W, kw, sw, pw);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c)
+            for (int i = 0; i < Ho; ++i)
+                for (int j = 0; j < Wo; ++j) {
+                    float best = -INFINITY;
+                    double sum = 0.0;
+                    for (int y = 0; y < kh; ++y)
+                        for (int x = 0; x < kw; ++x) {
+                            const int r = i * sh - ph + y;
+                            const int q = j * sw - pw + x;
+                            if (r < 0 || r >= H || q < 0 || q >= W)
+                                continue;
+                            const float v = src[at(layout, N, C, H, W, n, c, r, q)];
+                            if (v > best) best = v;
+                            sum += (double)v;
+                        }
+                    float out;
+                    if (mode == REF_POOL_MAX)
+                        out = best;
+                    else
+                        out = (float)(sum / (double)(kh * kw));   /* Eq. 2: /Y/X */
+                    dst[at(layout, N, C, Ho, Wo, n, c, i, j)] = out;
+                }
+    return REF_OK;
+}
+
+/* Softmax over the categories of each image (Section II.A, steps 1-5), on a
+ * row-major [N][classes] matrix. */
+int cnnmem_ref_softmax(const float *logits, float *probs, int N, int classes)
+{
+    if (!logits || !probs || N <= 0 || classes <= 0)
+        return REF_ERR_INVALID_ARG;
+    int failed = 0;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        const float *in = logits + (size_t)n * classes;
+        float *out = probs + (size_t)n * classes;
+        double *mid = (double *)malloc((size_t)classes * sizeof(double));
+        if (!mid) {
+#pragma omp atomic write
+            failed = 1;
+            continue;
+        }
+        /* step 1: Maxv[n] = max over categories */
+        float maxv = in[0];
+        for (int c = 1; c < classes; ++c)
+            if (in[c] > maxv) maxv = in[c];
+        /* step 2: Midv1 = In - Maxv */
+        for (int c = 0; c < classes; ++c)
+            mid[c] = (double)in[c] - (double)maxv;
+        /* step 3: Midv2 = exp(Midv1) */
+        for (int c = 0; c < classes; ++c)
+            mid[c] = exp(mid[c]);
+        /* step 4: Sumv[n] = sum over categories */
+        double sumv = 0.0;
+        for (int c = 0; c < classes; ++c)
+            sumv += mid[c];
+        /* step 5: Out = Midv2 / Sumv */
+        for (int c = 0; c < classes; ++c)
+            out[c] = (float)(mid[c] / sumv);
+        free(mid);
+    }
+    return failed ? REF_ERR_NOMEM : REF_OK;
+}
+
+/* Number of input loads a one-output-per-thread pooling of an L-long 1-D
+ * signal issues (Section V.A, Fig. 8): outputs * window. */
+int cnnmem_ref_naive_pool_loads_1d(int L, int k, int s)
+{
+    if (L < k || k <= 0 || s <= 0) return -1;
+    return pooled_extent(L, k, s, 0) * k;
+}
