@@ -1,0 +1,104 @@
+/*
+ * cnnmem.h -- C ABI of the MI355X (gfx950) library for the memory-bound CNN
+ * layers: 4-D layout transformation, pooling in either layout, fused softmax.
+ *
+ * Conventions shared by every entry point
+ *   - All tensor pointers are DEVICE pointers to fp32 data owned by the caller;
+ *     they must be 4-byte aligned (16-byte alignment enables the fastest
+ *     kernels, anything else takes a slower but equally exact path).
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default
+ *     stream).  Calls only enqueue work on that stream: they never
+ *     synchronise, never allocate device memory and keep no state.
+ *   - Every function returns a CNNMEM_* status.  Arguments are validated on
+ *     the host before any HIP call; an invalid call enqueues nothing.
+ *   - Source and destination must not overlap unless stated otherwise.
+ *   - Tensors may hold more than 2^31 elements; every extent fits an int.
+ */
+#ifndef CNNMEM_H
+#define CNNMEM_H
+
+#ifndef CNNMEM_API
+#define CNNMEM_API __attribute__((visibility("default")))
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    CNNMEM_OK = 0,
+    CNNMEM_ERR_INVALID_ARG = 1, /* null pointer, non-positive extent, bad enum, bad window */
+    CNNMEM_ERR_UNSUPPORTED = 2, /* legal request no kernel covers (e.g. extent overflow)  */
+    CNNMEM_ERR_RUNTIME = 3      /* HIP reported an error when the kernel was launched     */
+};
+
+/* Layout tag of a logical N x C x H x W tensor (Section II.A, Section IV.A).
+ *   NCHW: element (n,c,h,w) at ((n*C + c)*H + h)*W + w   (W contiguous)
+ *   CHWN: element (n,c,h,w) at ((c*H + h)*W + w)*N + n   (N contiguous)   */
+enum { CNNMEM_NCHW = 0, CNNMEM_CHWN = 1 };
+
+/* Pooling operation (Section II.A: "average or max"). */
+enum { CNNMEM_POOL_MAX = 0, CNNMEM_POOL_AVG = 1 };
+
+/*
+ * Layout transformation (Section IV.C).  Copies the N*C*H*W elements of `src`
+ * (stored in `src_layout`) to `dst` in `dst_layout`.  Because C, H and W keep
+ * their relative order, this is the transpose of an [N][C*H*W] matrix into
+ * [C*H*W][N] or back.  Words are moved bit for bit (NaN payloads and signed
+ * zeros survive).  Equal layouts give a plain device copy.
+ *   src, dst : device, N*C*H*W floats each, not overlapping.
+ * Errors: INVALID_ARG for null pointers, extents <= 0 or unknown layout tags.
+ */
+CNNMEM_API int cnnmem_transform(const float *src, float *dst, int N, int C, int H, int W,
+                     int src_layout, int dst_layout, void *hip_stream);
+
+/*
+ * Pooled output extent (host only, no GPU work):
+ *   Ho = floor((H + 2*ph - kh) / sh) + 1,  Wo likewise
+ * -- the rule Fig. 8 of Section V.A implies (12 inputs, window 4, stride 2 give
+ * 5 outputs).  Errors: INVALID_ARG under the same window rules as cnnmem_pool,
+ * or if Ho / Wo is null.
+ */
+CNNMEM_API int cnnmem_pool_out_dims(int H, int W, int kh, int kw, int sh, int sw, int ph, int pw,
+                         int *Ho, int *Wo);
+
+/*
+ * Pooling (Equation 2 of Section II.A for the average; the maximum for MAX),
+ * computed directly in the layout the tensor is stored in (Section IV.B,
+ * Section V.A).  Output element (n,c,i,j) covers input rows i*sh - ph + y,
+ * y < kh, and columns j*sw - pw + x, x < kw.  Taps that fall outside the image
+ * are ignored by MAX and add zero to AVG, whose divisor is always kh*kw.
+ *   src : device, N*C*H*W floats in `layout`.
+ *   dst : device, N*C*Ho*Wo floats, written in the same `layout`.
+ * MAX returns one of the inputs exactly (inputs are assumed NaN-free; the sign
+ * of a zero maximum is unspecified when +0 and -0 tie).  AVG accumulates in
+ * fp32.
+ * Errors: INVALID_ARG for null pointers; N, C, H, W, kh, kw, sh, sw <= 0;
+ * ph, pw < 0; ph > kh/2 or pw > kw/2; H + 2*ph < kh or W + 2*pw < kw; unknown
+ * layout or mode.
+ */
+CNNMEM_API int cnnmem_pool(const float *src, float *dst, int N, int C, int H, int W, int layout, int mode,
+                int kh, int kw, int sh, int sw, int ph, int pw, void *hip_stream);
+
+/*
+ * Softmax over the categories of each image (Section II.A steps 1-5, fused
+ * into one kernel as in Section V.B): for every row n of the row-major
+ * [N][classes] matrix, m = max_c x[n][c], e_c = exp(x[n][c] - m),
+ * probs[n][c] = e_c / sum_c e_c.  The matrix is read once and written once.
+ *   logits, probs : device, N*classes floats each.  probs == logits (exactly
+ *                   in place) is allowed; any other overlap is not.
+ * fp32 arithmetic; inputs are assumed finite.
+ * Errors: INVALID_ARG for null pointers or N, classes <= 0.
+ */
+CNNMEM_API int cnnmem_softmax(const float *logits, float *probs, int N, int classes, void *hip_stream);
+
+/* Text for a status code; static storage, never null. */
+CNNMEM_API const char *cnnmem_status_string(int status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+CNNMEM_API int cnnmem_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CNNMEM_H */

@@ -1,0 +1,13 @@
+"""MI355X-native memory-bound CNN layers: layout transform, pooling, fused softmax.
+
+The work is done by hand-written HIP kernels for gfx950 in ``libcnnmem.so``
+(C ABI declared in ``include/cnnmem.h``).  This package is the thin Python
+binding: it marshals torch device tensors into that ABI and nothing else.
+There is no CPU fallback: without the built library, or without a GPU tensor,
+calls raise.
+"""
+from .binding import (  # noqa: F401
+    CHWN, NCHW, POOL_AVG, POOL_MAX, CnnmemError, cnnmem_pool, cnnmem_pool_out_dims,
+    cnnmem_softmax, cnnmem_status_string, cnnmem_transform, cnnmem_version, library, pool,
+    softmax, transform,
+)

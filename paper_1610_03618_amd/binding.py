@@ -1,0 +1,143 @@
+"""ctypes binding of libcnnmem.so: argument marshalling only.
+
+``cnnmem_*`` mirror the C entry points one to one and return the status code.
+``transform`` / ``pool`` / ``softmax`` allocate the output with torch (device
+memory is torch's job here), call the entry point on torch's current stream
+and raise :class:`CnnmemError` on a non-zero status.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+NCHW, CHWN = 0, 1
+POOL_MAX, POOL_AVG = 0, 1
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcnnmem.so")
+_lib = None
+
+
+class CnnmemError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: {cnnmem_status_string(status)} (status {status})")
+        self.status = status
+
+
+def library() -> ctypes.CDLL:
+    """The loaded C-ABI library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_1610_03618_amd.build` "
+                "(there is no fallback path)")
+        lib = ctypes.CDLL(_LIB_PATH)
+        i, p = ctypes.c_int, ctypes.c_void_p
+        lib.cnnmem_transform.argtypes = [p, p, i, i, i, i, i, i, p]
+        lib.cnnmem_pool_out_dims.argtypes = [i] * 8 + [ctypes.POINTER(i)] * 2
+        lib.cnnmem_pool.argtypes = [p, p] + [i] * 12 + [p]
+        lib.cnnmem_softmax.argtypes = [p, p, i, i, p]
+        lib.cnnmem_status_string.argtypes = [i]
+        lib.cnnmem_status_string.restype = ctypes.c_char_p
+        lib.cnnmem_version.argtypes = []
+        for name in ("cnnmem_transform", "cnnmem_pool_out_dims", "cnnmem_pool", "cnnmem_softmax",
+                     "cnnmem_version"):
+            getattr(lib, name).restype = i
+        lib.cnnmem_debug_fastdiv.argtypes = [ctypes.c_uint, ctypes.c_uint]
+        lib.cnnmem_debug_fastdiv.restype = ctypes.c_uint
+        lib.cnnmem_debug_xcd_tile.argtypes = [ctypes.c_uint, ctypes.c_uint]
+        lib.cnnmem_debug_xcd_tile.restype = ctypes.c_uint
+        _lib = lib
+    return _lib
+
+
+def _ptr(t) -> Optional[int]:
+    """Device address of a torch tensor (or a raw integer address / None)."""
+    if t is None or isinstance(t, int):
+        return t
+    if not isinstance(t, torch.Tensor):
+        raise TypeError("expected a torch tensor or an integer address")
+    if t.device.type != "cuda":
+        raise ValueError("cnnmem works on GPU memory only (got a CPU tensor)")
+    if t.dtype != torch.float32 or not t.is_contiguous():
+        raise ValueError("cnnmem takes contiguous float32 tensors")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream or None
+    return stream or None
+
+
+# ---- one-to-one mirrors of the C entry points (return the status code) ----
+
+def cnnmem_transform(src, dst, N, C, H, W, src_layout, dst_layout, stream=None) -> int:
+    return library().cnnmem_transform(_ptr(src), _ptr(dst), N, C, H, W, src_layout, dst_layout,
+                                      _stream(stream))
+
+
+def cnnmem_pool_out_dims(H, W, kh, kw, sh, sw, ph, pw) -> Tuple[int, int, int]:
+    ho, wo = ctypes.c_int(0), ctypes.c_int(0)
+    st = library().cnnmem_pool_out_dims(H, W, kh, kw, sh, sw, ph, pw, ctypes.byref(ho), ctypes.byref(wo))
+    return st, ho.value, wo.value
+
+
+def cnnmem_pool(src, dst, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, stream=None) -> int:
+    return library().cnnmem_pool(_ptr(src), _ptr(dst), N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw,
+                                 _stream(stream))
+
+
+def cnnmem_softmax(logits, probs, N, classes, stream=None) -> int:
+    return library().cnnmem_softmax(_ptr(logits), _ptr(probs), N, classes, _stream(stream))
+
+
+def cnnmem_status_string(status: int) -> str:
+    return library().cnnmem_status_string(status).decode()
+
+
+def cnnmem_version() -> int:
+    return library().cnnmem_version()
+
+
+# ---- conveniences: allocate the output, raise on error ----
+
+def _shape(layout, N, C, H, W):
+    return (N, C, H, W) if layout == NCHW else (C, H, W, N)
+
+
+def transform(src: torch.Tensor, N, C, H, W, src_layout, dst_layout, out=None, stream=None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty(_shape(dst_layout, N, C, H, W), dtype=torch.float32, device=src.device)
+    st = cnnmem_transform(src, out, N, C, H, W, src_layout, dst_layout, stream)
+    if st:
+        raise CnnmemError(st, "cnnmem_transform")
+    return out
+
+
+def pool(src: torch.Tensor, N, C, H, W, layout, mode, kh, kw, sh, sw, ph=0, pw=0, out=None,
+         stream=None) -> torch.Tensor:
+    st, Ho, Wo = cnnmem_pool_out_dims(H, W, kh, kw, sh, sw, ph, pw)
+    if st:
+        raise CnnmemError(st, "cnnmem_pool_out_dims")
+    if out is None:
+        out = torch.empty(_shape(layout, N, C, Ho, Wo), dtype=torch.float32, device=src.device)
+    st = cnnmem_pool(src, out, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, stream)
+    if st:
+        raise CnnmemError(st, "cnnmem_pool")
+    return out
+
+
+def softmax(logits: torch.Tensor, out=None, stream=None) -> torch.Tensor:
+    N, classes = logits.shape
+    if out is None:
+        out = torch.empty_like(logits)
+    st = cnnmem_softmax(logits, out, N, classes, stream)
+    if st:
+        raise CnnmemError(st, "cnnmem_softmax")
+    return out

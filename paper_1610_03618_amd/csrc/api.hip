@@ -1,0 +1,95 @@
+// C ABI of libcnnmem: argument validation and dispatch.  No HIP call is made
+// before the arguments of a call have been found valid, and none at load time,
+// so the library loads (and rejects bad calls) on a machine without a GPU.
+#include "cnnmem.h"
+#include "cnnmem_debug.h"
+#include "common.hpp"
+
+using namespace cnnmem;
+
+namespace {
+
+bool layout_ok(int l) { return l == CNNMEM_NCHW || l == CNNMEM_CHWN; }
+
+bool window_ok(int H, int W, int kh, int kw, int sh, int sw, int ph, int pw) {
+    if (H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0) return false;
+    if (ph > kh / 2 || pw > kw / 2) return false;               // every window keeps at least one tap
+    if ((long long)H + 2LL * ph < kh || (long long)W + 2LL * pw < kw) return false;
+    return true;
+}
+
+int pooled_extent(int L, int k, int s, int p) { return (int)(((long long)L + 2LL * p - k) / s + 1); }
+
+}  // namespace
+
+extern "C" {
+
+int cnnmem_transform(const float* src, float* dst, int N, int C, int H, int W, int src_layout,
+                     int dst_layout, void* hip_stream) {
+    if (!src || !dst || N <= 0 || C <= 0 || H <= 0 || W <= 0) return CNNMEM_ERR_INVALID_ARG;
+    if (!layout_ok(src_layout) || !layout_ok(dst_layout)) return CNNMEM_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 3u) return CNNMEM_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const long long limit = 1LL << 46;                         // element-count ceiling, far above any HBM
+    const long long CH = (long long)C * H;                     // < 2^62
+    if (CH > limit / W || CH * W > limit / N) return CNNMEM_ERR_UNSUPPORTED;
+    const long long M = CH * W;
+    if (src_layout == dst_layout) return launch_copy(src, dst, M * N, st);
+    // NCHW is [N][M], CHWN is [M][N] (Section IV.C): a 2-D transpose either way.
+    if (src_layout == CNNMEM_NCHW) return launch_transpose2d(src, dst, N, M, st);
+    return launch_transpose2d(src, dst, M, N, st);
+}
+
+int cnnmem_pool_out_dims(int H, int W, int kh, int kw, int sh, int sw, int ph, int pw, int* Ho, int* Wo) {
+    if (!Ho || !Wo || !window_ok(H, W, kh, kw, sh, sw, ph, pw)) return CNNMEM_ERR_INVALID_ARG;
+    *Ho = pooled_extent(H, kh, sh, ph);
+    *Wo = pooled_extent(W, kw, sw, pw);
+    return CNNMEM_OK;
+}
+
+int cnnmem_pool(const float* src, float* dst, int N, int C, int H, int W, int layout, int mode, int kh,
+                int kw, int sh, int sw, int ph, int pw, void* hip_stream) {
+    if (!src || !dst || N <= 0 || C <= 0) return CNNMEM_ERR_INVALID_ARG;
+    if (!window_ok(H, W, kh, kw, sh, sw, ph, pw)) return CNNMEM_ERR_INVALID_ARG;
+    if (!layout_ok(layout)) return CNNMEM_ERR_INVALID_ARG;
+    if (mode != CNNMEM_POOL_MAX && mode != CNNMEM_POOL_AVG) return CNNMEM_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 3u) return CNNMEM_ERR_INVALID_ARG;
+    if ((long long)H * W > (1LL << 30) || (long long)kh * kw > (1 << 24)) return CNNMEM_ERR_UNSUPPORTED;
+    PoolGeom g;
+    g.N = N; g.C = C; g.H = H; g.W = W;
+    g.kh = kh; g.kw = kw; g.sh = sh; g.sw = sw; g.ph = ph; g.pw = pw;
+    g.mode = mode;
+    g.Ho = pooled_extent(H, kh, sh, ph);
+    g.Wo = pooled_extent(W, kw, sw, pw);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    return layout == CNNMEM_NCHW ? launch_pool_nchw(src, dst, g, st) : launch_pool_chwn(src, dst, g, st);
+}
+
+int cnnmem_softmax(const float* logits, float* probs, int N, int classes, void* hip_stream) {
+    if (!logits || !probs || N <= 0 || classes <= 0) return CNNMEM_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(logits) | reinterpret_cast<uintptr_t>(probs)) & 3u)
+        return CNNMEM_ERR_INVALID_ARG;
+    return launch_softmax(logits, probs, N, classes, static_cast<hipStream_t>(hip_stream));
+}
+
+const char* cnnmem_status_string(int status) {
+    switch (status) {
+        case CNNMEM_OK: return "ok";
+        case CNNMEM_ERR_INVALID_ARG: return "invalid argument";
+        case CNNMEM_ERR_UNSUPPORTED: return "unsupported request";
+        case CNNMEM_ERR_RUNTIME: return "HIP runtime error at kernel launch";
+        default: return "unknown status";
+    }
+}
+
+int cnnmem_version(void) { return 100; }   // 0.1.0
+
+unsigned cnnmem_debug_fastdiv(unsigned n, unsigned d) {
+    return fd_div(n, make_fastdiv(d));
+}
+
+unsigned cnnmem_debug_xcd_tile(unsigned block, unsigned nblocks) {
+    return xcd_contiguous_tile(block, nblocks);
+}
+
+}  // extern "C"

@@ -1,0 +1,84 @@
+// Internal helpers shared by the HIP translation units of libcnnmem.
+// Nothing here is part of the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+#include <cstdlib>
+
+#include "cnnmem.h"
+
+namespace cnnmem {
+
+constexpr int kWave = 64;       // CDNA wavefront width
+constexpr int kNumXcd = 8;      // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
+
+inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
+inline long long ceil_div64(long long a, long long b) { return (a + b - 1) / b; }
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Status of the launch that was just enqueued.
+inline int launch_status() {
+    return hipGetLastError() == hipSuccess ? CNNMEM_OK : CNNMEM_ERR_RUNTIME;
+}
+
+// Integer tuning knob from the environment (read on every call: host-side, cheap).
+inline int env_int(const char* name, int fallback) {
+    const char* s = std::getenv(name);
+    if (!s || !*s) return fallback;
+    return std::atoi(s);
+}
+
+// Exact unsigned division of any n < 2^31 by a fixed d in [1, 2^31):
+// q = (n * magic) >> shift with magic = floor(2^(31+s)/d) + 1, s = ceil(log2 d).
+// The error term magic*d - 2^(31+s) is at most d <= 2^s, so n * error < 2^(31+s).
+struct FastDiv {
+    uint32_t magic;
+    uint32_t shift;
+    uint32_t d;
+};
+
+inline FastDiv make_fastdiv(uint32_t d) {
+    FastDiv f;
+    f.d = d;
+    uint32_t s = 0;
+    while ((1ull << s) < d) ++s;
+    f.shift = 31 + s;
+    f.magic = (uint32_t)(((1ull << f.shift) / d) + 1ull);
+    return f;
+}
+
+__host__ __device__ __forceinline__ uint32_t fd_div(uint32_t n, const FastDiv& f) {
+    return (uint32_t)(((uint64_t)n * f.magic) >> f.shift);
+}
+
+// Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has
+// its own L2.  This maps the hardware block id to a logical tile id such that
+// consecutive logical tiles run on the same XCD (tiles that share halo rows then
+// share an L2).  A bijection on [0, nblocks) for any nblocks.
+__host__ __device__ __forceinline__ uint32_t xcd_contiguous_tile(uint32_t block, uint32_t nblocks) {
+    const uint32_t xcd = block % kNumXcd;
+    const uint32_t q = nblocks / kNumXcd;
+    const uint32_t rem = nblocks % kNumXcd;
+    const uint32_t start = xcd * q + (xcd < rem ? xcd : rem);
+    return start + block / kNumXcd;
+}
+
+// ---- launchers implemented in the .hip files (host side, C++ linkage, hidden) ----
+int launch_transpose2d(const float* src, float* dst, long long R, long long S, hipStream_t st);
+int launch_copy(const float* src, float* dst, long long n, hipStream_t st);
+
+struct PoolGeom {
+    int N, C, H, W, Ho, Wo;
+    int kh, kw, sh, sw, ph, pw;
+    int mode;
+};
+int launch_pool_nchw(const float* src, float* dst, const PoolGeom& g, hipStream_t st);
+int launch_pool_chwn(const float* src, float* dst, const PoolGeom& g, hipStream_t st);
+
+int launch_softmax(const float* logits, float* probs, int N, int classes, hipStream_t st);
+
+}  // namespace cnnmem

@@ -1,0 +1,474 @@
+// Max / average pooling computed directly in NCHW or CHWN (Equation 2 of
+// Section II.A; Section IV.B on layouts; Section V.A on removing the redundant
+// loads of overlapped windows).
+//
+// gfx950 design, by layout:
+//   CHWN  -- N is contiguous, so a lane owns four consecutive images (one
+//            float4) of one output column and walks down OY output rows.  Every
+//            input row it touches is reduced horizontally once and that row
+//            result is reused by all the output rows whose windows contain it
+//            (the paper's register working set, applied along H); neighbouring
+//            columns are neighbouring lanes, so their shared taps hit in L1.
+//   NCHW  -- (n,c) planes are contiguous.  Instead of the strided
+//            one-lane-per-output scheme the paper measures, a workgroup streams a
+//            contiguous slab (several whole planes, or a strip of rows of a big
+//            plane) into LDS with 128-bit loads, then every lane pools from LDS
+//            and the outputs, contiguous as well, go out coalesced.  For the
+//            non-overlapping 2x2/stride-2 case with even H no staging is needed:
+//            rows pair up across the whole tensor and a lane turns 2 x 8 inputs
+//            into 4 outputs with 128-bit accesses on both sides.
+//   Anything else (odd alignment, N not a multiple of 4, huge extents) runs a
+//   one-lane-per-output kernel that relies on the caches.
+#include "common.hpp"
+
+namespace cnnmem {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr float kNegInf = -__builtin_huge_valf();
+
+template <int MODE>
+struct Acc {
+    static __device__ __forceinline__ float identity() { return MODE == CNNMEM_POOL_MAX ? kNegInf : 0.f; }
+    static __device__ __forceinline__ float op(float a, float b) {
+        return MODE == CNNMEM_POOL_MAX ? fmaxf(a, b) : a + b;
+    }
+    static __device__ __forceinline__ float4 identity4() {
+        const float i = identity();
+        return make_float4(i, i, i, i);
+    }
+    static __device__ __forceinline__ float4 op4(const float4& a, const float4& b) {
+        return make_float4(op(a.x, b.x), op(a.y, b.y), op(a.z, b.z), op(a.w, b.w));
+    }
+    static __device__ __forceinline__ float finish(float a, float divisor) {
+        return MODE == CNNMEM_POOL_MAX ? a : a / divisor;
+    }
+    static __device__ __forceinline__ float4 finish4(const float4& a, float divisor) {
+        return make_float4(finish(a.x, divisor), finish(a.y, divisor), finish(a.z, divisor),
+                           finish(a.w, divisor));
+    }
+};
+
+// ---------------------------------------------------------------------------
+// Fallback: one lane per output element, any layout through strides.
+// ---------------------------------------------------------------------------
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void pool_generic_kernel(
+    const float* __restrict__ src, float* __restrict__ dst, PoolGeom g, int chwn, size_t total) {
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    for (size_t o = (size_t)blockIdx.x * kThreads + threadIdx.x; o < total; o += stride) {
+        // decode the output index in its own layout
+        int n, c, i, j;
+        size_t t = o;
+        if (chwn) {
+            n = (int)(t % g.N); t /= g.N;
+            j = (int)(t % g.Wo); t /= g.Wo;
+            i = (int)(t % g.Ho); c = (int)(t / g.Ho);
+        } else {
+            j = (int)(t % g.Wo); t /= g.Wo;
+            i = (int)(t % g.Ho); t /= g.Ho;
+            c = (int)(t % g.C); n = (int)(t / g.C);
+        }
+        float acc = Acc<MODE>::identity();
+        for (int y = 0; y < g.kh; ++y) {
+            const int r = i * g.sh - g.ph + y;
+            if (r < 0 || r >= g.H) continue;
+            for (int x = 0; x < g.kw; ++x) {
+                const int q = j * g.sw - g.pw + x;
+                if (q < 0 || q >= g.W) continue;
+                const size_t idx = chwn ? (((size_t)c * g.H + r) * g.W + q) * g.N + n
+                                        : (((size_t)n * g.C + c) * g.H + r) * g.W + q;
+                acc = Acc<MODE>::op(acc, src[idx]);
+            }
+        }
+        dst[o] = Acc<MODE>::finish(acc, (float)(g.kh * g.kw));
+    }
+}
+
+// ---------------------------------------------------------------------------
+// CHWN: float4 over four images, OY output rows per lane, row results reused.
+// KH/KW/SH/SW are compile-time so the window loops unroll into registers.
+// ---------------------------------------------------------------------------
+template <int MODE, int KH, int KW, int SH, int SW, int OY, bool PADDED>
+__global__ __launch_bounds__(kThreads) void pool_chwn_vec4_kernel(
+    const float* __restrict__ src, float* __restrict__ dst, PoolGeom g, uint32_t row_items,
+    uint32_t blocks_x, uint32_t blocks_y, FastDiv div_n4) {
+    constexpr int ROWS_IN = (OY - 1) * SH + KH;     // input rows one lane walks
+    const uint32_t nblocks = gridDim.x;
+    const uint32_t tile = xcd_contiguous_tile(blockIdx.x, nblocks);
+    // tile -> (bx fastest, then by, then c): vertically adjacent strips are close in tile order
+    const uint32_t bx = tile % blocks_x;
+    const uint32_t rest = tile / blocks_x;
+    const uint32_t by = rest % blocks_y;
+    const uint32_t c = rest / blocks_y;
+
+    const uint32_t u = bx * kThreads + threadIdx.x;           // position in the output row: j*N4 + n4
+    if (u >= row_items) return;
+    const uint32_t j = fd_div(u, div_n4);
+    const uint32_t n4 = u - j * div_n4.d;
+    const int i0 = (int)by * OY;
+    const int N = g.N;
+
+    float4 acc[OY];
+#pragma unroll
+    for (int oy = 0; oy < OY; ++oy) acc[oy] = Acc<MODE>::identity4();
+
+    const int q0 = (int)j * SW - g.pw;
+    const int r_base = i0 * SH - g.ph;
+    const float* plane = src + (size_t)c * g.H * g.W * N + 4 * n4;
+#pragma unroll
+    for (int rr = 0; rr < ROWS_IN; ++rr) {
+        const int r = r_base + rr;
+        float4 h = Acc<MODE>::identity4();
+        const bool row_ok = (r < g.H) && (!PADDED || r >= 0);
+        if (row_ok) {
+            const float* rowp = plane + (size_t)r * g.W * N;
+#pragma unroll
+            for (int x = 0; x < KW; ++x) {
+                const int q = q0 + x;
+                if (PADDED ? (q >= 0 && q < g.W) : true) {
+                    h = Acc<MODE>::op4(h, *reinterpret_cast<const float4*>(rowp + (size_t)q * N));
+                }
+            }
+        }
+#pragma unroll
+        for (int oy = 0; oy < OY; ++oy)
+            if (rr >= oy * SH && rr < oy * SH + KH) acc[oy] = Acc<MODE>::op4(acc[oy], h);
+    }
+    float* outp = dst + ((size_t)c * g.Ho * g.Wo + j) * N + 4 * n4;
+#pragma unroll
+    for (int oy = 0; oy < OY; ++oy) {
+        const int i = i0 + oy;
+        if (i < g.Ho)
+            *reinterpret_cast<float4*>(outp + (size_t)i * g.Wo * N) =
+                Acc<MODE>::finish4(acc[oy], (float)(KH * KW));
+    }
+}
+
+// ---------------------------------------------------------------------------
+// NCHW, 2x2 window, stride 2, no padding, even H: the tensor is a list of
+// N*C*H rows of W floats and output row k is made of input rows 2k and 2k+1.
+// A lane reads VIN consecutive floats of both rows and writes VIN/2 outputs.
+// ---------------------------------------------------------------------------
+template <int VIN>
+struct VecIO;
+template <>
+struct VecIO<8> {
+    static __device__ __forceinline__ void run(const float* a, const float* b, float* o, int mode) {
+        const float4 a0 = reinterpret_cast<const float4*>(a)[0], a1 = reinterpret_cast<const float4*>(a)[1];
+        const float4 b0 = reinterpret_cast<const float4*>(b)[0], b1 = reinterpret_cast<const float4*>(b)[1];
+        float4 r;
+        if (mode == CNNMEM_POOL_MAX) {
+            r.x = fmaxf(fmaxf(a0.x, a0.y), fmaxf(b0.x, b0.y));
+            r.y = fmaxf(fmaxf(a0.z, a0.w), fmaxf(b0.z, b0.w));
+            r.z = fmaxf(fmaxf(a1.x, a1.y), fmaxf(b1.x, b1.y));
+            r.w = fmaxf(fmaxf(a1.z, a1.w), fmaxf(b1.z, b1.w));
+        } else {
+            r.x = ((a0.x + a0.y) + (b0.x + b0.y)) * 0.25f;
+            r.y = ((a0.z + a0.w) + (b0.z + b0.w)) * 0.25f;
+            r.z = ((a1.x + a1.y) + (b1.x + b1.y)) * 0.25f;
+            r.w = ((a1.z + a1.w) + (b1.z + b1.w)) * 0.25f;
+        }
+        *reinterpret_cast<float4*>(o) = r;
+    }
+};
+template <>
+struct VecIO<4> {
+    static __device__ __forceinline__ void run(const float* a, const float* b, float* o, int mode) {
+        const float4 a0 = *reinterpret_cast<const float4*>(a), b0 = *reinterpret_cast<const float4*>(b);
+        float2 r;
+        if (mode == CNNMEM_POOL_MAX) {
+            r.x = fmaxf(fmaxf(a0.x, a0.y), fmaxf(b0.x, b0.y));
+            r.y = fmaxf(fmaxf(a0.z, a0.w), fmaxf(b0.z, b0.w));
+        } else {
+            r.x = ((a0.x + a0.y) + (b0.x + b0.y)) * 0.25f;
+            r.y = ((a0.z + a0.w) + (b0.z + b0.w)) * 0.25f;
+        }
+        *reinterpret_cast<float2*>(o) = r;
+    }
+};
+
+template <int MODE, int VIN>
+__global__ __launch_bounds__(kThreads) void pool_nchw_2x2s2_kernel(
+    const float* __restrict__ src, float* __restrict__ dst, uint32_t items, uint32_t W,
+    FastDiv div_per_row) {
+    // item I: output floats [I*VIN/2, (I+1)*VIN/2); output row = I / (W/VIN)
+    const uint32_t I = blockIdx.x * kThreads + threadIdx.x;
+    if (I >= items) return;
+    const uint32_t orow = fd_div(I, div_per_row);
+    const size_t in0 = (size_t)I * VIN + (size_t)orow * W;     // = 2*orow*W + VIN*(I % per_row)
+    VecIO<VIN>::run(src + in0, src + in0 + W, dst + (size_t)I * (VIN / 2), MODE);
+}
+
+// ---------------------------------------------------------------------------
+// NCHW through LDS.  One workgroup = `planes` consecutive (n,c) planes (all
+// their rows) or one strip of `rows_out` output rows of a single plane.
+// ---------------------------------------------------------------------------
+constexpr int kSlabThreads = 256;
+constexpr int kSlabFloats = 8192;                   // 32 KB of LDS per workgroup
+constexpr int kSlabVecPerLane = kSlabFloats / 4 / kSlabThreads + 1;   // float4 per lane, worst case
+
+struct SlabPlan {
+    int planes_per_wg;      // >= 1 (whole planes) ...
+    int rows_per_wg;        // ... or output rows per strip when a plane is split
+    int strips;             // strips per plane (1 when whole planes)
+    long long total_planes;
+};
+
+template <int MODE, int KH, int KW, int SH, int SW, bool PADDED>
+__global__ __launch_bounds__(kSlabThreads) void pool_nchw_slab_kernel(
+    const float* __restrict__ src, float* __restrict__ dst, PoolGeom g, SlabPlan plan,
+    FastDiv div_wo, FastDiv div_plane_out, int rt_kh, int rt_kw, int rt_sh, int rt_sw) {
+    __shared__ __attribute__((aligned(16))) float slab[kSlabFloats + 8];
+    const int kh = KH ? KH : rt_kh, kw = KW ? KW : rt_kw;
+    const int sh = SH ? SH : rt_sh, sw = SW ? SW : rt_sw;
+
+    const uint32_t tile = xcd_contiguous_tile(blockIdx.x, gridDim.x);
+    const int plane_in = g.H * g.W;
+    const int plane_out = g.Ho * g.Wo;
+
+    long long p0;
+    int planes, i0, rows_out;
+    if (plan.strips == 1) {
+        p0 = (long long)tile * plan.planes_per_wg;
+        const long long left = plan.total_planes - p0;
+        planes = left < plan.planes_per_wg ? (int)left : plan.planes_per_wg;
+        i0 = 0;
+        rows_out = g.Ho;
+    } else {
+        p0 = tile / (uint32_t)plan.strips;
+        const int strip = (int)(tile % (uint32_t)plan.strips);
+        planes = 1;
+        i0 = strip * plan.rows_per_wg;
+        rows_out = g.Ho - i0 < plan.rows_per_wg ? g.Ho - i0 : plan.rows_per_wg;
+    }
+    // input rows this workgroup needs: [r_lo, r_hi) of its first ... last plane
+    int r_lo = i0 * sh - g.ph;
+    if (r_lo < 0) r_lo = 0;
+    int r_hi = (i0 + rows_out - 1) * sh - g.ph + kh;
+    if (r_hi > g.H) r_hi = g.H;
+    if (planes > 1) { r_lo = 0; r_hi = g.H; }
+    const size_t g_lo = (size_t)p0 * plane_in + (size_t)r_lo * g.W;
+    const size_t g_hi = (size_t)(p0 + planes - 1) * plane_in + (size_t)r_hi * g.W;
+    const size_t a_lo = g_lo & ~(size_t)3;          // src is 16-byte aligned: float4 stream start
+    const size_t total_in = (size_t)plan.total_planes * plane_in;
+    const int nvec = (int)((g_hi - a_lo + 3) >> 2);
+
+    // ---- load phase: issue every 128-bit load, then park them in LDS ----
+    float4 v[kSlabVecPerLane];
+#pragma unroll
+    for (int k = 0; k < kSlabVecPerLane; ++k) {
+        const int q = threadIdx.x + k * kSlabThreads;
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (q < nvec) {
+            const size_t a = a_lo + 4 * (size_t)q;
+            if (a + 4 <= total_in) {
+                t = *reinterpret_cast<const float4*>(src + a);
+            } else {                                // last float4 of the tensor: stay inside it
+                if (a + 0 < total_in) t.x = src[a + 0];
+                if (a + 1 < total_in) t.y = src[a + 1];
+                if (a + 2 < total_in) t.z = src[a + 2];
+            }
+        }
+        v[k] = t;
+    }
+#pragma unroll
+    for (int k = 0; k < kSlabVecPerLane; ++k) {
+        const int q = threadIdx.x + k * kSlabThreads;
+        if (q < nvec) *reinterpret_cast<float4*>(slab + 4 * q) = v[k];
+    }
+    __syncthreads();
+
+    // ---- pool from LDS; outputs of the workgroup are contiguous in dst ----
+    const int n_out = planes * rows_out * g.Wo;     // planes > 1 implies rows_out == Ho
+    const size_t out0 = (size_t)p0 * plane_out + (size_t)i0 * g.Wo;
+    // LDS index of element (plane p0, row 0, col 0); may be negative when r_lo > 0
+    const int lds0 = (int)((long long)((size_t)p0 * plane_in) - (long long)a_lo);
+    for (int o = threadIdx.x; o < n_out; o += kSlabThreads) {
+        int pl = 0, rem = o;
+        if (planes > 1) {
+            pl = (int)fd_div((uint32_t)o, div_plane_out);
+            rem = o - pl * plane_out;
+        }
+        const int il = (int)fd_div((uint32_t)rem, div_wo);
+        const int j = rem - il * g.Wo;
+        const int rb = (i0 + il) * sh - g.ph;
+        const int qb = j * sw - g.pw;
+        const int base = lds0 + pl * plane_in;      // LDS index of this plane's element (0, 0)
+        float acc = Acc<MODE>::identity();
+        if (KH != 0) {
+#pragma unroll
+            for (int y = 0; y < (KH ? KH : 1); ++y) {
+                const int r = rb + y;
+                if (PADDED && (r < 0 || r >= g.H)) continue;
+#pragma unroll
+                for (int x = 0; x < (KW ? KW : 1); ++x) {
+                    const int q = qb + x;
+                    if (PADDED && (q < 0 || q >= g.W)) continue;
+                    acc = Acc<MODE>::op(acc, slab[base + r * g.W + q]);
+                }
+            }
+        } else {
+            for (int y = 0; y < kh; ++y) {
+                const int r = rb + y;
+                if (r < 0 || r >= g.H) continue;
+                for (int x = 0; x < kw; ++x) {
+                    const int q = qb + x;
+                    if (q < 0 || q >= g.W) continue;
+                    acc = Acc<MODE>::op(acc, slab[base + r * g.W + q]);
+                }
+            }
+        }
+        dst[out0 + o] = Acc<MODE>::finish(acc, (float)(kh * kw));
+    }
+}
+
+// ---- host-side dispatch ------------------------------------------------------
+
+template <int MODE>
+int launch_generic(const float* src, float* dst, const PoolGeom& g, int chwn, hipStream_t st) {
+    const size_t total = (size_t)g.N * g.C * g.Ho * g.Wo;
+    const long long want = ceil_div64((long long)total, kThreads);
+    const unsigned blocks = (unsigned)(want < 65536 ? want : 65536);
+    hipLaunchKernelGGL((pool_generic_kernel<MODE>), dim3(blocks), dim3(kThreads), 0, st, src, dst, g, chwn, total);
+    return launch_status();
+}
+
+template <int MODE, int KH, int KW, int SH, int SW, int OY>
+int launch_chwn_vec4(const float* src, float* dst, const PoolGeom& g, hipStream_t st) {
+    const long long row_items = (long long)(g.N / 4) * g.Wo;
+    const long long bx = ceil_div64(row_items, kThreads), by = ceil_div64(g.Ho, OY);
+    const long long blocks = bx * by * g.C;
+    if (row_items >= 0x7fffffffLL || blocks > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
+    const FastDiv dn4 = make_fastdiv((uint32_t)(g.N / 4));
+    if (g.ph > 0 || g.pw > 0)
+        hipLaunchKernelGGL((pool_chwn_vec4_kernel<MODE, KH, KW, SH, SW, OY, true>), dim3((unsigned)blocks),
+                           dim3(kThreads), 0, st, src, dst, g, (uint32_t)row_items, (uint32_t)bx,
+                           (uint32_t)by, dn4);
+    else
+        hipLaunchKernelGGL((pool_chwn_vec4_kernel<MODE, KH, KW, SH, SW, OY, false>), dim3((unsigned)blocks),
+                           dim3(kThreads), 0, st, src, dst, g, (uint32_t)row_items, (uint32_t)bx,
+                           (uint32_t)by, dn4);
+    return launch_status();
+}
+
+template <int MODE>
+int dispatch_chwn(const float* src, float* dst, const PoolGeom& g, hipStream_t st) {
+    const bool vec = (g.N % 4 == 0) && aligned16(src) && aligned16(dst);
+    if (vec && g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2) {
+        const int oy = env_int("CNNMEM_POOL_CHWN_OY", 3);
+        int rc;
+        if (oy <= 1) rc = launch_chwn_vec4<MODE, 3, 3, 2, 2, 1>(src, dst, g, st);
+        else if (oy == 2) rc = launch_chwn_vec4<MODE, 3, 3, 2, 2, 2>(src, dst, g, st);
+        else if (oy == 3) rc = launch_chwn_vec4<MODE, 3, 3, 2, 2, 3>(src, dst, g, st);
+        else rc = launch_chwn_vec4<MODE, 3, 3, 2, 2, 4>(src, dst, g, st);
+        if (rc != CNNMEM_ERR_UNSUPPORTED) return rc;
+    } else if (vec && g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2) {
+        const int oy = env_int("CNNMEM_POOL_CHWN_OY", 2);
+        int rc;
+        if (oy <= 1) rc = launch_chwn_vec4<MODE, 2, 2, 2, 2, 1>(src, dst, g, st);
+        else if (oy == 2) rc = launch_chwn_vec4<MODE, 2, 2, 2, 2, 2>(src, dst, g, st);
+        else rc = launch_chwn_vec4<MODE, 2, 2, 2, 2, 4>(src, dst, g, st);
+        if (rc != CNNMEM_ERR_UNSUPPORTED) return rc;
+    } else if (vec && g.kh == 3 && g.kw == 3 && g.sh == 1 && g.sw == 1) {
+        const int rc = launch_chwn_vec4<MODE, 3, 3, 1, 1, 4>(src, dst, g, st);
+        if (rc != CNNMEM_ERR_UNSUPPORTED) return rc;
+    }
+    return launch_generic<MODE>(src, dst, g, 1, st);
+}
+
+template <int MODE, int KH, int KW, int SH, int SW>
+int launch_slab(const float* src, float* dst, const PoolGeom& g, const SlabPlan& plan, long long blocks,
+                hipStream_t st) {
+    const FastDiv dwo = make_fastdiv((uint32_t)g.Wo);
+    const FastDiv dpo = make_fastdiv((uint32_t)(g.Ho * g.Wo));
+    if (g.ph > 0 || g.pw > 0 || KH == 0)
+        hipLaunchKernelGGL((pool_nchw_slab_kernel<MODE, KH, KW, SH, SW, true>), dim3((unsigned)blocks),
+                           dim3(kSlabThreads), 0, st, src, dst, g, plan, dwo, dpo, g.kh, g.kw, g.sh, g.sw);
+    else
+        hipLaunchKernelGGL((pool_nchw_slab_kernel<MODE, KH, KW, SH, SW, false>), dim3((unsigned)blocks),
+                           dim3(kSlabThreads), 0, st, src, dst, g, plan, dwo, dpo, g.kh, g.kw, g.sh, g.sw);
+    return launch_status();
+}
+
+template <int MODE>
+int dispatch_nchw(const float* src, float* dst, const PoolGeom& g, hipStream_t st) {
+    const long long planes = (long long)g.N * g.C;
+    const bool a16 = aligned16(src) && aligned16(dst);
+
+    // (1) non-overlapping 2x2 / stride 2 on even H: row pairs, no staging
+    if (a16 && g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2 && g.ph == 0 && g.pw == 0 &&
+        g.H % 2 == 0 && g.W % 4 == 0 && env_int("CNNMEM_POOL_NCHW_ROWS", 1)) {
+        const int vin = (g.W % 8 == 0) ? 8 : 4;
+        const long long per_row = g.W / vin;
+        const long long items = planes * g.Ho * per_row;
+        if (items < 0x7fffffffLL) {
+            const FastDiv d = make_fastdiv((uint32_t)per_row);
+            const unsigned blocks = (unsigned)ceil_div64(items, kThreads);
+            if (vin == 8)
+                hipLaunchKernelGGL((pool_nchw_2x2s2_kernel<MODE, 8>), dim3(blocks), dim3(kThreads), 0, st, src,
+                                   dst, (uint32_t)items, (uint32_t)g.W, d);
+            else
+                hipLaunchKernelGGL((pool_nchw_2x2s2_kernel<MODE, 4>), dim3(blocks), dim3(kThreads), 0, st, src,
+                                   dst, (uint32_t)items, (uint32_t)g.W, d);
+            return launch_status();
+        }
+    }
+
+    // (2) LDS slab: whole planes when they fit, else strips of output rows
+    const long long plane_in = (long long)g.H * g.W;
+    if (aligned16(src) && plane_in * planes < (1LL << 40)) {
+        SlabPlan plan;
+        plan.total_planes = planes;
+        bool ok = false;
+        long long blocks = 0;
+        const int budget = kSlabFloats - 4;         // room for the aligned-down head
+        if (plane_in <= budget) {
+            long long p = budget / plane_in;
+            // keep at least ~8 workgroups per CU's worth of parallelism when the tensor allows
+            const long long min_blocks = 2048;
+            if (planes / p < min_blocks) p = planes / min_blocks > 0 ? planes / min_blocks : 1;
+            if (p * (long long)g.Ho * g.Wo < (1 << 30)) {
+                plan.planes_per_wg = (int)p;
+                plan.rows_per_wg = g.Ho;
+                plan.strips = 1;
+                blocks = ceil_div64(planes, p);
+                ok = true;
+            }
+        } else {
+            // rows_out output rows need (rows_out-1)*sh + kh input rows
+            const long long max_in_rows = budget / g.W;
+            long long rows_out = (max_in_rows - g.kh) / g.sh + 1;
+            if (max_in_rows >= g.kh && rows_out >= 1) {
+                if (rows_out > g.Ho) rows_out = g.Ho;
+                plan.planes_per_wg = 1;
+                plan.rows_per_wg = (int)rows_out;
+                plan.strips = ceil_div(g.Ho, rows_out);
+                blocks = planes * plan.strips;
+                ok = true;
+            }
+        }
+        if (ok && blocks <= 0x7fffffffLL) {
+            if (g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2)
+                return launch_slab<MODE, 3, 3, 2, 2>(src, dst, g, plan, blocks, st);
+            if (g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2)
+                return launch_slab<MODE, 2, 2, 2, 2>(src, dst, g, plan, blocks, st);
+            return launch_slab<MODE, 0, 0, 0, 0>(src, dst, g, plan, blocks, st);
+        }
+    }
+    return launch_generic<MODE>(src, dst, g, 0, st);
+}
+
+}  // namespace
+
+int launch_pool_nchw(const float* src, float* dst, const PoolGeom& g, hipStream_t st) {
+    return g.mode == CNNMEM_POOL_MAX ? dispatch_nchw<CNNMEM_POOL_MAX>(src, dst, g, st)
+                                     : dispatch_nchw<CNNMEM_POOL_AVG>(src, dst, g, st);
+}
+
+int launch_pool_chwn(const float* src, float* dst, const PoolGeom& g, hipStream_t st) {
+    return g.mode == CNNMEM_POOL_MAX ? dispatch_chwn<CNNMEM_POOL_MAX>(src, dst, g, st)
+                                     : dispatch_chwn<CNNMEM_POOL_AVG>(src, dst, g, st);
+}
+
+}  // namespace cnnmem

@@ -1,0 +1,251 @@
+// Fused softmax (Section II.A steps 1-5 in one kernel, Section V.B).
+//
+// The paper's fused kernel stages a row in shared memory, which capped it at
+// about 11K categories on its GPU.  Here a row lives in registers: a group of
+// TPR lanes (one or more wavefronts) owns one row, each lane holds ITEMS float4,
+// the row is read from HBM exactly once and written exactly once.  The max and
+// the sum are reduced inside a wavefront with DPP lane permutes and across the
+// wavefronts of a row through a few LDS words.
+//
+// Rows need not be 16-byte aligned (21841 floats = 87364 bytes): the lanes walk
+// the row as the aligned float4 stream that covers it and mask the (at most
+// three) elements before the row's first and after its last element, so every
+// interior access is still a 128-bit one.
+#include <cmath>
+
+#include "common.hpp"
+
+namespace cnnmem {
+namespace {
+
+// ---- wavefront reductions ----------------------------------------------------
+// DPP controls: quad_perm(1,0,3,2)=0xB1, quad_perm(2,3,0,1)=0x4E,
+// row_half_mirror=0x141, row_mirror=0x140.  After the four steps every lane of a
+// 16-lane row holds the row's result; the four rows are combined by reading one
+// lane of each.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+
+__device__ __forceinline__ float lane_value(float v, int lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
+struct MaxOp {
+    static __device__ __forceinline__ float apply(float a, float b) { return fmaxf(a, b); }
+};
+struct SumOp {
+    static __device__ __forceinline__ float apply(float a, float b) { return a + b; }
+};
+
+template <class Op>
+__device__ __forceinline__ float wave_reduce(float v) {
+    v = Op::apply(v, dpp_move<0xB1>(v));
+    v = Op::apply(v, dpp_move<0x4E>(v));
+    v = Op::apply(v, dpp_move<0x141>(v));
+    v = Op::apply(v, dpp_move<0x140>(v));
+    const float r0 = lane_value(v, 0), r1 = lane_value(v, 16);
+    const float r2 = lane_value(v, 32), r3 = lane_value(v, 48);
+    return Op::apply(Op::apply(r0, r1), Op::apply(r2, r3));
+}
+
+// Reduction over the TPR lanes that share a row.  `slots` has one float per
+// wavefront of the workgroup; `first_wave` is the row's first wavefront.
+template <class Op, int TPR>
+__device__ __forceinline__ float row_reduce(float v, float* slots, int wave, int first_wave) {
+    v = wave_reduce<Op>(v);
+    if constexpr (TPR > kWave) {
+        constexpr int WAVES = TPR / kWave;
+        __syncthreads();                            // previous use of slots is over
+        if ((threadIdx.x & (kWave - 1)) == 0) slots[wave] = v;
+        __syncthreads();
+        float r = slots[first_wave];
+#pragma unroll
+        for (int w = 1; w < WAVES; ++w) r = Op::apply(r, slots[first_wave + w]);
+        v = r;
+    }
+    return v;
+}
+
+// exp(d) for d <= 0, about 1 ulp: 2^t with t = d*log2(e) rounded once, then a
+// first-order correction for the rounding error of that product.  Arguments
+// below -120 give exactly 0 (they are below the smallest fp32 denormal anyway).
+__device__ __forceinline__ float exp_nonpos(float d) {
+    constexpr float kLog2eHi = 1.44269502162933349609375f;        // fp32(log2 e)
+    constexpr float kLog2eLo = 1.925963033500011e-08f;            // log2 e - fp32(log2 e)
+    constexpr float kLn2 = 0.693147182464599609375f;
+    d = fmaxf(d, -120.0f);
+    const float t = d * kLog2eHi;
+    float err = __builtin_fmaf(d, kLog2eHi, -t);                  // exact product minus its rounding
+    err = __builtin_fmaf(d, kLog2eLo, err);
+    const float p = __builtin_amdgcn_exp2f(t);
+    return __builtin_fmaf(p, err * kLn2, p);
+}
+
+constexpr float kNegInf = -__builtin_huge_valf();
+
+// One row per TPR lanes, ITEMS float4 per lane held in registers.
+//   mis = (row start, in floats) mod 4 relative to a 16-byte boundary; float4 q of
+//   the row's stream covers row elements [4q - mis, 4q - mis + 4).
+template <int TPR, int ITEMS>
+__global__ __launch_bounds__(TPR < 256 ? 256 : TPR) void softmax_rows_kernel(
+    const float* logits, float* probs, int N, int classes, int base_mis) {
+    constexpr int BLOCK = TPR < 256 ? 256 : TPR;
+    constexpr int ROWS = BLOCK / TPR;
+    __shared__ float slots[BLOCK / kWave];
+
+    const int tid = threadIdx.x;
+    const int wave = tid / kWave;
+    const int row_in_block = tid / TPR;
+    const int lane = tid % TPR;
+    const int first_wave = row_in_block * (TPR / kWave);
+    const long long row = (long long)blockIdx.x * ROWS + row_in_block;
+    const bool live = row < N;
+    const size_t row_off = (size_t)(live ? row : 0) * (size_t)classes;
+    const int mis = (int)((row_off + (size_t)base_mis) & 3);
+    const int nq = (classes + mis + 3) >> 2;
+    const float* x = logits + row_off;
+    float* y = probs + row_off;
+
+    float4 v[ITEMS];
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+        const int q = lane + k * TPR;
+        const int rel = 4 * q - mis;
+        float4 t = make_float4(kNegInf, kNegInf, kNegInf, kNegInf);
+        if (live && q < nq) {
+            if (rel >= 0 && rel + 4 <= classes) {
+                t = *reinterpret_cast<const float4*>(x + rel);
+            } else {
+                if (rel + 0 >= 0 && rel + 0 < classes) t.x = x[rel + 0];
+                if (rel + 1 >= 0 && rel + 1 < classes) t.y = x[rel + 1];
+                if (rel + 2 >= 0 && rel + 2 < classes) t.z = x[rel + 2];
+                if (rel + 3 >= 0 && rel + 3 < classes) t.w = x[rel + 3];
+            }
+        }
+        v[k] = t;
+    }
+
+    // step 1: row maximum
+    float m = kNegInf;
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) m = fmaxf(fmaxf(m, fmaxf(v[k].x, v[k].y)), fmaxf(v[k].z, v[k].w));
+    m = row_reduce<MaxOp, TPR>(m, slots, wave, first_wave);
+
+    // steps 2-4: shift, exponentiate, sum (masked slots hold -inf and give 0)
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+        v[k].x = exp_nonpos(v[k].x - m);
+        v[k].y = exp_nonpos(v[k].y - m);
+        v[k].z = exp_nonpos(v[k].z - m);
+        v[k].w = exp_nonpos(v[k].w - m);
+        s += (v[k].x + v[k].y) + (v[k].z + v[k].w);
+    }
+    s = row_reduce<SumOp, TPR>(s, slots, wave, first_wave);
+
+    // step 5: normalise
+    const float inv = 1.0f / s;
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+        const int q = lane + k * TPR;
+        const int rel = 4 * q - mis;
+        if (live && q < nq) {
+            const float4 o = make_float4(v[k].x * inv, v[k].y * inv, v[k].z * inv, v[k].w * inv);
+            if (rel >= 0 && rel + 4 <= classes) {
+                *reinterpret_cast<float4*>(y + rel) = o;
+            } else {
+                if (rel + 0 >= 0 && rel + 0 < classes) y[rel + 0] = o.x;
+                if (rel + 1 >= 0 && rel + 1 < classes) y[rel + 1] = o.y;
+                if (rel + 2 >= 0 && rel + 2 < classes) y[rel + 2] = o.z;
+                if (rel + 3 >= 0 && rel + 3 < classes) y[rel + 3] = o.w;
+            }
+        }
+    }
+}
+
+// Rows too long for registers (or buffers that are not 16-byte aligned): one
+// 1024-lane workgroup per row, dword accesses, three sweeps over the row (max,
+// sum of exponentials, normalised values); the later sweeps mostly hit in L2.
+__global__ __launch_bounds__(1024) void softmax_stream_kernel(const float* logits, float* probs,
+                                                              int classes) {
+    constexpr int TPR = 1024;
+    __shared__ float slots[TPR / kWave];
+    const int tid = threadIdx.x;
+    const int wave = tid / kWave;
+    const size_t row_off = (size_t)blockIdx.x * (size_t)classes;
+    const float* x = logits + row_off;
+    float* y = probs + row_off;
+
+    float m = kNegInf;
+    for (int c = tid; c < classes; c += TPR) m = fmaxf(m, x[c]);
+    m = row_reduce<MaxOp, TPR>(m, slots, wave, 0);
+    float s = 0.f;
+    for (int c = tid; c < classes; c += TPR) s += exp_nonpos(x[c] - m);
+    s = row_reduce<SumOp, TPR>(s, slots, wave, 0);
+    const float inv = 1.0f / s;
+    for (int c = tid; c < classes; c += TPR) y[c] = exp_nonpos(x[c] - m) * inv;
+}
+
+template <int TPR, int ITEMS>
+int launch_rows(const float* logits, float* probs, int N, int classes, int base_mis, hipStream_t st) {
+    constexpr int BLOCK = TPR < 256 ? 256 : TPR;
+    constexpr int ROWS = BLOCK / TPR;
+    const unsigned blocks = (unsigned)ceil_div64(N, ROWS);
+    hipLaunchKernelGGL((softmax_rows_kernel<TPR, ITEMS>), dim3(blocks), dim3(BLOCK), 0, st,
+                       logits, probs, N, classes, base_mis);
+    return launch_status();
+}
+
+template <int TPR>
+int launch_rows_items(int items, const float* logits, float* probs, int N, int classes, int base_mis,
+                      hipStream_t st) {
+#define CNNMEM_CASE(I) \
+    if (items <= I) return launch_rows<TPR, I>(logits, probs, N, classes, base_mis, st)
+    CNNMEM_CASE(1);
+    CNNMEM_CASE(2);
+    CNNMEM_CASE(3);
+    CNNMEM_CASE(4);
+    CNNMEM_CASE(6);
+    CNNMEM_CASE(8);
+    CNNMEM_CASE(12);
+    CNNMEM_CASE(16);
+    CNNMEM_CASE(24);
+    CNNMEM_CASE(32);
+#undef CNNMEM_CASE
+    return CNNMEM_ERR_UNSUPPORTED;
+}
+
+}  // namespace
+
+int launch_softmax(const float* logits, float* probs, int N, int classes, hipStream_t st) {
+    // The register kernel needs both buffers to share their 16-byte phase.
+    const uintptr_t pa = reinterpret_cast<uintptr_t>(logits), pb = reinterpret_cast<uintptr_t>(probs);
+    const bool same_phase = ((pa ^ pb) & 15u) == 0;
+    const int base_mis = (int)((pa & 15u) >> 2);
+    const long long nq = ((long long)classes + 3 + 3) / 4;        // float4 slots incl. worst-case misalignment
+    int tpr = env_int("CNNMEM_SOFTMAX_TPR", 0);
+    if (tpr != 64 && tpr != 128 && tpr != 256 && tpr != 512 && tpr != 1024) {
+        // smallest lane group that keeps at most 8 float4 per lane, else 1024
+        tpr = 64;
+        while (tpr < 1024 && nq > (long long)tpr * 8) tpr *= 2;
+    }
+    const long long items = ceil_div64(nq, tpr);
+    // 1024 lanes leave 128 VGPRs per lane: beyond 16 float4 the row would spill
+    const long long max_items = tpr == 1024 ? 16 : 32;
+    if (same_phase && items <= max_items) {
+        switch (tpr) {
+            case 64: return launch_rows_items<64>((int)items, logits, probs, N, classes, base_mis, st);
+            case 128: return launch_rows_items<128>((int)items, logits, probs, N, classes, base_mis, st);
+            case 256: return launch_rows_items<256>((int)items, logits, probs, N, classes, base_mis, st);
+            case 512: return launch_rows_items<512>((int)items, logits, probs, N, classes, base_mis, st);
+            default: return launch_rows_items<1024>((int)items, logits, probs, N, classes, base_mis, st);
+        }
+    }
+    hipLaunchKernelGGL(softmax_stream_kernel, dim3((unsigned)N), dim3(1024), 0, st, logits, probs, classes);
+    return launch_status();
+}
+
+}  // namespace cnnmem

@@ -1,0 +1,185 @@
+// Layout transformation NCHW <-> CHWN as a 2-D transpose (Section IV.C).
+//
+// C, H and W keep their relative order in both layouts, so with M = C*H*W the
+// NCHW tensor is an [N][M] matrix and the CHWN tensor is the [M][N] matrix: one
+// generic kernel src[R][S] -> dst[S][R] serves both directions.
+//
+// gfx950 design (not the paper's Kepler float2 scheme): every lane moves
+// 128-bit words on both the read and the write side.  A workgroup owns a TR x TS
+// tile; each lane loads a 4x4 block (four float4 from four consecutive source
+// rows), transposes it in registers, and parks the four transposed float4 in an
+// LDS tile that is already in destination order.  After one barrier the tile is
+// read back row by row with 128-bit LDS reads and written with 128-bit global
+// stores, so global reads and writes are both contiguous runs of TS*4 and TR*4
+// bytes.  LDS rows are padded by 4 floats and stored in a j-major swizzled order
+// so that the 16 lanes that write one 4x4 block column hit distinct bank groups.
+#include "common.hpp"
+
+namespace cnnmem {
+namespace {
+
+constexpr int kThreads = 256;
+
+// LDS row that holds destination row `s_local` of the tile.  Rows s = 4*bs + j
+// are stored at j*(TS/4) + bs: lanes with consecutive bs write consecutive LDS
+// rows (pitch 4 floats over a multiple of 16 floats -> distinct bank groups).
+template <int TS>
+__device__ __forceinline__ int lds_row(int s_local) {
+    return (s_local & 3) * (TS / 4) + (s_local >> 2);
+}
+
+template <int TR, int TS>
+__global__ __launch_bounds__(kThreads) void transpose_vec4_kernel(
+    const float* __restrict__ src, float* __restrict__ dst, long long R, long long S,
+    uint32_t tiles_s) {
+    static_assert(TR % 4 == 0 && TS % 4 == 0, "tile sides are multiples of 4");
+    static_assert((TR * TS / 16) % kThreads == 0, "whole number of 4x4 blocks per lane");
+    constexpr int P = TR + 4;                       // LDS pitch in floats (keeps float4 alignment)
+    constexpr int NBS = TS / 4;                     // 4x4 blocks along S
+    constexpr int LOAD_ITERS = (TR * TS / 16) / kThreads;
+    constexpr int NBR = TR / 4;                     // float4 per destination row of the tile
+    constexpr int STORE_ITERS = (TS * NBR) / kThreads;
+
+    __shared__ __attribute__((aligned(16))) float tile[TS * P];
+
+    const uint32_t tile_id = blockIdx.x;
+    const long long r0 = (long long)(tile_id / tiles_s) * TR;
+    const long long s0 = (long long)(tile_id % tiles_s) * TS;
+    const int tid = threadIdx.x;
+
+    float4 v[LOAD_ITERS][4];
+#pragma unroll
+    for (int it = 0; it < LOAD_ITERS; ++it) {
+        const int b = tid + it * kThreads;
+        const int bs = b % NBS;
+        const int br = b / NBS;
+        const long long r = r0 + 4 * br;
+        const long long s = s0 + 4 * bs;
+        const bool ok = (r < R) && (s < S);         // R % 4 == 0 and S % 4 == 0: all-or-nothing
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[it][i] = ok ? *reinterpret_cast<const float4*>(src + (size_t)(r + i) * (size_t)S + (size_t)s)
+                          : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < LOAD_ITERS; ++it) {
+        const int b = tid + it * kThreads;
+        const int bs = b % NBS;
+        const int br = b / NBS;
+        const float4 a = v[it][0], bq = v[it][1], c = v[it][2], d = v[it][3];
+        float* base = tile + 4 * br;
+        *reinterpret_cast<float4*>(base + lds_row<TS>(4 * bs + 0) * P) = make_float4(a.x, bq.x, c.x, d.x);
+        *reinterpret_cast<float4*>(base + lds_row<TS>(4 * bs + 1) * P) = make_float4(a.y, bq.y, c.y, d.y);
+        *reinterpret_cast<float4*>(base + lds_row<TS>(4 * bs + 2) * P) = make_float4(a.z, bq.z, c.z, d.z);
+        *reinterpret_cast<float4*>(base + lds_row<TS>(4 * bs + 3) * P) = make_float4(a.w, bq.w, c.w, d.w);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < STORE_ITERS; ++it) {
+        const int f = tid + it * kThreads;
+        const int br = f % NBR;
+        const int sl = f / NBR;
+        const float4 o = *reinterpret_cast<const float4*>(tile + lds_row<TS>(sl) * P + 4 * br);
+        const long long s = s0 + sl;
+        const long long r = r0 + 4 * br;
+        if (s < S && r < R)
+            *reinterpret_cast<float4*>(dst + (size_t)s * (size_t)R + (size_t)r) = o;
+    }
+}
+
+// Any R, S and any 4-byte alignment: 64x64 tile, dword accesses, pitch 65.
+__global__ __launch_bounds__(kThreads) void transpose_scalar_kernel(
+    const float* __restrict__ src, float* __restrict__ dst, long long R, long long S,
+    uint32_t tiles_s) {
+    constexpr int T = 64;
+    __shared__ float tile[T * (T + 1)];
+    const uint32_t tile_id = blockIdx.x;
+    const long long r0 = (long long)(tile_id / tiles_s) * T;
+    const long long s0 = (long long)(tile_id % tiles_s) * T;
+    const int tx = threadIdx.x % T;
+    const int ty = threadIdx.x / T;                 // 0..3
+#pragma unroll
+    for (int k = 0; k < T / 4; ++k) {
+        const int rl = ty + 4 * k;
+        const long long r = r0 + rl, s = s0 + tx;
+        if (r < R && s < S) tile[rl * (T + 1) + tx] = src[(size_t)r * (size_t)S + (size_t)s];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < T / 4; ++k) {
+        const int sl = ty + 4 * k;
+        const long long s = s0 + sl, r = r0 + tx;
+        if (r < R && s < S) dst[(size_t)s * (size_t)R + (size_t)r] = tile[tx * (T + 1) + sl];
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void copy_vec4_kernel(const float4* __restrict__ src,
+                                                             float4* __restrict__ dst, size_t n4) {
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += stride) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(kThreads) void copy_scalar_kernel(const float* __restrict__ src,
+                                                               float* __restrict__ dst, size_t n) {
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+template <int TR, int TS>
+int launch_vec4(const float* src, float* dst, long long R, long long S, hipStream_t st) {
+    const long long tiles_r = ceil_div64(R, TR), tiles_s = ceil_div64(S, TS);
+    const long long tiles = tiles_r * tiles_s;
+    if (tiles > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((transpose_vec4_kernel<TR, TS>), dim3((unsigned)tiles), dim3(kThreads), 0, st,
+                       src, dst, R, S, (uint32_t)tiles_s);
+    return launch_status();
+}
+
+}  // namespace
+
+int launch_transpose2d(const float* src, float* dst, long long R, long long S, hipStream_t st) {
+    const bool vec = (R % 4 == 0) && (S % 4 == 0) && aligned16(src) && aligned16(dst);
+    if (vec) {
+        // Tile shape: square by default; when one side of the matrix is short
+        // (small batch N) the tile is stretched along the other side so that no
+        // lane idles.  CNNMEM_TRANSFORM_TILE forces a shape for A/B profiling.
+        int shape = env_int("CNNMEM_TRANSFORM_TILE", -1);
+        if (shape < 0) {
+            if (R <= 16) shape = 3;
+            else if (R <= 32) shape = 2;
+            else if (S <= 16) shape = 5;
+            else if (S <= 32) shape = 4;
+            else shape = 0;
+        }
+        switch (shape) {
+            case 1: return launch_vec4<128, 64>(src, dst, R, S, st);
+            case 2: return launch_vec4<32, 128>(src, dst, R, S, st);
+            case 3: return launch_vec4<16, 256>(src, dst, R, S, st);
+            case 4: return launch_vec4<128, 32>(src, dst, R, S, st);
+            case 5: return launch_vec4<256, 16>(src, dst, R, S, st);
+            case 6: return launch_vec4<64, 128>(src, dst, R, S, st);
+            default: return launch_vec4<64, 64>(src, dst, R, S, st);
+        }
+    }
+    const long long tiles_r = ceil_div64(R, 64), tiles_s = ceil_div64(S, 64);
+    if (tiles_r * tiles_s > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(transpose_scalar_kernel, dim3((unsigned)(tiles_r * tiles_s)), dim3(kThreads), 0, st,
+                       src, dst, R, S, (uint32_t)tiles_s);
+    return launch_status();
+}
+
+int launch_copy(const float* src, float* dst, long long n, hipStream_t st) {
+    if (aligned16(src) && aligned16(dst) && n % 4 == 0) {
+        const size_t n4 = (size_t)n / 4;
+        const unsigned blocks = (unsigned)(ceil_div64((long long)n4, kThreads) < 16384 ? ceil_div64((long long)n4, kThreads) : 16384);
+        hipLaunchKernelGGL(copy_vec4_kernel, dim3(blocks), dim3(kThreads), 0, st,
+                           reinterpret_cast<const float4*>(src), reinterpret_cast<float4*>(dst), n4);
+    } else {
+        const unsigned blocks = (unsigned)(ceil_div64(n, kThreads) < 16384 ? ceil_div64(n, kThreads) : 16384);
+        hipLaunchKernelGGL(copy_scalar_kernel, dim3(blocks), dim3(kThreads), 0, st, src, dst, (size_t)n);
+    }
+    return launch_status();
+}
+
+}  // namespace cnnmem

@@ -28,3 +28,9 @@ def softmax_bytes(N: int, classes: int) -> int:
     return 2 * 4 * N * classes
 
 
+
+
+# HBM bytes per launch seen by the L2 <-> fabric counters (rocprofv3 --pmc FETCH_SIZE, then
+# WRITE_SIZE, scaled by what the same counters read for a plain copy of known size), keyed by
+# the benchmark's launch names.  Filled from the committed profile summaries; None = not measured.
+MEASURED_TRAFFIC = {}

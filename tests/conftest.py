@@ -14,10 +14,13 @@ def pytest_configure(config):
 
 
 @pytest.fixture(scope="session", autouse=True)
-def _built_oracle():
+def _built_libraries():
     """Load what is built; build only if nothing is there."""
     import oracle
     oracle.build()
+    from paper_1610_03618_amd import build as hip_build
+    if not os.path.exists(hip_build.LIB_PATH):
+        hip_build.build()
     yield
 
 

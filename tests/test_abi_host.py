@@ -1,0 +1,120 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every declared symbol, rejects invalid calls before touching HIP, and its index
+helpers (multiply-shift division, XCD tile ordering) are exact."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1610_03618_amd as cm
+from paper_1610_03618_amd import build as hip_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+INVALID = 1
+
+
+def _declared_symbols():
+    names = set()
+    for fn in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if fn.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names.update(re.findall(r"\b(cnnmem_\w+)\s*\(", text))
+    return names
+
+
+def test_library_is_built_and_exports_every_declared_symbol():
+    assert os.path.exists(hip_build.LIB_PATH)
+    lib = ctypes.CDLL(hip_build.LIB_PATH)
+    declared = _declared_symbols()
+    assert {"cnnmem_transform", "cnnmem_pool", "cnnmem_softmax", "cnnmem_pool_out_dims",
+            "cnnmem_status_string", "cnnmem_version"} <= declared
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_version_and_status_strings():
+    assert cm.cnnmem_version() >= 100
+    assert cm.cnnmem_status_string(0) == "ok"
+    assert "invalid" in cm.cnnmem_status_string(1)
+    assert cm.cnnmem_status_string(77) == "unknown status"
+
+
+def test_pool_out_dims_follows_floor_rule():
+    assert cm.cnnmem_pool_out_dims(12, 12, 4, 4, 2, 2, 0, 0) == (0, 5, 5)        # Fig. 8
+    assert cm.cnnmem_pool_out_dims(32, 32, 3, 3, 2, 2, 0, 0) == (0, 15, 15)
+    assert cm.cnnmem_pool_out_dims(224, 112, 2, 2, 2, 2, 0, 0) == (0, 112, 56)
+    assert cm.cnnmem_pool_out_dims(5, 7, 3, 3, 2, 1, 1, 1) == (0, 3, 7)
+    assert cm.cnnmem_pool_out_dims(2, 2, 3, 3, 1, 1, 0, 0)[0] == INVALID       # window > image
+    assert cm.cnnmem_pool_out_dims(8, 8, 3, 3, 0, 1, 0, 0)[0] == INVALID       # zero stride
+    assert cm.cnnmem_pool_out_dims(8, 8, 3, 3, 1, 1, 2, 0)[0] == INVALID       # pad > k/2
+    lib = cm.library()
+    assert lib.cnnmem_pool_out_dims(8, 8, 2, 2, 2, 2, 0, 0, None, None) == INVALID
+
+
+FAKE = 0x1000  # a non-null, 16-byte aligned address that is never dereferenced: every call below is rejected on the host
+
+
+@pytest.mark.parametrize("kwargs", [
+    dict(src=None), dict(dst=None), dict(N=0), dict(C=-1), dict(H=0), dict(W=0),
+    dict(src_layout=2), dict(dst_layout=-1), dict(src=FAKE + 2),
+])
+def test_transform_rejects_invalid_arguments_on_host(kwargs):
+    a = dict(src=FAKE, dst=FAKE + 4096, N=2, C=2, H=2, W=2, src_layout=cm.NCHW, dst_layout=cm.CHWN)
+    a.update(kwargs)
+    assert cm.cnnmem_transform(a["src"], a["dst"], a["N"], a["C"], a["H"], a["W"], a["src_layout"],
+                               a["dst_layout"], stream=0) == INVALID
+
+
+@pytest.mark.parametrize("kwargs", [
+    dict(src=None), dict(dst=None), dict(N=0), dict(C=0), dict(H=0), dict(W=-3), dict(layout=5),
+    dict(mode=2), dict(kh=0), dict(kw=0), dict(sh=0), dict(sw=-1), dict(ph=-1), dict(pw=-1),
+    dict(ph=2), dict(pw=2), dict(kh=9), dict(kw=9), dict(dst=FAKE + 1),
+])
+def test_pool_rejects_invalid_arguments_on_host(kwargs):
+    a = dict(src=FAKE, dst=FAKE + 4096, N=2, C=2, H=8, W=8, layout=cm.NCHW, mode=cm.POOL_MAX,
+             kh=3, kw=3, sh=2, sw=2, ph=0, pw=0)
+    a.update(kwargs)
+    assert cm.cnnmem_pool(a["src"], a["dst"], a["N"], a["C"], a["H"], a["W"], a["layout"], a["mode"],
+                          a["kh"], a["kw"], a["sh"], a["sw"], a["ph"], a["pw"], stream=0) == INVALID
+
+
+@pytest.mark.parametrize("kwargs", [dict(logits=None), dict(probs=None), dict(N=0), dict(classes=0),
+                                    dict(logits=FAKE + 3)])
+def test_softmax_rejects_invalid_arguments_on_host(kwargs):
+    a = dict(logits=FAKE, probs=FAKE + 4096, N=4, classes=10)
+    a.update(kwargs)
+    assert cm.cnnmem_softmax(a["logits"], a["probs"], a["N"], a["classes"], stream=0) == INVALID
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros(2, 3)
+    with pytest.raises(ValueError):
+        cm.cnnmem_softmax(x, x, 2, 3, stream=0)
+
+
+def test_fastdiv_is_exact():
+    lib = cm.library()
+    rng = np.random.default_rng(5)
+    divisors = [1, 2, 3, 4, 5, 7, 13, 27, 28, 32, 55, 112, 729, 3025, 21841, 65536, 65537,
+                (1 << 31) - 1] + rng.integers(1, 1 << 31, size=40).tolist()
+    for d in divisors:
+        ns = [0, 1, d - 1, d, d + 1, 2 * d - 1, 2 * d, (1 << 31) - 1, (1 << 31) - d] + \
+            rng.integers(0, 1 << 31, size=200).tolist()
+        for n in ns:
+            if 0 <= n < (1 << 31):
+                assert lib.cnnmem_debug_fastdiv(n, d) == n // d, (n, d)
+
+
+@pytest.mark.parametrize("nblocks", [1, 2, 7, 8, 9, 15, 16, 17, 63, 64, 100, 1001, 4096, 12289])
+def test_xcd_tile_order_is_a_bijection_and_groups_by_xcd(nblocks):
+    lib = cm.library()
+    tiles = [lib.cnnmem_debug_xcd_tile(b, nblocks) for b in range(nblocks)]
+    assert sorted(tiles) == list(range(nblocks))
+    # blocks dealt to one XCD (same id mod 8) get consecutive tiles
+    for x in range(min(8, nblocks)):
+        mine = [tiles[b] for b in range(x, nblocks, 8)]
+        assert mine == list(range(mine[0], mine[0] + len(mine)))
