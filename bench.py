@@ -116,6 +116,14 @@ def build_ops(torch, cm, wl, rl, only):
         ps = [torch.empty_like(z) for _ in range(nset)]
         ops.append(Op("softmax", "softmax", rl.softmax_bytes(s.N, s.classes), s.N * s.classes, "elements",
                       lambda i: cm.cnnmem_softmax(zs[i], ps[i], s.N, s.classes), nset))
+    # ---- optional: plain copy of known size, the yardstick the traffic counters are scaled by ----
+    if "copy_calibration" in only:
+        n = t.numel
+        nset = 4
+        a = [torch.zeros(n, dtype=torch.float32, device=dev) for _ in range(nset)]
+        b = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(nset)]
+        ops.append(Op("copy_calibration", "copy", 2 * 4 * n, n, "elements",
+                      lambda i: cm.cnnmem_transform(a[i], b[i], t.N, t.C, t.H, t.W, cm.NCHW, cm.NCHW), nset))
     torch.cuda.synchronize()
     return ops, host
 

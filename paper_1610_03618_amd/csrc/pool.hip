@@ -116,20 +116,30 @@ __global__ __launch_bounds__(kThreads) void pool_chwn_vec4_kernel(
     const int q0 = (int)j * SW - g.pw;
     const int r_base = i0 * SH - g.ph;
     const float* plane = src + (size_t)c * g.H * g.W * N + 4 * n4;
+    // Overlapping windows re-read taps that a neighbouring lane or strip has just
+    // fetched, so those loads stay cacheable; disjoint windows stream.
+    constexpr bool kStream = (KH <= SH) && (KW <= SW);
+    // Every load is unconditional (a branch per row would make the compiler wait
+    // for each row before asking for the next): taps outside the image are read
+    // from a clamped, valid address and replaced by the identity.  Without padding
+    // the only rows past H belong to output rows >= Ho, which are never stored, so
+    // clamping alone is enough there.
 #pragma unroll
     for (int rr = 0; rr < ROWS_IN; ++rr) {
         const int r = r_base + rr;
+        const bool row_ok = !PADDED || (r >= 0 && r < g.H);
+        const int rc = r < 0 ? 0 : (r < g.H ? r : g.H - 1);
+        const float* rowp = plane + (size_t)rc * g.W * N;
         float4 h = Acc<MODE>::identity4();
-        const bool row_ok = (r < g.H) && (!PADDED || r >= 0);
-        if (row_ok) {
-            const float* rowp = plane + (size_t)r * g.W * N;
 #pragma unroll
-            for (int x = 0; x < KW; ++x) {
-                const int q = q0 + x;
-                if (PADDED ? (q >= 0 && q < g.W) : true) {
-                    h = Acc<MODE>::op4(h, *reinterpret_cast<const float4*>(rowp + (size_t)q * N));
-                }
-            }
+        for (int x = 0; x < KW; ++x) {
+            const int q = q0 + x;
+            const bool ok = row_ok && (!PADDED || (q >= 0 && q < g.W));
+            const int qc = PADDED ? (q < 0 ? 0 : (q < g.W ? q : g.W - 1)) : q;
+            float4 t = kStream ? ld4_stream(rowp + (size_t)qc * N)
+                               : *reinterpret_cast<const float4*>(rowp + (size_t)qc * N);
+            if (PADDED && !ok) t = Acc<MODE>::identity4();
+            h = Acc<MODE>::op4(h, t);
         }
 #pragma unroll
         for (int oy = 0; oy < OY; ++oy)
@@ -140,8 +150,7 @@ __global__ __launch_bounds__(kThreads) void pool_chwn_vec4_kernel(
     for (int oy = 0; oy < OY; ++oy) {
         const int i = i0 + oy;
         if (i < g.Ho)
-            *reinterpret_cast<float4*>(outp + (size_t)i * g.Wo * N) =
-                Acc<MODE>::finish4(acc[oy], (float)(KH * KW));
+            st4_stream(outp + (size_t)i * g.Wo * N, Acc<MODE>::finish4(acc[oy], (float)(KH * KW)));
     }
 }
 
@@ -155,8 +164,8 @@ struct VecIO;
 template <>
 struct VecIO<8> {
     static __device__ __forceinline__ void run(const float* a, const float* b, float* o, int mode) {
-        const float4 a0 = reinterpret_cast<const float4*>(a)[0], a1 = reinterpret_cast<const float4*>(a)[1];
-        const float4 b0 = reinterpret_cast<const float4*>(b)[0], b1 = reinterpret_cast<const float4*>(b)[1];
+        const float4 a0 = ld4_stream(a), a1 = ld4_stream(a + 4);
+        const float4 b0 = ld4_stream(b), b1 = ld4_stream(b + 4);
         float4 r;
         if (mode == CNNMEM_POOL_MAX) {
             r.x = fmaxf(fmaxf(a0.x, a0.y), fmaxf(b0.x, b0.y));
@@ -169,13 +178,13 @@ struct VecIO<8> {
             r.z = ((a1.x + a1.y) + (b1.x + b1.y)) * 0.25f;
             r.w = ((a1.z + a1.w) + (b1.z + b1.w)) * 0.25f;
         }
-        *reinterpret_cast<float4*>(o) = r;
+        st4_stream(o, r);
     }
 };
 template <>
 struct VecIO<4> {
     static __device__ __forceinline__ void run(const float* a, const float* b, float* o, int mode) {
-        const float4 a0 = *reinterpret_cast<const float4*>(a), b0 = *reinterpret_cast<const float4*>(b);
+        const float4 a0 = ld4_stream(a), b0 = ld4_stream(b);
         float2 r;
         if (mode == CNNMEM_POOL_MAX) {
             r.x = fmaxf(fmaxf(a0.x, a0.y), fmaxf(b0.x, b0.y));
@@ -184,7 +193,7 @@ struct VecIO<4> {
             r.x = ((a0.x + a0.y) + (b0.x + b0.y)) * 0.25f;
             r.y = ((a0.z + a0.w) + (b0.z + b0.w)) * 0.25f;
         }
-        *reinterpret_cast<float2*>(o) = r;
+        st2_stream(o, r.x, r.y);
     }
 };
 
@@ -255,27 +264,34 @@ __global__ __launch_bounds__(kSlabThreads) void pool_nchw_slab_kernel(
     const int nvec = (int)((g_hi - a_lo + 3) >> 2);
 
     // ---- load phase: issue every 128-bit load, then park them in LDS ----
+    // All loads are unconditional so that they are in flight together: lanes past
+    // the slab, and the one float4 in the whole tensor that would cross its end,
+    // re-read the last complete float4 instead (total_in >= 4 is a dispatch
+    // condition) and simply do not park it.  The up to three floats of a ragged
+    // tensor end are then fetched one by one by the lane that owns them.
+    const size_t a_last = (total_in - 4) & ~(size_t)3;
     float4 v[kSlabVecPerLane];
 #pragma unroll
     for (int k = 0; k < kSlabVecPerLane; ++k) {
         const int q = threadIdx.x + k * kSlabThreads;
-        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (q < nvec) {
-            const size_t a = a_lo + 4 * (size_t)q;
-            if (a + 4 <= total_in) {
-                t = *reinterpret_cast<const float4*>(src + a);
-            } else {                                // last float4 of the tensor: stay inside it
-                if (a + 0 < total_in) t.x = src[a + 0];
-                if (a + 1 < total_in) t.y = src[a + 1];
-                if (a + 2 < total_in) t.z = src[a + 2];
-            }
-        }
-        v[k] = t;
+        size_t a = a_lo + 4 * (size_t)(q < nvec ? q : 0);
+        a = a <= a_last ? a : a_last;
+        v[k] = ld4_stream(src + a);
     }
 #pragma unroll
     for (int k = 0; k < kSlabVecPerLane; ++k) {
         const int q = threadIdx.x + k * kSlabThreads;
-        if (q < nvec) *reinterpret_cast<float4*>(slab + 4 * q) = v[k];
+        const size_t a = a_lo + 4 * (size_t)q;
+        if (q < nvec && a <= a_last) *reinterpret_cast<float4*>(slab + 4 * q) = v[k];
+    }
+#pragma unroll
+    for (int k = 0; k < kSlabVecPerLane; ++k) {
+        const int q = threadIdx.x + k * kSlabThreads;
+        const size_t a = a_lo + 4 * (size_t)q;
+        if (q < nvec && a > a_last) {               // ragged end of the tensor (at most one lane, once)
+            for (int j = 0; j < 4; ++j)
+                if (a + j < total_in) slab[4 * q + j] = src[a + j];
+        }
     }
     __syncthreads();
 
@@ -319,7 +335,7 @@ __global__ __launch_bounds__(kSlabThreads) void pool_nchw_slab_kernel(
                 }
             }
         }
-        dst[out0 + o] = Acc<MODE>::finish(acc, (float)(kh * kw));
+        st1_stream(dst + out0 + o, Acc<MODE>::finish(acc, (float)(kh * kw)));
     }
 }
 
@@ -417,7 +433,7 @@ int dispatch_nchw(const float* src, float* dst, const PoolGeom& g, hipStream_t s
 
     // (2) LDS slab: whole planes when they fit, else strips of output rows
     const long long plane_in = (long long)g.H * g.W;
-    if (aligned16(src) && plane_in * planes < (1LL << 40)) {
+    if (aligned16(src) && plane_in * planes < (1LL << 40) && plane_in * planes >= 4) {
         SlabPlan plan;
         plan.total_planes = planes;
         bool ok = false;

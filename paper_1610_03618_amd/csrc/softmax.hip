@@ -87,8 +87,14 @@ __device__ __forceinline__ float exp_nonpos(float d) {
 constexpr float kNegInf = -__builtin_huge_valf();
 
 // One row per TPR lanes, ITEMS float4 per lane held in registers.
-//   mis = (row start, in floats) mod 4 relative to a 16-byte boundary; float4 q of
-//   the row's stream covers row elements [4q - mis, 4q - mis + 4).
+//
+// A row of `classes` floats starts `mis` floats past a 16-byte boundary.  It is
+// split into a head (the h = (4 - mis) & 3 floats up to the next boundary), a body
+// of nbody aligned float4 and a tail of t < 4 floats.  Body slot q = lane + k*TPR
+// is one unconditional 128-bit access (lanes past the end re-read the last slot
+// and discard it), so the compiler issues all ITEMS loads back to back; the at
+// most six head/tail floats are carried by lanes 0..h+t-1 in one extra register.
+// Requires classes >= 8 (then nbody >= 1).
 template <int TPR, int ITEMS>
 __global__ __launch_bounds__(TPR < 256 ? 256 : TPR) void softmax_rows_kernel(
     const float* logits, float* probs, int N, int classes, int base_mis) {
@@ -101,41 +107,45 @@ __global__ __launch_bounds__(TPR < 256 ? 256 : TPR) void softmax_rows_kernel(
     const int row_in_block = tid / TPR;
     const int lane = tid % TPR;
     const int first_wave = row_in_block * (TPR / kWave);
-    const long long row = (long long)blockIdx.x * ROWS + row_in_block;
-    const bool live = row < N;
-    const size_t row_off = (size_t)(live ? row : 0) * (size_t)classes;
+    const long long row_raw = (long long)blockIdx.x * ROWS + row_in_block;
+    const bool live = row_raw < N;
+    const long long row = live ? row_raw : (long long)N - 1;        // idle lane groups shadow the last row
+    const size_t row_off = (size_t)row * (size_t)classes;
     const int mis = (int)((row_off + (size_t)base_mis) & 3);
-    const int nq = (classes + mis + 3) >> 2;
+    const int h = (4 - mis) & 3;
+    const int nbody = (classes - h) >> 2;
+    const int t = classes - h - 4 * nbody;
     const float* x = logits + row_off;
     float* y = probs + row_off;
+    const float* xb = x + h;                                        // 16-byte aligned
+    float* yb = y + h;
 
     float4 v[ITEMS];
 #pragma unroll
     for (int k = 0; k < ITEMS; ++k) {
         const int q = lane + k * TPR;
-        const int rel = 4 * q - mis;
-        float4 t = make_float4(kNegInf, kNegInf, kNegInf, kNegInf);
-        if (live && q < nq) {
-            if (rel >= 0 && rel + 4 <= classes) {
-                t = *reinterpret_cast<const float4*>(x + rel);
-            } else {
-                if (rel + 0 >= 0 && rel + 0 < classes) t.x = x[rel + 0];
-                if (rel + 1 >= 0 && rel + 1 < classes) t.y = x[rel + 1];
-                if (rel + 2 >= 0 && rel + 2 < classes) t.z = x[rel + 2];
-                if (rel + 3 >= 0 && rel + 3 < classes) t.w = x[rel + 3];
-            }
-        }
-        v[k] = t;
+        const int qc = q < nbody ? q : nbody - 1;
+        v[k] = ld4_stream(xb + 4 * qc);
     }
+    // head / tail element of this lane, if any
+    const bool is_head = lane < h;
+    const bool is_edge = lane < h + t;
+    const int edge_idx = is_head ? lane : h + 4 * nbody + (lane - h);
+    float e = kNegInf;
+    if (is_edge) e = ld1_stream(x + edge_idx);
 
-    // step 1: row maximum
-    float m = kNegInf;
+    // step 1: row maximum (slots past the body are masked to -inf first)
+    float m = e;
 #pragma unroll
-    for (int k = 0; k < ITEMS; ++k) m = fmaxf(fmaxf(m, fmaxf(v[k].x, v[k].y)), fmaxf(v[k].z, v[k].w));
+    for (int k = 0; k < ITEMS; ++k) {
+        if (lane + k * TPR >= nbody) v[k] = make_float4(kNegInf, kNegInf, kNegInf, kNegInf);
+        m = fmaxf(fmaxf(m, fmaxf(v[k].x, v[k].y)), fmaxf(v[k].z, v[k].w));
+    }
     m = row_reduce<MaxOp, TPR>(m, slots, wave, first_wave);
 
     // steps 2-4: shift, exponentiate, sum (masked slots hold -inf and give 0)
-    float s = 0.f;
+    e = exp_nonpos(e - m);
+    float s = e;
 #pragma unroll
     for (int k = 0; k < ITEMS; ++k) {
         v[k].x = exp_nonpos(v[k].x - m);
@@ -151,19 +161,35 @@ __global__ __launch_bounds__(TPR < 256 ? 256 : TPR) void softmax_rows_kernel(
 #pragma unroll
     for (int k = 0; k < ITEMS; ++k) {
         const int q = lane + k * TPR;
-        const int rel = 4 * q - mis;
-        if (live && q < nq) {
-            const float4 o = make_float4(v[k].x * inv, v[k].y * inv, v[k].z * inv, v[k].w * inv);
-            if (rel >= 0 && rel + 4 <= classes) {
-                *reinterpret_cast<float4*>(y + rel) = o;
-            } else {
-                if (rel + 0 >= 0 && rel + 0 < classes) y[rel + 0] = o.x;
-                if (rel + 1 >= 0 && rel + 1 < classes) y[rel + 1] = o.y;
-                if (rel + 2 >= 0 && rel + 2 < classes) y[rel + 2] = o.z;
-                if (rel + 3 >= 0 && rel + 3 < classes) y[rel + 3] = o.w;
-            }
-        }
+        if (live && q < nbody)
+            st4_stream(yb + 4 * q, make_float4(v[k].x * inv, v[k].y * inv, v[k].z * inv, v[k].w * inv));
     }
+    if (live && is_edge) st1_stream(y + edge_idx, e * inv);
+}
+
+// Rows of fewer than 8 categories: one lane per row, everything in registers.
+__global__ __launch_bounds__(256) void softmax_tiny_kernel(const float* logits, float* probs, int N, int classes) {
+    const long long row = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (row >= N) return;
+    const float* x = logits + (size_t)row * classes;
+    float* y = probs + (size_t)row * classes;
+    float v[7];
+    float m = kNegInf;
+#pragma unroll
+    for (int c = 0; c < 7; ++c) {
+        v[c] = c < classes ? x[c] : kNegInf;
+        m = fmaxf(m, v[c]);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < 7; ++c) {
+        v[c] = exp_nonpos(v[c] - m);
+        s += v[c];
+    }
+    const float inv = 1.0f / s;
+#pragma unroll
+    for (int c = 0; c < 7; ++c)
+        if (c < classes) y[c] = v[c] * inv;
 }
 
 // Rows too long for registers (or buffers that are not 16-byte aligned): one
@@ -194,8 +220,8 @@ int launch_rows(const float* logits, float* probs, int N, int classes, int base_
     constexpr int BLOCK = TPR < 256 ? 256 : TPR;
     constexpr int ROWS = BLOCK / TPR;
     const unsigned blocks = (unsigned)ceil_div64(N, ROWS);
-    hipLaunchKernelGGL((softmax_rows_kernel<TPR, ITEMS>), dim3(blocks), dim3(BLOCK), 0, st,
-                       logits, probs, N, classes, base_mis);
+    hipLaunchKernelGGL((softmax_rows_kernel<TPR, ITEMS>), dim3(blocks), dim3(BLOCK), 0, st, logits, probs, N,
+                       classes, base_mis);
     return launch_status();
 }
 
@@ -225,7 +251,12 @@ int launch_softmax(const float* logits, float* probs, int N, int classes, hipStr
     const uintptr_t pa = reinterpret_cast<uintptr_t>(logits), pb = reinterpret_cast<uintptr_t>(probs);
     const bool same_phase = ((pa ^ pb) & 15u) == 0;
     const int base_mis = (int)((pa & 15u) >> 2);
-    const long long nq = ((long long)classes + 3 + 3) / 4;        // float4 slots incl. worst-case misalignment
+    if (classes < 8) {
+        hipLaunchKernelGGL(softmax_tiny_kernel, dim3((unsigned)ceil_div64(N, 256)), dim3(256), 0, st, logits, probs,
+                           N, classes);
+        return launch_status();
+    }
+    const long long nq = classes / 4;                             // most aligned float4 a row can hold
     int tpr = env_int("CNNMEM_SOFTMAX_TPR", 0);
     if (tpr != 64 && tpr != 128 && tpr != 256 && tpr != 512 && tpr != 1024) {
         // smallest lane group that keeps at most 8 float4 per lane, else 1024

@@ -28,17 +28,17 @@ __device__ __forceinline__ int lds_row(int s_local) {
     return (s_local & 3) * (TS / 4) + (s_local >> 2);
 }
 
-template <int TR, int TS>
-__global__ __launch_bounds__(kThreads) void transpose_vec4_kernel(
+template <int TR, int TS, int THREADS>
+__global__ __launch_bounds__(THREADS) void transpose_vec4_kernel(
     const float* __restrict__ src, float* __restrict__ dst, long long R, long long S,
     uint32_t tiles_s) {
     static_assert(TR % 4 == 0 && TS % 4 == 0, "tile sides are multiples of 4");
-    static_assert((TR * TS / 16) % kThreads == 0, "whole number of 4x4 blocks per lane");
+    static_assert((TR * TS / 16) % THREADS == 0, "whole number of 4x4 blocks per lane");
     constexpr int P = TR + 4;                       // LDS pitch in floats (keeps float4 alignment)
     constexpr int NBS = TS / 4;                     // 4x4 blocks along S
-    constexpr int LOAD_ITERS = (TR * TS / 16) / kThreads;
+    constexpr int LOAD_ITERS = (TR * TS / 16) / THREADS;
     constexpr int NBR = TR / 4;                     // float4 per destination row of the tile
-    constexpr int STORE_ITERS = (TS * NBR) / kThreads;
+    constexpr int STORE_ITERS = (TS * NBR) / THREADS;
 
     __shared__ __attribute__((aligned(16))) float tile[TS * P];
 
@@ -47,24 +47,27 @@ __global__ __launch_bounds__(kThreads) void transpose_vec4_kernel(
     const long long s0 = (long long)(tile_id % tiles_s) * TS;
     const int tid = threadIdx.x;
 
+    // Lanes whose 4x4 block falls outside the matrix (edge tiles) re-read the last
+    // block instead of branching: every load is unconditional, so all of a lane's
+    // loads are in flight together, and what those lanes park in LDS is never
+    // written out.  R and S are multiples of 4, hence R - 4 and S - 4 are valid.
     float4 v[LOAD_ITERS][4];
 #pragma unroll
     for (int it = 0; it < LOAD_ITERS; ++it) {
-        const int b = tid + it * kThreads;
+        const int b = tid + it * THREADS;
         const int bs = b % NBS;
         const int br = b / NBS;
-        const long long r = r0 + 4 * br;
-        const long long s = s0 + 4 * bs;
-        const bool ok = (r < R) && (s < S);         // R % 4 == 0 and S % 4 == 0: all-or-nothing
+        long long r = r0 + 4 * br;
+        long long s = s0 + 4 * bs;
+        r = r < R ? r : R - 4;
+        s = s < S ? s : S - 4;
+        const float* p = src + (size_t)r * (size_t)S + (size_t)s;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            v[it][i] = ok ? *reinterpret_cast<const float4*>(src + (size_t)(r + i) * (size_t)S + (size_t)s)
-                          : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
+        for (int i = 0; i < 4; ++i) v[it][i] = ld4_stream(p + (size_t)i * (size_t)S);
     }
 #pragma unroll
     for (int it = 0; it < LOAD_ITERS; ++it) {
-        const int b = tid + it * kThreads;
+        const int b = tid + it * THREADS;
         const int bs = b % NBS;
         const int br = b / NBS;
         const float4 a = v[it][0], bq = v[it][1], c = v[it][2], d = v[it][3];
@@ -77,14 +80,54 @@ __global__ __launch_bounds__(kThreads) void transpose_vec4_kernel(
     __syncthreads();
 #pragma unroll
     for (int it = 0; it < STORE_ITERS; ++it) {
-        const int f = tid + it * kThreads;
+        const int f = tid + it * THREADS;
         const int br = f % NBR;
         const int sl = f / NBR;
         const float4 o = *reinterpret_cast<const float4*>(tile + lds_row<TS>(sl) * P + 4 * br);
         const long long s = s0 + sl;
         const long long r = r0 + 4 * br;
         if (s < S && r < R)
-            *reinterpret_cast<float4*>(dst + (size_t)s * (size_t)R + (size_t)r) = o;
+            st4_stream(dst + (size_t)s * (size_t)R + (size_t)r, o);
+    }
+}
+
+// One float4 per lane (THREADS = TR*TS/4): the lane scatters its four words into
+// the transposed LDS tile with dword writes, and after the barrier reads one
+// float4 of a destination row back.  Fewer bytes in flight per lane than the
+// 4x4-block kernel; same LDS layout.
+template <int TR, int TS>
+__global__ __launch_bounds__(TR * TS / 4) void transpose_u1_kernel(
+    const float* __restrict__ src, float* __restrict__ dst, long long R, long long S, uint32_t tiles_s) {
+    constexpr int THREADS = TR * TS / 4;
+    constexpr int P = TR + 4;
+    constexpr int NC4 = TS / 4;                     // float4 per source row of the tile
+    constexpr int NBR = TR / 4;                     // float4 per destination row of the tile
+    __shared__ __attribute__((aligned(16))) float tile[TS * P];
+
+    const uint32_t tile_id = blockIdx.x;
+    const long long r0 = (long long)(tile_id / tiles_s) * TR;
+    const long long s0 = (long long)(tile_id % tiles_s) * TS;
+    const int tid = threadIdx.x;
+    {
+        const int c4 = tid % NC4;
+        const int rl = tid / NC4;
+        long long r = r0 + rl, s = s0 + 4 * c4;
+        r = r < R ? r : R - 1;                      // edge tiles: re-read a valid word, never written out
+        s = s < S ? s : S - 4;
+        const float4 v = ld4_stream(src + (size_t)r * (size_t)S + (size_t)s);
+        tile[lds_row<TS>(4 * c4 + 0) * P + rl] = v.x;
+        tile[lds_row<TS>(4 * c4 + 1) * P + rl] = v.y;
+        tile[lds_row<TS>(4 * c4 + 2) * P + rl] = v.z;
+        tile[lds_row<TS>(4 * c4 + 3) * P + rl] = v.w;
+    }
+    __syncthreads();
+    {
+        const int br = tid % NBR;
+        const int sl = tid / NBR;
+        const long long s = s0 + sl, r = r0 + 4 * br;
+        if (s < S && r < R)
+            st4_stream(dst + (size_t)s * (size_t)R + (size_t)r,
+                       *reinterpret_cast<const float4*>(tile + lds_row<TS>(sl) * P + 4 * br));
     }
 }
 
@@ -103,21 +146,24 @@ __global__ __launch_bounds__(kThreads) void transpose_scalar_kernel(
     for (int k = 0; k < T / 4; ++k) {
         const int rl = ty + 4 * k;
         const long long r = r0 + rl, s = s0 + tx;
-        if (r < R && s < S) tile[rl * (T + 1) + tx] = src[(size_t)r * (size_t)S + (size_t)s];
+        if (r < R && s < S) tile[rl * (T + 1) + tx] = ld1_stream(src + (size_t)r * (size_t)S + (size_t)s);
     }
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < T / 4; ++k) {
         const int sl = ty + 4 * k;
         const long long s = s0 + sl, r = r0 + tx;
-        if (r < R && s < S) dst[(size_t)s * (size_t)R + (size_t)r] = tile[tx * (T + 1) + sl];
+        if (r < R && s < S) st1_stream(dst + (size_t)s * (size_t)R + (size_t)r, tile[tx * (T + 1) + sl]);
     }
 }
 
-__global__ __launch_bounds__(kThreads) void copy_vec4_kernel(const float4* __restrict__ src,
-                                                             float4* __restrict__ dst, size_t n4) {
-    const size_t stride = (size_t)gridDim.x * kThreads;
-    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += stride) dst[i] = src[i];
+// One float4 per lane and as many workgroups as it takes: on MI355X this beats
+// deeper per-lane unrolling and persistent grids for a pure stream.
+__global__ __launch_bounds__(kThreads) void copy_vec4_kernel(const float* __restrict__ src,
+                                                             float* __restrict__ dst, size_t n4,
+                                                             size_t first) {
+    const size_t i = first + (size_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < n4) st4_stream(dst + 4 * i, ld4_stream(src + 4 * i));
 }
 
 __global__ __launch_bounds__(kThreads) void copy_scalar_kernel(const float* __restrict__ src,
@@ -126,12 +172,22 @@ __global__ __launch_bounds__(kThreads) void copy_scalar_kernel(const float* __re
     for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
-template <int TR, int TS>
+template <int TR, int TS, int THREADS = kThreads>
 int launch_vec4(const float* src, float* dst, long long R, long long S, hipStream_t st) {
     const long long tiles_r = ceil_div64(R, TR), tiles_s = ceil_div64(S, TS);
     const long long tiles = tiles_r * tiles_s;
     if (tiles > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((transpose_vec4_kernel<TR, TS>), dim3((unsigned)tiles), dim3(kThreads), 0, st,
+    hipLaunchKernelGGL((transpose_vec4_kernel<TR, TS, THREADS>), dim3((unsigned)tiles), dim3(THREADS), 0, st,
+                       src, dst, R, S, (uint32_t)tiles_s);
+    return launch_status();
+}
+
+template <int TR, int TS>
+int launch_u1(const float* src, float* dst, long long R, long long S, hipStream_t st) {
+    const long long tiles_r = ceil_div64(R, TR), tiles_s = ceil_div64(S, TS);
+    const long long tiles = tiles_r * tiles_s;
+    if (tiles > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((transpose_u1_kernel<TR, TS>), dim3((unsigned)tiles), dim3(TR * TS / 4), 0, st,
                        src, dst, R, S, (uint32_t)tiles_s);
     return launch_status();
 }
@@ -159,6 +215,22 @@ int launch_transpose2d(const float* src, float* dst, long long R, long long S, h
             case 4: return launch_vec4<128, 32>(src, dst, R, S, st);
             case 5: return launch_vec4<256, 16>(src, dst, R, S, st);
             case 6: return launch_vec4<64, 128>(src, dst, R, S, st);
+            case 7: return launch_vec4<32, 32, 64>(src, dst, R, S, st);
+            case 8: return launch_vec4<64, 32, 128>(src, dst, R, S, st);
+            case 9: return launch_vec4<32, 64, 128>(src, dst, R, S, st);
+            case 10: return launch_vec4<64, 64, 128>(src, dst, R, S, st);
+            case 11: return launch_vec4<128, 64, 512>(src, dst, R, S, st);
+            case 12: return launch_vec4<64, 64, 64>(src, dst, R, S, st);
+            case 13: return launch_vec4<128, 32, 128>(src, dst, R, S, st);
+            case 14: return launch_vec4<32, 128, 128>(src, dst, R, S, st);
+            case 20: return launch_u1<64, 64>(src, dst, R, S, st);
+            case 21: return launch_u1<32, 64>(src, dst, R, S, st);
+            case 22: return launch_u1<64, 32>(src, dst, R, S, st);
+            case 23: return launch_u1<32, 32>(src, dst, R, S, st);
+            case 24: return launch_u1<128, 32>(src, dst, R, S, st);
+            case 25: return launch_u1<32, 128>(src, dst, R, S, st);
+            case 26: return launch_u1<16, 64>(src, dst, R, S, st);
+            case 27: return launch_u1<64, 16>(src, dst, R, S, st);
             default: return launch_vec4<64, 64>(src, dst, R, S, st);
         }
     }
@@ -172,9 +244,12 @@ int launch_transpose2d(const float* src, float* dst, long long R, long long S, h
 int launch_copy(const float* src, float* dst, long long n, hipStream_t st) {
     if (aligned16(src) && aligned16(dst) && n % 4 == 0) {
         const size_t n4 = (size_t)n / 4;
-        const unsigned blocks = (unsigned)(ceil_div64((long long)n4, kThreads) < 16384 ? ceil_div64((long long)n4, kThreads) : 16384);
-        hipLaunchKernelGGL(copy_vec4_kernel, dim3(blocks), dim3(kThreads), 0, st,
-                           reinterpret_cast<const float4*>(src), reinterpret_cast<float4*>(dst), n4);
+        const size_t per_launch = (size_t)0x40000000 * kThreads;   // grid.x stays below 2^31
+        for (size_t first = 0; first < n4; first += per_launch) {
+            const size_t todo = n4 - first < per_launch ? n4 - first : per_launch;
+            hipLaunchKernelGGL(copy_vec4_kernel, dim3((unsigned)ceil_div64((long long)todo, kThreads)),
+                               dim3(kThreads), 0, st, src, dst, n4, first);
+        }
     } else {
         const unsigned blocks = (unsigned)(ceil_div64(n, kThreads) < 16384 ? ceil_div64(n, kThreads) : 16384);
         hipLaunchKernelGGL(copy_scalar_kernel, dim3(blocks), dim3(kThreads), 0, st, src, dst, (size_t)n);
