@@ -380,7 +380,7 @@ int dispatch_chwn(const float* src, float* dst, const PoolGeom& g, hipStream_t s
         else rc = launch_chwn_vec4<MODE, 3, 3, 2, 2, 4>(src, dst, g, st);
         if (rc != CNNMEM_ERR_UNSUPPORTED) return rc;
     } else if (vec && g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2) {
-        const int oy = env_int("CNNMEM_POOL_CHWN_OY", 2);
+        const int oy = env_int("CNNMEM_POOL_CHWN_OY", 1);     // disjoint windows: nothing to reuse, 1 is fastest
         int rc;
         if (oy <= 1) rc = launch_chwn_vec4<MODE, 2, 2, 2, 2, 1>(src, dst, g, st);
         else if (oy == 2) rc = launch_chwn_vec4<MODE, 2, 2, 2, 2, 2>(src, dst, g, st);

@@ -88,16 +88,20 @@ constexpr float kNegInf = -__builtin_huge_valf();
 
 // One row per TPR lanes, ITEMS float4 per lane held in registers.
 //
-// A row of `classes` floats starts `mis` floats past a 16-byte boundary.  It is
-// split into a head (the h = (4 - mis) & 3 floats up to the next boundary), a body
-// of nbody aligned float4 and a tail of t < 4 floats.  Body slot q = lane + k*TPR
-// is one unconditional 128-bit access (lanes past the end re-read the last slot
-// and discard it), so the compiler issues all ITEMS loads back to back; the at
-// most six head/tail floats are carried by lanes 0..h+t-1 in one extra register.
-// Requires classes >= 8 (then nbody >= 1).
+// A row of `classes` floats starts `mis` floats past a boundary of `align` floats
+// (align = 32, a 128-byte cache line, when both buffers sit at the same offset in
+// their lines, else 4, one float4).  It is split into a head (the
+// h = (align - mis) % align floats up to the next boundary), a body of nbody
+// float4 and a tail of t < 4 floats.  Body slot q = lane + k*TPR is one
+// unconditional 128-bit access (lanes past the end re-read the last slot and
+// discard it), so the compiler issues all ITEMS loads back to back, and with
+// align = 32 every wavefront reads and writes whole cache lines: no line is
+// fetched by two wavefronts or written in two pieces.  The at most align + 2
+// head/tail floats are carried by lanes 0..h+t-1 in one extra register.
+// Requires classes >= 2*align (then nbody >= 1).
 template <int TPR, int ITEMS>
 __global__ __launch_bounds__(TPR < 256 ? 256 : TPR) void softmax_rows_kernel(
-    const float* logits, float* probs, int N, int classes, int base_mis) {
+    const float* logits, float* probs, int N, int classes, int base_mis, int align) {
     constexpr int BLOCK = TPR < 256 ? 256 : TPR;
     constexpr int ROWS = BLOCK / TPR;
     __shared__ float slots[BLOCK / kWave];
@@ -111,8 +115,8 @@ __global__ __launch_bounds__(TPR < 256 ? 256 : TPR) void softmax_rows_kernel(
     const bool live = row_raw < N;
     const long long row = live ? row_raw : (long long)N - 1;        // idle lane groups shadow the last row
     const size_t row_off = (size_t)row * (size_t)classes;
-    const int mis = (int)((row_off + (size_t)base_mis) & 3);
-    const int h = (4 - mis) & 3;
+    const int mis = (int)((row_off + (size_t)base_mis) & (size_t)(align - 1));
+    const int h = (align - mis) & (align - 1);
     const int nbody = (classes - h) >> 2;
     const int t = classes - h - 4 * nbody;
     const float* x = logits + row_off;
@@ -216,20 +220,21 @@ __global__ __launch_bounds__(1024) void softmax_stream_kernel(const float* logit
 }
 
 template <int TPR, int ITEMS>
-int launch_rows(const float* logits, float* probs, int N, int classes, int base_mis, hipStream_t st) {
+int launch_rows(const float* logits, float* probs, int N, int classes, int base_mis, int align,
+                hipStream_t st) {
     constexpr int BLOCK = TPR < 256 ? 256 : TPR;
     constexpr int ROWS = BLOCK / TPR;
     const unsigned blocks = (unsigned)ceil_div64(N, ROWS);
     hipLaunchKernelGGL((softmax_rows_kernel<TPR, ITEMS>), dim3(blocks), dim3(BLOCK), 0, st, logits, probs, N,
-                       classes, base_mis);
+                       classes, base_mis, align);
     return launch_status();
 }
 
 template <int TPR>
 int launch_rows_items(int items, const float* logits, float* probs, int N, int classes, int base_mis,
-                      hipStream_t st) {
+                      int align, hipStream_t st) {
 #define CNNMEM_CASE(I) \
-    if (items <= I) return launch_rows<TPR, I>(logits, probs, N, classes, base_mis, st)
+    if (items <= I) return launch_rows<TPR, I>(logits, probs, N, classes, base_mis, align, st)
     CNNMEM_CASE(1);
     CNNMEM_CASE(2);
     CNNMEM_CASE(3);
@@ -250,7 +255,9 @@ int launch_softmax(const float* logits, float* probs, int N, int classes, hipStr
     // The register kernel needs both buffers to share their 16-byte phase.
     const uintptr_t pa = reinterpret_cast<uintptr_t>(logits), pb = reinterpret_cast<uintptr_t>(probs);
     const bool same_phase = ((pa ^ pb) & 15u) == 0;
-    const int base_mis = (int)((pa & 15u) >> 2);
+    // whole-line accesses need both buffers at the same offset inside their 128-byte lines
+    const int align = (((pa ^ pb) & 127u) == 0 && classes >= 64 && env_int("CNNMEM_SOFTMAX_ALIGN", 32) == 32) ? 32 : 4;
+    const int base_mis = (int)((pa & (uintptr_t)(4 * align - 1)) >> 2);
     if (classes < 8) {
         hipLaunchKernelGGL(softmax_tiny_kernel, dim3((unsigned)ceil_div64(N, 256)), dim3(256), 0, st, logits, probs,
                            N, classes);
@@ -268,11 +275,11 @@ int launch_softmax(const float* logits, float* probs, int N, int classes, hipStr
     const long long max_items = tpr == 1024 ? 16 : 32;
     if (same_phase && items <= max_items) {
         switch (tpr) {
-            case 64: return launch_rows_items<64>((int)items, logits, probs, N, classes, base_mis, st);
-            case 128: return launch_rows_items<128>((int)items, logits, probs, N, classes, base_mis, st);
-            case 256: return launch_rows_items<256>((int)items, logits, probs, N, classes, base_mis, st);
-            case 512: return launch_rows_items<512>((int)items, logits, probs, N, classes, base_mis, st);
-            default: return launch_rows_items<1024>((int)items, logits, probs, N, classes, base_mis, st);
+            case 64: return launch_rows_items<64>((int)items, logits, probs, N, classes, base_mis, align, st);
+            case 128: return launch_rows_items<128>((int)items, logits, probs, N, classes, base_mis, align, st);
+            case 256: return launch_rows_items<256>((int)items, logits, probs, N, classes, base_mis, align, st);
+            case 512: return launch_rows_items<512>((int)items, logits, probs, N, classes, base_mis, align, st);
+            default: return launch_rows_items<1024>((int)items, logits, probs, N, classes, base_mis, align, st);
         }
     }
     hipLaunchKernelGGL(softmax_stream_kernel, dim3((unsigned)N), dim3(1024), 0, st, logits, probs, classes);

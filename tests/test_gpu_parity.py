@@ -65,7 +65,7 @@ def test_transform_matches_oracle_bit_for_bit(shape):
     assert same_bits(host(same), x)
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("tile", list(range(11)))
 def test_transform_every_tile_shape(tile, monkeypatch):
     monkeypatch.setenv("CNNMEM_TRANSFORM_TILE", str(tile))
     for (N, C, H, W) in [(128, 3, 9, 12), (20, 5, 7, 4), (260, 1, 33, 4)]:
@@ -222,7 +222,7 @@ def check_softmax(z: np.ndarray, in_place=False):
     return got
 
 
-SOFTMAX_SHAPES = [(1, 1), (3, 2), (128, 10), (5, 63), (9, 64), (7, 65), (128, 1000), (7, 1001), (33, 1023),
+SOFTMAX_SHAPES = [(1, 1), (3, 2), (9, 5), (300, 7), (4, 8), (5, 9), (3, 11), (128, 10), (5, 63), (9, 64), (7, 65), (128, 1000), (7, 1001), (33, 1023),
                   (6, 2049), (10, 4097), (5, 8191), (3, 10000), (5, 21841), (3, 32768), (2, 49153),
                   (2, 65530), (2, 70001), (1, 140000)]
 
