@@ -259,7 +259,10 @@ __global__ __launch_bounds__(kSlabThreads) void pool_nchw_slab_kernel(
     if (planes > 1) { r_lo = 0; r_hi = g.H; }
     const size_t g_lo = (size_t)p0 * plane_in + (size_t)r_lo * g.W;
     const size_t g_hi = (size_t)(p0 + planes - 1) * plane_in + (size_t)r_hi * g.W;
-    const size_t a_lo = g_lo & ~(size_t)3;          // src is 16-byte aligned: float4 stream start
+    // The float4 stream starts on a 128-byte line of src when src itself is line
+    // aligned (always at least on a float4): wavefronts then fetch whole lines.
+    const size_t in_mask = (reinterpret_cast<uintptr_t>(src) & 127u) == 0 ? 31 : 3;
+    const size_t a_lo = g_lo & ~in_mask;
     const size_t total_in = (size_t)plan.total_planes * plane_in;
     const int nvec = (int)((g_hi - a_lo + 3) >> 2);
 
@@ -300,7 +303,11 @@ __global__ __launch_bounds__(kSlabThreads) void pool_nchw_slab_kernel(
     const size_t out0 = (size_t)p0 * plane_out + (size_t)i0 * g.Wo;
     // LDS index of element (plane p0, row 0, col 0); may be negative when r_lo > 0
     const int lds0 = (int)((long long)((size_t)p0 * plane_in) - (long long)a_lo);
-    for (int o = threadIdx.x; o < n_out; o += kSlabThreads) {
+    // Lane -> output assignment is shifted so that every wavefront's 256-byte
+    // store starts on a 128-byte line of dst (no line is written in two pieces).
+    const int lead = (int)(((reinterpret_cast<uintptr_t>(dst) >> 2) + out0) & 31);
+    for (int o = (int)threadIdx.x - lead; o < n_out; o += kSlabThreads) {
+        if (o < 0) continue;
         int pl = 0, rem = o;
         if (planes > 1) {
             pl = (int)fd_div((uint32_t)o, div_plane_out);
@@ -438,7 +445,7 @@ int dispatch_nchw(const float* src, float* dst, const PoolGeom& g, hipStream_t s
         plan.total_planes = planes;
         bool ok = false;
         long long blocks = 0;
-        const int budget = kSlabFloats - 4;         // room for the aligned-down head
+        const int budget = kSlabFloats - 32;        // room for the line-aligned head
         if (plane_in <= budget) {
             long long p = budget / plane_in;
             // keep at least ~8 workgroups per CU's worth of parallelism when the tensor allows
