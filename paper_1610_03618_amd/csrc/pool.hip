@@ -157,65 +157,36 @@ __global__ __launch_bounds__(kThreads) void pool_chwn_vec4_kernel(
 // ---------------------------------------------------------------------------
 // NCHW, 2x2 window, stride 2, no padding, even H: the tensor is a list of
 // N*C*H rows of W floats and output row k is made of input rows 2k and 2k+1.
-// A lane reads VIN consecutive floats of both rows and writes VIN/2 outputs.
+// A lane reads one float4 of both rows and writes two outputs: a wavefront's
+// load is one contiguous 1 KB run (two float4 per row per lane, 32 B apart
+// between lanes, measured 60 % against 76 % on 64x256x56x56).
 // ---------------------------------------------------------------------------
-template <int VIN>
-struct VecIO;
-template <>
-struct VecIO<8> {
-    static __device__ __forceinline__ void run(const float* a, const float* b, float* o, int mode) {
-        const float4 a0 = ld4_stream(a), a1 = ld4_stream(a + 4);
-        const float4 b0 = ld4_stream(b), b1 = ld4_stream(b + 4);
-        float4 r;
-        if (mode == CNNMEM_POOL_MAX) {
-            r.x = fmaxf(fmaxf(a0.x, a0.y), fmaxf(b0.x, b0.y));
-            r.y = fmaxf(fmaxf(a0.z, a0.w), fmaxf(b0.z, b0.w));
-            r.z = fmaxf(fmaxf(a1.x, a1.y), fmaxf(b1.x, b1.y));
-            r.w = fmaxf(fmaxf(a1.z, a1.w), fmaxf(b1.z, b1.w));
-        } else {
-            r.x = ((a0.x + a0.y) + (b0.x + b0.y)) * 0.25f;
-            r.y = ((a0.z + a0.w) + (b0.z + b0.w)) * 0.25f;
-            r.z = ((a1.x + a1.y) + (b1.x + b1.y)) * 0.25f;
-            r.w = ((a1.z + a1.w) + (b1.z + b1.w)) * 0.25f;
-        }
-        st4_stream(o, r);
-    }
-};
-template <>
-struct VecIO<4> {
-    static __device__ __forceinline__ void run(const float* a, const float* b, float* o, int mode) {
-        const float4 a0 = ld4_stream(a), b0 = ld4_stream(b);
-        float2 r;
-        if (mode == CNNMEM_POOL_MAX) {
-            r.x = fmaxf(fmaxf(a0.x, a0.y), fmaxf(b0.x, b0.y));
-            r.y = fmaxf(fmaxf(a0.z, a0.w), fmaxf(b0.z, b0.w));
-        } else {
-            r.x = ((a0.x + a0.y) + (b0.x + b0.y)) * 0.25f;
-            r.y = ((a0.z + a0.w) + (b0.z + b0.w)) * 0.25f;
-        }
-        st2_stream(o, r.x, r.y);
-    }
-};
-
-template <int MODE, int VIN>
+template <int MODE>
 __global__ __launch_bounds__(kThreads) void pool_nchw_2x2s2_kernel(
     const float* __restrict__ src, float* __restrict__ dst, uint32_t items, uint32_t W,
     FastDiv div_per_row) {
-    // item I: output floats [I*VIN/2, (I+1)*VIN/2); output row = I / (W/VIN)
+    // item I: output floats [2I, 2I + 2); output row = I / (W/4)
     const uint32_t I = blockIdx.x * kThreads + threadIdx.x;
     if (I >= items) return;
     const uint32_t orow = fd_div(I, div_per_row);
-    const size_t in0 = (size_t)I * VIN + (size_t)orow * W;     // = 2*orow*W + VIN*(I % per_row)
-    VecIO<VIN>::run(src + in0, src + in0 + W, dst + (size_t)I * (VIN / 2), MODE);
+    const size_t in0 = (size_t)I * 4 + (size_t)orow * W;       // = 2*orow*W + 4*(I % per_row)
+    const float4 a = ld4_stream(src + in0), b = ld4_stream(src + in0 + W);
+    float o0, o1;
+    if (MODE == CNNMEM_POOL_MAX) {
+        o0 = fmaxf(fmaxf(a.x, a.y), fmaxf(b.x, b.y));
+        o1 = fmaxf(fmaxf(a.z, a.w), fmaxf(b.z, b.w));
+    } else {
+        o0 = ((a.x + a.y) + (b.x + b.y)) * 0.25f;
+        o1 = ((a.z + a.w) + (b.z + b.w)) * 0.25f;
+    }
+    st2_stream(dst + (size_t)I * 2, o0, o1);
 }
 
 // ---------------------------------------------------------------------------
 // NCHW through LDS.  One workgroup = `planes` consecutive (n,c) planes (all
 // their rows) or one strip of `rows_out` output rows of a single plane.
 // ---------------------------------------------------------------------------
-constexpr int kSlabThreads = 256;
 constexpr int kSlabFloats = 8192;                   // 32 KB of LDS per workgroup
-constexpr int kSlabVecPerLane = kSlabFloats / 4 / kSlabThreads + 1;   // float4 per lane, worst case
 
 struct SlabPlan {
     int planes_per_wg;      // >= 1 (whole planes) ...
@@ -224,10 +195,12 @@ struct SlabPlan {
     long long total_planes;
 };
 
-template <int MODE, int KH, int KW, int SH, int SW, bool PADDED>
-__global__ __launch_bounds__(kSlabThreads) void pool_nchw_slab_kernel(
+template <int MODE, int KH, int KW, int SH, int SW, bool PADDED, int THREADS>
+__global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
     const float* __restrict__ src, float* __restrict__ dst, PoolGeom g, SlabPlan plan,
     FastDiv div_wo, FastDiv div_plane_out, int rt_kh, int rt_kw, int rt_sh, int rt_sw) {
+    constexpr int kSlabThreads = THREADS;
+    constexpr int kSlabVecPerLane = kSlabFloats / 4 / THREADS + 1;   // float4 per lane, worst case
     __shared__ __attribute__((aligned(16))) float slab[kSlabFloats + 8];
     const int kh = KH ? KH : rt_kh, kw = KW ? KW : rt_kw;
     const int sh = SH ? SH : rt_sh, sw = SW ? SW : rt_sw;
@@ -348,6 +321,20 @@ __global__ __launch_bounds__(kSlabThreads) void pool_nchw_slab_kernel(
 
 // ---- host-side dispatch ------------------------------------------------------
 
+// Occupancy throttle.  On tensors of hundreds of MB, HBM throughput on MI355X is
+// best with about 48-64 KB of loads in flight per CU; a full complement of eight
+// 256-lane workgroups per CU keeps 64-128 KB in flight and loses 2-3 points.
+// Asking for dynamic LDS that the kernel never touches caps the workgroups per CU
+// (160 KB of LDS per CU).  Smaller tensors want all the parallelism they can get,
+// so the throttle only applies from 512 MB of input.
+inline size_t throttle_lds(long long in_bytes, int workgroups_per_cu) {
+    const int forced = env_int("CNNMEM_POOL_LDS", -1);
+    if (forced >= 0) return (size_t)forced;
+    if (in_bytes < (512LL << 20)) return 0;
+    return (size_t)(160 * 1024 / workgroups_per_cu) - 1024;
+}
+
+
 template <int MODE>
 int launch_generic(const float* src, float* dst, const PoolGeom& g, int chwn, hipStream_t st) {
     const size_t total = (size_t)g.N * g.C * g.Ho * g.Wo;
@@ -364,13 +351,16 @@ int launch_chwn_vec4(const float* src, float* dst, const PoolGeom& g, hipStream_
     const long long blocks = bx * by * g.C;
     if (row_items >= 0x7fffffffLL || blocks > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
     const FastDiv dn4 = make_fastdiv((uint32_t)(g.N / 4));
+    // disjoint windows with one output row per lane: 64 B in flight per lane, best at 4 workgroups per CU
+    const size_t lds = (OY == 1 && KH <= SH && KW <= SW)
+                           ? throttle_lds(4LL * g.N * g.C * g.H * g.W, 4) : 0;
     if (g.ph > 0 || g.pw > 0)
         hipLaunchKernelGGL((pool_chwn_vec4_kernel<MODE, KH, KW, SH, SW, OY, true>), dim3((unsigned)blocks),
-                           dim3(kThreads), 0, st, src, dst, g, (uint32_t)row_items, (uint32_t)bx,
+                           dim3(kThreads), lds, st, src, dst, g, (uint32_t)row_items, (uint32_t)bx,
                            (uint32_t)by, dn4);
     else
         hipLaunchKernelGGL((pool_chwn_vec4_kernel<MODE, KH, KW, SH, SW, OY, false>), dim3((unsigned)blocks),
-                           dim3(kThreads), 0, st, src, dst, g, (uint32_t)row_items, (uint32_t)bx,
+                           dim3(kThreads), lds, st, src, dst, g, (uint32_t)row_items, (uint32_t)bx,
                            (uint32_t)by, dn4);
     return launch_status();
 }
@@ -400,18 +390,28 @@ int dispatch_chwn(const float* src, float* dst, const PoolGeom& g, hipStream_t s
     return launch_generic<MODE>(src, dst, g, 1, st);
 }
 
-template <int MODE, int KH, int KW, int SH, int SW>
-int launch_slab(const float* src, float* dst, const PoolGeom& g, const SlabPlan& plan, long long blocks,
-                hipStream_t st) {
+template <int MODE, int KH, int KW, int SH, int SW, int THREADS>
+int launch_slab_threads(const float* src, float* dst, const PoolGeom& g, const SlabPlan& plan, long long blocks,
+                        hipStream_t st) {
     const FastDiv dwo = make_fastdiv((uint32_t)g.Wo);
     const FastDiv dpo = make_fastdiv((uint32_t)(g.Ho * g.Wo));
     if (g.ph > 0 || g.pw > 0 || KH == 0)
-        hipLaunchKernelGGL((pool_nchw_slab_kernel<MODE, KH, KW, SH, SW, true>), dim3((unsigned)blocks),
-                           dim3(kSlabThreads), 0, st, src, dst, g, plan, dwo, dpo, g.kh, g.kw, g.sh, g.sw);
+        hipLaunchKernelGGL((pool_nchw_slab_kernel<MODE, KH, KW, SH, SW, true, THREADS>), dim3((unsigned)blocks),
+                           dim3(THREADS), 0, st, src, dst, g, plan, dwo, dpo, g.kh, g.kw, g.sh, g.sw);
     else
-        hipLaunchKernelGGL((pool_nchw_slab_kernel<MODE, KH, KW, SH, SW, false>), dim3((unsigned)blocks),
-                           dim3(kSlabThreads), 0, st, src, dst, g, plan, dwo, dpo, g.kh, g.kw, g.sh, g.sw);
+        hipLaunchKernelGGL((pool_nchw_slab_kernel<MODE, KH, KW, SH, SW, false, THREADS>), dim3((unsigned)blocks),
+                           dim3(THREADS), 0, st, src, dst, g, plan, dwo, dpo, g.kh, g.kw, g.sh, g.sw);
     return launch_status();
+}
+
+template <int MODE, int KH, int KW, int SH, int SW>
+int launch_slab(const float* src, float* dst, const PoolGeom& g, const SlabPlan& plan, long long blocks,
+                hipStream_t st) {
+    // lanes per slab: more lanes = fewer 128-bit loads in flight per lane for the same 32 KB
+    const int threads = env_int("CNNMEM_POOL_SLAB_THREADS", 512);   // 512 measured best (68 % vs 64 % / 49 %)
+    if (threads >= 1024) return launch_slab_threads<MODE, KH, KW, SH, SW, 1024>(src, dst, g, plan, blocks, st);
+    if (threads >= 512) return launch_slab_threads<MODE, KH, KW, SH, SW, 512>(src, dst, g, plan, blocks, st);
+    return launch_slab_threads<MODE, KH, KW, SH, SW, 256>(src, dst, g, plan, blocks, st);
 }
 
 template <int MODE>
@@ -422,18 +422,15 @@ int dispatch_nchw(const float* src, float* dst, const PoolGeom& g, hipStream_t s
     // (1) non-overlapping 2x2 / stride 2 on even H: row pairs, no staging
     if (a16 && g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2 && g.ph == 0 && g.pw == 0 &&
         g.H % 2 == 0 && g.W % 4 == 0 && env_int("CNNMEM_POOL_NCHW_ROWS", 1)) {
-        const int vin = (g.W % 8 == 0) ? 8 : 4;
-        const long long per_row = g.W / vin;
+        const long long per_row = g.W / 4;
         const long long items = planes * g.Ho * per_row;
         if (items < 0x7fffffffLL) {
             const FastDiv d = make_fastdiv((uint32_t)per_row);
             const unsigned blocks = (unsigned)ceil_div64(items, kThreads);
-            if (vin == 8)
-                hipLaunchKernelGGL((pool_nchw_2x2s2_kernel<MODE, 8>), dim3(blocks), dim3(kThreads), 0, st, src,
-                                   dst, (uint32_t)items, (uint32_t)g.W, d);
-            else
-                hipLaunchKernelGGL((pool_nchw_2x2s2_kernel<MODE, 4>), dim3(blocks), dim3(kThreads), 0, st, src,
-                                   dst, (uint32_t)items, (uint32_t)g.W, d);
+            // 32 B in flight per lane: best at 6 workgroups per CU on large tensors
+            const size_t lds = throttle_lds(4LL * planes * g.H * g.W, 6);
+            hipLaunchKernelGGL((pool_nchw_2x2s2_kernel<MODE>), dim3(blocks), dim3(kThreads), lds, st, src, dst,
+                               (uint32_t)items, (uint32_t)g.W, d);
             return launch_status();
         }
     }

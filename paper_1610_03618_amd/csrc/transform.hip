@@ -28,6 +28,8 @@ __device__ __forceinline__ int lds_row(int s_local) {
     return (s_local & 3) * (TS / 4) + (s_local >> 2);
 }
 
+extern __shared__ float4 dyn_tile[];                // 16-byte aligned dynamic LDS
+
 template <int TR, int TS, int THREADS>
 __global__ __launch_bounds__(THREADS) void transpose_vec4_kernel(
     const float* __restrict__ src, float* __restrict__ dst, long long R, long long S,
@@ -40,7 +42,7 @@ __global__ __launch_bounds__(THREADS) void transpose_vec4_kernel(
     constexpr int NBR = TR / 4;                     // float4 per destination row of the tile
     constexpr int STORE_ITERS = (TS * NBR) / THREADS;
 
-    __shared__ __attribute__((aligned(16))) float tile[TS * P];
+    float* tile = reinterpret_cast<float*>(dyn_tile);   // TS * P floats, sized by the launch
 
     const uint32_t tile_id = blockIdx.x;
     const long long r0 = (long long)(tile_id / tiles_s) * TR;
@@ -177,7 +179,13 @@ int launch_vec4(const float* src, float* dst, long long R, long long S, hipStrea
     const long long tiles_r = ceil_div64(R, TR), tiles_s = ceil_div64(S, TS);
     const long long tiles = tiles_r * tiles_s;
     if (tiles > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((transpose_vec4_kernel<TR, TS, THREADS>), dim3((unsigned)tiles), dim3(THREADS), 0, st,
+    constexpr size_t lds_bytes = sizeof(float) * TS * (TR + 4);
+    if (lds_bytes > 65536) {                        // above the default per-workgroup limit: opt in (gfx950 has 160 KB)
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&transpose_vec4_kernel<TR, TS, THREADS>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+            return CNNMEM_ERR_RUNTIME;
+    }
+    hipLaunchKernelGGL((transpose_vec4_kernel<TR, TS, THREADS>), dim3((unsigned)tiles), dim3(THREADS), lds_bytes, st,
                        src, dst, R, S, (uint32_t)tiles_s);
     return launch_status();
 }
@@ -225,6 +233,7 @@ int launch_transpose2d(const float* src, float* dst, long long R, long long S, h
             case 8: return launch_u1<32, 128>(src, dst, R, S, st);
             case 9: return launch_u1<128, 32>(src, dst, R, S, st);
             case 10: return launch_u1<64, 64>(src, dst, R, S, st);
+            case 11: return launch_vec4<128, 128, 1024>(src, dst, R, S, st);
             default: return launch_vec4<64, 64>(src, dst, R, S, st);
         }
     }
