@@ -46,6 +46,8 @@ def _load():
         lib.cnnmem_ref_pool.argtypes = [fp, fp] + [i] * 12
         lib.cnnmem_ref_softmax.argtypes = [fp, fp, i, i]
         lib.cnnmem_ref_naive_pool_loads_1d.argtypes = [i, i, i]
+        lib.cnnmem_ref_index.argtypes = [i] * 9
+        lib.cnnmem_ref_index.restype = ctypes.c_ulonglong
         for name in ("cnnmem_ref_transform", "cnnmem_ref_pool_out_dims", "cnnmem_ref_pool",
                      "cnnmem_ref_softmax", "cnnmem_ref_naive_pool_loads_1d", "cnnmem_ref_threads"):
             getattr(lib, name).restype = i
@@ -109,6 +111,11 @@ def softmax(logits: np.ndarray) -> np.ndarray:
     probs = np.empty_like(logits)
     _check(_load().cnnmem_ref_softmax(logits.ctypes.data, probs.ctypes.data, N, classes), "softmax")
     return probs
+
+
+def index(layout: int, N: int, C: int, H: int, W: int, n: int, c: int, h: int, w: int) -> int:
+    """Linear index of element (n, c, h, w) of an N x C x H x W tensor stored in ``layout``."""
+    return int(_load().cnnmem_ref_index(layout, N, C, H, W, n, c, h, w))
 
 
 def naive_pool_loads_1d(L: int, k: int, s: int) -> int:

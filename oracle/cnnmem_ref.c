@@ -56,6 +56,13 @@ static size_t at(int layout, int N, int C, int H, int W, int n, int c, int h, in
     return (((size_t)c * H + h) * W + w) * N + n;
 }
 
+/* Linear index of element (n, c, h, w) in `layout`, for checks on sampled
+ * elements of tensors too large to run through the loops below. */
+unsigned long long cnnmem_ref_index(int layout, int N, int C, int H, int W, int n, int c, int h, int w)
+{
+    return (unsigned long long)at(layout, N, C, H, W, n, c, h, w);
+}
+
 int cnnmem_ref_threads(void)
 {
 #ifdef _OPENMP

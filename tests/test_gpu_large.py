@@ -1,0 +1,95 @@
+"""Tensors with more than 2^31 elements (64-bit offsets inside the kernels).
+Inputs are generated on the device; outputs are checked on sampled elements
+that the oracle computes one by one (index arithmetic, small windows, rows)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1610_03618_amd as cm
+
+pytestmark = pytest.mark.gpu
+NCHW, CHWN, MAX, AVG = cm.NCHW, cm.CHWN, cm.POOL_MAX, cm.POOL_AVG
+
+
+def _free_gib():
+    free, _ = torch.cuda.mem_get_info()
+    return free / 2**30
+
+
+def test_transform_beyond_2g_elements_sampled():
+    if _free_gib() < 24:
+        pytest.skip("needs ~20 GiB of free device memory")
+    N, C, H, W = 128, 1000, 100, 170                        # 2 176 000 000 elements, 8.7 GB
+    total = N * C * H * W
+    assert total > 2**31
+    # word i holds i mod 2^31 as an int32 bit pattern, moved as fp32
+    src = (torch.arange(total, dtype=torch.int64, device="cuda") & 0x7FFFFFFF).to(torch.int32).view(torch.float32)
+    dst = torch.empty(total, dtype=torch.float32, device="cuda")
+    assert cm.cnnmem_transform(src, dst, N, C, H, W, NCHW, CHWN) == 0
+    rng = np.random.default_rng(7)
+    pts = np.stack([rng.integers(0, d, size=4000) for d in (N, C, H, W)], axis=1)
+    pts[:8] = [[0, 0, 0, 0], [N - 1, C - 1, H - 1, W - 1], [N - 1, 0, 0, 0], [0, C - 1, H - 1, W - 1],
+               [127, 999, 99, 168], [64, 500, 50, 85], [1, 999, 99, 169], [126, 0, 0, 1]]
+    si = torch.tensor([oracle.index(NCHW, N, C, H, W, *map(int, p)) for p in pts], device="cuda")
+    di = torch.tensor([oracle.index(CHWN, N, C, H, W, *map(int, p)) for p in pts], device="cuda")
+    assert int(di.max()) > 2**31
+    got = dst.view(torch.int32)[di].cpu().numpy()
+    want = (si & 0x7FFFFFFF).to(torch.int32).cpu().numpy()
+    np.testing.assert_array_equal(got, want)
+    # and back: the round trip is the identity on a strided sample of words
+    back = torch.empty(total, dtype=torch.float32, device="cuda")
+    assert cm.cnnmem_transform(dst, back, N, C, H, W, CHWN, NCHW) == 0
+    probe = torch.arange(0, total, 1000003, device="cuda")
+    assert torch.equal(back.view(torch.int32)[probe], src.view(torch.int32)[probe])
+    assert torch.equal(back.view(torch.int32)[-4096:], src.view(torch.int32)[-4096:])
+
+
+@pytest.mark.parametrize("layout", [NCHW, CHWN])
+def test_pool_beyond_2g_elements_sampled(layout):
+    if _free_gib() < 16:
+        pytest.skip("needs ~12 GiB of free device memory")
+    N, C, H, W = 64, 64, 736, 736                           # 2 218 786 816 elements
+    k, s = (2, 2) if layout == NCHW else (3, 2)
+    assert N * C * H * W > 2**31
+    g = torch.Generator(device="cuda").manual_seed(11)
+    x = torch.empty(N * C * H * W, dtype=torch.float32, device="cuda")
+    x.uniform_(0.0, 1.0, generator=g)
+    Ho, Wo = oracle.pool_out_dims(H, W, k, k, s, s, 0, 0)
+    rng = np.random.default_rng(8)
+    pts = np.stack([rng.integers(0, d, size=600) for d in (N, C, Ho, Wo)], axis=1)
+    pts[:4] = [[0, 0, 0, 0], [N - 1, C - 1, Ho - 1, Wo - 1], [N - 1, C - 1, 0, Wo - 1], [0, C - 1, Ho - 1, 0]]
+    for mode in (MAX, AVG):
+        out = torch.empty(N * C * Ho * Wo, dtype=torch.float32, device="cuda")
+        assert cm.cnnmem_pool(x, out, N, C, H, W, layout, mode, k, k, s, s, 0, 0) == 0
+        # gather each sampled window and its output, then let the oracle pool the k x k patch
+        idx = np.array([[oracle.index(layout, N, C, H, W, int(n), int(c), int(i) * s + y, int(j) * s + xx)
+                         for y in range(k) for xx in range(k)] for (n, c, i, j) in pts], dtype=np.int64)
+        oidx = np.array([oracle.index(layout, N, C, Ho, Wo, *map(int, p)) for p in pts], dtype=np.int64)
+        patches = x[torch.from_numpy(idx).cuda()].cpu().numpy().reshape(-1, 1, k, k)    # (samples, 1, k, k)
+        got = out[torch.from_numpy(oidx).cuda()].cpu().numpy()
+        want = oracle.pool(np.ascontiguousarray(patches), patches.shape[0], 1, k, k, NCHW, mode, k, k, s, s).ravel()
+        if mode == MAX:
+            np.testing.assert_array_equal(got, want)
+        else:
+            assert np.all(np.abs(got.astype(np.float64) - want) <= 1e-6 * np.abs(want))
+        del out
+
+
+def test_softmax_beyond_2g_elements_sampled_rows():
+    if _free_gib() < 22:
+        pytest.skip("needs ~18 GiB of free device memory")
+    N, classes = 70001, 32771                               # 2 294 002 771 elements, odd row length
+    assert N * classes > 2**31
+    g = torch.Generator(device="cuda").manual_seed(12)
+    z = torch.empty((N, classes), dtype=torch.float32, device="cuda")
+    z.normal_(0.0, 3.0, generator=g)
+    z[N - 1, 17] = 50.0
+    p = torch.empty_like(z)
+    assert cm.cnnmem_softmax(z, p, N, classes) == 0
+    rows = [0, 1, 7, 65535, 65536, 65537, N // 2, N - 2, N - 1]
+    want = oracle.softmax(np.ascontiguousarray(z[rows].cpu().numpy())).astype(np.float64)
+    got = p[rows].cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - want) <= np.maximum(2e-6 * want, 1e-7))
+    sums = p.sum(dim=1, dtype=torch.float64)
+    assert float((sums - 1.0).abs().max()) <= 1e-5

@@ -334,3 +334,14 @@ def test_softmax_ties_at_planted_maximum():
 
 def test_oracle_reports_threads():
     assert oracle.threads() >= 1
+
+
+def test_index_matches_numpy_strides():
+    N, C, H, W = 3, 4, 5, 6
+    a = np.arange(N * C * H * W).reshape(N, C, H, W)            # NCHW order: value = linear index
+    b = np.ascontiguousarray(a.transpose(1, 2, 3, 0))           # CHWN copy
+    for (n, c, h, w) in [(0, 0, 0, 0), (2, 3, 4, 5), (1, 2, 3, 4), (2, 0, 4, 1)]:
+        assert oracle.index(NCHW, N, C, H, W, n, c, h, w) == a[n, c, h, w]
+        assert b.ravel()[oracle.index(CHWN, N, C, H, W, n, c, h, w)] == a[n, c, h, w]
+    big = oracle.index(CHWN, 128, 1000, 100, 170, 127, 999, 99, 169)
+    assert big == 128 * 1000 * 100 * 170 - 1 and big > 2**31
