@@ -92,6 +92,51 @@ CNNMEM_API int cnnmem_pool(const float *src, float *dst, int N, int C, int H, in
  */
 CNNMEM_API int cnnmem_softmax(const float *logits, float *probs, int N, int classes, void *hip_stream);
 
+/* ---- layout selection (host only; every pointer below is a HOST pointer) ---- */
+
+/* Kind of layer, as far as layout selection cares. */
+enum { CNNMEM_LAYER_CONV = 0, CNNMEM_LAYER_POOL = 1, CNNMEM_LAYER_OTHER = 2 };
+
+/* What a pooling layer asks for.  The paper's GPUs pooled far faster in CHWN
+ * (Section IV.B: "CHWN is always preferred"); on MI355X this library pools at the
+ * same bandwidth in both layouts, so a pooling layer can simply keep the layout
+ * its input arrives in and save the transform. */
+enum { CNNMEM_POOL_PREFERS_CHWN = 0, CNNMEM_POOL_KEEPS_LAYOUT = 1 };
+
+/*
+ * Layout heuristic of Section IV.A for one layer.  Convolution with batch N and
+ * C input feature maps: CHWN if C < Ct or N >= Nt, otherwise NCHW ((Ct, Nt) is
+ * a property of the GPU: (32, 128) and (128, 64) on the paper's two).  Pooling:
+ * CHWN.  Other layers have no preference: *layout is left untouched and the
+ * function returns CNNMEM_OK.
+ * Errors: INVALID_ARG for a null pointer, an unknown kind, N, C <= 0 or
+ * Ct, Nt < 0.
+ */
+CNNMEM_API int cnnmem_choose_layout(int layer_kind, int N, int C, int Ct, int Nt, int *layout);
+
+/* One layer of a network for cnnmem_plan_layouts. */
+typedef struct cnnmem_layer {
+    int kind; /* CNNMEM_LAYER_* */
+    int N;    /* batch size */
+    int C;    /* input feature maps */
+} cnnmem_layer;
+
+/*
+ * Layout plan of Section IV.D: one scan over the network sets the layout field
+ * of every layer from the heuristic, and a transform is needed wherever a layer's
+ * layout differs from the layout its input arrives in.  `input_layout` is the
+ * layout of the network input.  Layers without a preference (and pooling under
+ * CNNMEM_POOL_KEEPS_LAYOUT) inherit the incoming layout.
+ *   layouts          : out, n_layers entries, the layout each layer runs in.
+ *   transform_before : out, n_layers entries, 1 if a cnnmem_transform is needed
+ *                      in front of layer i, else 0.
+ *   n_transforms     : out, optional (may be null), the number of ones above.
+ * Errors: INVALID_ARG for null arrays, n_layers <= 0, a bad layer, layout tag or
+ * policy.
+ */
+CNNMEM_API int cnnmem_plan_layouts(const cnnmem_layer *layers, int n_layers, int Ct, int Nt, int input_layout,
+                                   int pool_policy, int *layouts, int *transform_before, int *n_transforms);
+
 /* Text for a status code; static storage, never null. */
 CNNMEM_API const char *cnnmem_status_string(int status);
 

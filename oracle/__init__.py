@@ -46,6 +46,11 @@ def _load():
         lib.cnnmem_ref_pool.argtypes = [fp, fp] + [i] * 12
         lib.cnnmem_ref_softmax.argtypes = [fp, fp, i, i]
         lib.cnnmem_ref_naive_pool_loads_1d.argtypes = [i, i, i]
+        lib.cnnmem_ref_choose_layout.argtypes = [i] * 5
+        lib.cnnmem_ref_choose_layout.restype = i
+        ip = ctypes.POINTER(i)
+        lib.cnnmem_ref_plan_layouts.argtypes = [ip, ip, ip, i, i, i, i, i, ip, ip]
+        lib.cnnmem_ref_plan_layouts.restype = i
         lib.cnnmem_ref_index.argtypes = [i] * 9
         lib.cnnmem_ref_index.restype = ctypes.c_ulonglong
         for name in ("cnnmem_ref_transform", "cnnmem_ref_pool_out_dims", "cnnmem_ref_pool",
@@ -116,6 +121,27 @@ def softmax(logits: np.ndarray) -> np.ndarray:
 def index(layout: int, N: int, C: int, H: int, W: int, n: int, c: int, h: int, w: int) -> int:
     """Linear index of element (n, c, h, w) of an N x C x H x W tensor stored in ``layout``."""
     return int(_load().cnnmem_ref_index(layout, N, C, H, W, n, c, h, w))
+
+
+LAYER_CONV, LAYER_POOL, LAYER_OTHER = 0, 1, 2
+
+
+def choose_layout(kind: int, N: int, C: int, Ct: int, Nt: int) -> int:
+    """Preferred layout of one layer (Section IV.A / IV.B); -1 = no preference."""
+    return int(_load().cnnmem_ref_choose_layout(kind, N, C, Ct, Nt))
+
+
+def plan_layouts(layers, Ct: int, Nt: int, input_layout: int, pool_keeps_layout: bool = False):
+    """Layout plan for ``layers`` = [(kind, N, C), ...] (Section IV.D).
+
+    Returns (layouts, transform_before, n_transforms)."""
+    n = len(layers)
+    arr = lambda vals: (ctypes.c_int * n)(*vals)
+    kinds, Ns, Cs = arr([l[0] for l in layers]), arr([l[1] for l in layers]), arr([l[2] for l in layers])
+    layouts, tb = (ctypes.c_int * n)(), (ctypes.c_int * n)()
+    count = _load().cnnmem_ref_plan_layouts(kinds, Ns, Cs, n, Ct, Nt, input_layout, int(pool_keeps_layout),
+                                            layouts, tb)
+    return list(layouts), list(tb), int(count)
 
 
 def naive_pool_loads_1d(L: int, k: int, s: int) -> int:

@@ -13,6 +13,8 @@
  *     CHWN == [C*H*W][N], so the layout change is a 2-D transpose).
  *   - pooling: Equation 2 (average) and the prose of Section II.A (max).
  *   - softmax: the five steps of Section II.A, in the paper's order.
+ *   - layout choice: the (Ct, Nt) heuristic of Section IV.A and the one-scan plan
+ *     of Section IV.D.
  *
  * Readings taken where the paper is silent or garbled (each is pinned or
  * listed as a reading in the design notes):
@@ -198,6 +200,40 @@ int cnnmem_ref_softmax(const float *logits, float *probs, int N, int classes)
         free(mid);
     }
     return failed ? REF_ERR_NOMEM : REF_OK;
+}
+
+/* Layout heuristic (Section IV.A): a convolution prefers CHWN when it has fewer
+ * than Ct input feature maps or a batch of at least Nt images, NCHW otherwise;
+ * pooling prefers CHWN (Section IV.B).  kind: 0 convolution, 1 pooling, 2 other
+ * (no preference: returns -1). */
+int cnnmem_ref_choose_layout(int kind, int N, int C, int Ct, int Nt)
+{
+    if (kind == 0) {
+        if (C < Ct) return REF_CHWN;
+        if (N >= Nt) return REF_CHWN;
+        return REF_NCHW;
+    }
+    if (kind == 1) return REF_CHWN;
+    return -1;
+}
+
+/* Layout plan (Section IV.D): scan the layers once, give each its preferred
+ * layout, and mark a transform wherever the layout changes.  Layers without a
+ * preference keep the layout their input has; with pool_keeps != 0 so does
+ * pooling.  kinds/Ns/Cs have n entries; returns the number of transforms. */
+int cnnmem_ref_plan_layouts(const int *kinds, const int *Ns, const int *Cs, int n, int Ct, int Nt,
+                            int input_layout, int pool_keeps, int *layouts, int *transform_before)
+{
+    int current = input_layout, count = 0;
+    for (int i = 0; i < n; ++i) {
+        int want = cnnmem_ref_choose_layout(kinds[i], Ns[i], Cs[i], Ct, Nt);
+        if (want < 0 || (kinds[i] == 1 && pool_keeps)) want = current;
+        layouts[i] = want;
+        transform_before[i] = (want != current);
+        count += transform_before[i];
+        current = want;
+    }
+    return count;
 }
 
 /* Number of input loads a one-output-per-thread pooling of an L-long 1-D

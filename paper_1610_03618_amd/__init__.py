@@ -7,7 +7,8 @@ There is no CPU fallback: without the built library, or without a GPU tensor,
 calls raise.
 """
 from .binding import (  # noqa: F401
-    CHWN, NCHW, POOL_AVG, POOL_MAX, CnnmemError, cnnmem_pool, cnnmem_pool_out_dims,
+    CHWN, LAYER_CONV, LAYER_OTHER, LAYER_POOL, NCHW, POOL_AVG, POOL_KEEPS_LAYOUT, POOL_MAX, POOL_PREFERS_CHWN,
+    CnnmemError, cnnmem_choose_layout, cnnmem_plan_layouts, cnnmem_pool, cnnmem_pool_out_dims,
     cnnmem_softmax, cnnmem_status_string, cnnmem_transform, cnnmem_version, library, pool,
     softmax, transform,
 )

@@ -15,6 +15,12 @@ import torch
 
 NCHW, CHWN = 0, 1
 POOL_MAX, POOL_AVG = 0, 1
+LAYER_CONV, LAYER_POOL, LAYER_OTHER = 0, 1, 2
+POOL_PREFERS_CHWN, POOL_KEEPS_LAYOUT = 0, 1
+
+
+class _Layer(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int), ("N", ctypes.c_int), ("C", ctypes.c_int)]
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcnnmem.so")
 _lib = None
@@ -40,6 +46,11 @@ def library() -> ctypes.CDLL:
         lib.cnnmem_pool_out_dims.argtypes = [i] * 8 + [ctypes.POINTER(i)] * 2
         lib.cnnmem_pool.argtypes = [p, p] + [i] * 12 + [p]
         lib.cnnmem_softmax.argtypes = [p, p, i, i, p]
+        ip = ctypes.POINTER(i)
+        lib.cnnmem_choose_layout.argtypes = [i, i, i, i, i, ip]
+        lib.cnnmem_choose_layout.restype = i
+        lib.cnnmem_plan_layouts.argtypes = [ctypes.POINTER(_Layer), i, i, i, i, i, ip, ip, ip]
+        lib.cnnmem_plan_layouts.restype = i
         lib.cnnmem_status_string.argtypes = [i]
         lib.cnnmem_status_string.restype = ctypes.c_char_p
         lib.cnnmem_version.argtypes = []
@@ -95,6 +106,22 @@ def cnnmem_pool(src, dst, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, stre
 
 def cnnmem_softmax(logits, probs, N, classes, stream=None) -> int:
     return library().cnnmem_softmax(_ptr(logits), _ptr(probs), N, classes, _stream(stream))
+
+
+def cnnmem_choose_layout(kind: int, N: int, C: int, Ct: int, Nt: int, default: int = NCHW) -> Tuple[int, int]:
+    """(status, layout); ``default`` is what a layer without a preference reports."""
+    out = ctypes.c_int(default)
+    st = library().cnnmem_choose_layout(kind, N, C, Ct, Nt, ctypes.byref(out))
+    return st, out.value
+
+
+def cnnmem_plan_layouts(layers, Ct: int, Nt: int, input_layout: int, pool_policy: int = POOL_PREFERS_CHWN):
+    """(status, layouts, transform_before, n_transforms) for ``layers`` = [(kind, N, C), ...]."""
+    n = len(layers)
+    arr = (_Layer * max(n, 1))(*[_Layer(*l) for l in layers])
+    layouts, tb, cnt = (ctypes.c_int * max(n, 1))(), (ctypes.c_int * max(n, 1))(), ctypes.c_int(0)
+    st = library().cnnmem_plan_layouts(arr, n, Ct, Nt, input_layout, pool_policy, layouts, tb, ctypes.byref(cnt))
+    return st, list(layouts)[:n], list(tb)[:n], cnt.value
 
 
 def cnnmem_status_string(status: int) -> str:

@@ -72,6 +72,50 @@ int cnnmem_softmax(const float* logits, float* probs, int N, int classes, void* 
     return launch_softmax(logits, probs, N, classes, static_cast<hipStream_t>(hip_stream));
 }
 
+int cnnmem_choose_layout(int layer_kind, int N, int C, int Ct, int Nt, int* layout) {
+    if (!layout || N <= 0 || C <= 0 || Ct < 0 || Nt < 0) return CNNMEM_ERR_INVALID_ARG;
+    switch (layer_kind) {
+        case CNNMEM_LAYER_CONV:
+            // Section IV.A: few input maps make the NCHW unroll expensive; a large batch gives CHWN
+            // both coalescing and register reuse.
+            *layout = (C < Ct || N >= Nt) ? CNNMEM_CHWN : CNNMEM_NCHW;
+            return CNNMEM_OK;
+        case CNNMEM_LAYER_POOL:
+            *layout = CNNMEM_CHWN;                              // Section IV.B
+            return CNNMEM_OK;
+        case CNNMEM_LAYER_OTHER:
+            return CNNMEM_OK;
+        default:
+            return CNNMEM_ERR_INVALID_ARG;
+    }
+}
+
+int cnnmem_plan_layouts(const cnnmem_layer* layers, int n_layers, int Ct, int Nt, int input_layout,
+                        int pool_policy, int* layouts, int* transform_before, int* n_transforms) {
+    if (!layers || !layouts || !transform_before || n_layers <= 0) return CNNMEM_ERR_INVALID_ARG;
+    if (!layout_ok(input_layout)) return CNNMEM_ERR_INVALID_ARG;
+    if (pool_policy != CNNMEM_POOL_PREFERS_CHWN && pool_policy != CNNMEM_POOL_KEEPS_LAYOUT)
+        return CNNMEM_ERR_INVALID_ARG;
+    for (int i = 0; i < n_layers; ++i) {                        // validate everything before writing anything
+        int probe = CNNMEM_NCHW;
+        if (cnnmem_choose_layout(layers[i].kind, layers[i].N, layers[i].C, Ct, Nt, &probe) != CNNMEM_OK)
+            return CNNMEM_ERR_INVALID_ARG;
+    }
+    int current = input_layout, count = 0;
+    for (int i = 0; i < n_layers; ++i) {
+        int want = current;                                     // no preference: inherit
+        const bool inherits = layers[i].kind == CNNMEM_LAYER_OTHER ||
+                              (layers[i].kind == CNNMEM_LAYER_POOL && pool_policy == CNNMEM_POOL_KEEPS_LAYOUT);
+        if (!inherits) cnnmem_choose_layout(layers[i].kind, layers[i].N, layers[i].C, Ct, Nt, &want);
+        layouts[i] = want;
+        transform_before[i] = want != current;
+        count += transform_before[i];
+        current = want;
+    }
+    if (n_transforms) *n_transforms = count;
+    return CNNMEM_OK;
+}
+
 const char* cnnmem_status_string(int status) {
     switch (status) {
         case CNNMEM_OK: return "ok";
