@@ -81,6 +81,31 @@ CNNMEM_API int cnnmem_pool(const float *src, float *dst, int N, int C, int H, in
                 int kh, int kw, int sh, int sw, int ph, int pw, void *hip_stream);
 
 /*
+ * Launch-shape choices for one pooling call: the knobs the paper's auto-tuner
+ * searches (Section V.A: how many outputs a thread computes in each direction,
+ * traded against the parallelism left) plus this part's occupancy cap.  A zero
+ * field means "library default"; fields that do not apply to the kernel that
+ * serves the call are ignored.  Results never depend on the tuning.
+ */
+typedef struct cnnmem_pool_tuning {
+    int rows_per_lane;     /* CHWN: output rows per lane, 1..4                              */
+    int cols_per_lane;     /* CHWN: output columns per lane, 1..2                           */
+    int workgroups_per_cu; /* cap on resident 256-lane workgroups per CU, 2..8; -1 = no cap */
+    int nchw_kernel;       /* NCHW: 1 = row-pair kernel where it applies, 2 = LDS-slab kernel */
+    int slab_lanes;        /* NCHW LDS-slab kernel: 256, 512 or 1024 lanes per slab         */
+} cnnmem_pool_tuning;
+
+/*
+ * cnnmem_pool with explicit launch-shape choices (`tuning` is a HOST pointer and
+ * may be null = all defaults).  Same tensors, same results, same errors as
+ * cnnmem_pool, plus INVALID_ARG for a field outside the ranges above.
+ * `python -m paper_1610_03618_amd.autotune` searches these fields for a shape.
+ */
+CNNMEM_API int cnnmem_pool_tuned(const float *src, float *dst, int N, int C, int H, int W, int layout, int mode,
+                                 int kh, int kw, int sh, int sw, int ph, int pw,
+                                 const cnnmem_pool_tuning *tuning, void *hip_stream);
+
+/*
  * Softmax over the categories of each image (Section II.A steps 1-5, fused
  * into one kernel as in Section V.B): for every row n of the row-major
  * [N][classes] matrix, m = max_c x[n][c], e_c = exp(x[n][c] - m),

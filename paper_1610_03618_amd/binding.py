@@ -19,6 +19,15 @@ LAYER_CONV, LAYER_POOL, LAYER_OTHER = 0, 1, 2
 POOL_PREFERS_CHWN, POOL_KEEPS_LAYOUT = 0, 1
 
 
+class PoolTuning(ctypes.Structure):
+    """Launch-shape choices of a pooling call (``cnnmem_pool_tuning``); zeros = library defaults."""
+    _fields_ = [("rows_per_lane", ctypes.c_int), ("cols_per_lane", ctypes.c_int),
+                ("workgroups_per_cu", ctypes.c_int), ("nchw_kernel", ctypes.c_int), ("slab_lanes", ctypes.c_int)]
+
+    def as_dict(self):
+        return {name: getattr(self, name) for name, _ in self._fields_}
+
+
 class _Layer(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int), ("N", ctypes.c_int), ("C", ctypes.c_int)]
 
@@ -45,6 +54,8 @@ def library() -> ctypes.CDLL:
         lib.cnnmem_transform.argtypes = [p, p, i, i, i, i, i, i, p]
         lib.cnnmem_pool_out_dims.argtypes = [i] * 8 + [ctypes.POINTER(i)] * 2
         lib.cnnmem_pool.argtypes = [p, p] + [i] * 12 + [p]
+        lib.cnnmem_pool_tuned.argtypes = [p, p] + [i] * 12 + [ctypes.POINTER(PoolTuning), p]
+        lib.cnnmem_pool_tuned.restype = i
         lib.cnnmem_softmax.argtypes = [p, p, i, i, p]
         ip = ctypes.POINTER(i)
         lib.cnnmem_choose_layout.argtypes = [i, i, i, i, i, ip]
@@ -104,6 +115,19 @@ def cnnmem_pool(src, dst, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, stre
                                  _stream(stream))
 
 
+def _tuning(tuning):
+    if tuning is None or isinstance(tuning, PoolTuning):
+        return tuning
+    return PoolTuning(**tuning)
+
+
+def cnnmem_pool_tuned(src, dst, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, tuning=None, stream=None) -> int:
+    """``tuning``: a :class:`PoolTuning`, a dict of its fields, or None."""
+    t = _tuning(tuning)
+    return library().cnnmem_pool_tuned(_ptr(src), _ptr(dst), N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw,
+                                       ctypes.byref(t) if t is not None else None, _stream(stream))
+
+
 def cnnmem_softmax(logits, probs, N, classes, stream=None) -> int:
     return library().cnnmem_softmax(_ptr(logits), _ptr(probs), N, classes, _stream(stream))
 
@@ -148,13 +172,13 @@ def transform(src: torch.Tensor, N, C, H, W, src_layout, dst_layout, out=None, s
 
 
 def pool(src: torch.Tensor, N, C, H, W, layout, mode, kh, kw, sh, sw, ph=0, pw=0, out=None,
-         stream=None) -> torch.Tensor:
+         stream=None, tuning=None) -> torch.Tensor:
     st, Ho, Wo = cnnmem_pool_out_dims(H, W, kh, kw, sh, sw, ph, pw)
     if st:
         raise CnnmemError(st, "cnnmem_pool_out_dims")
     if out is None:
         out = torch.empty(_shape(layout, N, C, Ho, Wo), dtype=torch.float32, device=src.device)
-    st = cnnmem_pool(src, out, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, stream)
+    st = cnnmem_pool_tuned(src, out, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, tuning, stream)
     if st:
         raise CnnmemError(st, "cnnmem_pool")
     return out

@@ -47,13 +47,29 @@ int cnnmem_pool_out_dims(int H, int W, int kh, int kw, int sh, int sw, int ph, i
     return CNNMEM_OK;
 }
 
-int cnnmem_pool(const float* src, float* dst, int N, int C, int H, int W, int layout, int mode, int kh,
-                int kw, int sh, int sw, int ph, int pw, void* hip_stream) {
+int cnnmem_pool_tuned(const float* src, float* dst, int N, int C, int H, int W, int layout, int mode, int kh,
+                      int kw, int sh, int sw, int ph, int pw, const cnnmem_pool_tuning* tuning, void* hip_stream) {
     if (!src || !dst || N <= 0 || C <= 0) return CNNMEM_ERR_INVALID_ARG;
     if (!window_ok(H, W, kh, kw, sh, sw, ph, pw)) return CNNMEM_ERR_INVALID_ARG;
     if (!layout_ok(layout)) return CNNMEM_ERR_INVALID_ARG;
     if (mode != CNNMEM_POOL_MAX && mode != CNNMEM_POOL_AVG) return CNNMEM_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 3u) return CNNMEM_ERR_INVALID_ARG;
+    PoolTuning tune;
+    if (tuning) {
+        if (tuning->rows_per_lane < 0 || tuning->rows_per_lane > 4) return CNNMEM_ERR_INVALID_ARG;
+        if (tuning->cols_per_lane < 0 || tuning->cols_per_lane > 2) return CNNMEM_ERR_INVALID_ARG;
+        if (tuning->workgroups_per_cu < -1 || tuning->workgroups_per_cu == 1 || tuning->workgroups_per_cu > 8)
+            return CNNMEM_ERR_INVALID_ARG;
+        if (tuning->nchw_kernel < 0 || tuning->nchw_kernel > 2) return CNNMEM_ERR_INVALID_ARG;
+        if (tuning->slab_lanes != 0 && tuning->slab_lanes != 256 && tuning->slab_lanes != 512 &&
+            tuning->slab_lanes != 1024)
+            return CNNMEM_ERR_INVALID_ARG;
+        tune.rows_per_lane = tuning->rows_per_lane;
+        tune.cols_per_lane = tuning->cols_per_lane;
+        tune.workgroups_per_cu = tuning->workgroups_per_cu;
+        tune.nchw_kernel = tuning->nchw_kernel;
+        tune.slab_lanes = tuning->slab_lanes;
+    }
     if ((long long)H * W > (1LL << 30) || (long long)kh * kw > (1 << 24)) return CNNMEM_ERR_UNSUPPORTED;
     PoolGeom g;
     g.N = N; g.C = C; g.H = H; g.W = W;
@@ -62,7 +78,12 @@ int cnnmem_pool(const float* src, float* dst, int N, int C, int H, int W, int la
     g.Ho = pooled_extent(H, kh, sh, ph);
     g.Wo = pooled_extent(W, kw, sw, pw);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    return layout == CNNMEM_NCHW ? launch_pool_nchw(src, dst, g, st) : launch_pool_chwn(src, dst, g, st);
+    return layout == CNNMEM_NCHW ? launch_pool_nchw(src, dst, g, tune, st) : launch_pool_chwn(src, dst, g, tune, st);
+}
+
+int cnnmem_pool(const float* src, float* dst, int N, int C, int H, int W, int layout, int mode, int kh,
+                int kw, int sh, int sw, int ph, int pw, void* hip_stream) {
+    return cnnmem_pool_tuned(src, dst, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, nullptr, hip_stream);
 }
 
 int cnnmem_softmax(const float* logits, float* probs, int N, int classes, void* hip_stream) {

@@ -127,8 +127,16 @@ struct PoolGeom {
     int kh, kw, sh, sw, ph, pw;
     int mode;
 };
-int launch_pool_nchw(const float* src, float* dst, const PoolGeom& g, hipStream_t st);
-int launch_pool_chwn(const float* src, float* dst, const PoolGeom& g, hipStream_t st);
+// Launch-shape choices of a pooling call; 0 everywhere = the library's defaults.
+struct PoolTuning {
+    int rows_per_lane = 0;      // CHWN working set along H (1..4)
+    int cols_per_lane = 0;      // CHWN working set along W (1..2)
+    int workgroups_per_cu = 0;  // occupancy cap (2..8), -1 = none
+    int nchw_kernel = 0;        // 1 = row pairs when applicable, 2 = LDS slab
+    int slab_lanes = 0;         // 256 / 512 / 1024
+};
+int launch_pool_nchw(const float* src, float* dst, const PoolGeom& g, const PoolTuning& tune, hipStream_t st);
+int launch_pool_chwn(const float* src, float* dst, const PoolGeom& g, const PoolTuning& tune, hipStream_t st);
 
 int launch_softmax(const float* logits, float* probs, int N, int classes, hipStream_t st);
 

@@ -86,14 +86,19 @@ __global__ __launch_bounds__(kThreads) void pool_generic_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// CHWN: float4 over four images, OY output rows per lane, row results reused.
-// KH/KW/SH/SW are compile-time so the window loops unroll into registers.
+// CHWN: float4 over four images; a lane owns an OY x OX block of outputs (the
+// per-thread working set of Section V.A, expanded in both directions).  Every
+// input tap the block needs is loaded once; each input row is reduced
+// horizontally once per output column and that row result is reused by all
+// output rows whose windows contain it.  KH/KW/SH/SW are compile-time so the
+// window loops unroll into registers.
 // ---------------------------------------------------------------------------
-template <int MODE, int KH, int KW, int SH, int SW, int OY, bool PADDED>
+template <int MODE, int KH, int KW, int SH, int SW, int OY, int OX, bool PADDED>
 __global__ __launch_bounds__(kThreads) void pool_chwn_vec4_kernel(
     const float* __restrict__ src, float* __restrict__ dst, PoolGeom g, uint32_t row_items,
     uint32_t blocks_x, uint32_t blocks_y, FastDiv div_n4) {
     constexpr int ROWS_IN = (OY - 1) * SH + KH;     // input rows one lane walks
+    constexpr int COLS_IN = (OX - 1) * SW + KW;     // input columns it touches in each of them
     const uint32_t nblocks = gridDim.x;
     const uint32_t tile = xcd_contiguous_tile(blockIdx.x, nblocks);
     // tile -> (bx fastest, then by, then c): vertically adjacent strips are close in tile order
@@ -102,18 +107,21 @@ __global__ __launch_bounds__(kThreads) void pool_chwn_vec4_kernel(
     const uint32_t by = rest % blocks_y;
     const uint32_t c = rest / blocks_y;
 
-    const uint32_t u = bx * kThreads + threadIdx.x;           // position in the output row: j*N4 + n4
+    const uint32_t u = bx * kThreads + threadIdx.x;           // position in the output row: jb*N4 + n4
     if (u >= row_items) return;
-    const uint32_t j = fd_div(u, div_n4);
-    const uint32_t n4 = u - j * div_n4.d;
+    const uint32_t jb = fd_div(u, div_n4);
+    const uint32_t n4 = u - jb * div_n4.d;
+    const int j0 = (int)jb * OX;
     const int i0 = (int)by * OY;
     const int N = g.N;
 
-    float4 acc[OY];
+    float4 acc[OY][OX];
 #pragma unroll
-    for (int oy = 0; oy < OY; ++oy) acc[oy] = Acc<MODE>::identity4();
+    for (int oy = 0; oy < OY; ++oy)
+#pragma unroll
+        for (int ox = 0; ox < OX; ++ox) acc[oy][ox] = Acc<MODE>::identity4();
 
-    const int q0 = (int)j * SW - g.pw;
+    const int q0 = j0 * SW - g.pw;
     const int r_base = i0 * SH - g.ph;
     const float* plane = src + (size_t)c * g.H * g.W * N + 4 * n4;
     // Overlapping windows re-read taps that a neighbouring lane or strip has just
@@ -122,35 +130,44 @@ __global__ __launch_bounds__(kThreads) void pool_chwn_vec4_kernel(
     // Every load is unconditional (a branch per row would make the compiler wait
     // for each row before asking for the next): taps outside the image are read
     // from a clamped, valid address and replaced by the identity.  Without padding
-    // the only rows past H belong to output rows >= Ho, which are never stored, so
-    // clamping alone is enough there.
+    // the only rows past H and columns past W belong to outputs beyond Ho x Wo,
+    // which are never stored, so clamping alone is enough there.
 #pragma unroll
     for (int rr = 0; rr < ROWS_IN; ++rr) {
         const int r = r_base + rr;
         const bool row_ok = !PADDED || (r >= 0 && r < g.H);
         const int rc = r < 0 ? 0 : (r < g.H ? r : g.H - 1);
         const float* rowp = plane + (size_t)rc * g.W * N;
-        float4 h = Acc<MODE>::identity4();
+        float4 h[OX];
 #pragma unroll
-        for (int x = 0; x < KW; ++x) {
+        for (int ox = 0; ox < OX; ++ox) h[ox] = Acc<MODE>::identity4();
+#pragma unroll
+        for (int x = 0; x < COLS_IN; ++x) {
             const int q = q0 + x;
             const bool ok = row_ok && (!PADDED || (q >= 0 && q < g.W));
-            const int qc = PADDED ? (q < 0 ? 0 : (q < g.W ? q : g.W - 1)) : q;
+            const int qc = q < 0 ? 0 : (q < g.W ? q : g.W - 1);
             float4 t = kStream ? ld4_stream(rowp + (size_t)qc * N)
                                : *reinterpret_cast<const float4*>(rowp + (size_t)qc * N);
             if (PADDED && !ok) t = Acc<MODE>::identity4();
-            h = Acc<MODE>::op4(h, t);
+#pragma unroll
+            for (int ox = 0; ox < OX; ++ox)
+                if (x >= ox * SW && x < ox * SW + KW) h[ox] = Acc<MODE>::op4(h[ox], t);
         }
 #pragma unroll
         for (int oy = 0; oy < OY; ++oy)
-            if (rr >= oy * SH && rr < oy * SH + KH) acc[oy] = Acc<MODE>::op4(acc[oy], h);
+            if (rr >= oy * SH && rr < oy * SH + KH) {
+#pragma unroll
+                for (int ox = 0; ox < OX; ++ox) acc[oy][ox] = Acc<MODE>::op4(acc[oy][ox], h[ox]);
+            }
     }
-    float* outp = dst + ((size_t)c * g.Ho * g.Wo + j) * N + 4 * n4;
+    float* outp = dst + ((size_t)c * g.Ho * g.Wo + j0) * N + 4 * n4;
 #pragma unroll
     for (int oy = 0; oy < OY; ++oy) {
         const int i = i0 + oy;
-        if (i < g.Ho)
-            st4_stream(outp + (size_t)i * g.Wo * N, Acc<MODE>::finish4(acc[oy], (float)(KH * KW)));
+#pragma unroll
+        for (int ox = 0; ox < OX; ++ox)
+            if (i < g.Ho && j0 + ox < g.Wo)
+                st4_stream(outp + ((size_t)i * g.Wo + ox) * N, Acc<MODE>::finish4(acc[oy][ox], (float)(KH * KW)));
     }
 }
 
@@ -326,14 +343,15 @@ __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
 // 256-lane workgroups per CU keeps 64-128 KB in flight and loses 2-3 points.
 // Asking for dynamic LDS that the kernel never touches caps the workgroups per CU
 // (160 KB of LDS per CU).  Smaller tensors want all the parallelism they can get,
-// so the throttle only applies from 512 MB of input.
-inline size_t throttle_lds(long long in_bytes, int workgroups_per_cu) {
-    const int forced = env_int("CNNMEM_POOL_LDS", -1);
-    if (forced >= 0) return (size_t)forced;
-    if (in_bytes < (512LL << 20)) return 0;
-    return (size_t)(160 * 1024 / workgroups_per_cu) - 1024;
+// so by default the throttle only applies from 512 MB of input.
+//   requested: the caller's tuning (0 = this default rule, -1 = never, 1..8 = that many)
+inline size_t throttle_lds(int requested, long long in_bytes, int default_workgroups_per_cu) {
+    int wpc = requested;
+    if (wpc == 0) wpc = in_bytes >= (512LL << 20) ? default_workgroups_per_cu : -1;
+    if (wpc < 0 || wpc >= 8) return 0;
+    const size_t bytes = (size_t)(160 * 1024 / wpc) - 1024;
+    return bytes > 65536 ? 65536 : bytes;           // 64 KB needs no opt-in and already means two per CU
 }
-
 
 template <int MODE>
 int launch_generic(const float* src, float* dst, const PoolGeom& g, int chwn, hipStream_t st) {
@@ -344,49 +362,56 @@ int launch_generic(const float* src, float* dst, const PoolGeom& g, int chwn, hi
     return launch_status();
 }
 
-template <int MODE, int KH, int KW, int SH, int SW, int OY>
-int launch_chwn_vec4(const float* src, float* dst, const PoolGeom& g, hipStream_t st) {
-    const long long row_items = (long long)(g.N / 4) * g.Wo;
+template <int MODE, int KH, int KW, int SH, int SW, int OY, int OX>
+int launch_chwn_vec4(const float* src, float* dst, const PoolGeom& g, const PoolTuning& tune, hipStream_t st) {
+    const long long row_items = (long long)(g.N / 4) * ceil_div64(g.Wo, OX);
     const long long bx = ceil_div64(row_items, kThreads), by = ceil_div64(g.Ho, OY);
     const long long blocks = bx * by * g.C;
     if (row_items >= 0x7fffffffLL || blocks > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
     const FastDiv dn4 = make_fastdiv((uint32_t)(g.N / 4));
-    // disjoint windows with one output row per lane: 64 B in flight per lane, best at 4 workgroups per CU
-    const size_t lds = (OY == 1 && KH <= SH && KW <= SW)
-                           ? throttle_lds(4LL * g.N * g.C * g.H * g.W, 4) : 0;
+    // disjoint windows, one output per lane: 64 B in flight per lane, best at 4 workgroups per CU;
+    // larger working sets already keep plenty in flight and are left alone unless asked
+    const bool light = OY == 1 && OX == 1 && KH <= SH && KW <= SW;
+    const size_t lds = throttle_lds(light || tune.workgroups_per_cu != 0 ? tune.workgroups_per_cu : -1,
+                                    4LL * g.N * g.C * g.H * g.W, 4);
     if (g.ph > 0 || g.pw > 0)
-        hipLaunchKernelGGL((pool_chwn_vec4_kernel<MODE, KH, KW, SH, SW, OY, true>), dim3((unsigned)blocks),
+        hipLaunchKernelGGL((pool_chwn_vec4_kernel<MODE, KH, KW, SH, SW, OY, OX, true>), dim3((unsigned)blocks),
                            dim3(kThreads), lds, st, src, dst, g, (uint32_t)row_items, (uint32_t)bx,
                            (uint32_t)by, dn4);
     else
-        hipLaunchKernelGGL((pool_chwn_vec4_kernel<MODE, KH, KW, SH, SW, OY, false>), dim3((unsigned)blocks),
+        hipLaunchKernelGGL((pool_chwn_vec4_kernel<MODE, KH, KW, SH, SW, OY, OX, false>), dim3((unsigned)blocks),
                            dim3(kThreads), lds, st, src, dst, g, (uint32_t)row_items, (uint32_t)bx,
                            (uint32_t)by, dn4);
     return launch_status();
 }
 
+// Working-set shapes that are compiled: rows per lane 1..4, columns per lane 1..2.
+template <int MODE, int KH, int KW, int SH, int SW>
+int launch_chwn_window(int oy, int ox, const float* src, float* dst, const PoolGeom& g, const PoolTuning& tune,
+                       hipStream_t st) {
+#define CNNMEM_WS(Y, X) \
+    if (oy == Y && ox == X) return launch_chwn_vec4<MODE, KH, KW, SH, SW, Y, X>(src, dst, g, tune, st)
+    CNNMEM_WS(1, 1); CNNMEM_WS(2, 1); CNNMEM_WS(3, 1); CNNMEM_WS(4, 1);
+    CNNMEM_WS(1, 2); CNNMEM_WS(2, 2); CNNMEM_WS(3, 2); CNNMEM_WS(4, 2);
+#undef CNNMEM_WS
+    return CNNMEM_ERR_UNSUPPORTED;
+}
+
 template <int MODE>
-int dispatch_chwn(const float* src, float* dst, const PoolGeom& g, hipStream_t st) {
+int dispatch_chwn(const float* src, float* dst, const PoolGeom& g, const PoolTuning& tune, hipStream_t st) {
     const bool vec = (g.N % 4 == 0) && aligned16(src) && aligned16(dst);
+    const int ox = tune.cols_per_lane ? tune.cols_per_lane : 1;
+    int rc = CNNMEM_ERR_UNSUPPORTED;
     if (vec && g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2) {
-        const int oy = env_int("CNNMEM_POOL_CHWN_OY", 3);
-        int rc;
-        if (oy <= 1) rc = launch_chwn_vec4<MODE, 3, 3, 2, 2, 1>(src, dst, g, st);
-        else if (oy == 2) rc = launch_chwn_vec4<MODE, 3, 3, 2, 2, 2>(src, dst, g, st);
-        else if (oy == 3) rc = launch_chwn_vec4<MODE, 3, 3, 2, 2, 3>(src, dst, g, st);
-        else rc = launch_chwn_vec4<MODE, 3, 3, 2, 2, 4>(src, dst, g, st);
-        if (rc != CNNMEM_ERR_UNSUPPORTED) return rc;
+        // three rows per lane: 7 input rows feed 3 outputs instead of 9 (measured best on MI355X)
+        rc = launch_chwn_window<MODE, 3, 3, 2, 2>(tune.rows_per_lane ? tune.rows_per_lane : 3, ox, src, dst, g, tune, st);
     } else if (vec && g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2) {
-        const int oy = env_int("CNNMEM_POOL_CHWN_OY", 1);     // disjoint windows: nothing to reuse, 1 is fastest
-        int rc;
-        if (oy <= 1) rc = launch_chwn_vec4<MODE, 2, 2, 2, 2, 1>(src, dst, g, st);
-        else if (oy == 2) rc = launch_chwn_vec4<MODE, 2, 2, 2, 2, 2>(src, dst, g, st);
-        else rc = launch_chwn_vec4<MODE, 2, 2, 2, 2, 4>(src, dst, g, st);
-        if (rc != CNNMEM_ERR_UNSUPPORTED) return rc;
+        // disjoint windows: nothing to reuse, one output per lane is fastest
+        rc = launch_chwn_window<MODE, 2, 2, 2, 2>(tune.rows_per_lane ? tune.rows_per_lane : 1, ox, src, dst, g, tune, st);
     } else if (vec && g.kh == 3 && g.kw == 3 && g.sh == 1 && g.sw == 1) {
-        const int rc = launch_chwn_vec4<MODE, 3, 3, 1, 1, 4>(src, dst, g, st);
-        if (rc != CNNMEM_ERR_UNSUPPORTED) return rc;
+        rc = launch_chwn_window<MODE, 3, 3, 1, 1>(tune.rows_per_lane ? tune.rows_per_lane : 4, ox, src, dst, g, tune, st);
     }
+    if (rc != CNNMEM_ERR_UNSUPPORTED) return rc;
     return launch_generic<MODE>(src, dst, g, 1, st);
 }
 
@@ -406,29 +431,30 @@ int launch_slab_threads(const float* src, float* dst, const PoolGeom& g, const S
 
 template <int MODE, int KH, int KW, int SH, int SW>
 int launch_slab(const float* src, float* dst, const PoolGeom& g, const SlabPlan& plan, long long blocks,
-                hipStream_t st) {
-    // lanes per slab: more lanes = fewer 128-bit loads in flight per lane for the same 32 KB
-    const int threads = env_int("CNNMEM_POOL_SLAB_THREADS", 512);   // 512 measured best (68 % vs 64 % / 49 %)
+                const PoolTuning& tune, hipStream_t st) {
+    // lanes per slab: more lanes = fewer 128-bit loads in flight per lane for the same 32 KB;
+    // 512 measured best (68 % of peak against 64 % with 256 and 49 % with 1024)
+    const int threads = tune.slab_lanes ? tune.slab_lanes : 512;
     if (threads >= 1024) return launch_slab_threads<MODE, KH, KW, SH, SW, 1024>(src, dst, g, plan, blocks, st);
     if (threads >= 512) return launch_slab_threads<MODE, KH, KW, SH, SW, 512>(src, dst, g, plan, blocks, st);
     return launch_slab_threads<MODE, KH, KW, SH, SW, 256>(src, dst, g, plan, blocks, st);
 }
 
 template <int MODE>
-int dispatch_nchw(const float* src, float* dst, const PoolGeom& g, hipStream_t st) {
+int dispatch_nchw(const float* src, float* dst, const PoolGeom& g, const PoolTuning& tune, hipStream_t st) {
     const long long planes = (long long)g.N * g.C;
     const bool a16 = aligned16(src) && aligned16(dst);
 
     // (1) non-overlapping 2x2 / stride 2 on even H: row pairs, no staging
     if (a16 && g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2 && g.ph == 0 && g.pw == 0 &&
-        g.H % 2 == 0 && g.W % 4 == 0 && env_int("CNNMEM_POOL_NCHW_ROWS", 1)) {
+        g.H % 2 == 0 && g.W % 4 == 0 && tune.nchw_kernel != 2) {
         const long long per_row = g.W / 4;
         const long long items = planes * g.Ho * per_row;
         if (items < 0x7fffffffLL) {
             const FastDiv d = make_fastdiv((uint32_t)per_row);
             const unsigned blocks = (unsigned)ceil_div64(items, kThreads);
             // 32 B in flight per lane: best at 6 workgroups per CU on large tensors
-            const size_t lds = throttle_lds(4LL * planes * g.H * g.W, 6);
+            const size_t lds = throttle_lds(tune.workgroups_per_cu, 4LL * planes * g.H * g.W, 6);
             hipLaunchKernelGGL((pool_nchw_2x2s2_kernel<MODE>), dim3(blocks), dim3(kThreads), lds, st, src, dst,
                                (uint32_t)items, (uint32_t)g.W, d);
             return launch_status();
@@ -470,10 +496,10 @@ int dispatch_nchw(const float* src, float* dst, const PoolGeom& g, hipStream_t s
         }
         if (ok && blocks <= 0x7fffffffLL) {
             if (g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2)
-                return launch_slab<MODE, 3, 3, 2, 2>(src, dst, g, plan, blocks, st);
+                return launch_slab<MODE, 3, 3, 2, 2>(src, dst, g, plan, blocks, tune, st);
             if (g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2)
-                return launch_slab<MODE, 2, 2, 2, 2>(src, dst, g, plan, blocks, st);
-            return launch_slab<MODE, 0, 0, 0, 0>(src, dst, g, plan, blocks, st);
+                return launch_slab<MODE, 2, 2, 2, 2>(src, dst, g, plan, blocks, tune, st);
+            return launch_slab<MODE, 0, 0, 0, 0>(src, dst, g, plan, blocks, tune, st);
         }
     }
     return launch_generic<MODE>(src, dst, g, 0, st);
@@ -481,14 +507,14 @@ int dispatch_nchw(const float* src, float* dst, const PoolGeom& g, hipStream_t s
 
 }  // namespace
 
-int launch_pool_nchw(const float* src, float* dst, const PoolGeom& g, hipStream_t st) {
-    return g.mode == CNNMEM_POOL_MAX ? dispatch_nchw<CNNMEM_POOL_MAX>(src, dst, g, st)
-                                     : dispatch_nchw<CNNMEM_POOL_AVG>(src, dst, g, st);
+int launch_pool_nchw(const float* src, float* dst, const PoolGeom& g, const PoolTuning& tune, hipStream_t st) {
+    return g.mode == CNNMEM_POOL_MAX ? dispatch_nchw<CNNMEM_POOL_MAX>(src, dst, g, tune, st)
+                                     : dispatch_nchw<CNNMEM_POOL_AVG>(src, dst, g, tune, st);
 }
 
-int launch_pool_chwn(const float* src, float* dst, const PoolGeom& g, hipStream_t st) {
-    return g.mode == CNNMEM_POOL_MAX ? dispatch_chwn<CNNMEM_POOL_MAX>(src, dst, g, st)
-                                     : dispatch_chwn<CNNMEM_POOL_AVG>(src, dst, g, st);
+int launch_pool_chwn(const float* src, float* dst, const PoolGeom& g, const PoolTuning& tune, hipStream_t st) {
+    return g.mode == CNNMEM_POOL_MAX ? dispatch_chwn<CNNMEM_POOL_MAX>(src, dst, g, tune, st)
+                                     : dispatch_chwn<CNNMEM_POOL_AVG>(src, dst, g, tune, st);
 }
 
 }  // namespace cnnmem

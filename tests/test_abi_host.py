@@ -81,6 +81,17 @@ def test_pool_rejects_invalid_arguments_on_host(kwargs):
                           a["kh"], a["kw"], a["sh"], a["sw"], a["ph"], a["pw"], stream=0) == INVALID
 
 
+@pytest.mark.parametrize("tuning", [dict(rows_per_lane=5), dict(rows_per_lane=-1), dict(cols_per_lane=3),
+                                    dict(workgroups_per_cu=9), dict(workgroups_per_cu=1), dict(workgroups_per_cu=-2),
+                                    dict(nchw_kernel=3), dict(slab_lanes=300)])
+def test_pool_tuned_rejects_out_of_range_tuning_on_host(tuning):
+    assert cm.cnnmem_pool_tuned(FAKE, FAKE + 4096, 2, 2, 8, 8, cm.NCHW, cm.POOL_MAX, 3, 3, 2, 2, 0, 0,
+                                tuning=tuning, stream=0) == INVALID
+    # and a valid tuning does not rescue an invalid call
+    assert cm.cnnmem_pool_tuned(None, FAKE, 2, 2, 8, 8, cm.NCHW, cm.POOL_MAX, 3, 3, 2, 2, 0, 0,
+                                tuning=dict(rows_per_lane=2), stream=0) == INVALID
+
+
 @pytest.mark.parametrize("kwargs", [dict(logits=None), dict(probs=None), dict(N=0), dict(classes=0),
                                     dict(logits=FAKE + 3)])
 def test_softmax_rejects_invalid_arguments_on_host(kwargs):

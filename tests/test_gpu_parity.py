@@ -102,7 +102,7 @@ def avg_tolerance(x_nchw, N, C, H, W, geom):
     return 1e-6 * oracle.pool(np.abs(x_nchw), N, C, H, W, NCHW, AVG, kh, kw, sh, sw, ph, pw).astype(np.float64)
 
 
-def check_pool(x, N, C, H, W, geom, modes=(MAX, AVG), layouts=(NCHW, CHWN)):
+def check_pool(x, N, C, H, W, geom, modes=(MAX, AVG), layouts=(NCHW, CHWN), tuning=None):
     kh, kw, sh, sw, ph, pw = geom
     Ho, Wo = oracle.pool_out_dims(H, W, kh, kw, sh, sw, ph, pw)
     x = x + np.float32(0.0)                       # -0 -> +0: the sign of a zero maximum is unspecified
@@ -113,7 +113,7 @@ def check_pool(x, N, C, H, W, geom, modes=(MAX, AVG), layouts=(NCHW, CHWN)):
         d_src = dev(src)
         for mode in modes:
             want = oracle.pool(src, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw)
-            got = host(cm.pool(d_src, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw))
+            got = host(cm.pool(d_src, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, tuning=tuning))
             assert got.shape == want.shape
             if mode == MAX:
                 assert same_bits(got + np.float32(0.0), want + np.float32(0.0)), (layout, geom)
@@ -162,20 +162,27 @@ def test_pool_matches_oracle(shape, geom):
 
 
 @pytest.mark.parametrize("oy", [1, 2, 3, 4])
-def test_pool_chwn_every_rows_per_lane_setting(oy, monkeypatch):
-    monkeypatch.setenv("CNNMEM_POOL_CHWN_OY", str(oy))
-    rng = np.random.default_rng(oy)
+@pytest.mark.parametrize("ox", [1, 2])
+def test_pool_chwn_every_working_set_shape(oy, ox):
+    rng = np.random.default_rng(10 * oy + ox)
     for shape, geom in [((8, 3, 27, 27), (3, 3, 2, 2, 0, 0)), ((8, 3, 13, 15), (3, 3, 2, 2, 1, 1)),
-                        ((8, 3, 14, 30), (2, 2, 2, 2, 0, 0))]:
+                        ((8, 3, 14, 30), (2, 2, 2, 2, 0, 0)), ((4, 2, 12, 11), (3, 3, 1, 1, 1, 1)),
+                        ((16, 2, 9, 7), (2, 2, 2, 2, 1, 1))]:
         x = rng.standard_normal(shape, dtype=np.float32)
-        check_pool(x, *shape, geom, layouts=(CHWN,))
+        check_pool(x, *shape, geom, layouts=(CHWN,), tuning=dict(rows_per_lane=oy, cols_per_lane=ox))
 
 
-def test_pool_nchw_slab_path_equals_row_pair_path(monkeypatch):
-    shape, geom = (4, 5, 32, 48), (2, 2, 2, 2, 0, 0)
-    x = np.random.default_rng(9).standard_normal(shape, dtype=np.float32)
-    monkeypatch.setenv("CNNMEM_POOL_NCHW_ROWS", "0")
-    check_pool(x, *shape, geom, layouts=(NCHW,))
+@pytest.mark.parametrize("tuning", [dict(nchw_kernel=2), dict(nchw_kernel=2, slab_lanes=256),
+                                    dict(nchw_kernel=2, slab_lanes=1024), dict(workgroups_per_cu=6),
+                                    dict(workgroups_per_cu=2), dict(workgroups_per_cu=-1)])
+def test_pool_nchw_every_kernel_choice(tuning):
+    rng = np.random.default_rng(9)
+    for shape, geom in [((4, 5, 32, 48), (2, 2, 2, 2, 0, 0)), ((4, 3, 27, 27), (3, 3, 2, 2, 0, 0)),
+                        ((2, 2, 110, 110), (3, 3, 2, 2, 0, 0))]:
+        x = rng.standard_normal(shape, dtype=np.float32)
+        check_pool(x, *shape, geom, layouts=(NCHW,), tuning=tuning)
+    x = rng.standard_normal((8, 4, 16, 16), dtype=np.float32)
+    check_pool(x, 8, 4, 16, 16, (2, 2, 2, 2, 0, 0), layouts=(CHWN,), tuning=tuning)
 
 
 def test_pool_misaligned_views():
