@@ -38,6 +38,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--only", default="", help="comma list of op names to run (profiling aid)")
+    ap.add_argument("--workload", choices=["largest", "table1"], default="largest",
+                    help="largest: each kernel on its largest configured tensor (the headline run); "
+                         "table1: every pooling and classifier layer of the paper's Table 1")
     ap.add_argument("--verbose", action="store_true")
     return ap.parse_args()
 
@@ -128,6 +131,43 @@ def build_ops(torch, cm, wl, rl, only):
     return ops, host
 
 
+def build_table1_ops(torch, cm, wl, rl, only):
+    """Second workload: max-pooling of PL1..PL10 in both layouts and softmax of CLASS1..CLASS5 (Table 1)."""
+    dev = torch.device("cuda:0")
+    ops = []
+    gen = torch.Generator(device="cuda").manual_seed(1610)
+
+    def nsets_for(nbytes):
+        return int(min(16, max(2, (1 << 30) // nbytes + 1)))
+
+    for (name, N, hw, k, C, s) in wl.TABLE1_POOLS:
+        st, Ho, Wo = cm.cnnmem_pool_out_dims(hw, hw, k, k, s, s, 0, 0)
+        n_in, n_out = N * C * hw * hw, N * C * Ho * Wo
+        ns = nsets_for(4 * (n_in + n_out))
+        pb = rl.pool_bytes(N, C, hw, hw, k, k, s, s)
+        for layout, tag in ((cm.NCHW, "nchw"), (cm.CHWN, "chwn")):
+            opname = f"{name.lower()}_max_{tag}"
+            if only and opname not in only:
+                continue
+            xs = [torch.randn(n_in, device=dev, generator=gen).relu_() for _ in range(ns)]
+            ys = [torch.empty(n_out, dtype=torch.float32, device=dev) for _ in range(ns)]
+            ops.append(Op(opname, "pool", pb, n_in, "input elements",
+                          (lambda xs, ys, N, C, hw, layout, k, s:
+                           lambda i: cm.cnnmem_pool(xs[i], ys[i], N, C, hw, hw, layout, cm.POOL_MAX, k, k, s, s, 0, 0))(
+                              xs, ys, N, C, hw, layout, k, s), ns))
+    for (name, n, c) in wl.TABLE1_CLASSIFIERS:
+        opname = f"{name.lower()}_softmax"
+        if only and opname not in only:
+            continue
+        ns = 16
+        zs = [torch.randn((n, c), device=dev, generator=gen) * 3 for _ in range(ns)]
+        ps = [torch.empty_like(zs[0]) for _ in range(ns)]
+        ops.append(Op(opname, "softmax", rl.softmax_bytes(n, c), n * c, "elements",
+                      (lambda zs, ps, n, c: lambda i: cm.cnnmem_softmax(zs[i], ps[i], n, c))(zs, ps, n, c), ns))
+    torch.cuda.synchronize()
+    return ops, {}
+
+
 def cpu_baseline(wl, rl, host):
     """The oracle, as it stands, timed on one pass over the same inputs (host copies)."""
     import oracle
@@ -182,7 +222,11 @@ def main():
     cm.library()                                  # fails loudly if the HIP library is not built
     torch.cuda.set_device(0)
     only = set(filter(None, args.only.split(",")))
-    ops, host_inputs = build_ops(torch, cm, wl, rl, only)
+    if args.workload == "table1":
+        ops, host_inputs = build_table1_ops(torch, cm, wl, rl, only)
+        args.no_cpu_baseline = True                # the oracle baseline is reported for the headline workload
+    else:
+        ops, host_inputs = build_ops(torch, cm, wl, rl, only)
     if not ops:
         print("no op selected", file=sys.stderr)
         sys.exit(2)
@@ -244,9 +288,10 @@ def main():
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "largest tensor per kernel: transform 128x96x55x55 both directions (config 2), "
-                               "max+avg pool 2x2/s2 on 64x64x224x224 in NCHW and CHWN (config 4), "
-                               "softmax 4096x21841 (config 5)",
+        "config": {"workload": ("largest tensor per kernel: transform 128x96x55x55 both directions (config 2), "
+                                "max+avg pool 2x2/s2 on 64x64x224x224 in NCHW and CHWN (config 4), "
+                                "softmax 4096x21841 (config 5)") if args.workload == "largest" else
+                               "Table 1 of the paper: max-pool PL1..PL10 in NCHW and CHWN, softmax CLASS1..CLASS5",
                    "launches_per_step": len(ops), "alg_bytes_per_step": step_bytes,
                    "cache_control": "rotating buffer sets, each larger than the 256 MB last-level cache"},
         "per_layer": per_kind,

@@ -34,11 +34,11 @@ def softmax_bytes(N: int, classes: int) -> int:
 # WRITE_SIZE, scaled by what the same counters read for a plain copy of known size), keyed by
 # the benchmark's launch names.  Filled from the committed profile summaries; None = not measured.
 MEASURED_TRAFFIC = {
-    "transform_nchw_to_chwn": 297308745,
-    "transform_chwn_to_nchw": 297352714,
-    "pool_max_nchw": 1034474465,
-    "pool_max_chwn": 1027390274,
-    "pool_avg_nchw": 1029526204,
-    "pool_avg_chwn": 1027392407,
-    "softmax": 716935718,
+    "transform_nchw_to_chwn": 297289896,
+    "transform_chwn_to_nchw": 297303668,
+    "pool_max_nchw": 1027310443,
+    "pool_max_chwn": 1027321192,
+    "pool_avg_nchw": 1027306732,
+    "pool_avg_chwn": 1027320040,
+    "softmax": 716973707,
 }
