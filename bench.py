@@ -31,16 +31,36 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+WORKLOADS = {
+    "largest": "each kernel on its largest configured tensor (the headline run)",
+    "table1": "every pooling and classifier layer of the paper's Table 1",
+    "softmax_sweep": "softmax over batch size x categories (Fig. 13's range)",
+    "layout_policy": "the three AlexNet pooling layers of config 3 under both layout policies: pool where the "
+                     "data is (NCHW) against transform + pool in CHWN + transform back (Section IV.B, IV.D)",
+}
+WORKLOAD_TEXT = {
+    "largest": "largest tensor per kernel: transform 128x96x55x55 both directions (config 2), "
+               "max+avg pool 2x2/s2 on 64x64x224x224 in NCHW and CHWN (config 4), softmax 4096x21841 (config 5)",
+    "table1": "Table 1 of the paper: max-pool PL1..PL10 in NCHW and CHWN, softmax CLASS1..CLASS5",
+    "softmax_sweep": "softmax, batch 32..256 x categories 10..10000 (the range of Fig. 13)",
+    "layout_policy": "config 3 (AlexNet, N=128) max-pool 3x3/s2 x3: NCHW in place vs NCHW->CHWN + pool + CHWN->NCHW",
+}
+
+
 def parse_args():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--only", default="", help="comma list of op names to run (profiling aid)")
-    ap.add_argument("--workload", choices=["largest", "table1"], default="largest",
-                    help="largest: each kernel on its largest configured tensor (the headline run); "
-                         "table1: every pooling and classifier layer of the paper's Table 1")
+    ap.add_argument("--workload", choices=sorted(WORKLOADS), default="largest",
+                    help="; ".join(f"{k}: {v}" for k, v in sorted(WORKLOADS.items())))
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture the step into a HIP graph and time its replays (removes the host's launch "
+                         "cost, which dominates workloads of very small tensors)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the warm-cache and same-bytes-copy yardsticks measured after the timed region")
     ap.add_argument("--verbose", action="store_true")
     return ap.parse_args()
 
@@ -137,9 +157,7 @@ def build_table1_ops(torch, cm, wl, rl, only):
     ops = []
     gen = torch.Generator(device="cuda").manual_seed(1610)
 
-    def nsets_for(nbytes):
-        return int(min(16, max(2, (1 << 30) // nbytes + 1)))
-
+    nsets_for = _nsets_for
     for (name, N, hw, k, C, s) in wl.TABLE1_POOLS:
         st, Ho, Wo = cm.cnnmem_pool_out_dims(hw, hw, k, k, s, s, 0, 0)
         n_in, n_out = N * C * hw * hw, N * C * Ho * Wo
@@ -168,41 +186,187 @@ def build_table1_ops(torch, cm, wl, rl, only):
     return ops, {}
 
 
-def cpu_baseline(wl, rl, host):
-    """The oracle, as it stands, timed on one pass over the same inputs (host copies)."""
+def _nsets_for(nbytes):
+    return int(min(16, max(2, (1 << 30) // nbytes + 1)))
+
+
+def build_softmax_sweep_ops(torch, cm, wl, rl, only):
+    """Softmax over a batch x categories grid (the range Fig. 13 covers)."""
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device="cuda").manual_seed(1613)
+    ops = []
+    for (n, c) in wl.SOFTMAX_SWEEP:
+        opname = f"softmax_{n}x{c}"
+        if only and opname not in only:
+            continue
+        ns = _nsets_for(8 * n * c)
+        zs = [torch.randn((n, c), device=dev, generator=gen) * 3 for _ in range(ns)]
+        ps = [torch.empty_like(zs[0]) for _ in range(ns)]
+        ops.append(Op(opname, "softmax", rl.softmax_bytes(n, c), n * c, "elements",
+                      (lambda zs, ps, n, c: lambda i: cm.cnnmem_softmax(zs[i], ps[i], n, c))(zs, ps, n, c), ns))
+    torch.cuda.synchronize()
+    return ops, {}
+
+
+def build_layout_policy_ops(torch, cm, wl, rl, only):
+    """Config 3's three pooling layers, data arriving and leaving in NCHW (what the neighbouring
+    convolutions of AlexNet prefer at N = 128, C >= 96 under Section IV.A's rule): either pool in NCHW, or follow
+    the always-CHWN rule for pooling and pay a transform before and after."""
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device="cuda").manual_seed(1614)
+    ops = []
+    for li, pc in enumerate(wl.config(3).pools):
+        t = pc.tensor
+        st, Ho, Wo = cm.cnnmem_pool_out_dims(t.H, t.W, pc.k, pc.k, pc.s, pc.s, 0, 0)
+        n_in, n_out = t.numel, t.N * t.C * Ho * Wo
+        ns = _nsets_for(8 * (n_in + n_out))
+        x = [torch.randn(n_in, device=dev, generator=gen).relu_() for _ in range(ns)]
+        xc = [torch.empty(n_in, dtype=torch.float32, device=dev) for _ in range(ns)]
+        y = [torch.empty(n_out, dtype=torch.float32, device=dev) for _ in range(ns)]
+        yc = [torch.empty(n_out, dtype=torch.float32, device=dev) for _ in range(ns)]
+        pb = rl.pool_bytes(t.N, t.C, t.H, t.W, pc.k, pc.k, pc.s, pc.s)
+        N, C, H, W, k, s_ = t.N, t.C, t.H, t.W, pc.k, pc.s
+        tag = f"l{li + 1}_{C}x{H}x{W}"
+        mk = [
+            (f"{tag}:keep:pool_nchw", "pool", pb,
+             lambda i, x=x, y=y, N=N, C=C, H=H, W=W, k=k, s_=s_:
+                 cm.cnnmem_pool(x[i], y[i], N, C, H, W, cm.NCHW, cm.POOL_MAX, k, k, s_, s_, 0, 0)),
+            (f"{tag}:chwn:transform_in", "transform", rl.transform_bytes(N, C, H, W),
+             lambda i, x=x, xc=xc, N=N, C=C, H=H, W=W: cm.cnnmem_transform(x[i], xc[i], N, C, H, W, cm.NCHW, cm.CHWN)),
+            (f"{tag}:chwn:pool_chwn", "pool", pb,
+             lambda i, xc=xc, yc=yc, N=N, C=C, H=H, W=W, k=k, s_=s_:
+                 cm.cnnmem_pool(xc[i], yc[i], N, C, H, W, cm.CHWN, cm.POOL_MAX, k, k, s_, s_, 0, 0)),
+            (f"{tag}:chwn:transform_out", "transform", rl.transform_bytes(N, C, Ho, Wo),
+             lambda i, yc=yc, y=y, N=N, C=C, Ho=Ho, Wo=Wo: cm.cnnmem_transform(yc[i], y[i], N, C, Ho, Wo, cm.CHWN, cm.NCHW)),
+        ]
+        for name, kind, b, fn in mk:
+            if only and name not in only:
+                continue
+            ops.append(Op(name, kind, b, n_in, "input elements", fn, ns))
+    torch.cuda.synchronize()
+    return ops, {}
+
+
+def layout_policy_summary(kernels):
+    """Per layer: microseconds for pooling in place (NCHW) against transform + CHWN pooling + transform."""
+    layers = {}
+    for k in kernels:
+        tag, policy, _ = k["name"].split(":")
+        layers.setdefault(tag, {"keep_layout_us": 0.0, "always_chwn_us": 0.0})
+        layers[tag]["keep_layout_us" if policy == "keep" else "always_chwn_us"] += k["median_ms"] * 1e3
+    for v in layers.values():
+        v["keep_layout_us"] = round(v["keep_layout_us"], 2)
+        v["always_chwn_us"] = round(v["always_chwn_us"], 2)
+        v["ratio"] = round(v["always_chwn_us"] / v["keep_layout_us"], 3) if v["keep_layout_us"] else None
+    return layers
+
+
+def measure_extras(torch, cm, ops, iters=20):
+    """Two yardsticks beside every launch, measured after the timed region:
+
+    warm -- the same launch repeated on one buffer set (the last-level cache may serve it);
+    copy -- the library's plain copy kernel moving the same number of bytes (half read, half
+            written) between rotating buffers: the practical ceiling of this memory system.
+    """
+    dev = torch.device("cuda:0")
+    out = {}
+    copy_cache = {}
+
+    # a launch of a millisecond or so that goes first, so that the host has queued every timed launch
+    # before the GPU reaches it and the events bracket GPU time only
+    pa = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+    pb = torch.empty_like(pa)
+
+    def timed(fn, n):
+        for i in range(3):
+            fn(i)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        torch.cuda.synchronize()
+        for _ in range(3):
+            cm.cnnmem_transform(pa, pb, 1, 1, 1, pa.numel(), cm.NCHW, cm.NCHW)
+        for i, (a, b) in enumerate(ev):
+            a.record()
+            fn(i)
+            b.record()
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in ev)
+        return ms[len(ms) // 2]
+
+    for op in ops:
+        warm_ms = timed(lambda i, op=op: op.launch(0), iters)
+        if op.alg_bytes not in copy_cache:
+            n = max(4, (op.alg_bytes // 8) // 4 * 4)           # floats each way
+            ns = _nsets_for(8 * n)
+            a = [torch.zeros(n, dtype=torch.float32, device=dev) for _ in range(ns)]
+            b = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(ns)]
+            copy_cache[op.alg_bytes] = timed(
+                lambda i, a=a, b=b, n=n, ns=ns: cm.cnnmem_transform(a[i % ns], b[i % ns], 1, 1, 1, n, cm.NCHW, cm.NCHW),
+                iters)
+            del a, b
+        out[op.name] = (warm_ms, copy_cache[op.alg_bytes])
+    return out
+
+
+def cpu_baseline(wl, rl, host, reps=3):
+    """The oracle, as it stands, timed on the same inputs (host copies): best of ``reps`` passes over
+    the full workload on all host threads, and one pass on one thread over an eighth of every tensor."""
     import oracle
     t = wl.config(2).transforms[0]
     p = wl.config(4).pools[0].tensor
     s = wl.config(5).softmaxes[0]
-    total_bytes, parts = 0, {}
     t_start = time.perf_counter()
-    if "transform" in host:
-        t0 = time.perf_counter()
-        xtc = oracle.transform(host["transform"], t.N, t.C, t.H, t.W, oracle.NCHW, oracle.CHWN)
-        oracle.transform(xtc, t.N, t.C, t.H, t.W, oracle.CHWN, oracle.NCHW)
-        parts["transform"] = (2 * rl.transform_bytes(t.N, t.C, t.H, t.W), time.perf_counter() - t0)
-        del xtc
-    if "pool" in host:
-        xp = host["pool"]
-        xpc = oracle.transform(xp, p.N, p.C, p.H, p.W, oracle.NCHW, oracle.CHWN)   # input prep, not timed
-        t0 = time.perf_counter()
-        for mode in (oracle.POOL_MAX, oracle.POOL_AVG):
-            oracle.pool(xp, p.N, p.C, p.H, p.W, oracle.NCHW, mode, 2, 2, 2, 2)
-            oracle.pool(xpc, p.N, p.C, p.H, p.W, oracle.CHWN, mode, 2, 2, 2, 2)
-        parts["pool"] = (4 * rl.pool_bytes(p.N, p.C, p.H, p.W, 2, 2, 2, 2), time.perf_counter() - t0)
-        del xpc
-    if "softmax" in host:
-        t0 = time.perf_counter()
-        oracle.softmax(host["softmax"])
-        parts["softmax"] = (rl.softmax_bytes(s.N, s.classes), time.perf_counter() - t0)
-    total_bytes = sum(b for b, _ in parts.values())
-    dt = sum(d for _, d in parts.values())
-    return {"value": round(total_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.threads(),
+    xpc = None
+    if "pool" in host:                                           # input prep, not timed
+        xpc = oracle.transform(host["pool"], p.N, p.C, p.H, p.W, oracle.NCHW, oracle.CHWN)
+
+    def one_pass(frac):
+        """Times one pass over the first 1/frac of every tensor (whole images / whole rows)."""
+        parts = {}
+        if "transform" in host:
+            n = t.N // frac
+            x = host["transform"][:n]
+            t0 = time.perf_counter()
+            xtc = oracle.transform(x, n, t.C, t.H, t.W, oracle.NCHW, oracle.CHWN)
+            oracle.transform(xtc, n, t.C, t.H, t.W, oracle.CHWN, oracle.NCHW)
+            parts["transform"] = (2 * rl.transform_bytes(n, t.C, t.H, t.W), time.perf_counter() - t0)
+        if "pool" in host:
+            c = p.C // frac                                     # CHWN slices along C stay contiguous
+            xn, xc = host["pool"][:, :c], xpc[:c]
+            if frac > 1:
+                import numpy as np
+                xn = np.ascontiguousarray(xn)
+            t0 = time.perf_counter()
+            for mode in (oracle.POOL_MAX, oracle.POOL_AVG):
+                oracle.pool(xn, p.N, c, p.H, p.W, oracle.NCHW, mode, 2, 2, 2, 2)
+                oracle.pool(xc, p.N, c, p.H, p.W, oracle.CHWN, mode, 2, 2, 2, 2)
+            parts["pool"] = (4 * rl.pool_bytes(p.N, c, p.H, p.W, 2, 2, 2, 2), time.perf_counter() - t0)
+        if "softmax" in host:
+            n = s.N // frac
+            t0 = time.perf_counter()
+            oracle.softmax(host["softmax"][:n])
+            parts["softmax"] = (rl.softmax_bytes(n, s.classes), time.perf_counter() - t0)
+        return parts
+
+    best = None
+    for _ in range(reps):
+        parts = one_pass(1)
+        if best is None or sum(d for _, d in parts.values()) < sum(d for _, d in best.values()):
+            best = parts
+    cores = oracle.threads()
+    oracle.set_threads(1)
+    single = one_pass(8)
+    oracle.set_threads(cores)
+    total_bytes = sum(b for b, _ in best.values())
+    dt = sum(d for _, d in best.values())
+    sb, sd = sum(b for b, _ in single.values()), sum(d for _, d in single.values())
+    return {"value": round(total_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": cores,
             "kind": "oracle", "seconds": round(dt, 3),
-            "per_layer": {k: round(b / d / 1e9, 3) for k, (b, d) in parts.items()},
-            "sample": f"one pass of the same launches over the full workload "
-                      f"({total_bytes / 1e6:.0f} MB algorithmic, {time.perf_counter() - t_start:.1f} s wall "
-                      f"including untimed input preparation)"}
+            "per_layer": {k: round(b / d / 1e9, 3) for k, (b, d) in best.items()},
+            "single_thread": {"value": round(sb / sd / 1e9, 3), "unit": "GB/s", "seconds": round(sd, 3),
+                              "sample": "one pass over the first eighth of every tensor on one thread"},
+            "sample": f"best of {reps} passes of the same launches over the full workload "
+                      f"({total_bytes / 1e6:.0f} MB algorithmic per pass; {time.perf_counter() - t_start:.1f} s wall "
+                      f"including untimed input preparation and the single-thread pass)"}
 
 
 def main():
@@ -222,22 +386,24 @@ def main():
     cm.library()                                  # fails loudly if the HIP library is not built
     torch.cuda.set_device(0)
     only = set(filter(None, args.only.split(",")))
-    if args.workload == "table1":
-        ops, host_inputs = build_table1_ops(torch, cm, wl, rl, only)
+    builders = {"largest": build_ops, "table1": build_table1_ops, "softmax_sweep": build_softmax_sweep_ops,
+                "layout_policy": build_layout_policy_ops}
+    ops, host_inputs = builders[args.workload](torch, cm, wl, rl, only)
+    if args.workload != "largest":
         args.no_cpu_baseline = True                # the oracle baseline is reported for the headline workload
-    else:
-        ops, host_inputs = build_ops(torch, cm, wl, rl, only)
     if not ops:
         print("no op selected", file=sys.stderr)
         sys.exit(2)
 
+    # One event before the first launch of a step and one after every launch: launch k of a step lasted
+    # from event k to event k + 1 (the launches of a step run back to back on one stream).
     def one_step(step, events=None):
+        if events is not None:
+            events[0].record()
         for k, op in enumerate(ops):
-            if events is not None:
-                events[k][0].record()
             st = op.launch(step % op.nsets)
             if events is not None:
-                events[k][1].record()
+                events[k + 1].record()
             if st != 0:
                 raise RuntimeError(f"{op.name}: status {st}")
 
@@ -245,8 +411,7 @@ def main():
         one_step(w)
     torch.cuda.synchronize()
 
-    all_events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in ops]
-                  for _ in range(args.steps)]
+    all_events = [[torch.cuda.Event(enable_timing=True) for _ in range(len(ops) + 1)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
@@ -256,8 +421,29 @@ def main():
 
     for s in range(args.steps):
         for k, op in enumerate(ops):
-            op.ms.append(all_events[s][k][0].elapsed_time(all_events[s][k][1]))
+            op.ms.append(all_events[s][k].elapsed_time(all_events[s][k + 1]))
 
+    graph_info = None
+    if args.graph:
+        # One graph holds as many consecutive steps as the deepest buffer rotation, so replays keep
+        # cycling through the buffer sets exactly like the eager loop.
+        per_graph = max(op.nsets for op in ops)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for s in range(per_graph):
+                one_step(s)
+        graph.replay()
+        torch.cuda.synchronize()
+        reps = max(1, -(-args.steps // per_graph))
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        gwall = (time.perf_counter() - t0) / (reps * per_graph)
+        graph_info = {"steps_per_graph": per_graph, "replays": reps, "ms_per_step": round(gwall * 1e3, 4),
+                      "value": round(sum(op.alg_bytes for op in ops) / gwall / 1e9, 1), "unit": "GB/s"}
+
+    extras = {} if args.no_extras else measure_extras(torch, cm, ops)
     step_bytes = sum(op.alg_bytes for op in ops)
     ms_per_step = wall / args.steps * 1e3
     value = step_bytes / (wall / args.steps) / 1e9
@@ -270,6 +456,11 @@ def main():
                         "min_ms": round(min(op.ms), 5), "alg_bytes": op.alg_bytes,
                         "achieved": round(gbps, 1), "frac": round(gbps / rl.PEAK_HBM_GBPS, 4),
                         "traffic": rl.MEASURED_TRAFFIC.get(op.name)})
+        if op.name in extras:
+            warm_ms, copy_ms = extras[op.name]
+            kernels[-1]["warm_median_ms"] = round(warm_ms, 5)
+            kernels[-1]["copy_same_bytes_median_ms"] = round(copy_ms, 5)
+            kernels[-1]["frac_of_copy"] = round(copy_ms / med_ms, 4)
     dominant = max(kernels, key=lambda k: k["avg_ms"])
     roofline = {"bound": "hbm", "kernel": dominant["name"], "achieved": dominant["achieved"],
                 "peak": rl.PEAK_HBM_GBPS, "unit": "GB/s", "frac": dominant["frac"],
@@ -288,16 +479,17 @@ def main():
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": ("largest tensor per kernel: transform 128x96x55x55 both directions (config 2), "
-                                "max+avg pool 2x2/s2 on 64x64x224x224 in NCHW and CHWN (config 4), "
-                                "softmax 4096x21841 (config 5)") if args.workload == "largest" else
-                               "Table 1 of the paper: max-pool PL1..PL10 in NCHW and CHWN, softmax CLASS1..CLASS5",
+        "config": {"workload": WORKLOAD_TEXT[args.workload],
                    "launches_per_step": len(ops), "alg_bytes_per_step": step_bytes,
                    "cache_control": "rotating buffer sets, each larger than the 256 MB last-level cache"},
         "per_layer": per_kind,
         "roofline": roofline,
         "kernels": kernels,
     }
+    if graph_info:
+        out["graph"] = graph_info
+    if args.workload == "layout_policy":
+        out["layout_policy"] = layout_policy_summary(kernels)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, rl, host_inputs)
     print(json.dumps(out), flush=True)

@@ -54,7 +54,8 @@ def _load():
         lib.cnnmem_ref_index.argtypes = [i] * 9
         lib.cnnmem_ref_index.restype = ctypes.c_ulonglong
         for name in ("cnnmem_ref_transform", "cnnmem_ref_pool_out_dims", "cnnmem_ref_pool",
-                     "cnnmem_ref_softmax", "cnnmem_ref_naive_pool_loads_1d", "cnnmem_ref_threads"):
+                     "cnnmem_ref_softmax", "cnnmem_ref_naive_pool_loads_1d", "cnnmem_ref_threads",
+                     "cnnmem_ref_set_threads"):
             getattr(lib, name).restype = i
         _lib = lib
     return _lib
@@ -74,6 +75,12 @@ def _f32(a: np.ndarray) -> np.ndarray:
 def threads() -> int:
     """Threads the oracle's OpenMP loops will use."""
     return int(_load().cnnmem_ref_threads())
+
+
+def set_threads(n: int) -> None:
+    """Caps the threads of the oracle's loops (timing aid; results do not depend on it)."""
+    _load().cnnmem_ref_set_threads.argtypes = [ctypes.c_int]
+    _load().cnnmem_ref_set_threads(int(n))
 
 
 def shape_of(layout: int, N: int, C: int, H: int, W: int):

@@ -65,6 +65,16 @@ unsigned long long cnnmem_ref_index(int layout, int N, int C, int H, int W, int 
     return (unsigned long long)at(layout, N, C, H, W, n, c, h, w);
 }
 
+/* Caps the threads of the loops below (timing aid; results do not depend on it). */
+int cnnmem_ref_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#endif
+    (void)n;
+    return REF_OK;
+}
+
 int cnnmem_ref_threads(void)
 {
 #ifdef _OPENMP

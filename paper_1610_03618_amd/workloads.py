@@ -174,3 +174,8 @@ TABLE1_CLASSIFIERS: List[Tuple[str, int, int]] = [
     ("CLASS1", 128, 10), ("CLASS2", 128, 10), ("CLASS3", 128, 1000),
     ("CLASS4", 64, 1000), ("CLASS5", 32, 1000),
 ]
+
+
+# Softmax sweep in the spirit of Fig. 13: batch size x number of categories.  The figure's own list of
+# configurations is not legible in the text, so this grid spans its stated range (up to 10000 categories).
+SOFTMAX_SWEEP: List[Tuple[int, int]] = [(n, c) for n in (32, 64, 128, 256) for c in (10, 100, 1000, 10000)]

@@ -45,3 +45,17 @@ def test_table1_classifier_full_size(row):
     got = cm.softmax(torch.from_numpy(z).cuda()).cpu().numpy().astype(np.float64)
     assert np.all(np.abs(got - want) <= np.maximum(2e-6 * want, 1e-7)), name
     assert np.all(np.abs(got.sum(axis=1) - 1.0) <= 1e-6)
+
+
+@pytest.mark.parametrize("shape", wl.SOFTMAX_SWEEP, ids=[f"{n}x{c}" for n, c in wl.SOFTMAX_SWEEP])
+def test_softmax_sweep_batch_by_categories(shape):
+    """The batch x categories range of Fig. 13 (10 to 10000 categories)."""
+    n, c = shape
+    rng = np.random.default_rng(n * 13 + c)
+    z = wl.normal_logits(rng, n, c, 3.0)
+    want = oracle.softmax(z).astype(np.float64)
+    got = cm.softmax(torch.from_numpy(z).cuda()).cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - want) <= np.maximum(2e-6 * want, 1e-7)), shape
+    assert np.all(np.abs(got.sum(axis=1) - 1.0) <= 1e-5)
+    rows = np.arange(n)
+    assert np.array_equal(got[rows, z.argmax(axis=1)], got.max(axis=1))   # the largest logit keeps the largest probability
