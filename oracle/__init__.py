@@ -51,6 +51,10 @@ def _load():
         ip = ctypes.POINTER(i)
         lib.cnnmem_ref_plan_layouts.argtypes = [ip, ip, ip, i, i, i, i, i, ip, ip]
         lib.cnnmem_ref_plan_layouts.restype = i
+        lib.cnnmem_ref_permute.argtypes = [fp, fp, ip, ip]
+        lib.cnnmem_ref_permute.restype = i
+        lib.cnnmem_ref_relayout.argtypes = [fp, fp, i, i, i, i, ctypes.c_char_p, ctypes.c_char_p]
+        lib.cnnmem_ref_relayout.restype = i
         lib.cnnmem_ref_index.argtypes = [i] * 9
         lib.cnnmem_ref_index.restype = ctypes.c_ulonglong
         for name in ("cnnmem_ref_transform", "cnnmem_ref_pool_out_dims", "cnnmem_ref_pool",
@@ -95,6 +99,27 @@ def transform(src: np.ndarray, N: int, C: int, H: int, W: int,
     dst = np.empty(shape_of(dst_layout, N, C, H, W), dtype=np.float32)
     _check(_load().cnnmem_ref_transform(src.ctypes.data, dst.ctypes.data, N, C, H, W,
                                         src_layout, dst_layout), "transform")
+    return dst
+
+
+def permute(src: np.ndarray, dims, perm) -> np.ndarray:
+    """Axis permutation of a 4-D tensor: destination axis i is source axis ``perm[i]`` (Section I)."""
+    src = _f32(src)
+    assert src.size == int(np.prod(dims)) and len(dims) == 4 and len(perm) == 4
+    dst = np.empty(tuple(dims[p] for p in perm), dtype=np.float32)
+    _check(_load().cnnmem_ref_permute(src.ctypes.data, dst.ctypes.data, (ctypes.c_int * 4)(*dims),
+                                      (ctypes.c_int * 4)(*perm)), "permute")
+    return dst
+
+
+def relayout(src: np.ndarray, N: int, C: int, H: int, W: int, src_layout: str, dst_layout: str) -> np.ndarray:
+    """Storage-order change between two spelled layouts such as "NCHW" -> "NHWC" (Section I, IV.A)."""
+    src = _f32(src)
+    assert src.size == N * C * H * W
+    ext = dict(N=N, C=C, H=H, W=W)
+    dst = np.empty(tuple(ext[l] for l in dst_layout) if len(dst_layout) == 4 else (N * C * H * W,), dtype=np.float32)
+    _check(_load().cnnmem_ref_relayout(src.ctypes.data, dst.ctypes.data, N, C, H, W,
+                                       src_layout.encode(), dst_layout.encode()), "relayout")
     return dst
 
 

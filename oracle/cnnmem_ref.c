@@ -15,6 +15,9 @@
  *   - softmax: the five steps of Section II.A, in the paper's order.
  *   - layout choice: the (Ct, Nt) heuristic of Section IV.A and the one-scan plan
  *     of Section IV.D.
+ *   - the other storage orders: Section I (a 4-D tensor has 24), Section IV.A
+ *     (HWCN beside CHWN), the NHWC order of the comparison libraries: a general
+ *     axis permutation and a change between two spelled layouts.
  *
  * Readings taken where the paper is silent or garbled (each is pinned or
  * listed as a reading in the design notes):
@@ -41,6 +44,7 @@
 #include <stddef.h>
 #include <stdint.h>
 #include <stdlib.h>
+#include <string.h>
 #ifdef _OPENMP
 #include <omp.h>
 #endif
@@ -252,4 +256,82 @@ int cnnmem_ref_naive_pool_loads_1d(int L, int k, int s)
 {
     if (L < k || k <= 0 || s <= 0) return -1;
     return pooled_extent(L, k, s, 0) * k;
+}
+
+/* ---- any of the 24 storage orders of a 4-D tensor (Section I counts 24; Section IV.A
+ * names CHWN and HWCN as the batch-fastest candidates; NHWC is the third order the
+ * libraries of the paper's comparison offer) ---- */
+
+/* General axis permutation.  `dims` are the source extents, slowest axis first;
+ * destination axis i is source axis perm[i] (so the destination extents are
+ * dims[perm[0..3]]).  Words move as 32-bit integers. */
+int cnnmem_ref_permute(const float *src, float *dst, const int *dims, const int *perm)
+{
+    if (!src || !dst || !dims || !perm) return REF_ERR_INVALID_ARG;
+    int seen[4] = {0, 0, 0, 0};
+    for (int i = 0; i < 4; ++i) {
+        if (dims[i] <= 0 || perm[i] < 0 || perm[i] > 3 || seen[perm[i]]) return REF_ERR_INVALID_ARG;
+        seen[perm[i]] = 1;
+    }
+    size_t ss[4];                                   /* source strides in words */
+    ss[3] = 1;
+    for (int a = 2; a >= 0; --a) ss[a] = ss[a + 1] * (size_t)dims[a + 1];
+    const int e0 = dims[perm[0]], e1 = dims[perm[1]], e2 = dims[perm[2]], e3 = dims[perm[3]];
+    const size_t t0 = ss[perm[0]], t1 = ss[perm[1]], t2 = ss[perm[2]], t3 = ss[perm[3]];
+    const uint32_t *s = (const uint32_t *)src;
+    uint32_t *d = (uint32_t *)dst;
+#pragma omp parallel for schedule(static)
+    for (int i0 = 0; i0 < e0; ++i0)
+        for (int i1 = 0; i1 < e1; ++i1)
+            for (int i2 = 0; i2 < e2; ++i2)
+                for (int i3 = 0; i3 < e3; ++i3)
+                    d[(((size_t)i0 * e1 + i1) * e2 + i2) * e3 + i3] = s[i0 * t0 + i1 * t1 + i2 * t2 + i3 * t3];
+    return REF_OK;
+}
+
+/* Stride, in words, of the axis called `letter` when an N x C x H x W tensor is
+ * stored in the order spelled by `layout` (four letters, slowest first). */
+static int letter_stride(const char *layout, char letter, int N, int C, int H, int W, size_t *stride)
+{
+    size_t st = 1;
+    for (int i = 3; i >= 0; --i) {
+        const char l = layout[i];
+        if (l == letter) { *stride = st; return 1; }
+        st *= (size_t)(l == 'N' ? N : l == 'C' ? C : l == 'H' ? H : W);
+    }
+    return 0;
+}
+
+static int layout_ok(const char *layout)
+{
+    if (!layout || strlen(layout) != 4) return 0;
+    int n = 0, c = 0, h = 0, w = 0;
+    for (int i = 0; i < 4; ++i) {
+        n += layout[i] == 'N'; c += layout[i] == 'C'; h += layout[i] == 'H'; w += layout[i] == 'W';
+    }
+    return n == 1 && c == 1 && h == 1 && w == 1;
+}
+
+/* Storage-order change between two spelled layouts, e.g. "NCHW" -> "NHWC":
+ * element (n, c, h, w) is read where the source order puts it and written where
+ * the destination order puts it. */
+int cnnmem_ref_relayout(const float *src, float *dst, int N, int C, int H, int W,
+                        const char *src_layout, const char *dst_layout)
+{
+    if (!src || !dst || N <= 0 || C <= 0 || H <= 0 || W <= 0 || !layout_ok(src_layout) || !layout_ok(dst_layout))
+        return REF_ERR_INVALID_ARG;
+    size_t sn, sc, sh, sw, dn, dc, dh, dw;
+    letter_stride(src_layout, 'N', N, C, H, W, &sn); letter_stride(dst_layout, 'N', N, C, H, W, &dn);
+    letter_stride(src_layout, 'C', N, C, H, W, &sc); letter_stride(dst_layout, 'C', N, C, H, W, &dc);
+    letter_stride(src_layout, 'H', N, C, H, W, &sh); letter_stride(dst_layout, 'H', N, C, H, W, &dh);
+    letter_stride(src_layout, 'W', N, C, H, W, &sw); letter_stride(dst_layout, 'W', N, C, H, W, &dw);
+    const uint32_t *s = (const uint32_t *)src;
+    uint32_t *d = (uint32_t *)dst;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c)
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w)
+                    d[n * dn + c * dc + h * dh + w * dw] = s[n * sn + c * sc + h * sh + w * sw];
+    return REF_OK;
 }
