@@ -53,6 +53,33 @@ CNNMEM_API int cnnmem_transform(const float *src, float *dst, int N, int C, int 
                      int src_layout, int dst_layout, void *hip_stream);
 
 /*
+ * General storage-order change.  A 4-D tensor can be stored in 24 orders
+ * (Section I); besides NCHW and CHWN the paper names HWCN (Section IV.A) and the
+ * NHWC order of the libraries it compares with.  `dims` holds the four source
+ * extents, slowest axis first; destination axis i is source axis perm[i], so the
+ * destination extents are dims[perm[0]], ..., dims[perm[3]]
+ * (dst[i0][i1][i2][i3] = src at the coordinates j with j[perm[k]] = ik).
+ * Words are moved bit for bit.
+ *   src, dst   : device, dims[0]*dims[1]*dims[2]*dims[3] floats each, not
+ *                overlapping, 4-byte aligned (16-byte alignment enables 128-bit
+ *                accesses).
+ *   dims, perm : host, four ints each, read before the call returns.
+ * Errors: INVALID_ARG for null pointers, extents <= 0 or a perm that is not a
+ * permutation of 0..3; UNSUPPORTED beyond 2^31 - 1 tiles or items in one launch.
+ */
+CNNMEM_API int cnnmem_permute(const float *src, float *dst, const int *dims, const int *perm, void *hip_stream);
+
+/*
+ * The same between two spelled layouts: `src_layout` and `dst_layout` are
+ * strings of the four letters N, C, H, W, each once, slowest axis first
+ * ("NCHW", "CHWN", "NHWC", "HWCN", ... all 24).  Equal layouts give a device copy.
+ *   src, dst : device, N*C*H*W floats each, not overlapping.
+ * Errors: INVALID_ARG for null pointers, extents <= 0 or a malformed layout string.
+ */
+CNNMEM_API int cnnmem_relayout(const float *src, float *dst, int N, int C, int H, int W,
+                               const char *src_layout, const char *dst_layout, void *hip_stream);
+
+/*
  * Pooled output extent (host only, no GPU work):
  *   Ho = floor((H + 2*ph - kh) / sh) + 1,  Wo likewise
  * -- the rule Fig. 8 of Section V.A implies (12 inputs, window 4, stride 2 give

@@ -22,6 +22,13 @@ CNNMEM_API unsigned cnnmem_debug_fastdiv(unsigned n, unsigned d);
  * Host only. */
 CNNMEM_API unsigned cnnmem_debug_xcd_tile(unsigned block, unsigned nblocks);
 
+/* Canonical form cnnmem_permute reduces a permutation to before it picks a
+ * kernel: axes of extent 1 dropped, source axes that stay neighbours in the
+ * destination merged.  Writes the rank (0..4), the merged source extents and the
+ * permutation over them; returns 0, or 1 for invalid arguments.  Host only. */
+CNNMEM_API int cnnmem_debug_canonical_permutation(const int *dims, const int *perm, int *rank,
+                                                  long long *canonical_dims, int *canonical_perm);
+
 #ifdef __cplusplus
 }
 #endif

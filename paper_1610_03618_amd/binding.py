@@ -52,6 +52,13 @@ def library() -> ctypes.CDLL:
         lib = ctypes.CDLL(_LIB_PATH)
         i, p = ctypes.c_int, ctypes.c_void_p
         lib.cnnmem_transform.argtypes = [p, p, i, i, i, i, i, i, p]
+        lib.cnnmem_permute.argtypes = [p, p, ctypes.POINTER(i), ctypes.POINTER(i), p]
+        lib.cnnmem_permute.restype = i
+        lib.cnnmem_relayout.argtypes = [p, p, i, i, i, i, ctypes.c_char_p, ctypes.c_char_p, p]
+        lib.cnnmem_relayout.restype = i
+        lib.cnnmem_debug_canonical_permutation.argtypes = [ctypes.POINTER(i), ctypes.POINTER(i), ctypes.POINTER(i),
+                                                           ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(i)]
+        lib.cnnmem_debug_canonical_permutation.restype = i
         lib.cnnmem_pool_out_dims.argtypes = [i] * 8 + [ctypes.POINTER(i)] * 2
         lib.cnnmem_pool.argtypes = [p, p] + [i] * 12 + [p]
         lib.cnnmem_pool_tuned.argtypes = [p, p] + [i] * 12 + [ctypes.POINTER(PoolTuning), p]
@@ -102,6 +109,25 @@ def _stream(stream) -> Optional[int]:
 def cnnmem_transform(src, dst, N, C, H, W, src_layout, dst_layout, stream=None) -> int:
     return library().cnnmem_transform(_ptr(src), _ptr(dst), N, C, H, W, src_layout, dst_layout,
                                       _stream(stream))
+
+
+def cnnmem_permute(src, dst, dims, perm, stream=None) -> int:
+    return library().cnnmem_permute(_ptr(src), _ptr(dst), (ctypes.c_int * 4)(*dims), (ctypes.c_int * 4)(*perm),
+                                    _stream(stream))
+
+
+def cnnmem_relayout(src, dst, N, C, H, W, src_layout: str, dst_layout: str, stream=None) -> int:
+    return library().cnnmem_relayout(_ptr(src), _ptr(dst), N, C, H, W, src_layout.encode(), dst_layout.encode(),
+                                     _stream(stream))
+
+
+def cnnmem_debug_canonical_permutation(dims, perm):
+    """(status, rank, merged source extents, permutation over them): host-only debug hook."""
+    rank = ctypes.c_int(0)
+    cd, cp = (ctypes.c_longlong * 4)(), (ctypes.c_int * 4)()
+    st = library().cnnmem_debug_canonical_permutation((ctypes.c_int * 4)(*dims), (ctypes.c_int * 4)(*perm),
+                                                      ctypes.byref(rank), cd, cp)
+    return st, rank.value, list(cd)[:rank.value], list(cp)[:rank.value]
 
 
 def cnnmem_pool_out_dims(H, W, kh, kw, sh, sw, ph, pw) -> Tuple[int, int, int]:
@@ -168,6 +194,26 @@ def transform(src: torch.Tensor, N, C, H, W, src_layout, dst_layout, out=None, s
     st = cnnmem_transform(src, out, N, C, H, W, src_layout, dst_layout, stream)
     if st:
         raise CnnmemError(st, "cnnmem_transform")
+    return out
+
+
+def permute(src: torch.Tensor, dims, perm, out=None, stream=None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty(tuple(dims[a] for a in perm), dtype=torch.float32, device=src.device)
+    st = cnnmem_permute(src, out, dims, perm, stream)
+    if st:
+        raise CnnmemError(st, "cnnmem_permute")
+    return out
+
+
+def relayout(src: torch.Tensor, N, C, H, W, src_layout: str, dst_layout: str, out=None, stream=None) -> torch.Tensor:
+    if out is None:
+        ext = dict(N=N, C=C, H=H, W=W)
+        shape = tuple(ext.get(l, 0) for l in dst_layout) if len(dst_layout) == 4 else (N * C * H * W,)
+        out = torch.empty(shape if all(shape) else (N * C * H * W,), dtype=torch.float32, device=src.device)
+    st = cnnmem_relayout(src, out, N, C, H, W, src_layout, dst_layout, stream)
+    if st:
+        raise CnnmemError(st, "cnnmem_relayout")
     return out
 
 

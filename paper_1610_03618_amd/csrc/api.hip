@@ -40,6 +40,48 @@ int cnnmem_transform(const float* src, float* dst, int N, int C, int H, int W, i
     return launch_transpose2d(src, dst, M, N, st);
 }
 
+int cnnmem_permute(const float* src, float* dst, const int* dims, const int* perm, void* hip_stream) {
+    if (!src || !dst || !dims || !perm) return CNNMEM_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 3u) return CNNMEM_ERR_INVALID_ARG;
+    bool seen[4] = {false, false, false, false};
+    long long total = 1;
+    const long long limit = 1LL << 46;
+    for (int i = 0; i < 4; ++i) {
+        if (dims[i] <= 0 || perm[i] < 0 || perm[i] > 3 || seen[perm[i]]) return CNNMEM_ERR_INVALID_ARG;
+        seen[perm[i]] = true;
+        if (total > limit / dims[i]) return CNNMEM_ERR_UNSUPPORTED;
+        total *= dims[i];
+    }
+    return launch_permute(src, dst, dims, perm, static_cast<hipStream_t>(hip_stream));
+}
+
+int cnnmem_relayout(const float* src, float* dst, int N, int C, int H, int W, const char* src_layout,
+                    const char* dst_layout, void* hip_stream) {
+    if (!src || !dst || N <= 0 || C <= 0 || H <= 0 || W <= 0 || !src_layout || !dst_layout)
+        return CNNMEM_ERR_INVALID_ARG;
+    // a layout is the four letters N, C, H, W, each once, slowest axis first
+    auto letter = [](char c) { return c == 'N' ? 0 : c == 'C' ? 1 : c == 'H' ? 2 : c == 'W' ? 3 : -1; };
+    const int extent[4] = {N, C, H, W};
+    int where_in_src[4] = {-1, -1, -1, -1};                    // letter -> axis of the source
+    int dims[4], perm[4];
+    for (int i = 0; i < 4; ++i) {
+        const int l = src_layout[i] ? letter(src_layout[i]) : -1;
+        if (l < 0 || where_in_src[l] >= 0) return CNNMEM_ERR_INVALID_ARG;
+        where_in_src[l] = i;
+        dims[i] = extent[l];
+    }
+    if (src_layout[4] != 0) return CNNMEM_ERR_INVALID_ARG;
+    bool used[4] = {false, false, false, false};
+    for (int i = 0; i < 4; ++i) {
+        const int l = dst_layout[i] ? letter(dst_layout[i]) : -1;
+        if (l < 0 || used[l]) return CNNMEM_ERR_INVALID_ARG;
+        used[l] = true;
+        perm[i] = where_in_src[l];
+    }
+    if (dst_layout[4] != 0) return CNNMEM_ERR_INVALID_ARG;
+    return cnnmem_permute(src, dst, dims, perm, hip_stream);
+}
+
 int cnnmem_pool_out_dims(int H, int W, int kh, int kw, int sh, int sw, int ph, int pw, int* Ho, int* Wo) {
     if (!Ho || !Wo || !window_ok(H, W, kh, kw, sh, sw, ph, pw)) return CNNMEM_ERR_INVALID_ARG;
     *Ho = pooled_extent(H, kh, sh, ph);
@@ -151,6 +193,18 @@ int cnnmem_version(void) { return 100; }   // 0.1.0
 
 unsigned cnnmem_debug_fastdiv(unsigned n, unsigned d) {
     return fd_div(n, make_fastdiv(d));
+}
+
+int cnnmem_debug_canonical_permutation(const int* dims, const int* perm, int* rank, long long* canonical_dims,
+                                       int* canonical_perm) {
+    if (!dims || !perm || !rank || !canonical_dims || !canonical_perm) return 1;
+    bool seen[4] = {false, false, false, false};
+    for (int i = 0; i < 4; ++i) {
+        if (dims[i] <= 0 || perm[i] < 0 || perm[i] > 3 || seen[perm[i]]) return 1;
+        seen[perm[i]] = true;
+    }
+    canonical_permutation(dims, perm, rank, canonical_dims, canonical_perm);
+    return 0;
 }
 
 unsigned cnnmem_debug_xcd_tile(unsigned block, unsigned nblocks) {

@@ -121,6 +121,10 @@ __device__ __forceinline__ void st1_stream(float* p, float a) {
 // ---- launchers implemented in the .hip files (host side, C++ linkage, hidden) ----
 int launch_transpose2d(const float* src, float* dst, long long R, long long S, hipStream_t st);
 int launch_copy(const float* src, float* dst, long long n, hipStream_t st);
+// General 4-D axis permutation: dims = source extents (slowest first), destination axis i = source axis perm[i].
+int launch_permute(const float* src, float* dst, const int* dims, const int* perm, hipStream_t st);
+// Canonical form of a permutation: extent-1 axes dropped, axes that stay neighbours merged (host only).
+void canonical_permutation(const int* dims, const int* perm, int* rank, long long* cdims, int* cperm);
 
 struct PoolGeom {
     int N, C, H, W, Ho, Wo;
