@@ -95,6 +95,25 @@ __device__ __forceinline__ void st4_stream(float* p, const float4& a) {
     *reinterpret_cast<v4f_t*>(p) = v;
 #endif
 }
+// 128-bit accesses at any 4-byte aligned address (gfx950 global memory accepts dword-aligned
+// multi-dword accesses; the type's alignment tells the compiler, which picks the instruction).
+typedef v4f_t v4f_unaligned_t __attribute__((aligned(4)));
+__device__ __forceinline__ float4 ld4u_stream(const float* p) {
+#if CNNMEM_STREAM_NT
+    const v4f_unaligned_t v = __builtin_nontemporal_load(reinterpret_cast<const v4f_unaligned_t*>(p));
+#else
+    const v4f_unaligned_t v = *reinterpret_cast<const v4f_unaligned_t*>(p);
+#endif
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st4u_stream(float* p, const float4& a) {
+    const v4f_unaligned_t v = {a.x, a.y, a.z, a.w};
+#if CNNMEM_STREAM_NT
+    __builtin_nontemporal_store(v, reinterpret_cast<v4f_unaligned_t*>(p));
+#else
+    *reinterpret_cast<v4f_unaligned_t*>(p) = v;
+#endif
+}
 __device__ __forceinline__ void st2_stream(float* p, float a, float b) {
     const v2f_t v = {a, b};
 #if CNNMEM_STREAM_NT
@@ -121,6 +140,7 @@ __device__ __forceinline__ void st1_stream(float* p, float a) {
 // ---- launchers implemented in the .hip files (host side, C++ linkage, hidden) ----
 int launch_transpose2d(const float* src, float* dst, long long R, long long S, hipStream_t st);
 int launch_copy(const float* src, float* dst, long long n, hipStream_t st);
+int launch_transpose2d_any(const float* src, float* dst, long long R, long long S, hipStream_t st);
 // General 4-D axis permutation: dims = source extents (slowest first), destination axis i = source axis perm[i].
 int launch_permute(const float* src, float* dst, const int* dims, const int* perm, hipStream_t st);
 // Canonical form of a permutation: extent-1 axes dropped, axes that stay neighbours merged (host only).

@@ -15,8 +15,8 @@
 //                                  add an offset on both sides.
 //
 // The tiled kernel is the strided, batched form of the 2-D transpose: global
-// accesses run along the fastest axis of the side they touch (128-bit where
-// extents and alignment allow, else dwords, independently per side), a tile is
+// accesses run along the fastest axis of the side they touch, 128 bits per lane
+// at any 4-byte alignment (rows of odd length start at every phase), a tile is
 // turned through LDS, all loads are unconditional from clamped addresses.
 #include "common.hpp"
 
@@ -32,6 +32,7 @@ struct TilePlan {
     long long sb0, sb1;         // source strides of the batch axes
     long long db0, db1;         // destination strides of the batch axes
     uint32_t tiles_s, tiles_plane;
+    int xcd_order;              // neighbouring tiles on one XCD (they share partly written lines)
 };
 
 template <int TS>
@@ -39,22 +40,25 @@ __device__ __forceinline__ int lds_row(int s_local) {
     return (s_local & 3) * (TS / 4) + (s_local >> 2);
 }
 
-// TR x TS tile, 256 lanes.  VL / VS: 128-bit accesses on the load / store side.
-// LDS holds the tile in destination order: row s (swizzled as in the 2-D kernel),
-// pitch TR + 4 floats.
-template <int TR, int TS, bool VL, bool VS>
-__global__ __launch_bounds__(kThreads) void permute_tile_kernel(
+// TR x TS tile, 256 lanes.  Both sides move 128 bits per lane along their own
+// fastest axis at whatever 4-byte alignment the rows happen to have (rows of odd
+// length start at every phase); only a source narrower than four words (LV =
+// false) is read word by word.  LDS holds the tile in destination order: row s
+// (swizzled as in the 2-D kernel), pitch TR + 4 floats.
+template <int TR, int TS, int THREADS, bool LV>
+__global__ __launch_bounds__(THREADS) void permute_tile_kernel(
     const float* __restrict__ src, float* __restrict__ dst, TilePlan p, FastDiv d_plane, FastDiv d_tiles_s,
     FastDiv d_nb1) {
     static_assert(TR % 4 == 0 && TS % 4 == 0, "tile sides are multiples of 4");
-    static_assert((TR * TS / 4) % kThreads == 0, "whole number of float4 per lane");
+    static_assert((TR * TS / 4) % THREADS == 0, "whole number of float4 per lane");
     constexpr int P = TR + 4;
     constexpr int NBR = TR / 4;
-    constexpr int WORDS = TR * TS / kThreads;           // dwords per lane
-    __shared__ __attribute__((aligned(16))) float tile[TS * P];
+    constexpr int WORDS = TR * TS / THREADS;            // dwords per lane
+    __shared__ __attribute__((aligned(16))) float tile[(TS + 1) * P];   // one spare row, never read
 
-    const uint32_t batch = fd_div(blockIdx.x, d_plane);
-    const uint32_t in_plane = blockIdx.x - batch * p.tiles_plane;
+    const uint32_t tile_id = p.xcd_order ? xcd_contiguous_tile(blockIdx.x, gridDim.x) : blockIdx.x;
+    const uint32_t batch = fd_div(tile_id, d_plane);
+    const uint32_t in_plane = tile_id - batch * p.tiles_plane;
     const uint32_t tr = fd_div(in_plane, d_tiles_s);
     const uint32_t ts = in_plane - tr * p.tiles_s;
     const uint32_t b0 = fd_div(batch, d_nb1);
@@ -64,35 +68,41 @@ __global__ __launch_bounds__(kThreads) void permute_tile_kernel(
     dst += (size_t)b0 * (size_t)p.db0 + (size_t)b1 * (size_t)p.db1;
     const int tid = threadIdx.x;
 
-    if (VL) {
-        // 128-bit loads along s, one source row per load; the four words of a load belong to
-        // four destination rows and are scattered into the tile with dword writes
+    if (LV) {
+        // One source row per load.  A load that would run past the end of the row starts at S - 4
+        // instead (S >= 4 here) and its words are filed under the columns they really are; rows
+        // past R re-read the last row and land in tile rows that are never written out.  All
+        // loads are unconditional, hence in flight together.
         constexpr int NC4 = TS / 4;
         float4 v[WORDS / 4];
+        int col[WORDS / 4];                             // tile column of v[it].x; may be -3..-1 in the last tile
 #pragma unroll
         for (int it = 0; it < WORDS / 4; ++it) {
-            const int f = tid + it * kThreads;
+            const int f = tid + it * THREADS;
             const int c4 = f % NC4, rl = f / NC4;
             long long r = r0 + rl, s = s0 + 4 * c4;
-            r = r < p.R ? r : p.R - 1;              // edge tiles re-read valid words that are never written out
-            s = s < p.S ? s : p.S - 4;              // S is a multiple of 4 on this path
-            v[it] = ld4_stream(src + (size_t)r * (size_t)p.ss_r + (size_t)s);
+            r = r < p.R ? r : p.R - 1;
+            s = s + 4 <= p.S ? s : p.S - 4;
+            col[it] = (int)(s - s0);
+            v[it] = ld4u_stream(src + (size_t)r * (size_t)p.ss_r + (size_t)s);
         }
 #pragma unroll
         for (int it = 0; it < WORDS / 4; ++it) {
-            const int f = tid + it * kThreads;
-            const int c4 = f % NC4, rl = f / NC4;
-            tile[lds_row<TS>(4 * c4 + 0) * P + rl] = v[it].x;
-            tile[lds_row<TS>(4 * c4 + 1) * P + rl] = v[it].y;
-            tile[lds_row<TS>(4 * c4 + 2) * P + rl] = v[it].z;
-            tile[lds_row<TS>(4 * c4 + 3) * P + rl] = v[it].w;
+            const int rl = (tid + it * THREADS) / NC4;
+            const int c = col[it];
+            const float w[4] = {v[it].x, v[it].y, v[it].z, v[it].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {               // words left of the tile go to the spare row
+                const int row = c + j >= 0 ? lds_row<TS>(c + j) : TS;
+                tile[row * P + rl] = w[j];
+            }
         }
     } else {
-        // dword loads, consecutive lanes along s; out-of-range lanes re-read the last valid word
+        // fewer than four words per source row: dword loads, lanes along s, clamped to valid words
         float v[WORDS];
 #pragma unroll
         for (int it = 0; it < WORDS; ++it) {
-            const int e = tid + it * kThreads;
+            const int e = tid + it * THREADS;
             const int sl = e % TS, rl = e / TS;
             long long r = r0 + rl, s = s0 + sl;
             r = r < p.R ? r : p.R - 1;
@@ -101,61 +111,72 @@ __global__ __launch_bounds__(kThreads) void permute_tile_kernel(
         }
 #pragma unroll
         for (int it = 0; it < WORDS; ++it) {
-            const int e = tid + it * kThreads;
+            const int e = tid + it * THREADS;
             const int sl = e % TS, rl = e / TS;
             tile[lds_row<TS>(sl) * P + rl] = v[it];
         }
     }
     __syncthreads();
-    if (VS) {
 #pragma unroll
-        for (int it = 0; it < (TS * NBR) / kThreads; ++it) {
-            const int f = tid + it * kThreads;
-            const int br = f % NBR, sl = f / NBR;
-            const float4 o = *reinterpret_cast<const float4*>(tile + lds_row<TS>(sl) * P + 4 * br);
-            const long long s = s0 + sl, r = r0 + 4 * br;
-            if (s < p.S && r < p.R) st4_stream(dst + (size_t)s * (size_t)p.ds_s + (size_t)r, o);
-        }
-    } else {
-#pragma unroll
-        for (int it = 0; it < WORDS; ++it) {
-            const int e = tid + it * kThreads;
-            const int rl = e % TR, sl = e / TR;
-            const long long s = s0 + sl, r = r0 + rl;
-            if (s < p.S && r < p.R) st1_stream(dst + (size_t)s * (size_t)p.ds_s + (size_t)r, tile[lds_row<TS>(sl) * P + rl]);
+    for (int it = 0; it < (TS * NBR) / THREADS; ++it) {
+        const int f = tid + it * THREADS;
+        const int br = f % NBR, sl = f / NBR;
+        const float4 o = *reinterpret_cast<const float4*>(tile + lds_row<TS>(sl) * P + 4 * br);
+        const long long s = s0 + sl, r = r0 + 4 * br;
+        if (s < p.S) {
+            float* q = dst + (size_t)s * (size_t)p.ds_s + (size_t)r;
+            if (r + 4 <= p.R) {
+                st4u_stream(q, o);
+            } else {                                    // ragged end of a destination row
+                if (r < p.R) st1_stream(q, o.x);
+                if (r + 1 < p.R) st1_stream(q + 1, o.y);
+                if (r + 2 < p.R) st1_stream(q + 2, o.z);
+            }
         }
     }
 }
 
 struct RowPlan {
     long long t0, t1, t2;       // source strides of the destination's outer axes (slowest first), in floats
-    uint32_t per_row;           // items (float4 or floats) per run of the fastest axis
-    uint32_t items;             // all items
+    uint32_t L;                 // extent of the fastest axis (the run length)
+    uint32_t total;             // all elements
 };
 
-// The fastest axis is the same on both sides: item i of the destination (a
-// float4 or a float of a run) comes from the run's place in the source.
-template <bool VEC>
-__global__ __launch_bounds__(kThreads) void permute_rows_kernel(
-    const float* __restrict__ src, float* __restrict__ dst, RowPlan p, FastDiv d_row, FastDiv d_e2, FastDiv d_e1) {
-    const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
-    if (i >= p.items) return;
-    const uint32_t run = fd_div(i, d_row);
-    const uint32_t in_run = i - run * p.per_row;
+__device__ __forceinline__ size_t run_source(uint32_t run, const RowPlan& p, const FastDiv& d_e2, const FastDiv& d_e1) {
     const uint32_t q = fd_div(run, d_e2);
     const uint32_t o2 = run - q * d_e2.d;
     const uint32_t o0 = fd_div(q, d_e1);
     const uint32_t o1 = q - o0 * d_e1.d;
-    const size_t from = (size_t)o0 * (size_t)p.t0 + (size_t)o1 * (size_t)p.t1 + (size_t)o2 * (size_t)p.t2;
-    if (VEC)
-        st4_stream(dst + 4 * (size_t)i, ld4_stream(src + from + 4 * (size_t)in_run));
-    else
-        st1_stream(dst + (size_t)i, ld1_stream(src + from + in_run));
+    return (size_t)o0 * (size_t)p.t0 + (size_t)o1 * (size_t)p.t1 + (size_t)o2 * (size_t)p.t2;
 }
 
-template <int TR, int TS>
-int launch_tile(const float* src, float* dst, const TilePlan& p, long long nb0, long long nb1, bool vl, bool vs,
-                hipStream_t st) {
+// The fastest axis is the same on both sides: the destination is a sequence of
+// runs of L words, each contiguous in the source too.  A lane owns four
+// consecutive destination words (one 128-bit store; DA = the destination is
+// 16-byte aligned); when they lie in one run they are one 128-bit load at the
+// run's own alignment, else (run boundary inside the four, or the end of the
+// tensor) they are fetched one by one.
+template <bool DA>
+__global__ __launch_bounds__(kThreads) void permute_rows_kernel(
+    const float* __restrict__ src, float* __restrict__ dst, RowPlan p, FastDiv d_L, FastDiv d_e2, FastDiv d_e1) {
+    const uint32_t e = 4u * (blockIdx.x * kThreads + threadIdx.x);
+    if (e >= p.total) return;
+    const uint32_t run = fd_div(e, d_L);
+    const uint32_t in_run = e - run * p.L;
+    if (in_run + 4 <= p.L) {                            // e + 4 <= total follows
+        const float4 v = ld4u_stream(src + run_source(run, p, d_e2, d_e1) + in_run);
+        if (DA) st4_stream(dst + e, v);
+        else st4u_stream(dst + e, v);
+        return;
+    }
+    for (uint32_t j = 0; j < 4 && e + j < p.total; ++j) {
+        const uint32_t rj = fd_div(e + j, d_L);
+        dst[e + j] = src[run_source(rj, p, d_e2, d_e1) + (e + j - rj * p.L)];
+    }
+}
+
+template <int TR, int TS, int THREADS = kThreads>
+int launch_tile(const float* src, float* dst, const TilePlan& p, long long nb0, long long nb1, hipStream_t st) {
     TilePlan q = p;
     const long long tiles_r = ceil_div64(p.R, TR), tiles_s = ceil_div64(p.S, TS);
     const long long plane = tiles_r * tiles_s;
@@ -163,25 +184,63 @@ int launch_tile(const float* src, float* dst, const TilePlan& p, long long nb0, 
         return CNNMEM_ERR_UNSUPPORTED;
     q.tiles_s = (uint32_t)tiles_s;
     q.tiles_plane = (uint32_t)plane;
+    q.xcd_order = env_int("CNNMEM_PERMUTE_XCD", p.xcd_order);
     const FastDiv d_plane = make_fastdiv((uint32_t)plane), d_tiles_s = make_fastdiv((uint32_t)tiles_s),
                   d_nb1 = make_fastdiv((uint32_t)nb1);
-    const dim3 grid((unsigned)(plane * nb0 * nb1)), block(kThreads);
-    if (vl && vs)
-        hipLaunchKernelGGL((permute_tile_kernel<TR, TS, true, true>), grid, block, 0, st, src, dst, q, d_plane,
-                           d_tiles_s, d_nb1);
-    else if (vl)
-        hipLaunchKernelGGL((permute_tile_kernel<TR, TS, true, false>), grid, block, 0, st, src, dst, q, d_plane,
-                           d_tiles_s, d_nb1);
-    else if (vs)
-        hipLaunchKernelGGL((permute_tile_kernel<TR, TS, false, true>), grid, block, 0, st, src, dst, q, d_plane,
+    const dim3 grid((unsigned)(plane * nb0 * nb1)), block(THREADS);
+    if (p.S >= 4)
+        hipLaunchKernelGGL((permute_tile_kernel<TR, TS, THREADS, true>), grid, block, 0, st, src, dst, q, d_plane,
                            d_tiles_s, d_nb1);
     else
-        hipLaunchKernelGGL((permute_tile_kernel<TR, TS, false, false>), grid, block, 0, st, src, dst, q, d_plane,
+        hipLaunchKernelGGL((permute_tile_kernel<TR, TS, THREADS, false>), grid, block, 0, st, src, dst, q, d_plane,
                            d_tiles_s, d_nb1);
     return launch_status();
 }
 
+int launch_tile_shape(const float* src, float* dst, const TilePlan& p, long long nb0, long long nb1, hipStream_t st) {
+    // Tile shape.  Rows whose length is not a whole number of 128-byte lines start at every
+    // phase, so each segment a tile reads or writes ends in partly used lines: the side with
+    // such rows gets the long side of the tile (measured on MI355X, 128x96x55x55:
+    // NHWC -> NCHW 38 % of peak with 64 x 64, 63 % with 256 x 32).  A short side stretches the
+    // tile along the other one.  CNNMEM_PERMUTE_TILE forces a shape for A/B profiling.
+    int shape = env_int("CNNMEM_PERMUTE_TILE", -1);
+    if (shape < 0) {
+        const bool ragged_dst = p.R % 32 != 0, ragged_src = p.S % 32 != 0;
+        if (p.R <= 16) shape = 3;
+        else if (p.R <= 32) shape = ragged_src && p.S >= 256 ? 8 : 1;
+        else if (p.S <= 16) shape = 4;
+        else if (p.S <= 32) shape = ragged_dst && p.R >= 256 ? 11 : 2;
+        else if (ragged_dst && !ragged_src && p.R >= 256) shape = 11;
+        else if (ragged_src && !ragged_dst && p.S >= 256) shape = 8;
+        else shape = 0;
+    }
+    switch (shape) {
+        case 1: return launch_tile<32, 128>(src, dst, p, nb0, nb1, st);
+        case 2: return launch_tile<128, 32>(src, dst, p, nb0, nb1, st);
+        case 3: return launch_tile<16, 256>(src, dst, p, nb0, nb1, st);
+        case 4: return launch_tile<256, 16>(src, dst, p, nb0, nb1, st);
+        case 5: return launch_tile<128, 64, 512>(src, dst, p, nb0, nb1, st);
+        case 6: return launch_tile<64, 128, 512>(src, dst, p, nb0, nb1, st);
+        case 7: return launch_tile<256, 32, 512>(src, dst, p, nb0, nb1, st);
+        case 8: return launch_tile<32, 256, 512>(src, dst, p, nb0, nb1, st);
+        case 9: return launch_tile<128, 64, 256>(src, dst, p, nb0, nb1, st);
+        case 10: return launch_tile<64, 128, 256>(src, dst, p, nb0, nb1, st);
+        case 11: return launch_tile<256, 32, 256>(src, dst, p, nb0, nb1, st);
+        case 12: return launch_tile<32, 256, 256>(src, dst, p, nb0, nb1, st);
+        default: return launch_tile<64, 64>(src, dst, p, nb0, nb1, st);
+    }
+}
+
 }  // namespace
+
+// src[R][S] -> dst[S][R] for any R, S and any 4-byte alignment (the 2-D transpose's general path).
+int launch_transpose2d_any(const float* src, float* dst, long long R, long long S, hipStream_t st) {
+    TilePlan p;
+    p.R = R; p.S = S; p.ss_r = S; p.ds_s = R;
+    p.sb0 = p.sb1 = p.db0 = p.db1 = 0;
+    p.xcd_order = 0;
+    return launch_tile_shape(src, dst, p, 1, 1, st);
+}
 
 void canonical_permutation(const int* dims, const int* perm, int* rank, long long* cdims, int* cperm) {
     // source axes of extent > 1, in destination order
@@ -234,15 +293,10 @@ int launch_permute(const float* src, float* dst, const int* dims, const int* per
     for (int i = 0; i < k; ++i) e[i] = d[pm[i]];
     ds[k - 1] = 1;
     for (int i = k - 2; i >= 0; --i) ds[i] = ds[i + 1] * e[i + 1];
-    const bool a16 = aligned16(src) && aligned16(dst);
-
     if (pm[k - 1] == k - 1) {
         // the fastest axis stays: gather its runs
         const long long L = d[k - 1];
-        const bool vec = a16 && L % 4 == 0;
-        const long long per_row = vec ? L / 4 : L;
-        const long long runs = total / L;
-        if (per_row * runs >= 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
+        if (total >= 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
         RowPlan p;
         // outer destination axes, padded at the slow end to three
         long long oe[3] = {1, 1, 1}, ot[3] = {0, 0, 0};
@@ -251,15 +305,15 @@ int launch_permute(const float* src, float* dst, const int* dims, const int* per
             ot[3 - (k - 1) + i] = ss[pm[i]];
         }
         p.t0 = ot[0]; p.t1 = ot[1]; p.t2 = ot[2];
-        p.per_row = (uint32_t)per_row;
-        p.items = (uint32_t)(per_row * runs);
-        const FastDiv d_row = make_fastdiv((uint32_t)per_row), d_e2 = make_fastdiv((uint32_t)oe[2]),
+        p.L = (uint32_t)L;
+        p.total = (uint32_t)total;
+        const FastDiv d_L = make_fastdiv((uint32_t)L), d_e2 = make_fastdiv((uint32_t)oe[2]),
                       d_e1 = make_fastdiv((uint32_t)oe[1]);
-        const dim3 grid((unsigned)ceil_div64(p.items, kThreads)), block(kThreads);
-        if (vec)
-            hipLaunchKernelGGL((permute_rows_kernel<true>), grid, block, 0, st, src, dst, p, d_row, d_e2, d_e1);
+        const dim3 grid((unsigned)ceil_div64(ceil_div64(total, 4), kThreads)), block(kThreads);
+        if (aligned16(dst))
+            hipLaunchKernelGGL((permute_rows_kernel<true>), grid, block, 0, st, src, dst, p, d_L, d_e2, d_e1);
         else
-            hipLaunchKernelGGL((permute_rows_kernel<false>), grid, block, 0, st, src, dst, p, d_row, d_e2, d_e1);
+            hipLaunchKernelGGL((permute_rows_kernel<false>), grid, block, 0, st, src, dst, p, d_L, d_e2, d_e1);
         return launch_status();
     }
 
@@ -275,23 +329,20 @@ int launch_permute(const float* src, float* dst, const int* dims, const int* per
     p.ds_s = ds[pos_s];
     long long nb[2] = {1, 1};
     p.sb0 = p.sb1 = p.db0 = p.db1 = 0;
+    // When every batch axis is slower than both tile axes on both sides, each batch entry is a
+    // contiguous block and tiles run in plain order.  Otherwise a batch axis sits between the
+    // tile axes in memory (NCHW <-> HWCN: the channel axis), the segments of neighbouring
+    // tiles interleave, and keeping neighbours on one XCD measured 5-10 points better.
+    p.xcd_order = 0;
     int nbatch = 0;
     for (int i = 0; i < k; ++i) {                   // remaining axes, in destination order
         if (i == k - 1 || i == pos_s) continue;
+        if (i > pos_s || pm[i] > ar) p.xcd_order = 1;
         if (nbatch == 0 && k == 4) { nb[0] = e[i]; p.sb0 = ss[pm[i]]; p.db0 = ds[i]; }
         else { nb[1] = e[i]; p.sb1 = ss[pm[i]]; p.db1 = ds[i]; }
         ++nbatch;
     }
-    // every source stride is a multiple of S and every destination stride a multiple of R, so each side
-    // can use 128-bit accesses on its own as soon as its fastest extent is a multiple of 4
-    const bool vl = a16 && p.S % 4 == 0;
-    const bool vs = a16 && p.R % 4 == 0;
-    // tile shape: stretch along the longer side when the other is short
-    if (p.R <= 16) return launch_tile<16, 256>(src, dst, p, nb[0], nb[1], vl, vs, st);
-    if (p.R <= 32) return launch_tile<32, 128>(src, dst, p, nb[0], nb[1], vl, vs, st);
-    if (p.S <= 16) return launch_tile<256, 16>(src, dst, p, nb[0], nb[1], vl, vs, st);
-    if (p.S <= 32) return launch_tile<128, 32>(src, dst, p, nb[0], nb[1], vl, vs, st);
-    return launch_tile<64, 64>(src, dst, p, nb[0], nb[1], vl, vs, st);
+    return launch_tile_shape(src, dst, p, nb[0], nb[1], st);
 }
 
 }  // namespace cnnmem

@@ -237,6 +237,9 @@ int launch_transpose2d(const float* src, float* dst, long long R, long long S, h
             default: return launch_vec4<64, 64>(src, dst, R, S, st);
         }
     }
+    // any R, S and any 4-byte alignment: the strided tile kernel of the general permutation,
+    // 128-bit accesses at dword alignment (CNNMEM_TRANSFORM_TILE=100 forces the dword kernel for A/B runs)
+    if (env_int("CNNMEM_TRANSFORM_TILE", -1) != 100) return launch_transpose2d_any(src, dst, R, S, st);
     const long long tiles_r = ceil_div64(R, 64), tiles_s = ceil_div64(S, 64);
     if (tiles_r * tiles_s > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(transpose_scalar_kernel, dim3((unsigned)(tiles_r * tiles_s)), dim3(kThreads), 0, st,
