@@ -136,6 +136,112 @@ __global__ __launch_bounds__(THREADS) void permute_tile_kernel(
     }
 }
 
+// ---- thin planes: one tile axis has at most 8 entries (RGB images between NCHW and NHWC) ----
+//
+// With T <= 8 rows on one side the square tiles above would idle most lanes.  Here a
+// workgroup takes all T entries of the thin axis and kThin entries of the long one; on the
+// side where the thin axis is the fastest, that block is one contiguous piece of memory
+// (the launcher checks the stride) and is moved as a linear 128-bit stream.
+
+constexpr int kThin = 1024;     // entries of the long axis per workgroup
+
+// Destination rows are thin: dst[s][r], r < T, rows back to back (ds_s == T).
+template <int T>
+__global__ __launch_bounds__(kThreads) void permute_thin_dst_kernel(
+    const float* __restrict__ src, float* __restrict__ dst, TilePlan p, FastDiv d_plane, FastDiv d_nb1) {
+    __shared__ __attribute__((aligned(16))) float tile[kThin * T + 4 * T];   // + room for words left of the tile
+    const uint32_t batch = fd_div(blockIdx.x, d_plane);
+    const uint32_t ts = blockIdx.x - batch * p.tiles_plane;
+    const uint32_t b0 = fd_div(batch, d_nb1);
+    const uint32_t b1 = batch - b0 * d_nb1.d;
+    src += (size_t)b0 * (size_t)p.sb0 + (size_t)b1 * (size_t)p.sb1;
+    dst += (size_t)b0 * (size_t)p.db0 + (size_t)b1 * (size_t)p.db1;
+    const long long s0 = (long long)ts * kThin;
+    const int ns = (int)(p.S - s0 < kThin ? p.S - s0 : kThin);
+    const int tid = threadIdx.x;
+
+    // T source rows of kThin words: one float4 per lane per row, clamped like the tile kernel
+    long long s = s0 + 4 * tid;
+    s = s + 4 <= p.S ? s : p.S - 4;                     // S >= 4 (launcher)
+    const int col = (int)(s - s0);                      // -3 .. kThin - 4
+    float4 v[T];
+#pragma unroll
+    for (int r = 0; r < T; ++r) v[r] = ld4u_stream(src + (size_t)r * (size_t)p.ss_r + (size_t)s);
+    float* t0 = tile + 4 * T;                           // tile[(c) * T + r], c may be -3..-1
+#pragma unroll
+    for (int r = 0; r < T; ++r) {
+        t0[(col + 0) * T + r] = v[r].x;
+        t0[(col + 1) * T + r] = v[r].y;
+        t0[(col + 2) * T + r] = v[r].z;
+        t0[(col + 3) * T + r] = v[r].w;
+    }
+    __syncthreads();
+    // the block's ns * T destination words are contiguous
+    float* out = dst + (size_t)s0 * T;
+    const int total = ns * T;
+    for (int i = 4 * tid; i < total; i += 4 * kThreads) {
+        if (i + 4 <= total) {
+            st4u_stream(out + i, make_float4(t0[i], t0[i + 1], t0[i + 2], t0[i + 3]));
+        } else {
+            for (int j = i; j < total; ++j) st1_stream(out + j, t0[j]);
+        }
+    }
+}
+
+// Source rows are thin: src[r][s], s < T, rows back to back (ss_r == T).
+template <int T>
+__global__ __launch_bounds__(kThreads) void permute_thin_src_kernel(
+    const float* __restrict__ src, float* __restrict__ dst, TilePlan p, FastDiv d_plane, FastDiv d_nb1) {
+    __shared__ __attribute__((aligned(16))) float tile[kThin * T + 4];
+    const uint32_t batch = fd_div(blockIdx.x, d_plane);
+    const uint32_t tr = blockIdx.x - batch * p.tiles_plane;
+    const uint32_t b0 = fd_div(batch, d_nb1);
+    const uint32_t b1 = batch - b0 * d_nb1.d;
+    src += (size_t)b0 * (size_t)p.sb0 + (size_t)b1 * (size_t)p.sb1;
+    dst += (size_t)b0 * (size_t)p.db0 + (size_t)b1 * (size_t)p.db1;
+    const long long r0 = (long long)tr * kThin;
+    const int nr = (int)(p.R - r0 < kThin ? p.R - r0 : kThin);
+    const int tid = threadIdx.x;
+
+    // the block's nr * T source words are contiguous: linear float4 stream, the last one shifted
+    // back so that it ends with the block (the whole plane holds R * T >= 4 words: launcher)
+    const float* in = src + (size_t)r0 * T;
+    const int total = nr * T;
+    const long long before = r0 * T;                    // words of this plane in front of the block
+    float4 v[T];
+    int at[T];
+#pragma unroll
+    for (int k = 0; k < T; ++k) {
+        int i = 4 * (tid + k * kThreads);
+        i = i + 4 <= total ? i : total - 4;
+        if ((long long)i + before < 0) i = (int)-before;   // tiny first block: start at the plane's first word
+        at[k] = i;
+        v[k] = ld4u_stream(in + i);
+    }
+    float* t0 = tile + 4;
+#pragma unroll
+    for (int k = 0; k < T; ++k) {
+        // words in front of the block (at[k] < 0) fall into the 4 spare words before t0
+        t0[at[k] + 0] = v[k].x;
+        t0[at[k] + 1] = v[k].y;
+        t0[at[k] + 2] = v[k].z;
+        t0[at[k] + 3] = v[k].w;
+    }
+    __syncthreads();
+    // T destination rows of nr words
+#pragma unroll
+    for (int sidx = 0; sidx < T; ++sidx) {
+        const int r = 4 * tid;
+        float* q = dst + (size_t)sidx * (size_t)p.ds_s + (size_t)(r0 + r);
+        if (r + 4 <= nr) {
+            st4u_stream(q, make_float4(t0[(r + 0) * T + sidx], t0[(r + 1) * T + sidx], t0[(r + 2) * T + sidx],
+                                       t0[(r + 3) * T + sidx]));
+        } else {
+            for (int j = r; j < nr; ++j) st1_stream(q + (j - r), t0[j * T + sidx]);
+        }
+    }
+}
+
 struct RowPlan {
     long long t0, t1, t2;       // source strides of the destination's outer axes (slowest first), in floats
     uint32_t L;                 // extent of the fastest axis (the run length)
@@ -197,7 +303,45 @@ int launch_tile(const float* src, float* dst, const TilePlan& p, long long nb0, 
     return launch_status();
 }
 
+template <int T>
+int launch_thin(bool thin_dst, const float* src, float* dst, const TilePlan& p, long long nb0, long long nb1,
+                hipStream_t st) {
+    TilePlan q = p;
+    const long long plane = ceil_div64(thin_dst ? p.S : p.R, kThin);
+    if (plane >= 0x7fffffffLL || nb0 * nb1 >= 0x7fffffffLL || plane * nb0 * nb1 >= 0x7fffffffLL)
+        return CNNMEM_ERR_UNSUPPORTED;
+    q.tiles_plane = (uint32_t)plane;
+    q.tiles_s = thin_dst ? (uint32_t)plane : 1;
+    const FastDiv d_plane = make_fastdiv((uint32_t)plane), d_nb1 = make_fastdiv((uint32_t)nb1);
+    const dim3 grid((unsigned)(plane * nb0 * nb1)), block(kThreads);
+    if (thin_dst)
+        hipLaunchKernelGGL((permute_thin_dst_kernel<T>), grid, block, 0, st, src, dst, q, d_plane, d_nb1);
+    else
+        hipLaunchKernelGGL((permute_thin_src_kernel<T>), grid, block, 0, st, src, dst, q, d_plane, d_nb1);
+    return launch_status();
+}
+
+int launch_thin_any(int T, bool thin_dst, const float* src, float* dst, const TilePlan& p, long long nb0,
+                    long long nb1, hipStream_t st) {
+    switch (T) {
+        case 2: return launch_thin<2>(thin_dst, src, dst, p, nb0, nb1, st);
+        case 3: return launch_thin<3>(thin_dst, src, dst, p, nb0, nb1, st);
+        case 4: return launch_thin<4>(thin_dst, src, dst, p, nb0, nb1, st);
+        case 5: return launch_thin<5>(thin_dst, src, dst, p, nb0, nb1, st);
+        case 6: return launch_thin<6>(thin_dst, src, dst, p, nb0, nb1, st);
+        case 7: return launch_thin<7>(thin_dst, src, dst, p, nb0, nb1, st);
+        default: return launch_thin<8>(thin_dst, src, dst, p, nb0, nb1, st);
+    }
+}
+
 int launch_tile_shape(const float* src, float* dst, const TilePlan& p, long long nb0, long long nb1, hipStream_t st) {
+    // thin planes (2..8 entries on one tile axis, contiguous on the side where that axis is fastest)
+    if (env_int("CNNMEM_PERMUTE_TILE", -1) < 0) {
+        if (p.R >= 2 && p.R <= 8 && p.ds_s == p.R && p.S >= 4)
+            return launch_thin_any((int)p.R, true, src, dst, p, nb0, nb1, st);
+        if (p.S >= 2 && p.S <= 8 && p.ss_r == p.S && p.R * p.S >= 4)
+            return launch_thin_any((int)p.S, false, src, dst, p, nb0, nb1, st);
+    }
     // Tile shape.  Rows whose length is not a whole number of 128-byte lines start at every
     // phase, so each segment a tile reads or writes ends in partly used lines: the side with
     // such rows gets the long side of the tile (measured on MI355X, 128x96x55x55:

@@ -116,3 +116,25 @@ def test_first_layer_rgb_tensor():
         want = oracle.relayout(x, N, C, H, W, src, dst)
         got = cm.relayout(torch.from_numpy(x).cuda(), N, C, H, W, src, dst).cpu().numpy()
         assert np.array_equal(bits(got), bits(want)), (src, dst)
+
+
+@pytest.mark.parametrize("T", [2, 3, 4, 5, 6, 7, 8])
+def test_thin_axes_both_directions(T):
+    """Two to eight feature maps: the thin-plane kernels, several blocks with a ragged last one."""
+    for (N, H, W) in [(2, 37, 61), (1, 50, 50), (3, 1, 1025), (2, 1, 3)]:
+        rng = np.random.default_rng(T * 100 + H)
+        canon = random_words(rng, (N, T, H, W))
+        d = torch.from_numpy(canon).cuda()
+        nhwc = cm.relayout(d, N, T, H, W, "NCHW", "NHWC")
+        assert np.array_equal(bits(nhwc.cpu().numpy()), bits(oracle.relayout(canon, N, T, H, W, "NCHW", "NHWC")))
+        back = cm.relayout(nhwc, N, T, H, W, "NHWC", "NCHW")
+        assert np.array_equal(bits(back.cpu().numpy()), bits(canon))
+        # thin batch: T images, N-fastest layouts
+        chwn = cm.relayout(d, N, T, H, W, "NCHW", "CHWN")
+        assert np.array_equal(bits(chwn.cpu().numpy()), bits(oracle.relayout(canon, N, T, H, W, "NCHW", "CHWN")))
+        x2 = random_words(rng, (T, 5, H, W))
+        d2 = torch.from_numpy(x2).cuda()
+        got = cm.relayout(d2, T, 5, H, W, "NCHW", "CHWN")
+        assert np.array_equal(bits(got.cpu().numpy()), bits(oracle.relayout(x2, T, 5, H, W, "NCHW", "CHWN")))
+        got = cm.relayout(got, T, 5, H, W, "CHWN", "NCHW")
+        assert np.array_equal(bits(got.cpu().numpy()), bits(x2))
