@@ -35,6 +35,8 @@ WORKLOADS = {
     "largest": "each kernel on its largest configured tensor (the headline run)",
     "table1": "every pooling and classifier layer of the paper's Table 1",
     "softmax_sweep": "softmax over batch size x categories (Fig. 13's range)",
+    "layouts": "changes between the named storage orders (NCHW, NHWC, CHWN, HWCN) on the config 2 tensor, a VGG "
+               "tensor and an RGB input batch (Section I, IV.A)",
     "layout_policy": "the three AlexNet pooling layers of config 3 under both layout policies: pool where the "
                      "data is (NCHW) against transform + pool in CHWN + transform back (Section IV.B, IV.D)",
 }
@@ -43,6 +45,7 @@ WORKLOAD_TEXT = {
                "max+avg pool 2x2/s2 on 64x64x224x224 in NCHW and CHWN (config 4), softmax 4096x21841 (config 5)",
     "table1": "Table 1 of the paper: max-pool PL1..PL10 in NCHW and CHWN, softmax CLASS1..CLASS5",
     "softmax_sweep": "softmax, batch 32..256 x categories 10..10000 (the range of Fig. 13)",
+    "layouts": "storage-order changes among NCHW / NHWC / CHWN / HWCN on 128x96x55x55, 64x64x112x112 and 64x3x224x224",
     "layout_policy": "config 3 (AlexNet, N=128) max-pool 3x3/s2 x3: NCHW in place vs NCHW->CHWN + pool + CHWN->NCHW",
 }
 
@@ -204,6 +207,29 @@ def build_softmax_sweep_ops(torch, cm, wl, rl, only):
         ps = [torch.empty_like(zs[0]) for _ in range(ns)]
         ops.append(Op(opname, "softmax", rl.softmax_bytes(n, c), n * c, "elements",
                       (lambda zs, ps, n, c: lambda i: cm.cnnmem_softmax(zs[i], ps[i], n, c))(zs, ps, n, c), ns))
+    torch.cuda.synchronize()
+    return ops, {}
+
+
+def build_layouts_ops(torch, cm, wl, rl, only):
+    """Changes between the storage orders the paper names, on three tensor shapes."""
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device="cuda").manual_seed(1615)
+    pairs = [("NCHW", "NHWC"), ("NHWC", "NCHW"), ("NCHW", "CHWN"), ("CHWN", "NCHW"), ("CHWN", "HWCN"),
+             ("HWCN", "CHWN"), ("NCHW", "HWCN"), ("HWCN", "NCHW")]
+    ops = []
+    for (N, C, H, W) in [(128, 96, 55, 55), (64, 64, 112, 112), (64, 3, 224, 224)]:
+        n = N * C * H * W
+        ns = _nsets_for(8 * n)
+        a = [torch.randn(n, device=dev, generator=gen) for _ in range(ns)]
+        b = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(ns)]
+        for (s_, d_) in pairs:
+            name = f"{N}x{C}x{H}x{W}:{s_}>{d_}"
+            if only and name not in only:
+                continue
+            ops.append(Op(name, "transform", rl.transform_bytes(N, C, H, W), n, "elements",
+                          (lambda a, b, N, C, H, W, s_, d_: lambda i: cm.cnnmem_relayout(a[i], b[i], N, C, H, W, s_, d_))(
+                              a, b, N, C, H, W, s_, d_), ns))
     torch.cuda.synchronize()
     return ops, {}
 
@@ -387,7 +413,7 @@ def main():
     torch.cuda.set_device(0)
     only = set(filter(None, args.only.split(",")))
     builders = {"largest": build_ops, "table1": build_table1_ops, "softmax_sweep": build_softmax_sweep_ops,
-                "layout_policy": build_layout_policy_ops}
+                "layout_policy": build_layout_policy_ops, "layouts": build_layouts_ops}
     ops, host_inputs = builders[args.workload](torch, cm, wl, rl, only)
     if args.workload != "largest":
         args.no_cpu_baseline = True                # the oracle baseline is reported for the headline workload
