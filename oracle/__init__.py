@@ -55,6 +55,16 @@ def _load():
         lib.cnnmem_ref_permute.restype = i
         lib.cnnmem_ref_relayout.argtypes = [fp, fp, i, i, i, i, ctypes.c_char_p, ctypes.c_char_p]
         lib.cnnmem_ref_relayout.restype = i
+        lib.cnnmem_ref_widen16.argtypes = [ctypes.c_uint, i]
+        lib.cnnmem_ref_widen16.restype = ctypes.c_double
+        lib.cnnmem_ref_narrow16.argtypes = [ctypes.c_double, i]
+        lib.cnnmem_ref_narrow16.restype = ctypes.c_uint
+        lib.cnnmem_ref_transform16.argtypes = [fp, fp, i, i, i, i, i, i]
+        lib.cnnmem_ref_transform16.restype = i
+        lib.cnnmem_ref_pool16.argtypes = [fp, fp] + [i] * 13
+        lib.cnnmem_ref_pool16.restype = i
+        lib.cnnmem_ref_softmax16.argtypes = [fp, fp, i, i, i]
+        lib.cnnmem_ref_softmax16.restype = i
         lib.cnnmem_ref_index.argtypes = [i] * 9
         lib.cnnmem_ref_index.restype = ctypes.c_ulonglong
         for name in ("cnnmem_ref_transform", "cnnmem_ref_pool_out_dims", "cnnmem_ref_pool",
@@ -178,3 +188,51 @@ def plan_layouts(layers, Ct: int, Nt: int, input_layout: int, pool_keeps_layout:
 
 def naive_pool_loads_1d(L: int, k: int, s: int) -> int:
     return int(_load().cnnmem_ref_naive_pool_loads_1d(L, k, s))
+
+
+# ---- 16-bit storage: arrays of uint16 bit patterns; F16 = IEEE binary16, BF16 = upper half of binary32 ----
+F32, F16, BF16 = 0, 1, 2
+
+
+def _u16(a: np.ndarray) -> np.ndarray:
+    if a.dtype != np.uint16 or not a.flags["C_CONTIGUOUS"]:
+        raise TypeError("the 16-bit oracle takes C-contiguous uint16 arrays of bit patterns")
+    return a
+
+
+def widen16(bits: int, dtype: int) -> float:
+    """Exact value of one 16-bit pattern."""
+    return float(_load().cnnmem_ref_widen16(int(bits), dtype))
+
+
+def narrow16(x: float, dtype: int) -> int:
+    """Nearest 16-bit pattern (ties to even) to a double."""
+    return int(_load().cnnmem_ref_narrow16(float(x), dtype))
+
+
+def transform16(src: np.ndarray, N, C, H, W, src_layout, dst_layout) -> np.ndarray:
+    src = _u16(src)
+    assert src.size == N * C * H * W
+    dst = np.empty(shape_of(dst_layout, N, C, H, W), dtype=np.uint16)
+    _check(_load().cnnmem_ref_transform16(src.ctypes.data, dst.ctypes.data, N, C, H, W, src_layout, dst_layout),
+           "transform16")
+    return dst
+
+
+def pool16(src: np.ndarray, N, C, H, W, layout, mode, kh, kw, sh, sw, ph=0, pw=0, dtype=F16) -> np.ndarray:
+    src = _u16(src)
+    assert src.size == N * C * H * W
+    Ho, Wo = pool_out_dims(H, W, kh, kw, sh, sw, ph, pw)
+    dst = np.empty(shape_of(layout, N, C, Ho, Wo), dtype=np.uint16)
+    _check(_load().cnnmem_ref_pool16(src.ctypes.data, dst.ctypes.data, N, C, H, W, layout, mode,
+                                     kh, kw, sh, sw, ph, pw, dtype), "pool16")
+    return dst
+
+
+def softmax16(logits: np.ndarray, dtype=F16) -> np.ndarray:
+    logits = _u16(logits)
+    assert logits.ndim == 2
+    N, classes = logits.shape
+    probs = np.empty_like(logits)
+    _check(_load().cnnmem_ref_softmax16(logits.ctypes.data, probs.ctypes.data, N, classes, dtype), "softmax16")
+    return probs

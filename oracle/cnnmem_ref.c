@@ -335,3 +335,156 @@ int cnnmem_ref_relayout(const float *src, float *dst, int N, int C, int H, int W
                     d[n * dn + c * dc + h * dh + w * dw] = s[n * sn + c * sc + h * sh + w * sw];
     return REF_OK;
 }
+
+/* ---- 16-bit storage (the paper's closing remarks expect FP16 hardware to matter for
+ * these layers; bf16 is the other 16-bit format of current GPUs) ----
+ *
+ * Only the storage changes: a stored value is widened exactly, every result is
+ * computed as above in fp64 and rounded ONCE, to nearest with ties to even, to the
+ * storage format.  fp16 is IEEE binary16 (1 + 5 + 10 bits, bias 15); bf16 is the
+ * upper half of binary32 (1 + 8 + 7 bits, bias 127).  Both have subnormals,
+ * infinities and NaNs. */
+enum { REF_F32 = 0, REF_F16 = 1, REF_BF16 = 2 };
+
+static int frac_bits_of(int dtype) { return dtype == REF_F16 ? 10 : 7; }
+static int exp_bits_of(int dtype) { return dtype == REF_F16 ? 5 : 8; }
+
+/* Exact value of a 16-bit pattern. */
+static double widen16(uint16_t h, int dtype)
+{
+    const int fb = frac_bits_of(dtype), eb = exp_bits_of(dtype);
+    const int bias = (1 << (eb - 1)) - 1;
+    const int sign = h >> 15;
+    const int e = (h >> fb) & ((1 << eb) - 1);
+    const int f = h & ((1 << fb) - 1);
+    double v;
+    if (e == (1 << eb) - 1)
+        v = f ? NAN : INFINITY;
+    else if (e == 0)
+        v = ldexp((double)f, 1 - bias - fb);                  /* subnormal: f * 2^(emin - fb) */
+    else
+        v = ldexp((double)((1 << fb) + f), e - bias - fb);    /* (1 + f/2^fb) * 2^(e - bias) */
+    return sign ? -v : v;
+}
+
+/* Nearest 16-bit pattern to x, ties to even; overflow gives infinity. */
+static uint16_t narrow16(double x, int dtype)
+{
+    const int fb = frac_bits_of(dtype), eb = exp_bits_of(dtype);
+    const int bias = (1 << (eb - 1)) - 1;
+    const int emax_field = (1 << eb) - 1;
+    const uint16_t sign = (uint16_t)(signbit(x) ? 0x8000 : 0);
+    if (isnan(x)) return (uint16_t)(sign | (emax_field << fb) | (1 << (fb - 1)));
+    const double a = fabs(x);
+    if (isinf(a)) return (uint16_t)(sign | (emax_field << fb));
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);                                       /* a = m * 2^e, m in [0.5, 1) */
+    e -= 1;                                                   /* a in [2^e, 2^(e+1)) */
+    if (e < 1 - bias) e = 1 - bias;                           /* subnormal range: fixed spacing */
+    /* a / spacing, spacing = 2^(e - fb); nearbyint rounds to nearest even in the default mode */
+    double q = nearbyint(ldexp(a, fb - e));
+    if (q >= (double)(2 << fb)) {                             /* rounded up into the next binade */
+        q = (double)(1 << fb);
+        e += 1;
+    }
+    int field = e + bias;
+    long long frac = (long long)q;
+    if (frac < (1 << fb))
+        field = 0;                                            /* stayed subnormal */
+    else
+        frac -= (1 << fb);
+    if (field >= emax_field) return (uint16_t)(sign | (emax_field << fb));
+    return (uint16_t)(sign | (field << fb) | (int)frac);
+}
+
+/* The conversions themselves, exported so that tests can pin them against library conversions. */
+double cnnmem_ref_widen16(unsigned h, int dtype) { return widen16((uint16_t)h, dtype); }
+unsigned cnnmem_ref_narrow16(double x, int dtype) { return narrow16(x, dtype); }
+
+static int dtype16_ok(int dtype) { return dtype == REF_F16 || dtype == REF_BF16; }
+
+/* Layout change of a tensor of 16-bit words (Section IV.C): words move untouched. */
+int cnnmem_ref_transform16(const uint16_t *src, uint16_t *dst, int N, int C, int H, int W,
+                           int src_layout, int dst_layout)
+{
+    if (!src || !dst || N <= 0 || C <= 0 || H <= 0 || W <= 0)
+        return REF_ERR_INVALID_ARG;
+    if ((src_layout != REF_NCHW && src_layout != REF_CHWN) ||
+        (dst_layout != REF_NCHW && dst_layout != REF_CHWN))
+        return REF_ERR_INVALID_ARG;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c)
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w)
+                    dst[at(dst_layout, N, C, H, W, n, c, h, w)] =
+                        src[at(src_layout, N, C, H, W, n, c, h, w)];
+    return REF_OK;
+}
+
+/* Pooling (Equation 2) on 16-bit storage: the maximum is one of the inputs, the
+ * average is the exact sum over kh*kw, rounded once. */
+int cnnmem_ref_pool16(const uint16_t *src, uint16_t *dst, int N, int C, int H, int W, int layout,
+                      int mode, int kh, int kw, int sh, int sw, int ph, int pw, int dtype)
+{
+    if (!src || !dst || !dtype16_ok(dtype) || !pool_args_ok(N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw))
+        return REF_ERR_INVALID_ARG;
+    const int Ho = pooled_extent(H, kh, sh, ph);
+    const int Wo = pooled_extent(W, kw, sw, pw);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c)
+            for (int i = 0; i < Ho; ++i)
+                for (int j = 0; j < Wo; ++j) {
+                    double best = -INFINITY, sum = 0.0;
+                    uint16_t best_bits = (uint16_t)(0x8000 | (((1 << exp_bits_of(dtype)) - 1) << frac_bits_of(dtype)));
+                    for (int y = 0; y < kh; ++y)
+                        for (int x = 0; x < kw; ++x) {
+                            const int r = i * sh - ph + y;
+                            const int q = j * sw - pw + x;
+                            if (r < 0 || r >= H || q < 0 || q >= W)
+                                continue;
+                            const uint16_t bits = src[at(layout, N, C, H, W, n, c, r, q)];
+                            const double v = widen16(bits, dtype);
+                            if (v > best) { best = v; best_bits = bits; }
+                            sum += v;                          /* exact: few terms of <= 11 significant bits */
+                        }
+                    dst[at(layout, N, C, Ho, Wo, n, c, i, j)] =
+                        mode == REF_POOL_MAX ? best_bits : narrow16(sum / (double)(kh * kw), dtype);
+                }
+    return REF_OK;
+}
+
+/* Softmax (Section II.A, steps 1-5) on 16-bit storage. */
+int cnnmem_ref_softmax16(const uint16_t *logits, uint16_t *probs, int N, int classes, int dtype)
+{
+    if (!logits || !probs || N <= 0 || classes <= 0 || !dtype16_ok(dtype))
+        return REF_ERR_INVALID_ARG;
+    int failed = 0;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        const uint16_t *in = logits + (size_t)n * classes;
+        uint16_t *out = probs + (size_t)n * classes;
+        double *mid = (double *)malloc((size_t)classes * sizeof(double));
+        if (!mid) {
+#pragma omp atomic write
+            failed = 1;
+            continue;
+        }
+        double maxv = widen16(in[0], dtype);                   /* step 1 */
+        for (int c = 1; c < classes; ++c) {
+            const double v = widen16(in[c], dtype);
+            if (v > maxv) maxv = v;
+        }
+        double sumv = 0.0;
+        for (int c = 0; c < classes; ++c) {                    /* steps 2-4 */
+            mid[c] = exp(widen16(in[c], dtype) - maxv);
+            sumv += mid[c];
+        }
+        for (int c = 0; c < classes; ++c)                      /* step 5 */
+            out[c] = narrow16(mid[c] / sumv, dtype);
+        free(mid);
+    }
+    return failed ? REF_ERR_NOMEM : REF_OK;
+}
