@@ -80,6 +80,31 @@ CNNMEM_API int cnnmem_relayout(const float *src, float *dst, int N, int C, int H
                                const char *src_layout, const char *dst_layout, void *hip_stream);
 
 /*
+ * Storage formats.  CNNMEM_F32 is what every entry point above works on.  With
+ * CNNMEM_F16 (IEEE binary16) or CNNMEM_BF16 (the upper half of binary32) a tensor
+ * element is 16 bits: the paper's closing remarks expect half precision to push
+ * these layers further towards the memory bound, and it halves the bytes they move.
+ * Only storage changes: stored values are widened exactly, pooling sums and the
+ * softmax are computed in fp32 as for CNNMEM_F32, and each result is rounded once,
+ * to nearest even, to the storage format.  The transform moves 16-bit words bit for
+ * bit, the maximum of a window is one of its inputs bit for bit.
+ */
+enum { CNNMEM_F32 = 0, CNNMEM_F16 = 1, CNNMEM_BF16 = 2 };
+
+/*
+ * cnnmem_transform / cnnmem_pool / cnnmem_softmax on tensors of `dtype`.  Arguments,
+ * layouts, ownership and errors are those of the fp32 entry points; pointers must be
+ * aligned to the element size (16-byte alignment enables the 128-bit kernels), and
+ * an unknown dtype is an INVALID_ARG.  With CNNMEM_F32 they are the fp32 calls.
+ */
+CNNMEM_API int cnnmem_transform_dtype(const void *src, void *dst, int N, int C, int H, int W, int src_layout,
+                                      int dst_layout, int dtype, void *hip_stream);
+CNNMEM_API int cnnmem_pool_dtype(const void *src, void *dst, int N, int C, int H, int W, int layout, int mode,
+                                 int kh, int kw, int sh, int sw, int ph, int pw, int dtype, void *hip_stream);
+CNNMEM_API int cnnmem_softmax_dtype(const void *logits, void *probs, int N, int classes, int dtype,
+                                    void *hip_stream);
+
+/*
  * Pooled output extent (host only, no GPU work):
  *   Ho = floor((H + 2*ph - kh) / sh) + 1,  Wo likewise
  * -- the rule Fig. 8 of Section V.A implies (12 inputs, window 4, stride 2 give

@@ -17,6 +17,8 @@ NCHW, CHWN = 0, 1
 POOL_MAX, POOL_AVG = 0, 1
 LAYER_CONV, LAYER_POOL, LAYER_OTHER = 0, 1, 2
 POOL_PREFERS_CHWN, POOL_KEEPS_LAYOUT = 0, 1
+F32, F16, BF16 = 0, 1, 2                       # storage formats (cnnmem.h: CNNMEM_F32 / _F16 / _BF16)
+_DTYPE_OF = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 
 
 class PoolTuning(ctypes.Structure):
@@ -59,6 +61,11 @@ def library() -> ctypes.CDLL:
         lib.cnnmem_debug_canonical_permutation.argtypes = [ctypes.POINTER(i), ctypes.POINTER(i), ctypes.POINTER(i),
                                                            ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(i)]
         lib.cnnmem_debug_canonical_permutation.restype = i
+        lib.cnnmem_transform_dtype.argtypes = [p, p, i, i, i, i, i, i, i, p]
+        lib.cnnmem_pool_dtype.argtypes = [p, p] + [i] * 13 + [p]
+        lib.cnnmem_softmax_dtype.argtypes = [p, p, i, i, i, p]
+        for name in ("cnnmem_transform_dtype", "cnnmem_pool_dtype", "cnnmem_softmax_dtype"):
+            getattr(lib, name).restype = i
         lib.cnnmem_pool_out_dims.argtypes = [i] * 8 + [ctypes.POINTER(i)] * 2
         lib.cnnmem_pool.argtypes = [p, p] + [i] * 12 + [p]
         lib.cnnmem_pool_tuned.argtypes = [p, p] + [i] * 12 + [ctypes.POINTER(PoolTuning), p]
@@ -83,7 +90,7 @@ def library() -> ctypes.CDLL:
     return _lib
 
 
-def _ptr(t) -> Optional[int]:
+def _ptr(t, dtype: int = F32) -> Optional[int]:
     """Device address of a torch tensor (or a raw integer address / None)."""
     if t is None or isinstance(t, int):
         return t
@@ -91,9 +98,18 @@ def _ptr(t) -> Optional[int]:
         raise TypeError("expected a torch tensor or an integer address")
     if t.device.type != "cuda":
         raise ValueError("cnnmem works on GPU memory only (got a CPU tensor)")
-    if t.dtype != torch.float32 or not t.is_contiguous():
-        raise ValueError("cnnmem takes contiguous float32 tensors")
+    if _DTYPE_OF.get(t.dtype) != dtype or not t.is_contiguous():
+        raise ValueError("cnnmem takes contiguous tensors of the stated storage format "
+                         "(float32 unless a dtype is given)")
     return t.data_ptr()
+
+
+def dtype_of(t: torch.Tensor) -> int:
+    """Storage-format tag of a torch tensor (float32 / float16 / bfloat16)."""
+    try:
+        return _DTYPE_OF[t.dtype]
+    except KeyError:
+        raise ValueError("cnnmem stores float32, float16 or bfloat16") from None
 
 
 def _stream(stream) -> Optional[int]:
@@ -128,6 +144,20 @@ def cnnmem_debug_canonical_permutation(dims, perm):
     st = library().cnnmem_debug_canonical_permutation((ctypes.c_int * 4)(*dims), (ctypes.c_int * 4)(*perm),
                                                       ctypes.byref(rank), cd, cp)
     return st, rank.value, list(cd)[:rank.value], list(cp)[:rank.value]
+
+
+def cnnmem_transform_dtype(src, dst, N, C, H, W, src_layout, dst_layout, dtype, stream=None) -> int:
+    return library().cnnmem_transform_dtype(_ptr(src, dtype), _ptr(dst, dtype), N, C, H, W, src_layout, dst_layout,
+                                            dtype, _stream(stream))
+
+
+def cnnmem_pool_dtype(src, dst, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, dtype, stream=None) -> int:
+    return library().cnnmem_pool_dtype(_ptr(src, dtype), _ptr(dst, dtype), N, C, H, W, layout, mode, kh, kw, sh, sw,
+                                       ph, pw, dtype, _stream(stream))
+
+
+def cnnmem_softmax_dtype(logits, probs, N, classes, dtype, stream=None) -> int:
+    return library().cnnmem_softmax_dtype(_ptr(logits, dtype), _ptr(probs, dtype), N, classes, dtype, _stream(stream))
 
 
 def cnnmem_pool_out_dims(H, W, kh, kw, sh, sw, ph, pw) -> Tuple[int, int, int]:
@@ -190,8 +220,8 @@ def _shape(layout, N, C, H, W):
 
 def transform(src: torch.Tensor, N, C, H, W, src_layout, dst_layout, out=None, stream=None) -> torch.Tensor:
     if out is None:
-        out = torch.empty(_shape(dst_layout, N, C, H, W), dtype=torch.float32, device=src.device)
-    st = cnnmem_transform(src, out, N, C, H, W, src_layout, dst_layout, stream)
+        out = torch.empty(_shape(dst_layout, N, C, H, W), dtype=src.dtype, device=src.device)
+    st = cnnmem_transform_dtype(src, out, N, C, H, W, src_layout, dst_layout, dtype_of(src), stream)
     if st:
         raise CnnmemError(st, "cnnmem_transform")
     return out
@@ -223,8 +253,11 @@ def pool(src: torch.Tensor, N, C, H, W, layout, mode, kh, kw, sh, sw, ph=0, pw=0
     if st:
         raise CnnmemError(st, "cnnmem_pool_out_dims")
     if out is None:
-        out = torch.empty(_shape(layout, N, C, Ho, Wo), dtype=torch.float32, device=src.device)
-    st = cnnmem_pool_tuned(src, out, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, tuning, stream)
+        out = torch.empty(_shape(layout, N, C, Ho, Wo), dtype=src.dtype, device=src.device)
+    if dtype_of(src) != F32:
+        st = cnnmem_pool_dtype(src, out, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, dtype_of(src), stream)
+    else:
+        st = cnnmem_pool_tuned(src, out, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, tuning, stream)
     if st:
         raise CnnmemError(st, "cnnmem_pool")
     return out
@@ -234,7 +267,7 @@ def softmax(logits: torch.Tensor, out=None, stream=None) -> torch.Tensor:
     N, classes = logits.shape
     if out is None:
         out = torch.empty_like(logits)
-    st = cnnmem_softmax(logits, out, N, classes, stream)
+    st = cnnmem_softmax_dtype(logits, out, N, classes, dtype_of(logits), stream)
     if st:
         raise CnnmemError(st, "cnnmem_softmax")
     return out

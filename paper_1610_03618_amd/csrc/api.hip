@@ -135,6 +135,52 @@ int cnnmem_softmax(const float* logits, float* probs, int N, int classes, void* 
     return launch_softmax(logits, probs, N, classes, static_cast<hipStream_t>(hip_stream));
 }
 
+int cnnmem_transform_dtype(const void* src, void* dst, int N, int C, int H, int W, int src_layout, int dst_layout,
+                           int dtype, void* hip_stream) {
+    if (dtype == CNNMEM_F32)
+        return cnnmem_transform(static_cast<const float*>(src), static_cast<float*>(dst), N, C, H, W, src_layout,
+                                dst_layout, hip_stream);
+    if (dtype != CNNMEM_F16 && dtype != CNNMEM_BF16) return CNNMEM_ERR_INVALID_ARG;
+    if (!src || !dst || N <= 0 || C <= 0 || H <= 0 || W <= 0) return CNNMEM_ERR_INVALID_ARG;
+    if (!layout_ok(src_layout) || !layout_ok(dst_layout)) return CNNMEM_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 1u) return CNNMEM_ERR_INVALID_ARG;
+    const long long limit = 1LL << 46;
+    const long long CH = (long long)C * H;
+    if (CH > limit / W || CH * W > limit / N) return CNNMEM_ERR_UNSUPPORTED;
+    return launch_transform16(src, dst, N, CH * W, src_layout, dst_layout, static_cast<hipStream_t>(hip_stream));
+}
+
+int cnnmem_pool_dtype(const void* src, void* dst, int N, int C, int H, int W, int layout, int mode, int kh, int kw,
+                      int sh, int sw, int ph, int pw, int dtype, void* hip_stream) {
+    if (dtype == CNNMEM_F32)
+        return cnnmem_pool(static_cast<const float*>(src), static_cast<float*>(dst), N, C, H, W, layout, mode, kh, kw,
+                           sh, sw, ph, pw, hip_stream);
+    if (dtype != CNNMEM_F16 && dtype != CNNMEM_BF16) return CNNMEM_ERR_INVALID_ARG;
+    if (!src || !dst || N <= 0 || C <= 0) return CNNMEM_ERR_INVALID_ARG;
+    if (!window_ok(H, W, kh, kw, sh, sw, ph, pw)) return CNNMEM_ERR_INVALID_ARG;
+    if (!layout_ok(layout)) return CNNMEM_ERR_INVALID_ARG;
+    if (mode != CNNMEM_POOL_MAX && mode != CNNMEM_POOL_AVG) return CNNMEM_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 1u) return CNNMEM_ERR_INVALID_ARG;
+    if ((long long)H * W > (1LL << 30) || (long long)kh * kw > (1 << 24)) return CNNMEM_ERR_UNSUPPORTED;
+    PoolGeom g;
+    g.N = N; g.C = C; g.H = H; g.W = W;
+    g.kh = kh; g.kw = kw; g.sh = sh; g.sw = sw; g.ph = ph; g.pw = pw;
+    g.mode = mode;
+    g.Ho = pooled_extent(H, kh, sh, ph);
+    g.Wo = pooled_extent(W, kw, sw, pw);
+    return launch_pool16(src, dst, g, layout, dtype, static_cast<hipStream_t>(hip_stream));
+}
+
+int cnnmem_softmax_dtype(const void* logits, void* probs, int N, int classes, int dtype, void* hip_stream) {
+    if (dtype == CNNMEM_F32)
+        return cnnmem_softmax(static_cast<const float*>(logits), static_cast<float*>(probs), N, classes, hip_stream);
+    if (dtype != CNNMEM_F16 && dtype != CNNMEM_BF16) return CNNMEM_ERR_INVALID_ARG;
+    if (!logits || !probs || N <= 0 || classes <= 0) return CNNMEM_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(logits) | reinterpret_cast<uintptr_t>(probs)) & 1u)
+        return CNNMEM_ERR_INVALID_ARG;
+    return launch_softmax16(logits, probs, N, classes, dtype, static_cast<hipStream_t>(hip_stream));
+}
+
 int cnnmem_choose_layout(int layer_kind, int N, int C, int Ct, int Nt, int* layout) {
     if (!layout || N <= 0 || C <= 0 || Ct < 0 || Nt < 0) return CNNMEM_ERR_INVALID_ARG;
     switch (layer_kind) {

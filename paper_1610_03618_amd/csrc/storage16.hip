@@ -1,0 +1,803 @@
+// The hot path on 16-bit storage: fp16 (IEEE binary16) and bf16 tensors.
+//
+// The paper's closing remarks expect half precision to shift these layers further
+// towards memory: every element is 2 bytes, so the same 8 TB/s moves twice the
+// elements.  Arithmetic does not change: values are widened exactly to fp32,
+// pooling sums and the softmax run in fp32 exactly as in the fp32 kernels, and a
+// result is rounded once, to nearest even, to the storage format.  A lane still
+// moves 128 bits per access, which is now 8 elements:
+//   transform -- 2-D transpose of 16-bit words; a lane loads 8 words of two
+//                neighbouring source rows and files the eight (row, row+1) pairs
+//                as dwords in an LDS tile that is already in destination order;
+//   pooling   -- CHWN: a lane owns 8 images; NCHW: row pairs for 2x2 / stride 2,
+//                else contiguous slabs through LDS, as for fp32;
+//   softmax   -- a row in registers, 8 categories per 128-bit access, rows split
+//                into head / line-aligned body / tail.
+#include "common.hpp"
+#include "rowmath.hpp"
+
+namespace cnnmem {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr float kNegInf = kRowNegInf;
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef u32x4 u32x4_unaligned __attribute__((aligned(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ u32x4 ld16_stream(const uint16_t* p) {       // 16-byte aligned
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+__device__ __forceinline__ u32x4 ld16_cached(const uint16_t* p) {
+    return *reinterpret_cast<const u32x4*>(p);
+}
+__device__ __forceinline__ u32x4 ld16u_stream(const uint16_t* p) {      // 4-byte aligned
+    const u32x4_unaligned v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_unaligned*>(p));
+    return v;
+}
+__device__ __forceinline__ void st16_stream(uint16_t* p, u32x4 v) {
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
+}
+__device__ __forceinline__ void st16u_stream(uint16_t* p, u32x4 v) {
+    const u32x4_unaligned w = v;
+    __builtin_nontemporal_store(w, reinterpret_cast<u32x4_unaligned*>(p));
+}
+__device__ __forceinline__ void st8_stream(uint16_t* p, u32x2 v) {
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(p));
+}
+
+// ---- the two storage formats -------------------------------------------------
+struct Half {                                       // IEEE binary16
+    // Both conversions are single instructions written as inline asm on purpose.  Given the
+    // _Float16 type, the compiler notices that a maximum of widened halves is itself a half,
+    // rewrites the fp32 max chain into v_max_f16 / v_max3_f16, and then ORs the 16-bit result
+    // into a dword assuming its upper half is zero; on this target v_max3_f16 leaves the upper
+    // half of its destination untouched, and the neighbouring output came out corrupted
+    // (2x2 max-pooling, caught by the parity test).  Opaque conversions keep every
+    // operation in fp32, and the explicit mask makes the packing independent of what the
+    // conversion leaves in the upper half.
+    static __device__ __forceinline__ float widen(uint32_t bits16) {
+        float f;
+        asm("v_cvt_f32_f16_e32 %0, %1" : "=v"(f) : "v"(bits16));    // reads the low 16 bits
+        return f;
+    }
+    static __device__ __forceinline__ uint32_t narrow(float x) {       // nearest even (default rounding mode)
+        uint32_t h;
+        asm("v_cvt_f16_f32_e32 %0, %1" : "=v"(h) : "v"(x));
+        return h & 0xffffu;
+    }
+};
+struct BFloat {                                     // upper half of binary32
+    static __device__ __forceinline__ float widen(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+    static __device__ __forceinline__ uint32_t narrow(float x) {
+        const uint32_t u = __float_as_uint(x);
+        if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
+        return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;                  // nearest even; overflow carries into infinity
+    }
+};
+
+template <class E>
+__device__ __forceinline__ void unpack8(const u32x4& w, float* f) {
+    f[0] = E::widen(w.x & 0xffffu); f[1] = E::widen(w.x >> 16);
+    f[2] = E::widen(w.y & 0xffffu); f[3] = E::widen(w.y >> 16);
+    f[4] = E::widen(w.z & 0xffffu); f[5] = E::widen(w.z >> 16);
+    f[6] = E::widen(w.w & 0xffffu); f[7] = E::widen(w.w >> 16);
+}
+template <class E>
+__device__ __forceinline__ u32x4 pack8(const float* f) {
+    u32x4 w;
+    w.x = E::narrow(f[0]) | (E::narrow(f[1]) << 16);
+    w.y = E::narrow(f[2]) | (E::narrow(f[3]) << 16);
+    w.z = E::narrow(f[4]) | (E::narrow(f[5]) << 16);
+    w.w = E::narrow(f[6]) | (E::narrow(f[7]) << 16);
+    return w;
+}
+
+// =============================================================================
+// Transform (Section IV.C): src[R][S] -> dst[S][R], 16-bit words.
+// =============================================================================
+
+// R and S even (rows then start on dword boundaries), S >= 8.  Work item = two
+// neighbouring source rows x 8 columns: two 128-bit loads, eight dword LDS writes
+// (each dword is the pair (r, r+1) of one destination row), and after the barrier a
+// lane reads four dwords of a destination row and stores 128 bits.  LDS rows have
+// an odd pitch in dwords, which spreads both the column-wise writes and the
+// row-wise reads over the banks.
+template <int TR, int TS>
+__global__ __launch_bounds__(kThreads) void transpose16_kernel(
+    const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, long long R, long long S, uint32_t tiles_s) {
+    static_assert(TR % 16 == 0 && TS % 8 == 0 && (TR * TS / 16) % kThreads == 0, "tile shape");
+    constexpr int PD = TR / 2 + 1;                  // LDS pitch in dwords
+    constexpr int NC8 = TS / 8;
+    constexpr int NB8 = TR / 8;
+    constexpr int LOADS = (TR * TS / 16) / kThreads;
+    constexpr int STORES = (TS * NB8) / kThreads;
+    __shared__ uint32_t tile[(TS + 1) * PD];        // one spare row for words left of the tile
+
+    const long long r0 = (long long)(blockIdx.x / tiles_s) * TR;
+    const long long s0 = (long long)(blockIdx.x % tiles_s) * TS;
+    const int tid = threadIdx.x;
+
+    u32x4 a[LOADS], b[LOADS];
+    int col[LOADS];
+#pragma unroll
+    for (int it = 0; it < LOADS; ++it) {
+        const int w = tid + it * kThreads;
+        const int c8 = w % NC8, rp = w / NC8;
+        long long r = r0 + 2 * rp, s = s0 + 8 * c8;
+        r = r < R ? r : R - 2;                      // R is even: row r + 1 exists whenever r does
+        s = s + 8 <= S ? s : S - 8;
+        col[it] = (int)(s - s0);                    // even, >= -6
+        const uint16_t* q = src + (size_t)r * (size_t)S + (size_t)s;
+        a[it] = ld16u_stream(q);
+        b[it] = ld16u_stream(q + S);
+    }
+#pragma unroll
+    for (int it = 0; it < LOADS; ++it) {
+        const int rp = (tid + it * kThreads) / NC8;
+        const uint32_t lo[4] = {a[it].x, a[it].y, a[it].z, a[it].w};
+        const uint32_t hi[4] = {b[it].x, b[it].y, b[it].z, b[it].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = col[it] + 2 * j;          // columns c and c + 1 have the same sign (c is even)
+            const int row0 = c >= 0 ? c : TS, row1 = c >= 0 ? c + 1 : TS;
+            tile[row0 * PD + rp] = (lo[j] & 0xffffu) | (hi[j] << 16);
+            tile[row1 * PD + rp] = (lo[j] >> 16) | (hi[j] & 0xffff0000u);
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < STORES; ++it) {
+        const int f = tid + it * kThreads;
+        const int b8 = f % NB8, sl = f / NB8;
+        const uint32_t* t = tile + sl * PD + 4 * b8;
+        u32x4 o;
+        o.x = t[0]; o.y = t[1]; o.z = t[2]; o.w = t[3];
+        const long long s = s0 + sl, r = r0 + 8 * b8;
+        if (s < S) {
+            uint16_t* q = dst + (size_t)s * (size_t)R + (size_t)r;
+            if (r + 8 <= R) {
+                st16u_stream(q, o);
+            } else {                                // ragged end of a destination row (R is even: whole dwords)
+                const uint32_t w[4] = {o.x, o.y, o.z, o.w};
+                for (int j = 0; j < 4; ++j)
+                    if (r + 2 * j < R) *reinterpret_cast<uint32_t*>(q + 2 * j) = w[j];
+            }
+        }
+    }
+}
+
+// Any R, S: word by word through a 64 x 64 tile.
+__global__ __launch_bounds__(kThreads) void transpose16_scalar_kernel(
+    const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, long long R, long long S, uint32_t tiles_s) {
+    constexpr int T = 64;
+    __shared__ uint16_t tile[T * (T + 2)];
+    const long long r0 = (long long)(blockIdx.x / tiles_s) * T;
+    const long long s0 = (long long)(blockIdx.x % tiles_s) * T;
+    const int tx = threadIdx.x % T, ty = threadIdx.x / T;
+#pragma unroll
+    for (int k = 0; k < T / 4; ++k) {
+        const int rl = ty + 4 * k;
+        const long long r = r0 + rl, s = s0 + tx;
+        if (r < R && s < S) tile[rl * (T + 2) + tx] = src[(size_t)r * (size_t)S + (size_t)s];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < T / 4; ++k) {
+        const int sl = ty + 4 * k;
+        const long long s = s0 + sl, r = r0 + tx;
+        if (r < R && s < S) dst[(size_t)s * (size_t)R + (size_t)r] = tile[tx * (T + 2) + sl];
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void copy16_kernel(const uint16_t* __restrict__ src, uint16_t* __restrict__ dst,
+                                                          size_t n) {
+    // 8 words per lane where the pointers allow it, the rest word by word
+    const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    const bool vec = ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) == 0;
+    if (vec) {
+        if (8 * i + 8 <= n) st16_stream(dst + 8 * i, ld16_stream(src + 8 * i));
+        else for (size_t j = 8 * i; j < n; ++j) dst[j] = src[j];
+    } else {
+        for (size_t j = 8 * i; j < n && j < 8 * i + 8; ++j) dst[j] = src[j];
+    }
+}
+
+template <int TR, int TS>
+int launch_t16(const uint16_t* src, uint16_t* dst, long long R, long long S, hipStream_t st) {
+    const long long tiles_r = ceil_div64(R, TR), tiles_s = ceil_div64(S, TS);
+    if (tiles_r * tiles_s > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((transpose16_kernel<TR, TS>), dim3((unsigned)(tiles_r * tiles_s)), dim3(kThreads), 0, st, src,
+                       dst, R, S, (uint32_t)tiles_s);
+    return launch_status();
+}
+
+int launch_transpose16(const uint16_t* src, uint16_t* dst, long long R, long long S, hipStream_t st) {
+    const bool dword_ok = ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 3u) == 0;
+    if (dword_ok && R % 2 == 0 && S % 2 == 0 && S >= 8 && R >= 2) {
+        int shape = env_int("CNNMEM_TRANSFORM16_TILE", -1);
+        if (shape < 0) {
+            if (R <= 16) shape = 3;
+            else if (R <= 32) shape = 2;
+            else if (S <= 16) shape = 5;
+            else if (S <= 32) shape = 4;
+            else if (R >= 128 && S >= 128) shape = 1;
+            else shape = 0;
+        }
+        switch (shape) {
+            case 1: return launch_t16<128, 128>(src, dst, R, S, st);
+            case 2: return launch_t16<32, 128>(src, dst, R, S, st);
+            case 3: return launch_t16<16, 256>(src, dst, R, S, st);
+            case 4: return launch_t16<128, 32>(src, dst, R, S, st);
+            case 5: return launch_t16<256, 16>(src, dst, R, S, st);
+            case 6: return launch_t16<64, 128>(src, dst, R, S, st);
+            case 7: return launch_t16<128, 64>(src, dst, R, S, st);
+            case 8: return launch_t16<64, 256>(src, dst, R, S, st);
+            case 9: return launch_t16<256, 64>(src, dst, R, S, st);
+            default: return launch_t16<64, 64>(src, dst, R, S, st);
+        }
+    }
+    const long long tiles_r = ceil_div64(R, 64), tiles_s = ceil_div64(S, 64);
+    if (tiles_r * tiles_s > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(transpose16_scalar_kernel, dim3((unsigned)(tiles_r * tiles_s)), dim3(kThreads), 0, st, src, dst,
+                       R, S, (uint32_t)tiles_s);
+    return launch_status();
+}
+
+// =============================================================================
+// Pooling (Equation 2; Section IV.B, V.A)
+// =============================================================================
+template <int MODE>
+struct Acc {
+    static __device__ __forceinline__ float identity() { return MODE == CNNMEM_POOL_MAX ? kNegInf : 0.f; }
+    static __device__ __forceinline__ float op(float a, float b) {
+        return MODE == CNNMEM_POOL_MAX ? fmaxf(a, b) : a + b;
+    }
+    static __device__ __forceinline__ float finish(float a, float divisor) {
+        return MODE == CNNMEM_POOL_MAX ? a : a / divisor;
+    }
+};
+
+// Fallback: one lane per output, any layout through strides.
+template <class E, int MODE>
+__global__ __launch_bounds__(kThreads) void pool16_generic_kernel(
+    const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, PoolGeom g, int chwn, size_t total) {
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    for (size_t o = (size_t)blockIdx.x * kThreads + threadIdx.x; o < total; o += stride) {
+        int n, c, i, j;
+        size_t t = o;
+        if (chwn) {
+            n = (int)(t % g.N); t /= g.N;
+            j = (int)(t % g.Wo); t /= g.Wo;
+            i = (int)(t % g.Ho); c = (int)(t / g.Ho);
+        } else {
+            j = (int)(t % g.Wo); t /= g.Wo;
+            i = (int)(t % g.Ho); t /= g.Ho;
+            c = (int)(t % g.C); n = (int)(t / g.C);
+        }
+        float acc = Acc<MODE>::identity();
+        for (int y = 0; y < g.kh; ++y) {
+            const int r = i * g.sh - g.ph + y;
+            if (r < 0 || r >= g.H) continue;
+            for (int x = 0; x < g.kw; ++x) {
+                const int q = j * g.sw - g.pw + x;
+                if (q < 0 || q >= g.W) continue;
+                const size_t idx = chwn ? (((size_t)c * g.H + r) * g.W + q) * g.N + n
+                                        : (((size_t)n * g.C + c) * g.H + r) * g.W + q;
+                acc = Acc<MODE>::op(acc, E::widen(src[idx]));
+            }
+        }
+        dst[o] = (uint16_t)E::narrow(Acc<MODE>::finish(acc, (float)(g.kh * g.kw)));
+    }
+}
+
+// CHWN: a lane owns 8 consecutive images of one output column and walks down OY
+// output rows; each input row it touches is reduced horizontally once and that row
+// result is reused by every output row whose window contains it (Section V.A's
+// working set, in registers).  Loads are unconditional from clamped addresses.
+template <class E, int MODE, int KH, int KW, int SH, int SW, int OY, bool PADDED>
+__global__ __launch_bounds__(kThreads) void pool16_chwn_kernel(
+    const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, PoolGeom g, uint32_t row_items,
+    uint32_t blocks_x, uint32_t blocks_y, FastDiv div_n8) {
+    constexpr int ROWS_IN = (OY - 1) * SH + KH;
+    const uint32_t tile = xcd_contiguous_tile(blockIdx.x, gridDim.x);
+    const uint32_t bx = tile % blocks_x;
+    const uint32_t rest = tile / blocks_x;
+    const uint32_t by = rest % blocks_y;
+    const uint32_t c = rest / blocks_y;
+    const uint32_t u = bx * kThreads + threadIdx.x;           // position in the output row: j * N8 + n8
+    if (u >= row_items) return;
+    const uint32_t j = fd_div(u, div_n8);
+    const uint32_t n8 = u - j * div_n8.d;
+    const int i0 = (int)by * OY;
+    const int N = g.N;
+
+    float acc[OY][8];
+#pragma unroll
+    for (int oy = 0; oy < OY; ++oy)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[oy][e] = Acc<MODE>::identity();
+
+    const int q0 = (int)j * SW - g.pw;
+    const int r_base = i0 * SH - g.ph;
+    const uint16_t* plane = src + (size_t)c * g.H * g.W * N + 8 * n8;
+    constexpr bool kStream = (KH <= SH) && (KW <= SW);        // disjoint windows: every tap is read once
+#pragma unroll
+    for (int rr = 0; rr < ROWS_IN; ++rr) {
+        const int r = r_base + rr;
+        const bool row_ok = !PADDED || (r >= 0 && r < g.H);
+        const int rc = r < 0 ? 0 : (r < g.H ? r : g.H - 1);
+        const uint16_t* rowp = plane + (size_t)rc * g.W * N;
+        float h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = Acc<MODE>::identity();
+#pragma unroll
+        for (int x = 0; x < KW; ++x) {
+            const int q = q0 + x;
+            const bool ok = row_ok && (!PADDED || (q >= 0 && q < g.W));
+            const int qc = q < 0 ? 0 : (q < g.W ? q : g.W - 1);
+            const u32x4 w = kStream ? ld16_stream(rowp + (size_t)qc * N) : ld16_cached(rowp + (size_t)qc * N);
+            float t[8];
+            unpack8<E>(w, t);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if (PADDED && !ok) t[e] = Acc<MODE>::identity();
+                h[e] = Acc<MODE>::op(h[e], t[e]);
+            }
+        }
+#pragma unroll
+        for (int oy = 0; oy < OY; ++oy)
+            if (rr >= oy * SH && rr < oy * SH + KH) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[oy][e] = Acc<MODE>::op(acc[oy][e], h[e]);
+            }
+    }
+    uint16_t* outp = dst + ((size_t)c * g.Ho * g.Wo + j) * N + 8 * n8;
+#pragma unroll
+    for (int oy = 0; oy < OY; ++oy) {
+        const int i = i0 + oy;
+        if (i < g.Ho) {
+            float o[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = Acc<MODE>::finish(acc[oy][e], (float)(KH * KW));
+            st16_stream(outp + (size_t)i * g.Wo * N, pack8<E>(o));
+        }
+    }
+}
+
+// NCHW, 2x2 / stride 2, no padding, even H, W a multiple of 8: the tensor is a list
+// of rows of W words and output row k is made of input rows 2k, 2k + 1.  A lane
+// reads 8 words of both rows and writes 4 outputs.
+template <class E, int MODE>
+__global__ __launch_bounds__(kThreads) void pool16_nchw_2x2s2_kernel(
+    const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, uint32_t items, uint32_t W, FastDiv div_per_row) {
+    const uint32_t I = blockIdx.x * kThreads + threadIdx.x;
+    if (I >= items) return;
+    const uint32_t orow = fd_div(I, div_per_row);
+    const size_t in0 = (size_t)I * 8 + (size_t)orow * W;       // = 2*orow*W + 8*(I % per_row)
+    float a[8], b[8], o[4];
+    unpack8<E>(ld16_stream(src + in0), a);
+    unpack8<E>(ld16_stream(src + in0 + W), b);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        if (MODE == CNNMEM_POOL_MAX) o[k] = fmaxf(fmaxf(a[2 * k], a[2 * k + 1]), fmaxf(b[2 * k], b[2 * k + 1]));
+        else o[k] = ((a[2 * k] + a[2 * k + 1]) + (b[2 * k] + b[2 * k + 1])) * 0.25f;
+    }
+    u32x2 w;
+    w.x = E::narrow(o[0]) | (E::narrow(o[1]) << 16);
+    w.y = E::narrow(o[2]) | (E::narrow(o[3]) << 16);
+    st8_stream(dst + (size_t)I * 4, w);
+}
+
+// NCHW through LDS: a workgroup streams a contiguous slab (whole planes, or a strip
+// of rows of one plane with its halo) into 32 KB of LDS with line-aligned 128-bit
+// loads, pools from LDS, and writes its outputs, which are contiguous too.
+constexpr int kSlabWords = 16384;                   // 32 KB
+constexpr int kSlabThreads = 512;
+
+struct Slab16Plan {
+    int planes_per_wg, rows_per_wg, strips;
+    long long total_planes;
+};
+
+template <class E, int MODE, int KH, int KW, int SH, int SW>
+__global__ __launch_bounds__(kSlabThreads) void pool16_nchw_slab_kernel(
+    const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, PoolGeom g, Slab16Plan plan, FastDiv div_wo,
+    FastDiv div_plane_out) {
+    constexpr int VEC = kSlabWords / 8 / kSlabThreads + 1;      // 128-bit loads per lane, worst case
+    __shared__ __attribute__((aligned(16))) uint16_t slab[kSlabWords + 16];
+    const int kh = KH ? KH : g.kh, kw = KW ? KW : g.kw, sh = SH ? SH : g.sh, sw = SW ? SW : g.sw;
+    const uint32_t tile = xcd_contiguous_tile(blockIdx.x, gridDim.x);
+    const int plane_in = g.H * g.W, plane_out = g.Ho * g.Wo;
+
+    long long p0;
+    int planes, i0, rows_out;
+    if (plan.strips == 1) {
+        p0 = (long long)tile * plan.planes_per_wg;
+        const long long left = plan.total_planes - p0;
+        planes = left < plan.planes_per_wg ? (int)left : plan.planes_per_wg;
+        i0 = 0;
+        rows_out = g.Ho;
+    } else {
+        p0 = tile / (uint32_t)plan.strips;
+        const int strip = (int)(tile % (uint32_t)plan.strips);
+        planes = 1;
+        i0 = strip * plan.rows_per_wg;
+        rows_out = g.Ho - i0 < plan.rows_per_wg ? g.Ho - i0 : plan.rows_per_wg;
+    }
+    int r_lo = i0 * sh - g.ph;
+    if (r_lo < 0) r_lo = 0;
+    int r_hi = (i0 + rows_out - 1) * sh - g.ph + kh;
+    if (r_hi > g.H) r_hi = g.H;
+    if (planes > 1) { r_lo = 0; r_hi = g.H; }
+    const size_t g_lo = (size_t)p0 * plane_in + (size_t)r_lo * g.W;
+    const size_t g_hi = (size_t)(p0 + planes - 1) * plane_in + (size_t)r_hi * g.W;
+    // the 128-bit stream starts on a 128-byte line of src when src is line aligned (src is 16-byte aligned)
+    const size_t in_mask = (reinterpret_cast<uintptr_t>(src) & 127u) == 0 ? 63 : 7;
+    const size_t a_lo = g_lo & ~in_mask;
+    const size_t total_in = (size_t)plan.total_planes * plane_in;
+    const int nvec = (int)((g_hi - a_lo + 7) >> 3);
+    // every load is unconditional: lanes past the slab, and the one vector of the whole tensor that would
+    // cross its end, re-read the last complete vector (total_in >= 8 is a dispatch condition)
+    const size_t a_last = (total_in - 8) & ~(size_t)7;
+    u32x4 v[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+        const int q = threadIdx.x + k * kSlabThreads;
+        size_t a = a_lo + 8 * (size_t)(q < nvec ? q : 0);
+        a = a <= a_last ? a : a_last;
+        v[k] = ld16_stream(src + a);
+    }
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+        const int q = threadIdx.x + k * kSlabThreads;
+        const size_t a = a_lo + 8 * (size_t)q;
+        if (q < nvec && a <= a_last) *reinterpret_cast<u32x4*>(slab + 8 * q) = v[k];
+    }
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+        const int q = threadIdx.x + k * kSlabThreads;
+        const size_t a = a_lo + 8 * (size_t)q;
+        if (q < nvec && a > a_last) {               // ragged end of the tensor (at most one lane, once)
+            for (int j = 0; j < 8; ++j)
+                if (a + j < total_in) slab[8 * q + j] = src[a + j];
+        }
+    }
+    __syncthreads();
+
+    const int n_out = planes * rows_out * g.Wo;
+    const size_t out0 = (size_t)p0 * plane_out + (size_t)i0 * g.Wo;
+    const int lds0 = (int)((long long)((size_t)p0 * plane_in) - (long long)a_lo);
+    // a lane computes two neighbouring outputs and stores them as one dword; the pairs are laid so that
+    // dwords (and each wavefront's 256-byte store) are aligned in dst
+    const int lead = (int)(((reinterpret_cast<uintptr_t>(dst) >> 1) + out0) & 63);
+    for (int o = 2 * (int)threadIdx.x - lead; o < n_out; o += 2 * kSlabThreads) {
+        uint32_t bits[2] = {0, 0};
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int oo = o + half;
+            if (oo < 0 || oo >= n_out) continue;
+            int pl = 0, rem = oo;
+            if (planes > 1) {
+                pl = (int)fd_div((uint32_t)oo, div_plane_out);
+                rem = oo - pl * plane_out;
+            }
+            const int il = (int)fd_div((uint32_t)rem, div_wo);
+            const int j = rem - il * g.Wo;
+            const int rb = (i0 + il) * sh - g.ph, qb = j * sw - g.pw;
+            const int base = lds0 + pl * plane_in;
+            float acc = Acc<MODE>::identity();
+            for (int y = 0; y < kh; ++y) {
+                const int r = rb + y;
+                if (r < 0 || r >= g.H) continue;
+                for (int x = 0; x < kw; ++x) {
+                    const int q = qb + x;
+                    if (q < 0 || q >= g.W) continue;
+                    acc = Acc<MODE>::op(acc, E::widen(slab[base + r * g.W + q]));
+                }
+            }
+            bits[half] = E::narrow(Acc<MODE>::finish(acc, (float)(kh * kw)));
+        }
+        const bool lo_ok = o >= 0;                  // o < n_out by the loop condition
+        const bool hi_ok = o + 1 >= 0 && o + 1 < n_out;
+        if (lo_ok && hi_ok) *reinterpret_cast<uint32_t*>(dst + out0 + o) = bits[0] | (bits[1] << 16);
+        else if (lo_ok) dst[out0 + o] = (uint16_t)bits[0];
+        else if (hi_ok) dst[out0 + o + 1] = (uint16_t)bits[1];
+    }
+}
+
+template <class E, int MODE>
+int launch_pool16_generic(const uint16_t* src, uint16_t* dst, const PoolGeom& g, int chwn, hipStream_t st) {
+    const size_t total = (size_t)g.N * g.C * g.Ho * g.Wo;
+    const long long want = ceil_div64((long long)total, kThreads);
+    const unsigned blocks = (unsigned)(want < 65536 ? want : 65536);
+    hipLaunchKernelGGL((pool16_generic_kernel<E, MODE>), dim3(blocks), dim3(kThreads), 0, st, src, dst, g, chwn, total);
+    return launch_status();
+}
+
+template <class E, int MODE, int KH, int KW, int SH, int SW, int OY>
+int launch_pool16_chwn(const uint16_t* src, uint16_t* dst, const PoolGeom& g, hipStream_t st) {
+    const long long row_items = (long long)(g.N / 8) * g.Wo;
+    const long long bx = ceil_div64(row_items, kThreads), by = ceil_div64(g.Ho, OY);
+    const long long blocks = bx * by * g.C;
+    if (row_items >= 0x7fffffffLL || blocks > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
+    const FastDiv dn8 = make_fastdiv((uint32_t)(g.N / 8));
+    if (g.ph > 0 || g.pw > 0)
+        hipLaunchKernelGGL((pool16_chwn_kernel<E, MODE, KH, KW, SH, SW, OY, true>), dim3((unsigned)blocks),
+                           dim3(kThreads), 0, st, src, dst, g, (uint32_t)row_items, (uint32_t)bx, (uint32_t)by, dn8);
+    else
+        hipLaunchKernelGGL((pool16_chwn_kernel<E, MODE, KH, KW, SH, SW, OY, false>), dim3((unsigned)blocks),
+                           dim3(kThreads), 0, st, src, dst, g, (uint32_t)row_items, (uint32_t)bx, (uint32_t)by, dn8);
+    return launch_status();
+}
+
+template <class E, int MODE, int KH, int KW, int SH, int SW>
+int launch_pool16_slab(const uint16_t* src, uint16_t* dst, const PoolGeom& g, const Slab16Plan& plan, long long blocks,
+                       hipStream_t st) {
+    const FastDiv dwo = make_fastdiv((uint32_t)g.Wo), dpo = make_fastdiv((uint32_t)(g.Ho * g.Wo));
+    hipLaunchKernelGGL((pool16_nchw_slab_kernel<E, MODE, KH, KW, SH, SW>), dim3((unsigned)blocks), dim3(kSlabThreads),
+                       0, st, src, dst, g, plan, dwo, dpo);
+    return launch_status();
+}
+
+template <class E, int MODE>
+int dispatch_pool16(const uint16_t* src, uint16_t* dst, const PoolGeom& g, int layout, hipStream_t st) {
+    const bool a16 = aligned16(src) && aligned16(dst);
+    if (layout == CNNMEM_CHWN) {
+        if (a16 && g.N % 8 == 0 && (long long)g.H * g.W * g.N < (1LL << 40)) {
+            if (g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2)
+                return launch_pool16_chwn<E, MODE, 3, 3, 2, 2, 3>(src, dst, g, st);
+            if (g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2)
+                return launch_pool16_chwn<E, MODE, 2, 2, 2, 2, 1>(src, dst, g, st);
+            if (g.kh == 3 && g.kw == 3 && g.sh == 1 && g.sw == 1)
+                return launch_pool16_chwn<E, MODE, 3, 3, 1, 1, 3>(src, dst, g, st);
+        }
+        return launch_pool16_generic<E, MODE>(src, dst, g, 1, st);
+    }
+    const long long planes = (long long)g.N * g.C;
+    if (a16 && g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2 && g.ph == 0 && g.pw == 0 && g.H % 2 == 0 &&
+        g.W % 8 == 0) {
+        const long long per_row = g.W / 8;
+        const long long items = planes * g.Ho * per_row;
+        if (items < 0x7fffffffLL) {
+            const FastDiv d = make_fastdiv((uint32_t)per_row);
+            hipLaunchKernelGGL((pool16_nchw_2x2s2_kernel<E, MODE>), dim3((unsigned)ceil_div64(items, kThreads)),
+                               dim3(kThreads), 0, st, src, dst, (uint32_t)items, (uint32_t)g.W, d);
+            return launch_status();
+        }
+    }
+    const long long plane_in = (long long)g.H * g.W;
+    // the slab kernel stores dwords: dst must be 4-byte aligned (a16 covers it)
+    if (a16 && plane_in * planes < (1LL << 40) && plane_in * planes >= 8) {
+        Slab16Plan plan;
+        plan.total_planes = planes;
+        bool ok = false;
+        long long blocks = 0;
+        const int budget = kSlabWords - 64;         // room for the line-aligned head
+        if (plane_in <= budget) {
+            long long p = budget / plane_in;
+            const long long min_blocks = 2048;      // keep the chip busy when the tensor allows
+            if (planes / p < min_blocks) p = planes / min_blocks > 0 ? planes / min_blocks : 1;
+            if (p * (long long)g.Ho * g.Wo < (1 << 30)) {
+                plan.planes_per_wg = (int)p;
+                plan.rows_per_wg = g.Ho;
+                plan.strips = 1;
+                blocks = ceil_div64(planes, p);
+                ok = true;
+            }
+        } else {
+            const long long max_in_rows = budget / g.W;
+            long long rows_out = (max_in_rows - g.kh) / g.sh + 1;
+            if (max_in_rows >= g.kh && rows_out >= 1) {
+                if (rows_out > g.Ho) rows_out = g.Ho;
+                plan.planes_per_wg = 1;
+                plan.rows_per_wg = (int)rows_out;
+                plan.strips = ceil_div(g.Ho, rows_out);
+                blocks = planes * plan.strips;
+                ok = true;
+            }
+        }
+        if (ok && blocks <= 0x7fffffffLL) {
+            if (g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2)
+                return launch_pool16_slab<E, MODE, 3, 3, 2, 2>(src, dst, g, plan, blocks, st);
+            if (g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2)
+                return launch_pool16_slab<E, MODE, 2, 2, 2, 2>(src, dst, g, plan, blocks, st);
+            return launch_pool16_slab<E, MODE, 0, 0, 0, 0>(src, dst, g, plan, blocks, st);
+        }
+    }
+    return launch_pool16_generic<E, MODE>(src, dst, g, 0, st);
+}
+
+// =============================================================================
+// Softmax (Section II.A steps 1-5, Section V.B)
+// =============================================================================
+
+// One row per TPR lanes, ITEMS 128-bit vectors (8 categories each) per lane, kept in
+// registers as fp32.  A row starts `mis` words past a boundary of `align` words
+// (64 = a 128-byte line when both buffers share their offset inside lines, else 8)
+// and is split into a head of h = (align - mis) % align words, a body of nbody
+// aligned vectors and a tail of t < 8 words; head and tail words ride in one extra
+// register of lanes 0 .. h + t - 1 (h + t <= 70 <= TPR).
+template <class E, int TPR, int ITEMS>
+__global__ __launch_bounds__(TPR < 256 ? 256 : TPR) void softmax16_rows_kernel(
+    const uint16_t* logits, uint16_t* probs, int N, int classes, int base_mis, int align) {
+    constexpr int BLOCK = TPR < 256 ? 256 : TPR;
+    constexpr int ROWS = BLOCK / TPR;
+    __shared__ float slots[BLOCK / kWave];
+    const int tid = threadIdx.x;
+    const int wave = tid / kWave;
+    const int row_in_block = tid / TPR;
+    const int lane = tid % TPR;
+    const int first_wave = row_in_block * (TPR / kWave);
+    const long long row_raw = (long long)blockIdx.x * ROWS + row_in_block;
+    const bool live = row_raw < N;
+    const long long row = live ? row_raw : (long long)N - 1;
+    const size_t row_off = (size_t)row * (size_t)classes;
+    const int mis = (int)((row_off + (size_t)base_mis) & (size_t)(align - 1));
+    const int h = (align - mis) & (align - 1);
+    const int nbody = (classes - h) >> 3;
+    const int t = classes - h - 8 * nbody;
+    const uint16_t* x = logits + row_off;
+    uint16_t* y = probs + row_off;
+
+    u32x4 raw[ITEMS];
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+        const int q = lane + k * TPR;
+        const int qc = q < nbody ? q : nbody - 1;
+        raw[k] = ld16_stream(x + h + 8 * qc);
+    }
+    const bool is_edge = lane < h + t;
+    const int edge_idx = lane < h ? lane : h + 8 * nbody + (lane - h);
+    float e = kNegInf;
+    if (is_edge) e = E::widen(x[edge_idx]);
+
+    float v[ITEMS][8];
+    float m = e;
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+        unpack8<E>(raw[k], v[k]);
+        const bool in_row = lane + k * TPR < nbody;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            if (!in_row) v[k][c] = kNegInf;
+            m = fmaxf(m, v[k][c]);
+        }
+    }
+    m = row_reduce<MaxOp, TPR>(m, slots, wave, first_wave);
+
+    e = exp_nonpos(e - m);
+    float s = e;
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+        float part = 0.f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            v[k][c] = exp_nonpos(v[k][c] - m);
+            part += v[k][c];
+        }
+        s += part;
+    }
+    s = row_reduce<SumOp, TPR>(s, slots, wave, first_wave);
+
+    const float inv = 1.0f / s;
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+        const int q = lane + k * TPR;
+        if (live && q < nbody) {
+            float o[8];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) o[c] = v[k][c] * inv;
+            st16_stream(y + h + 8 * q, pack8<E>(o));
+        }
+    }
+    if (live && is_edge) y[edge_idx] = (uint16_t)E::narrow(e * inv);
+}
+
+// Short rows, rows too long for registers, or buffers whose 16-byte phases differ:
+// one workgroup of 256 lanes per row, word accesses, three sweeps over the row.
+template <class E>
+__global__ __launch_bounds__(256) void softmax16_stream_kernel(const uint16_t* logits, uint16_t* probs, int classes) {
+    constexpr int TPR = 256;
+    __shared__ float slots[TPR / kWave];
+    const int tid = threadIdx.x;
+    const int wave = tid / kWave;
+    const size_t row_off = (size_t)blockIdx.x * (size_t)classes;
+    const uint16_t* x = logits + row_off;
+    uint16_t* y = probs + row_off;
+    float m = kNegInf;
+    for (int c = tid; c < classes; c += TPR) m = fmaxf(m, E::widen(x[c]));
+    m = row_reduce<MaxOp, TPR>(m, slots, wave, 0);
+    float s = 0.f;
+    for (int c = tid; c < classes; c += TPR) s += exp_nonpos(E::widen(x[c]) - m);
+    s = row_reduce<SumOp, TPR>(s, slots, wave, 0);
+    const float inv = 1.0f / s;
+    for (int c = tid; c < classes; c += TPR) y[c] = (uint16_t)E::narrow(exp_nonpos(E::widen(x[c]) - m) * inv);
+}
+
+template <class E, int TPR, int ITEMS>
+int launch_rows16(const uint16_t* logits, uint16_t* probs, int N, int classes, int base_mis, int align,
+                  hipStream_t st) {
+    constexpr int BLOCK = TPR < 256 ? 256 : TPR;
+    constexpr int ROWS = BLOCK / TPR;
+    hipLaunchKernelGGL((softmax16_rows_kernel<E, TPR, ITEMS>), dim3((unsigned)ceil_div64(N, ROWS)), dim3(BLOCK), 0, st,
+                       logits, probs, N, classes, base_mis, align);
+    return launch_status();
+}
+
+template <class E, int TPR>
+int launch_rows16_items(int items, const uint16_t* logits, uint16_t* probs, int N, int classes, int base_mis, int align,
+                        hipStream_t st) {
+#define CNNMEM_CASE(I) \
+    if (items <= I) return launch_rows16<E, TPR, I>(logits, probs, N, classes, base_mis, align, st)
+    CNNMEM_CASE(1);
+    CNNMEM_CASE(2);
+    CNNMEM_CASE(3);
+    CNNMEM_CASE(4);
+    CNNMEM_CASE(6);
+    CNNMEM_CASE(8);
+#undef CNNMEM_CASE
+    return CNNMEM_ERR_UNSUPPORTED;
+}
+
+template <class E>
+int dispatch_softmax16(const uint16_t* logits, uint16_t* probs, int N, int classes, hipStream_t st) {
+    const uintptr_t pa = reinterpret_cast<uintptr_t>(logits), pb = reinterpret_cast<uintptr_t>(probs);
+    const bool same_phase = ((pa ^ pb) & 15u) == 0;
+    // lanes 0 .. h + t - 1 carry the edges: whole-line alignment (h < 64) needs at least 128 lanes per row
+    int tpr = 64;
+    const long long nq = classes / 8;
+    while (tpr < 1024 && nq > (long long)tpr * 4) tpr *= 2;
+    const int align = (((pa ^ pb) & 127u) == 0 && classes >= 256 && tpr >= 128) ? 64 : 8;
+    const int base_mis = (int)((pa & (uintptr_t)(2 * align - 1)) >> 1);
+    const long long items = ceil_div64(nq, tpr);
+    if (same_phase && classes >= 32 && items <= 8) {
+        switch (tpr) {
+            case 64: return launch_rows16_items<E, 64>((int)items, logits, probs, N, classes, base_mis, align, st);
+            case 128: return launch_rows16_items<E, 128>((int)items, logits, probs, N, classes, base_mis, align, st);
+            case 256: return launch_rows16_items<E, 256>((int)items, logits, probs, N, classes, base_mis, align, st);
+            case 512: return launch_rows16_items<E, 512>((int)items, logits, probs, N, classes, base_mis, align, st);
+            default: return launch_rows16_items<E, 1024>((int)items, logits, probs, N, classes, base_mis, align, st);
+        }
+    }
+    hipLaunchKernelGGL((softmax16_stream_kernel<E>), dim3((unsigned)N), dim3(256), 0, st, logits, probs, classes);
+    return launch_status();
+}
+
+}  // namespace
+
+// ---- entry points for api.hip (dtype: CNNMEM_F16 or CNNMEM_BF16) ----------------
+int launch_transform16(const void* src, void* dst, long long N, long long M, int src_layout, int dst_layout,
+                       hipStream_t st) {
+    const uint16_t* s = static_cast<const uint16_t*>(src);
+    uint16_t* d = static_cast<uint16_t*>(dst);
+    if (src_layout == dst_layout) {
+        const long long n = N * M;
+        const long long blocks = ceil_div64(ceil_div64(n, 8), kThreads);
+        if (blocks > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(copy16_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, s, d, (size_t)n);
+        return launch_status();
+    }
+    if (src_layout == CNNMEM_NCHW) return launch_transpose16(s, d, N, M, st);
+    return launch_transpose16(s, d, M, N, st);
+}
+
+int launch_pool16(const void* src, void* dst, const PoolGeom& g, int layout, int dtype, hipStream_t st) {
+    const uint16_t* s = static_cast<const uint16_t*>(src);
+    uint16_t* d = static_cast<uint16_t*>(dst);
+    if (dtype == CNNMEM_F16)
+        return g.mode == CNNMEM_POOL_MAX ? dispatch_pool16<Half, CNNMEM_POOL_MAX>(s, d, g, layout, st)
+                                         : dispatch_pool16<Half, CNNMEM_POOL_AVG>(s, d, g, layout, st);
+    return g.mode == CNNMEM_POOL_MAX ? dispatch_pool16<BFloat, CNNMEM_POOL_MAX>(s, d, g, layout, st)
+                                     : dispatch_pool16<BFloat, CNNMEM_POOL_AVG>(s, d, g, layout, st);
+}
+
+int launch_softmax16(const void* logits, void* probs, int N, int classes, int dtype, hipStream_t st) {
+    const uint16_t* x = static_cast<const uint16_t*>(logits);
+    uint16_t* y = static_cast<uint16_t*>(probs);
+    return dtype == CNNMEM_F16 ? dispatch_softmax16<Half>(x, y, N, classes, st)
+                               : dispatch_softmax16<BFloat>(x, y, N, classes, st);
+}
+
+}  // namespace cnnmem
