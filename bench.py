@@ -59,6 +59,8 @@ def parse_args():
     ap.add_argument("--only", default="", help="comma list of op names to run (profiling aid)")
     ap.add_argument("--workload", choices=sorted(WORKLOADS), default="largest",
                     help="; ".join(f"{k}: {v}" for k, v in sorted(WORKLOADS.items())))
+    ap.add_argument("--dtype", choices=["f32", "f16", "bf16"], default="f32",
+                    help="storage format of the tensors of the headline workload (arithmetic is fp32 in every case)")
     ap.add_argument("--graph", action="store_true",
                     help="also capture the step into a HIP graph and time its replays (removes the host's launch "
                          "cost, which dominates workloads of very small tensors)")
@@ -78,10 +80,13 @@ class Op:
         self.ms = []
 
 
-def build_ops(torch, cm, wl, rl, only):
+def build_ops(torch, cm, wl, rl, only, dtype="f32"):
     dev = torch.device("cuda:0")
     ops = []
     host = {}
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[dtype]
+    tag = {"f32": cm.F32, "f16": cm.F16, "bf16": cm.BF16}[dtype]
+    scale = 1 if dtype == "f32" else 2                       # bytes per element: 4 / scale
 
     def rotating(t, n):
         return [t] + [t.clone() for _ in range(n - 1)]
@@ -93,38 +98,41 @@ def build_ops(torch, cm, wl, rl, only):
     t = wl.config(2).transforms[0]
     if want("transform_nchw_to_chwn") or want("transform_chwn_to_nchw"):
         host["transform"] = wl.make_tensor(t, wl.rng_for(2))
-        x = torch.from_numpy(host["transform"]).to(dev)
-        nset = 4                                             # 4 x (149 + 149) MB > 1 GB
+        x = torch.from_numpy(host["transform"]).to(dev).to(tdt)
+        nset = 4 * scale                                     # 4 x (149 + 149) MB > 1 GB
         xs = rotating(x, nset)
-        cs = [torch.empty((t.C, t.H, t.W, t.N), dtype=torch.float32, device=dev) for _ in range(nset)]
-        bs = [torch.empty((t.N, t.C, t.H, t.W), dtype=torch.float32, device=dev) for _ in range(nset)]
+        cs = [torch.empty((t.C, t.H, t.W, t.N), dtype=tdt, device=dev) for _ in range(nset)]
+        bs = [torch.empty((t.N, t.C, t.H, t.W), dtype=tdt, device=dev) for _ in range(nset)]
         for i in range(nset):
             cm.transform(xs[i], t.N, t.C, t.H, t.W, cm.NCHW, cm.CHWN, out=cs[i])
-        tb = rl.transform_bytes(t.N, t.C, t.H, t.W)
+        tb = rl.transform_bytes(t.N, t.C, t.H, t.W) // scale
         if want("transform_nchw_to_chwn"):
             ops.append(Op("transform_nchw_to_chwn", "transform", tb, t.numel, "elements",
-                          lambda i: cm.cnnmem_transform(xs[i], cs[i], t.N, t.C, t.H, t.W, cm.NCHW, cm.CHWN), nset))
+                          lambda i: cm.cnnmem_transform_dtype(xs[i], cs[i], t.N, t.C, t.H, t.W, cm.NCHW, cm.CHWN, tag),
+                          nset))
         if want("transform_chwn_to_nchw"):
             ops.append(Op("transform_chwn_to_nchw", "transform", tb, t.numel, "elements",
-                          lambda i: cm.cnnmem_transform(cs[i], bs[i], t.N, t.C, t.H, t.W, cm.CHWN, cm.NCHW), nset))
+                          lambda i: cm.cnnmem_transform_dtype(cs[i], bs[i], t.N, t.C, t.H, t.W, cm.CHWN, cm.NCHW, tag),
+                          nset))
 
     # ---- pooling: config 4, first tensor ----------------------------------------------
     p = wl.config(4).pools[0].tensor
     pool_names = ["pool_max_nchw", "pool_max_chwn", "pool_avg_nchw", "pool_avg_chwn"]
     if any(want(n) for n in pool_names):
         host["pool"] = wl.make_tensor(p, wl.rng_for(4, 0))
-        x = torch.from_numpy(host["pool"]).to(dev)
-        nset = 2                                             # 2 x (822 + 206) MB
+        x = torch.from_numpy(host["pool"]).to(dev).to(tdt)
+        nset = 2 * scale                                     # 2 x (822 + 206) MB
         st, Ho, Wo = cm.cnnmem_pool_out_dims(p.H, p.W, 2, 2, 2, 2, 0, 0)
         assert st == 0
-        pb = rl.pool_bytes(p.N, p.C, p.H, p.W, 2, 2, 2, 2)
+        pb = rl.pool_bytes(p.N, p.C, p.H, p.W, 2, 2, 2, 2) // scale
         xn = rotating(x, nset)
         xc = [cm.transform(xn[i], p.N, p.C, p.H, p.W, cm.NCHW, cm.CHWN) for i in range(nset)]
-        on = [torch.empty((p.N, p.C, Ho, Wo), dtype=torch.float32, device=dev) for _ in range(nset)]
-        oc = [torch.empty((p.C, Ho, Wo, p.N), dtype=torch.float32, device=dev) for _ in range(nset)]
+        on = [torch.empty((p.N, p.C, Ho, Wo), dtype=tdt, device=dev) for _ in range(nset)]
+        oc = [torch.empty((p.C, Ho, Wo, p.N), dtype=tdt, device=dev) for _ in range(nset)]
 
         def pool_launch(src, dst, layout, mode):
-            return lambda i: cm.cnnmem_pool(src[i], dst[i], p.N, p.C, p.H, p.W, layout, mode, 2, 2, 2, 2, 0, 0)
+            return lambda i: cm.cnnmem_pool_dtype(src[i], dst[i], p.N, p.C, p.H, p.W, layout, mode, 2, 2, 2, 2, 0, 0,
+                                                  tag)
 
         table = {"pool_max_nchw": (xn, on, cm.NCHW, cm.POOL_MAX), "pool_max_chwn": (xc, oc, cm.CHWN, cm.POOL_MAX),
                  "pool_avg_nchw": (xn, on, cm.NCHW, cm.POOL_AVG), "pool_avg_chwn": (xc, oc, cm.CHWN, cm.POOL_AVG)}
@@ -136,12 +144,12 @@ def build_ops(torch, cm, wl, rl, only):
     s = wl.config(5).softmaxes[0]
     if want("softmax"):
         host["softmax"] = wl.make_logits(s, wl.rng_for(5, 0))
-        z = torch.from_numpy(host["softmax"]).to(dev)
-        nset = 2                                             # 2 x (358 + 358) MB
+        z = torch.from_numpy(host["softmax"]).to(dev).to(tdt)
+        nset = 2 * scale                                     # 2 x (358 + 358) MB
         zs = rotating(z, nset)
         ps = [torch.empty_like(z) for _ in range(nset)]
-        ops.append(Op("softmax", "softmax", rl.softmax_bytes(s.N, s.classes), s.N * s.classes, "elements",
-                      lambda i: cm.cnnmem_softmax(zs[i], ps[i], s.N, s.classes), nset))
+        ops.append(Op("softmax", "softmax", rl.softmax_bytes(s.N, s.classes) // scale, s.N * s.classes, "elements",
+                      lambda i: cm.cnnmem_softmax_dtype(zs[i], ps[i], s.N, s.classes, tag), nset))
     # ---- optional: plain copy of known size, the yardstick the traffic counters are scaled by ----
     if "copy_calibration" in only:
         n = t.numel
@@ -414,8 +422,14 @@ def main():
     only = set(filter(None, args.only.split(",")))
     builders = {"largest": build_ops, "table1": build_table1_ops, "softmax_sweep": build_softmax_sweep_ops,
                 "layout_policy": build_layout_policy_ops, "layouts": build_layouts_ops}
-    ops, host_inputs = builders[args.workload](torch, cm, wl, rl, only)
-    if args.workload != "largest":
+    if args.workload == "largest":
+        ops, host_inputs = build_ops(torch, cm, wl, rl, only, args.dtype)
+    else:
+        if args.dtype != "f32":
+            print("--dtype applies to the headline workload only", file=sys.stderr)
+            sys.exit(2)
+        ops, host_inputs = builders[args.workload](torch, cm, wl, rl, only)
+    if args.workload != "largest" or args.dtype != "f32":
         args.no_cpu_baseline = True                # the oracle baseline is reported for the headline workload
     if not ops:
         print("no op selected", file=sys.stderr)
@@ -481,7 +495,7 @@ def main():
         kernels.append({"name": op.name, "kind": op.kind, "avg_ms": round(avg_ms, 5), "median_ms": round(med_ms, 5),
                         "min_ms": round(min(op.ms), 5), "alg_bytes": op.alg_bytes,
                         "achieved": round(gbps, 1), "frac": round(gbps / rl.PEAK_HBM_GBPS, 4),
-                        "traffic": rl.MEASURED_TRAFFIC.get(op.name)})
+                        "traffic": rl.MEASURED_TRAFFIC.get(op.name) if args.dtype == "f32" else None})
         if op.name in extras:
             warm_ms, copy_ms = extras[op.name]
             kernels[-1]["warm_median_ms"] = round(warm_ms, 5)
@@ -490,7 +504,7 @@ def main():
     dominant = max(kernels, key=lambda k: k["avg_ms"])
     roofline = {"bound": "hbm", "kernel": dominant["name"], "achieved": dominant["achieved"],
                 "peak": rl.PEAK_HBM_GBPS, "unit": "GB/s", "frac": dominant["frac"],
-                "traffic": rl.MEASURED_TRAFFIC.get(dominant["name"]),
+                "traffic": dominant["traffic"],
                 "alg_bytes_per_launch": dominant["alg_bytes"], "avg_ms": dominant["avg_ms"]}
     per_kind = {}
     for kind in ("transform", "pool", "softmax"):
@@ -504,8 +518,8 @@ def main():
         "metric": "achieved HBM GB/s (and % of peak) per layer: transform, pool, softmax",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": WORKLOAD_TEXT[args.workload],
+        "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": WORKLOAD_TEXT[args.workload] + ("" if args.dtype == "f32" else f", tensors stored as {args.dtype}"),
                    "launches_per_step": len(ops), "alg_bytes_per_step": step_bytes,
                    "cache_control": "rotating buffer sets, each larger than the 256 MB last-level cache"},
         "per_layer": per_kind,

@@ -67,6 +67,7 @@ struct Half {                                       // IEEE binary16
         asm("v_cvt_f16_f32_e32 %0, %1" : "=v"(h) : "v"(x));
         return h & 0xffffu;
     }
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi) { return narrow(lo) | (narrow(hi) << 16); }
 };
 struct BFloat {                                     // upper half of binary32
     static __device__ __forceinline__ float widen(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
@@ -74,6 +75,12 @@ struct BFloat {                                     // upper half of binary32
         const uint32_t u = __float_as_uint(x);
         if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
         return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;                  // nearest even; overflow carries into infinity
+    }
+    // two values at once with the gfx950 conversion instruction (nearest even): low half = lo, high half = hi
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+        uint32_t w;
+        asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(w) : "v"(lo), "v"(hi));
+        return w;
     }
 };
 
@@ -87,10 +94,10 @@ __device__ __forceinline__ void unpack8(const u32x4& w, float* f) {
 template <class E>
 __device__ __forceinline__ u32x4 pack8(const float* f) {
     u32x4 w;
-    w.x = E::narrow(f[0]) | (E::narrow(f[1]) << 16);
-    w.y = E::narrow(f[2]) | (E::narrow(f[3]) << 16);
-    w.z = E::narrow(f[4]) | (E::narrow(f[5]) << 16);
-    w.w = E::narrow(f[6]) | (E::narrow(f[7]) << 16);
+    w.x = E::pack2(f[0], f[1]);
+    w.y = E::pack2(f[2], f[3]);
+    w.z = E::pack2(f[4], f[5]);
+    w.w = E::pack2(f[6], f[7]);
     return w;
 }
 
@@ -385,8 +392,8 @@ __global__ __launch_bounds__(kThreads) void pool16_nchw_2x2s2_kernel(
         else o[k] = ((a[2 * k] + a[2 * k + 1]) + (b[2 * k] + b[2 * k + 1])) * 0.25f;
     }
     u32x2 w;
-    w.x = E::narrow(o[0]) | (E::narrow(o[1]) << 16);
-    w.y = E::narrow(o[2]) | (E::narrow(o[3]) << 16);
+    w.x = E::pack2(o[0], o[1]);
+    w.y = E::pack2(o[2], o[3]);
     st8_stream(dst + (size_t)I * 4, w);
 }
 
