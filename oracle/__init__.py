@@ -65,6 +65,10 @@ def _load():
         lib.cnnmem_ref_pool16.restype = i
         lib.cnnmem_ref_softmax16.argtypes = [fp, fp, i, i, i]
         lib.cnnmem_ref_softmax16.restype = i
+        lib.cnnmem_ref_pool_backward.argtypes = [fp, fp, fp] + [i] * 12
+        lib.cnnmem_ref_pool_backward.restype = i
+        lib.cnnmem_ref_softmax_backward.argtypes = [fp, fp, fp, i, i]
+        lib.cnnmem_ref_softmax_backward.restype = i
         lib.cnnmem_ref_index.argtypes = [i] * 9
         lib.cnnmem_ref_index.restype = ctypes.c_ulonglong
         for name in ("cnnmem_ref_transform", "cnnmem_ref_pool_out_dims", "cnnmem_ref_pool",
@@ -149,6 +153,33 @@ def pool(src: np.ndarray, N: int, C: int, H: int, W: int, layout: int, mode: int
     _check(_load().cnnmem_ref_pool(src.ctypes.data, dst.ctypes.data, N, C, H, W, layout, mode,
                                    kh, kw, sh, sw, ph, pw), "pool")
     return dst
+
+
+def pool_backward(src, ddst: np.ndarray, N: int, C: int, H: int, W: int, layout: int, mode: int,
+                  kh: int, kw: int, sh: int, sw: int, ph: int = 0, pw: int = 0) -> np.ndarray:
+    """Gradient of ``pool`` with respect to its input; ``src`` may be None for the average."""
+    ddst = _f32(ddst)
+    Ho, Wo = pool_out_dims(H, W, kh, kw, sh, sw, ph, pw)
+    assert ddst.size == N * C * Ho * Wo
+    if src is not None:
+        src = _f32(src)
+        assert src.size == N * C * H * W
+    dsrc = np.empty(shape_of(layout, N, C, H, W), dtype=np.float32)
+    _check(_load().cnnmem_ref_pool_backward(src.ctypes.data if src is not None else None, ddst.ctypes.data,
+                                            dsrc.ctypes.data, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw),
+           "pool_backward")
+    return dsrc
+
+
+def softmax_backward(probs: np.ndarray, dprobs: np.ndarray) -> np.ndarray:
+    """Gradient with respect to the logits, given the softmax output and the gradient arriving at it."""
+    probs, dprobs = _f32(probs), _f32(dprobs)
+    assert probs.ndim == 2 and probs.shape == dprobs.shape
+    N, classes = probs.shape
+    out = np.empty_like(probs)
+    _check(_load().cnnmem_ref_softmax_backward(probs.ctypes.data, dprobs.ctypes.data, out.ctypes.data, N, classes),
+           "softmax_backward")
+    return out
 
 
 def softmax(logits: np.ndarray) -> np.ndarray:

@@ -488,3 +488,81 @@ int cnnmem_ref_softmax16(const uint16_t *logits, uint16_t *probs, int N, int cla
     }
     return failed ? REF_ERR_NOMEM : REF_OK;
 }
+
+/* ---- backward passes (training; the paper's footnote in Section II.A notes that the same
+ * data structures serve the forward and the backward pass).  The paper defines only the
+ * forward operations; these are their textbook derivatives, written as scatters over the
+ * forward definition above. ---- */
+
+/* Pooling backward.  Every output (n, c, i, j) sends its incoming gradient ddst back over
+ * its window: the average gives each in-image tap 1/(kh*kw) of it (Equation 2's divisor);
+ * the maximum gives all of it to the tap that holds the maximum, the first one in scan
+ * order (rows, then columns) when several taps tie.  Gradients are accumulated in fp64
+ * and rounded once.  `src` is the forward input (unused for the average, may be NULL),
+ * `dsrc` has the shape and layout of `src`, `ddst` those of the forward output. */
+int cnnmem_ref_pool_backward(const float *src, const float *ddst, float *dsrc, int N, int C, int H, int W,
+                             int layout, int mode, int kh, int kw, int sh, int sw, int ph, int pw)
+{
+    if (!ddst || !dsrc || (mode == REF_POOL_MAX && !src) ||
+        !pool_args_ok(N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw))
+        return REF_ERR_INVALID_ARG;
+    const int Ho = pooled_extent(H, kh, sh, ph);
+    const int Wo = pooled_extent(W, kw, sw, pw);
+    int failed = 0;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c) {
+            double *acc = (double *)calloc((size_t)H * W, sizeof(double));
+            if (!acc) {
+#pragma omp atomic write
+                failed = 1;
+                continue;
+            }
+            for (int i = 0; i < Ho; ++i)
+                for (int j = 0; j < Wo; ++j) {
+                    const double g = (double)ddst[at(layout, N, C, Ho, Wo, n, c, i, j)];
+                    int best_r = -1, best_q = -1;
+                    float best = -INFINITY;
+                    for (int y = 0; y < kh; ++y)
+                        for (int x = 0; x < kw; ++x) {
+                            const int r = i * sh - ph + y;
+                            const int q = j * sw - pw + x;
+                            if (r < 0 || r >= H || q < 0 || q >= W)
+                                continue;
+                            if (mode == REF_POOL_AVG) {
+                                acc[(size_t)r * W + q] += g / (double)(kh * kw);
+                            } else {
+                                const float v = src[at(layout, N, C, H, W, n, c, r, q)];
+                                if (best_r < 0 || v > best) { best = v; best_r = r; best_q = q; }
+                            }
+                        }
+                    if (mode == REF_POOL_MAX)
+                        acc[(size_t)best_r * W + best_q] += g;
+                }
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w)
+                    dsrc[at(layout, N, C, H, W, n, c, h, w)] = (float)acc[(size_t)h * W + w];
+            free(acc);
+        }
+    return failed ? REF_ERR_NOMEM : REF_OK;
+}
+
+/* Softmax backward: with p = softmax(z) row by row, dz_c = p_c * (dp_c - sum_k dp_k p_k)
+ * (the Jacobian diag(p) - p p^T applied to dp). */
+int cnnmem_ref_softmax_backward(const float *probs, const float *dprobs, float *dlogits, int N, int classes)
+{
+    if (!probs || !dprobs || !dlogits || N <= 0 || classes <= 0)
+        return REF_ERR_INVALID_ARG;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        const float *p = probs + (size_t)n * classes;
+        const float *dp = dprobs + (size_t)n * classes;
+        float *dz = dlogits + (size_t)n * classes;
+        double dot = 0.0;
+        for (int c = 0; c < classes; ++c)
+            dot += (double)dp[c] * (double)p[c];
+        for (int c = 0; c < classes; ++c)
+            dz[c] = (float)((double)p[c] * ((double)dp[c] - dot));
+    }
+    return REF_OK;
+}

@@ -129,3 +129,25 @@ def test_xcd_tile_order_is_a_bijection_and_groups_by_xcd(nblocks):
     for x in range(min(8, nblocks)):
         mine = [tiles[b] for b in range(x, nblocks, 8)]
         assert mine == list(range(mine[0], mine[0] + len(mine)))
+
+
+@pytest.mark.parametrize("dtype", [3, -1, 99])
+def test_dtype_entry_points_reject_unknown_formats_on_host(dtype):
+    assert cm.cnnmem_transform_dtype(FAKE, FAKE + 4096, 2, 2, 2, 2, cm.NCHW, cm.CHWN, dtype, stream=0) == INVALID
+    assert cm.cnnmem_pool_dtype(FAKE, FAKE + 4096, 2, 2, 4, 4, cm.NCHW, cm.POOL_MAX, 2, 2, 2, 2, 0, 0, dtype,
+                                stream=0) == INVALID
+    assert cm.cnnmem_softmax_dtype(FAKE, FAKE + 4096, 2, 10, dtype, stream=0) == INVALID
+
+
+@pytest.mark.parametrize("dtype", [1, 2])
+def test_dtype_entry_points_validate_like_the_fp32_ones(dtype):
+    assert cm.cnnmem_transform_dtype(FAKE, FAKE + 4096, 0, 2, 2, 2, cm.NCHW, cm.CHWN, dtype, stream=0) == INVALID
+    assert cm.cnnmem_transform_dtype(FAKE + 1, FAKE + 4096, 2, 2, 2, 2, cm.NCHW, cm.CHWN, dtype, stream=0) == INVALID
+    assert cm.cnnmem_transform_dtype(FAKE, FAKE + 4096, 2, 2, 2, 2, cm.NCHW, 7, dtype, stream=0) == INVALID
+    assert cm.cnnmem_pool_dtype(FAKE, FAKE + 4096, 2, 2, 4, 4, cm.NCHW, cm.POOL_MAX, 9, 9, 2, 2, 0, 0, dtype,
+                                stream=0) == INVALID
+    assert cm.cnnmem_pool_dtype(FAKE, FAKE + 4097, 2, 2, 4, 4, cm.NCHW, cm.POOL_MAX, 2, 2, 2, 2, 0, 0, dtype,
+                                stream=0) == INVALID
+    assert cm.cnnmem_pool_dtype(None, FAKE, 2, 2, 4, 4, cm.NCHW, cm.POOL_MAX, 2, 2, 2, 2, 0, 0, dtype, stream=0) == INVALID
+    assert cm.cnnmem_softmax_dtype(FAKE, FAKE + 4096, 2, 0, dtype, stream=0) == INVALID
+    assert cm.cnnmem_softmax_dtype(FAKE + 1, FAKE + 4096, 2, 10, dtype, stream=0) == INVALID
