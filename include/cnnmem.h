@@ -80,6 +80,32 @@ CNNMEM_API int cnnmem_relayout(const float *src, float *dst, int N, int C, int H
                                const char *src_layout, const char *dst_layout, void *hip_stream);
 
 /*
+ * Backward passes (fp32).  The paper's forward definitions (Equation 2, the softmax
+ * steps of Section II.A) differentiated; its footnote in Section II.A notes that the
+ * same data structures serve both passes.
+ *
+ * cnnmem_pool_backward: gradient of cnnmem_pool with respect to its input.
+ *   src  : device, the forward input, N*C*H*W floats in `layout`; needed for
+ *          CNNMEM_POOL_MAX only (may be null for CNNMEM_POOL_AVG).
+ *   ddst : device, the gradient arriving at the forward output, N*C*Ho*Wo floats in `layout`.
+ *   dsrc : device, out, N*C*H*W floats in `layout`; every element is written (inputs that
+ *          no window covers get 0).  Must not overlap src or ddst.
+ *   Average: each in-image tap of a window receives ddst / (kh*kw).  Maximum: the whole
+ *   ddst of a window goes to the tap holding the maximum, the first in scan order (rows,
+ *   then columns) when several tie.  No index tensor from the forward pass is needed: the
+ *   windows are re-scanned.
+ * cnnmem_softmax_backward: dlogits[n][c] = probs[n][c] * (dprobs[n][c] - sum_k dprobs[n][k]*probs[n][k]).
+ *   probs : device, the forward output; dprobs: device, the gradient arriving at it;
+ *   dlogits: device, out; N*classes floats each.  dlogits may alias dprobs or probs.
+ * Errors as for the forward entry points.
+ */
+CNNMEM_API int cnnmem_pool_backward(const float *src, const float *ddst, float *dsrc, int N, int C, int H, int W,
+                                    int layout, int mode, int kh, int kw, int sh, int sw, int ph, int pw,
+                                    void *hip_stream);
+CNNMEM_API int cnnmem_softmax_backward(const float *probs, const float *dprobs, float *dlogits, int N, int classes,
+                                       void *hip_stream);
+
+/*
  * Storage formats.  CNNMEM_F32 is what every entry point above works on.  With
  * CNNMEM_F16 (IEEE binary16) or CNNMEM_BF16 (the upper half of binary32) a tensor
  * element is 16 bits: the paper's closing remarks expect half precision to push

@@ -61,6 +61,10 @@ def library() -> ctypes.CDLL:
         lib.cnnmem_debug_canonical_permutation.argtypes = [ctypes.POINTER(i), ctypes.POINTER(i), ctypes.POINTER(i),
                                                            ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(i)]
         lib.cnnmem_debug_canonical_permutation.restype = i
+        lib.cnnmem_pool_backward.argtypes = [p, p, p] + [i] * 12 + [p]
+        lib.cnnmem_pool_backward.restype = i
+        lib.cnnmem_softmax_backward.argtypes = [p, p, p, i, i, p]
+        lib.cnnmem_softmax_backward.restype = i
         lib.cnnmem_transform_dtype.argtypes = [p, p, i, i, i, i, i, i, i, p]
         lib.cnnmem_pool_dtype.argtypes = [p, p] + [i] * 13 + [p]
         lib.cnnmem_softmax_dtype.argtypes = [p, p, i, i, i, p]
@@ -144,6 +148,15 @@ def cnnmem_debug_canonical_permutation(dims, perm):
     st = library().cnnmem_debug_canonical_permutation((ctypes.c_int * 4)(*dims), (ctypes.c_int * 4)(*perm),
                                                       ctypes.byref(rank), cd, cp)
     return st, rank.value, list(cd)[:rank.value], list(cp)[:rank.value]
+
+
+def cnnmem_pool_backward(src, ddst, dsrc, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, stream=None) -> int:
+    return library().cnnmem_pool_backward(_ptr(src), _ptr(ddst), _ptr(dsrc), N, C, H, W, layout, mode, kh, kw, sh, sw,
+                                          ph, pw, _stream(stream))
+
+
+def cnnmem_softmax_backward(probs, dprobs, dlogits, N, classes, stream=None) -> int:
+    return library().cnnmem_softmax_backward(_ptr(probs), _ptr(dprobs), _ptr(dlogits), N, classes, _stream(stream))
 
 
 def cnnmem_transform_dtype(src, dst, N, C, H, W, src_layout, dst_layout, dtype, stream=None) -> int:
@@ -260,6 +273,26 @@ def pool(src: torch.Tensor, N, C, H, W, layout, mode, kh, kw, sh, sw, ph=0, pw=0
         st = cnnmem_pool_tuned(src, out, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, tuning, stream)
     if st:
         raise CnnmemError(st, "cnnmem_pool")
+    return out
+
+
+def pool_backward(src, ddst: torch.Tensor, N, C, H, W, layout, mode, kh, kw, sh, sw, ph=0, pw=0, out=None,
+                  stream=None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty(_shape(layout, N, C, H, W), dtype=torch.float32, device=ddst.device)
+    st = cnnmem_pool_backward(src, ddst, out, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, stream)
+    if st:
+        raise CnnmemError(st, "cnnmem_pool_backward")
+    return out
+
+
+def softmax_backward(probs: torch.Tensor, dprobs: torch.Tensor, out=None, stream=None) -> torch.Tensor:
+    N, classes = probs.shape
+    if out is None:
+        out = torch.empty_like(probs)
+    st = cnnmem_softmax_backward(probs, dprobs, out, N, classes, stream)
+    if st:
+        raise CnnmemError(st, "cnnmem_softmax_backward")
     return out
 
 

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 LIB_PATH = os.path.join(HERE, "libcnnmem.so")
-SOURCES = ["api.hip", "transform.hip", "permute.hip", "pool.hip", "softmax.hip", "storage16.hip"]
+SOURCES = ["api.hip", "transform.hip", "permute.hip", "pool.hip", "softmax.hip", "storage16.hip", "backward.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

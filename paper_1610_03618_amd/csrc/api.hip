@@ -135,6 +135,34 @@ int cnnmem_softmax(const float* logits, float* probs, int N, int classes, void* 
     return launch_softmax(logits, probs, N, classes, static_cast<hipStream_t>(hip_stream));
 }
 
+int cnnmem_pool_backward(const float* src, const float* ddst, float* dsrc, int N, int C, int H, int W, int layout,
+                         int mode, int kh, int kw, int sh, int sw, int ph, int pw, void* hip_stream) {
+    if (!ddst || !dsrc || N <= 0 || C <= 0) return CNNMEM_ERR_INVALID_ARG;
+    if (!window_ok(H, W, kh, kw, sh, sw, ph, pw)) return CNNMEM_ERR_INVALID_ARG;
+    if (!layout_ok(layout)) return CNNMEM_ERR_INVALID_ARG;
+    if (mode != CNNMEM_POOL_MAX && mode != CNNMEM_POOL_AVG) return CNNMEM_ERR_INVALID_ARG;
+    if (mode == CNNMEM_POOL_MAX && !src) return CNNMEM_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(ddst) | reinterpret_cast<uintptr_t>(dsrc)) & 3u)
+        return CNNMEM_ERR_INVALID_ARG;
+    if ((long long)H * W > (1LL << 30) || (long long)kh * kw > (1 << 24)) return CNNMEM_ERR_UNSUPPORTED;
+    PoolGeom g;
+    g.N = N; g.C = C; g.H = H; g.W = W;
+    g.kh = kh; g.kw = kw; g.sh = sh; g.sw = sw; g.ph = ph; g.pw = pw;
+    g.mode = mode;
+    g.Ho = pooled_extent(H, kh, sh, ph);
+    g.Wo = pooled_extent(W, kw, sw, pw);
+    return launch_pool_backward(src, ddst, dsrc, g, layout, static_cast<hipStream_t>(hip_stream));
+}
+
+int cnnmem_softmax_backward(const float* probs, const float* dprobs, float* dlogits, int N, int classes,
+                            void* hip_stream) {
+    if (!probs || !dprobs || !dlogits || N <= 0 || classes <= 0) return CNNMEM_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(probs) | reinterpret_cast<uintptr_t>(dprobs) |
+         reinterpret_cast<uintptr_t>(dlogits)) & 3u)
+        return CNNMEM_ERR_INVALID_ARG;
+    return launch_softmax_backward(probs, dprobs, dlogits, N, classes, static_cast<hipStream_t>(hip_stream));
+}
+
 int cnnmem_transform_dtype(const void* src, void* dst, int N, int C, int H, int W, int src_layout, int dst_layout,
                            int dtype, void* hip_stream) {
     if (dtype == CNNMEM_F32)

@@ -164,6 +164,12 @@ int launch_pool_chwn(const float* src, float* dst, const PoolGeom& g, const Pool
 
 int launch_softmax(const float* logits, float* probs, int N, int classes, hipStream_t st);
 
+// backward passes (fp32)
+int launch_pool_backward(const float* src, const float* ddst, float* dsrc, const PoolGeom& g, int layout,
+                         hipStream_t st);
+int launch_softmax_backward(const float* probs, const float* dprobs, float* dlogits, int N, int classes,
+                            hipStream_t st);
+
 // 16-bit storage (dtype CNNMEM_F16 / CNNMEM_BF16); the transform sees the tensor as an [N][M] / [M][N] matrix
 int launch_transform16(const void* src, void* dst, long long N, long long M, int src_layout, int dst_layout,
                        hipStream_t st);
