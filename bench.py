@@ -37,6 +37,8 @@ WORKLOADS = {
     "softmax_sweep": "softmax over batch size x categories (Fig. 13's range)",
     "layouts": "changes between the named storage orders (NCHW, NHWC, CHWN, HWCN) on the config 2 tensor, a VGG "
                "tensor and an RGB input batch (Section I, IV.A)",
+    "backward": "backward passes: pooling 2x2/s2 on 64x64x224x224 and 3x3/s2 on 128x96x55x55 (both layouts, max and "
+                "avg), softmax on 4096x21841",
     "layout_policy": "the three AlexNet pooling layers of config 3 under both layout policies: pool where the "
                      "data is (NCHW) against transform + pool in CHWN + transform back (Section IV.B, IV.D)",
 }
@@ -46,6 +48,7 @@ WORKLOAD_TEXT = {
     "table1": "Table 1 of the paper: max-pool PL1..PL10 in NCHW and CHWN, softmax CLASS1..CLASS5",
     "softmax_sweep": "softmax, batch 32..256 x categories 10..10000 (the range of Fig. 13)",
     "layouts": "storage-order changes among NCHW / NHWC / CHWN / HWCN on 128x96x55x55, 64x64x112x112 and 64x3x224x224",
+    "backward": "backward of max/avg pooling (64x64x224x224 2x2/s2, 128x96x55x55 3x3/s2; NCHW and CHWN) and of softmax (4096x21841)",
     "layout_policy": "config 3 (AlexNet, N=128) max-pool 3x3/s2 x3: NCHW in place vs NCHW->CHWN + pool + CHWN->NCHW",
 }
 
@@ -242,6 +245,40 @@ def build_layouts_ops(torch, cm, wl, rl, only):
     return ops, {}
 
 
+def build_backward_ops(torch, cm, wl, rl, only):
+    """Backward passes on the headline tensors."""
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device="cuda").manual_seed(1616)
+    ops = []
+    for (N, C, H, W, k, s_) in [(64, 64, 224, 224, 2, 2), (128, 96, 55, 55, 3, 2)]:
+        st, Ho, Wo = cm.cnnmem_pool_out_dims(H, W, k, k, s_, s_, 0, 0)
+        n_in, n_out = N * C * H * W, N * C * Ho * Wo
+        ns = _nsets_for(4 * (2 * n_in + n_out))
+        x = [torch.randn(n_in, device=dev, generator=gen).relu_() for _ in range(ns)]
+        dy = [torch.randn(n_out, device=dev, generator=gen) for _ in range(ns)]
+        dx = [torch.empty(n_in, dtype=torch.float32, device=dev) for _ in range(ns)]
+        for layout, ltag in ((cm.NCHW, "nchw"), (cm.CHWN, "chwn")):
+            for mode, mtag in ((cm.POOL_MAX, "max"), (cm.POOL_AVG, "avg")):
+                name = f"pool_bwd_{mtag}_{ltag}_{C}x{H}x{W}"
+                if only and name not in only:
+                    continue
+                b = rl.pool_backward_bytes(N, C, H, W, k, k, s_, s_, needs_input=(mode == cm.POOL_MAX))
+                ops.append(Op(name, "pool", b, n_in, "input elements",
+                              (lambda x, dy, dx, N, C, H, W, layout, mode, k, s_:
+                               lambda i: cm.cnnmem_pool_backward(x[i], dy[i], dx[i], N, C, H, W, layout, mode, k, k, s_, s_, 0, 0))(
+                                  x, dy, dx, N, C, H, W, layout, mode, k, s_), ns))
+    n, c = 4096, 21841
+    if not only or "softmax_bwd" in only:
+        ns = 2
+        p = [torch.softmax(torch.randn((n, c), device=dev, generator=gen) * 3, dim=1) for _ in range(ns)]
+        dp = [torch.randn((n, c), device=dev, generator=gen) for _ in range(ns)]
+        dz = [torch.empty((n, c), dtype=torch.float32, device=dev) for _ in range(ns)]
+        ops.append(Op("softmax_bwd", "softmax", rl.softmax_backward_bytes(n, c), n * c, "elements",
+                      lambda i: cm.cnnmem_softmax_backward(p[i], dp[i], dz[i], n, c), ns))
+    torch.cuda.synchronize()
+    return ops, {}
+
+
 def build_layout_policy_ops(torch, cm, wl, rl, only):
     """Config 3's three pooling layers, data arriving and leaving in NCHW (what the neighbouring
     convolutions of AlexNet prefer at N = 128, C >= 96 under Section IV.A's rule): either pool in NCHW, or follow
@@ -421,7 +458,8 @@ def main():
     torch.cuda.set_device(0)
     only = set(filter(None, args.only.split(",")))
     builders = {"largest": build_ops, "table1": build_table1_ops, "softmax_sweep": build_softmax_sweep_ops,
-                "layout_policy": build_layout_policy_ops, "layouts": build_layouts_ops}
+                "layout_policy": build_layout_policy_ops, "layouts": build_layouts_ops,
+                "backward": build_backward_ops}
     if args.workload == "largest":
         ops, host_inputs = build_ops(torch, cm, wl, rl, only, args.dtype)
     else:

@@ -142,7 +142,373 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_chwn_vec4_kernel(
     st4_stream(dsrc + 4 * (size_t)u, acc);
 }
 
-// Windows larger than 8 x 8 in the compiled-for-any-window instance fall back to the generic kernel (host).
+// ---- CHWN, no padding, square window K and stride S known at compile time ---------------
+// A lane owns four images of one S x S cell of inputs (the inputs that share their set of
+// windows).  The NW x NW windows that touch the cell span RR x RR taps, RR = S*(NW-1) + K:
+// the lane loads them once (25 float4 for 3x3 / stride 2 instead of the 81 that four
+// separate lanes would ask for), finds the first maximum of each window once, and hands
+// each window's gradient to the cell element that holds it.
+template <int MODE, int K, int S>
+__global__ __launch_bounds__(kThreads) void pool_bwd_chwn_cell_kernel(
+    const float* __restrict__ src, const float* __restrict__ ddst, float* __restrict__ dsrc, PoolGeom g,
+    uint32_t items, FastDiv div_n4, FastDiv div_cw, FastDiv div_ch) {
+    constexpr int NW = (K - 1) / S + 1;             // windows per axis that touch a cell
+    constexpr int RR = S * (NW - 1) + K;            // taps per axis they span
+    const uint32_t u = blockIdx.x * kThreads + threadIdx.x;
+    if (u >= items) return;
+    // u = ((c*cells_h + ci)*cells_w + cj)*N4 + n4
+    uint32_t t = fd_div(u, div_n4);
+    const uint32_t n4 = u - t * div_n4.d;
+    uint32_t t2 = fd_div(t, div_cw);
+    const int cj = (int)(t - t2 * div_cw.d);
+    const uint32_t c = fd_div(t2, div_ch);
+    const int ci = (int)(t2 - c * div_ch.d);
+    const int N = g.N;
+    const int i0 = ci - (NW - 1), j0 = cj - (NW - 1);          // first window of the cell, may be negative
+    const int r0 = S * i0, q0 = S * j0;                        // first tap row / column, may be negative
+
+    // incoming gradients of the NW x NW windows; windows outside the output contribute nothing
+    float4 gy[NW][NW];
+    const float* gplane = ddst + (size_t)c * g.Ho * g.Wo * N + 4 * n4;
+#pragma unroll
+    for (int a = 0; a < NW; ++a)
+#pragma unroll
+        for (int b = 0; b < NW; ++b) {
+            const int i = i0 + a, j = j0 + b;
+            const bool ok = i >= 0 && i < g.Ho && j >= 0 && j < g.Wo;
+            const int ic = i < 0 ? 0 : (i < g.Ho ? i : g.Ho - 1), jc = j < 0 ? 0 : (j < g.Wo ? j : g.Wo - 1);
+            float4 v = *reinterpret_cast<const float4*>(gplane + ((size_t)ic * g.Wo + jc) * N);
+            if (!ok) v = make_float4(0.f, 0.f, 0.f, 0.f);
+            gy[a][b] = v;
+        }
+
+    float4 dx[S][S];
+#pragma unroll
+    for (int ey = 0; ey < S; ++ey)
+#pragma unroll
+        for (int ex = 0; ex < S; ++ex) dx[ey][ex] = make_float4(0.f, 0.f, 0.f, 0.f);
+
+    if (MODE == CNNMEM_POOL_AVG) {
+#pragma unroll
+        for (int a = 0; a < NW; ++a)
+#pragma unroll
+            for (int b = 0; b < NW; ++b)
+#pragma unroll
+                for (int ey = 0; ey < S; ++ey)
+#pragma unroll
+                    for (int ex = 0; ex < S; ++ex) {
+                        // cell element (ey, ex) is tap (y, x) of window (a, b) when 0 <= y, x < K
+                        const int y = S * (NW - 1 - a) + ey, x = S * (NW - 1 - b) + ex;
+                        if (y < K && x < K) {
+                            dx[ey][ex].x += gy[a][b].x; dx[ey][ex].y += gy[a][b].y;
+                            dx[ey][ex].z += gy[a][b].z; dx[ey][ex].w += gy[a][b].w;
+                        }
+                    }
+        const float inv = 1.0f / (float)(K * K);
+#pragma unroll
+        for (int ey = 0; ey < S; ++ey)
+#pragma unroll
+            for (int ex = 0; ex < S; ++ex)
+                dx[ey][ex] = make_float4(dx[ey][ex].x * inv, dx[ey][ex].y * inv, dx[ey][ex].z * inv, dx[ey][ex].w * inv);
+    } else {
+        // every tap the windows span, loaded once from clamped addresses (a clamped tap only ever
+        // belongs to a window outside the output, whose gradient is zero)
+        const float* plane = src + (size_t)c * g.H * g.W * N + 4 * n4;
+        float4 xv[RR][RR];
+#pragma unroll
+        for (int y = 0; y < RR; ++y) {
+            const int r = r0 + y;
+            const int rc = r < 0 ? 0 : (r < g.H ? r : g.H - 1);
+#pragma unroll
+            for (int x = 0; x < RR; ++x) {
+                const int q = q0 + x;
+                const int qc = q < 0 ? 0 : (q < g.W ? q : g.W - 1);
+                xv[y][x] = *reinterpret_cast<const float4*>(plane + ((size_t)rc * g.W + qc) * N);
+            }
+        }
+#pragma unroll
+        for (int a = 0; a < NW; ++a)
+#pragma unroll
+            for (int b = 0; b < NW; ++b) {
+                // first maximum of window (a, b) in scan order, per image: index y*K + x
+                float4 best = xv[S * a][S * b];
+                int kx = 0, ky = 0, kz = 0, kw = 0;
+#pragma unroll
+                for (int y = 0; y < K; ++y)
+#pragma unroll
+                    for (int x = 0; x < K; ++x) {
+                        if (y == 0 && x == 0) continue;
+                        const float4 v = xv[S * a + y][S * b + x];
+                        const int idx = y * K + x;
+                        if (v.x > best.x) { best.x = v.x; kx = idx; }
+                        if (v.y > best.y) { best.y = v.y; ky = idx; }
+                        if (v.z > best.z) { best.z = v.z; kz = idx; }
+                        if (v.w > best.w) { best.w = v.w; kw = idx; }
+                    }
+#pragma unroll
+                for (int ey = 0; ey < S; ++ey)
+#pragma unroll
+                    for (int ex = 0; ex < S; ++ex) {
+                        const int y = S * (NW - 1 - a) + ey, x = S * (NW - 1 - b) + ex;
+                        if (y < K && x < K) {
+                            const int idx = y * K + x;
+                            if (kx == idx) dx[ey][ex].x += gy[a][b].x;
+                            if (ky == idx) dx[ey][ex].y += gy[a][b].y;
+                            if (kz == idx) dx[ey][ex].z += gy[a][b].z;
+                            if (kw == idx) dx[ey][ex].w += gy[a][b].w;
+                        }
+                    }
+            }
+    }
+    float* oplane = dsrc + (size_t)c * g.H * g.W * N + 4 * n4;
+#pragma unroll
+    for (int ey = 0; ey < S; ++ey) {
+        const int h = S * ci + ey;
+#pragma unroll
+        for (int ex = 0; ex < S; ++ex) {
+            const int w = S * cj + ex;
+            if (h < g.H && w < g.W) st4_stream(oplane + ((size_t)h * g.W + w) * N, dx[ey][ex]);
+        }
+    }
+}
+
+// ---- NCHW through LDS --------------------------------------------------------------------
+// A workgroup takes whole (n, c) planes, or a strip of input rows of one plane, streams
+// the incoming gradients of every window that touches them (and, for the maximum, the
+// input rows those windows span) into LDS with line-aligned 128-bit loads, and then one
+// lane per input element gathers from LDS.  The strip's gradients leave as one
+// contiguous run with line-aligned wavefront stores.
+constexpr int kBwdSlabFloats = 15360;               // at most 60 KB of LDS per workgroup (sized per launch)
+constexpr int kBwdThreads = 512;
+
+struct BwdSlabPlan {
+    int planes_per_wg;      // whole planes per workgroup ...
+    int rows_per_wg;        // ... or input rows per strip
+    int strips;
+    long long total_planes;
+};
+
+// streams floats [lo, hi) of `p` (16-byte aligned base, `total` floats long) into dst_lds so that
+// element e sits at dst_lds[e - a_lo]; returns a_lo, the aligned start.  All loads unconditional.
+template <int VEC>
+__device__ __forceinline__ size_t stream_to_lds(const float* __restrict__ p, size_t lo, size_t hi, size_t total,
+                                                float* dst_lds) {
+    const size_t mask = (reinterpret_cast<uintptr_t>(p) & 127u) == 0 ? 31 : 3;
+    const size_t a_lo = lo & ~mask;
+    const int nvec = (int)((hi - a_lo + 3) >> 2);
+    const size_t a_last = (total - 4) & ~(size_t)3;            // total >= 4 (dispatch)
+    // rounds of kBwdThreads vectors; a round past the end of the part is skipped by the whole
+    // workgroup (uniform), inside a round every load is unconditional
+    float4 v[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+        if (k * kBwdThreads >= nvec) break;
+        const int q = threadIdx.x + k * kBwdThreads;
+        size_t a = a_lo + 4 * (size_t)(q < nvec ? q : 0);
+        a = a <= a_last ? a : a_last;
+        v[k] = ld4_stream(p + a);
+    }
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+        if (k * kBwdThreads >= nvec) break;
+        const int q = threadIdx.x + k * kBwdThreads;
+        const size_t a = a_lo + 4 * (size_t)q;
+        if (q < nvec && a <= a_last) *reinterpret_cast<float4*>(dst_lds + 4 * q) = v[k];
+        if (q < nvec && a > a_last)
+            for (int j = 0; j < 4; ++j)
+                if (a + j < total) dst_lds[4 * q + j] = p[a + j];
+    }
+    return a_lo;
+}
+
+extern __shared__ float4 bwd_dyn_lds[];             // 16-byte aligned dynamic LDS, sized by the launch
+
+// LDS: [ input rows, later the results | gradient rows | position of each window's first maximum (maximum only) ]
+// Phase A (maximum): one lane per window finds its first maximum once.  Phase B: a lane takes four
+// consecutive input elements, adds up the gradients of the windows that own each (one LDS compare per
+// window instead of a re-scan), and stores 128 bits.
+template <int MODE, int KH, int KW, int SH, int SW>
+__global__ __launch_bounds__(kBwdThreads) void pool_bwd_nchw_slab_kernel(
+    const float* __restrict__ src, const float* __restrict__ ddst, float* __restrict__ dsrc, PoolGeom g,
+    BwdSlabPlan plan, int x_floats, int gy_floats, FastDiv div_w, FastDiv div_plane_in, FastDiv div_wo,
+    FastDiv div_plane_out) {
+    constexpr int VEC = kBwdSlabFloats / 4 / kBwdThreads + 1;
+    float* slab = reinterpret_cast<float*>(bwd_dyn_lds);
+    const int kh = KH ? KH : g.kh, kw = KW ? KW : g.kw, sh = SH ? SH : g.sh, sw = SW ? SW : g.sw;
+    const uint32_t tile = xcd_contiguous_tile(blockIdx.x, gridDim.x);
+    const int plane_in = g.H * g.W, plane_out = g.Ho * g.Wo;
+
+    long long p0;
+    int planes, h0, rows;
+    if (plan.strips == 1) {
+        p0 = (long long)tile * plan.planes_per_wg;
+        const long long left = plan.total_planes - p0;
+        planes = left < plan.planes_per_wg ? (int)left : plan.planes_per_wg;
+        h0 = 0;
+        rows = g.H;
+    } else {
+        p0 = tile / (uint32_t)plan.strips;
+        planes = 1;
+        h0 = (int)(tile % (uint32_t)plan.strips) * plan.rows_per_wg;
+        rows = g.H - h0 < plan.rows_per_wg ? g.H - h0 : plan.rows_per_wg;
+    }
+    // windows (rows of ddst) that touch input rows [h0, h0 + rows)
+    int i_lo, i_hi, tmp;
+    window_range(h0, kh, sh, g.ph, g.Ho, i_lo, tmp);
+    window_range(h0 + rows - 1, kh, sh, g.ph, g.Ho, tmp, i_hi);
+    if (planes > 1) { i_lo = 0; i_hi = g.Ho - 1; }
+    const bool have_windows = i_hi >= i_lo;
+    float* gy_lds = slab + x_floats;                  // x_floats and gy_floats are multiples of 4
+    int* amax_lds = reinterpret_cast<int*>(slab + x_floats + gy_floats);
+    size_t gy_a_lo = 0, x_a_lo = 0;
+    if (have_windows) {
+        const size_t lo = (size_t)p0 * plane_out + (size_t)i_lo * g.Wo;
+        const size_t hi = (size_t)(p0 + planes - 1) * plane_out + (size_t)(i_hi + 1) * g.Wo;
+        gy_a_lo = stream_to_lds<VEC>(ddst, lo, hi, (size_t)plan.total_planes * plane_out, gy_lds);
+        if (MODE == CNNMEM_POOL_MAX) {
+            int xr_lo = i_lo * sh - g.ph, xr_hi = i_hi * sh - g.ph + kh;
+            if (xr_lo < 0) xr_lo = 0;
+            if (xr_hi > g.H) xr_hi = g.H;
+            if (planes > 1) { xr_lo = 0; xr_hi = g.H; }
+            const size_t xlo = (size_t)p0 * plane_in + (size_t)xr_lo * g.W;
+            const size_t xhi = (size_t)(p0 + planes - 1) * plane_in + (size_t)xr_hi * g.W;
+            x_a_lo = stream_to_lds<VEC>(src, xlo, xhi, (size_t)plan.total_planes * plane_in, slab);
+        }
+    }
+    __syncthreads();
+    // LDS index of element (plane p0, row 0, col 0) of x and of ddst
+    const long long x_base = (long long)((size_t)p0 * plane_in) - (long long)x_a_lo;
+    const long long gy_base = (long long)((size_t)p0 * plane_out) - (long long)gy_a_lo;
+
+    if (MODE == CNNMEM_POOL_MAX && have_windows) {
+        // phase A: window (pl, i, j), i in [i_lo, i_hi], flattened like its place in ddst
+        const int win_rows = i_hi - i_lo + 1;
+        const int n_win = planes > 1 ? planes * plane_out : win_rows * g.Wo;
+        for (int v = threadIdx.x; v < n_win; v += kBwdThreads) {
+            int pl = 0, rem = v;
+            if (planes > 1) {
+                pl = (int)fd_div((uint32_t)v, div_plane_out);
+                rem = v - pl * plane_out;
+            }
+            const int il = (int)fd_div((uint32_t)rem, div_wo);
+            const int j = rem - il * g.Wo;
+            const int i = i_lo + il;
+            const float* xs = slab + (x_base + (long long)pl * plane_in);
+            float best = kNegInf;
+            int where = -1;
+            for (int y = 0; y < kh; ++y) {
+                const int r = i * sh - g.ph + y;
+                if (r < 0 || r >= g.H) continue;
+                for (int x = 0; x < kw; ++x) {
+                    const int q = j * sw - g.pw + x;
+                    if (q < 0 || q >= g.W) continue;
+                    const float val = xs[r * g.W + q];
+                    if (where < 0 || val > best) { best = val; where = r * g.W + q; }
+                }
+            }
+            amax_lds[gy_base + (long long)pl * plane_out + i * g.Wo + j] = where;
+        }
+        __syncthreads();
+    }
+
+    const int n_elems = planes * rows * g.W;          // planes > 1 implies rows == H
+    const size_t out0 = (size_t)p0 * plane_in + (size_t)h0 * g.W;
+    // phase B writes the input gradients into LDS over the input rows, which phase A was the last to read
+    float* stage = slab;
+    if (KH != 0 && KH == KW && SH == SW && g.ph == 0 && g.pw == 0) {
+        // Compile-time square window without padding: a lane takes one S x S cell of inputs, the
+        // inputs that share their NW x NW windows, reads those windows' gradients (and owners)
+        // once, and writes S runs of S words.  Strips start on cell boundaries (launcher).
+        constexpr int K = KH ? KH : 1, S = SH ? SH : 1;
+        constexpr int NW = (K - 1) / S + 1;
+        const int cells_w = (g.W + S - 1) / S;
+        const int cell_rows = (rows + S - 1) / S;
+        const int n_cells = planes * cell_rows * cells_w;
+        const int ci0 = h0 / S;
+        for (int v = threadIdx.x; v < n_cells; v += kBwdThreads) {
+            const int per_plane = cell_rows * cells_w;
+            const int pl = planes > 1 ? v / per_plane : 0;
+            const int rem = v - pl * per_plane;
+            const int cil = rem / cells_w;
+            const int cj = rem - cil * cells_w;
+            const int ci = ci0 + cil;
+            const long long gofs = gy_base + (long long)pl * plane_out;
+            float gyv[NW][NW];
+            int own[NW][NW];
+#pragma unroll
+            for (int a = 0; a < NW; ++a)
+#pragma unroll
+                for (int b = 0; b < NW; ++b) {
+                    const int i = ci - (NW - 1) + a, j = cj - (NW - 1) + b;
+                    const bool ok = i >= 0 && i < g.Ho && j >= 0 && j < g.Wo;
+                    gyv[a][b] = ok ? gy_lds[gofs + i * g.Wo + j] : 0.f;
+                    own[a][b] = (ok && MODE == CNNMEM_POOL_MAX) ? amax_lds[gofs + i * g.Wo + j] : -1;
+                }
+            float* oplane = stage + (long long)pl * plane_in - (long long)h0 * g.W;
+#pragma unroll
+            for (int ey = 0; ey < S; ++ey) {
+                const int h = S * ci + ey;
+                if (h >= g.H) continue;
+#pragma unroll
+                for (int ex = 0; ex < S; ++ex) {
+                    const int w = S * cj + ex;
+                    if (w >= g.W) continue;
+                    const int me = h * g.W + w;
+                    float acc = 0.f;
+#pragma unroll
+                    for (int a = 0; a < NW; ++a)
+#pragma unroll
+                        for (int b = 0; b < NW; ++b) {
+                            const int y = S * (NW - 1 - a) + ey, x = S * (NW - 1 - b) + ex;
+                            if (y < K && x < K) {
+                                if (MODE == CNNMEM_POOL_AVG) acc += gyv[a][b];
+                                else if (own[a][b] == me) acc += gyv[a][b];
+                            }
+                        }
+                    oplane[me] = MODE == CNNMEM_POOL_AVG ? acc * (1.0f / (float)(K * K)) : acc;
+                }
+            }
+        }
+    } else {
+        // any window: one lane per input element
+        for (int o = threadIdx.x; o < n_elems; o += kBwdThreads) {
+            int pl = 0, rem = o;
+            if (planes > 1) {
+                pl = (int)fd_div((uint32_t)o, div_plane_in);
+                rem = o - pl * plane_in;
+            }
+            const int hl = (int)fd_div((uint32_t)rem, div_w);
+            const int w = rem - hl * g.W;
+            const int h = h0 + hl;
+            int a_lo, a_hi, b_lo, b_hi;
+            window_range(h, kh, sh, g.ph, g.Ho, a_lo, a_hi);
+            window_range(w, kw, sw, g.pw, g.Wo, b_lo, b_hi);
+            const long long gofs = gy_base + (long long)pl * plane_out;
+            const int me = h * g.W + w;
+            float acc = 0.f;
+            for (int i = a_lo; i <= a_hi; ++i)
+                for (int j = b_lo; j <= b_hi; ++j) {
+                    const float gyv = gy_lds[gofs + i * g.Wo + j];
+                    if (MODE == CNNMEM_POOL_AVG) acc += gyv;
+                    else if (amax_lds[gofs + i * g.Wo + j] == me) acc += gyv;
+                }
+            stage[o] = MODE == CNNMEM_POOL_AVG ? acc / (float)(kh * kw) : acc;
+        }
+    }
+    __syncthreads();
+    // phase C: the workgroup's gradients leave as one contiguous run, 128 bits per lane, each
+    // wavefront's 1 KB starting on a line of dsrc
+    const int lead = (int)(((reinterpret_cast<uintptr_t>(dsrc) >> 2) + out0) & 31);
+    for (int o = 4 * (int)threadIdx.x - lead; o < n_elems; o += 4 * kBwdThreads) {
+        float* q = dsrc + out0 + o;
+        if (o >= 0 && o + 4 <= n_elems) {
+            st4_stream(q, make_float4(stage[o], stage[o + 1], stage[o + 2], stage[o + 3]));
+        } else {
+            for (int e = 0; e < 4; ++e)
+                if (o + e >= 0 && o + e < n_elems) q[e] = stage[o + e];
+        }
+    }
+}
 
 // ---- NCHW, 2x2 / stride 2, no padding, even H, W a multiple of 4 ------------------------
 // Rows pair up across the whole tensor, every input belongs to exactly one window: a lane
@@ -205,13 +571,38 @@ int launch_bwd_chwn(const float* src, const float* ddst, float* dsrc, const Pool
     return launch_status();
 }
 
+template <int MODE, int K, int S>
+int launch_bwd_chwn_cell(const float* src, const float* ddst, float* dsrc, const PoolGeom& g, hipStream_t st) {
+    const long long cells_h = ceil_div64(g.H, S), cells_w = ceil_div64(g.W, S);
+    const long long items = (long long)g.C * cells_h * cells_w * (g.N / 4);
+    if (items >= 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((pool_bwd_chwn_cell_kernel<MODE, K, S>), dim3((unsigned)ceil_div64(items, kThreads)),
+                       dim3(kThreads), 0, st, src, ddst, dsrc, g, (uint32_t)items, make_fastdiv((uint32_t)(g.N / 4)),
+                       make_fastdiv((uint32_t)cells_w), make_fastdiv((uint32_t)cells_h));
+    return launch_status();
+}
+
+template <int MODE, int KH, int KW, int SH, int SW>
+int launch_bwd_slab(const float* src, const float* ddst, float* dsrc, const PoolGeom& g, const BwdSlabPlan& plan,
+                    int x_floats, int gy_floats, long long blocks, hipStream_t st) {
+    const size_t lds = sizeof(float) * (size_t)(x_floats + gy_floats * (MODE == CNNMEM_POOL_MAX ? 2 : 1));
+    hipLaunchKernelGGL((pool_bwd_nchw_slab_kernel<MODE, KH, KW, SH, SW>), dim3((unsigned)blocks), dim3(kBwdThreads), lds,
+                       st, src, ddst, dsrc, g, plan, x_floats, gy_floats, make_fastdiv((uint32_t)g.W),
+                       make_fastdiv((uint32_t)(g.H * g.W)), make_fastdiv((uint32_t)g.Wo),
+                       make_fastdiv((uint32_t)(g.Ho * g.Wo)));
+    return launch_status();
+}
+
 template <int MODE>
 int dispatch_pool_backward(const float* src, const float* ddst, float* dsrc, const PoolGeom& g, int layout,
                            hipStream_t st) {
     const bool a16 = aligned16(ddst) && aligned16(dsrc) && (MODE == CNNMEM_POOL_AVG || aligned16(src));
+    const bool square = g.kh == g.kw && g.sh == g.sw && g.ph == 0 && g.pw == 0;
     if (layout == CNNMEM_CHWN) {
         const long long items = (long long)g.C * g.H * g.W * (g.N / 4);
         if (a16 && g.N % 4 == 0 && items < 0x7fffffffLL && g.kh <= 8 && g.kw <= 8) {
+            if (square && g.kh == 3 && g.sh == 2) return launch_bwd_chwn_cell<MODE, 3, 2>(src, ddst, dsrc, g, st);
+            if (square && g.kh == 2 && g.sh == 2) return launch_bwd_chwn_cell<MODE, 2, 2>(src, ddst, dsrc, g, st);
             if (g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2)
                 return launch_bwd_chwn<MODE, 3, 3, 2, 2>(src, ddst, dsrc, g, st);
             if (g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2)
@@ -220,15 +611,77 @@ int dispatch_pool_backward(const float* src, const float* ddst, float* dsrc, con
         }
         return launch_bwd_generic<MODE>(src, ddst, dsrc, g, 1, st);
     }
+    const long long planes = (long long)g.N * g.C;
     if (a16 && g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2 && g.ph == 0 && g.pw == 0 && g.H % 2 == 0 &&
         g.W % 4 == 0) {
         const long long per_row = g.W / 4;
-        const long long items = (long long)g.N * g.C * g.Ho * per_row;
+        const long long items = planes * g.Ho * per_row;
         if (items < 0x7fffffffLL) {
             hipLaunchKernelGGL((pool_bwd_nchw_2x2s2_kernel<MODE>), dim3((unsigned)ceil_div64(items, kThreads)),
                                dim3(kThreads), 0, st, src, ddst, dsrc, (uint32_t)items, (uint32_t)g.W,
                                make_fastdiv((uint32_t)per_row));
             return launch_status();
+        }
+    }
+    // LDS slab: input rows, gradient rows and (maximum) one position per window share 60 KB
+    const long long plane_in = (long long)g.H * g.W, plane_out = (long long)g.Ho * g.Wo;
+    if (a16 && plane_in * planes < (1LL << 40) && plane_in * planes >= 4 && plane_out * planes >= 4) {
+        constexpr bool kMax = MODE == CNNMEM_POOL_MAX;
+        // each streamed part may start up to 31 floats before its first element and is padded to float4
+        auto part = [](long long floats) { return (int)((floats + 32 + 3) / 4 * 4); };
+        BwdSlabPlan plan;
+        plan.total_planes = planes;
+        bool ok = false;
+        long long blocks = 0;
+        int x_floats = 0, gy_floats = 0;
+        // the x part also stages the results, so the average needs it as well
+        // 32 KB per workgroup measured best on MI355X (four 512-lane workgroups per CU); up to 60 KB
+        // is accepted for planes that need it (CNNMEM_BWD_SLAB_FLOATS overrides for A/B runs)
+        int cap = env_int("CNNMEM_BWD_SLAB_FLOATS", 8192);
+        if (cap < 1024 || cap > kBwdSlabFloats) cap = kBwdSlabFloats;
+        if (part(plane_in) + part(plane_out) * (kMax ? 2 : 1) > cap && g.H * (long long)g.W <= kBwdSlabFloats)
+            cap = kBwdSlabFloats;                   // a whole plane does not fit the preferred size: take the large one
+        auto fits = [&](long long xf, long long gf) { return part(xf) + part(gf) * (kMax ? 2 : 1) <= cap; };
+        if (fits(plane_in, plane_out)) {
+            long long p = 1;
+            while (fits((p + 1) * plane_in, (p + 1) * plane_out)) ++p;
+            const long long min_blocks = 2048;
+            if (planes / p < min_blocks) p = planes / min_blocks > 0 ? planes / min_blocks : 1;
+            plan.planes_per_wg = (int)p;
+            plan.rows_per_wg = g.H;
+            plan.strips = 1;
+            blocks = ceil_div64(planes, p);
+            x_floats = part(p * plane_in);
+            gy_floats = part(p * plane_out);
+            ok = true;
+        } else {
+            // a strip of r input rows: its windows span at most r + 2*(kh - 1) input rows and
+            // (r + kh - 2) / sh + 1 gradient rows
+            auto xrows = [&](long long r) { return r + 2LL * (g.kh - 1) < g.H ? r + 2LL * (g.kh - 1) : (long long)g.H; };
+            auto grows = [&](long long r) {
+                const long long n = (r + g.kh - 2) / g.sh + 2;
+                return n < g.Ho ? n : (long long)g.Ho;
+            };
+            long long rows = g.H;
+            while (rows > 1 && !fits(xrows(rows) * g.W, grows(rows) * g.Wo)) rows = rows * 3 / 4;
+            // whole cells of sh input rows per strip (the compile-time-window kernels work on cells)
+            if (rows >= g.sh) rows = rows / g.sh * g.sh;
+            if (fits(xrows(rows) * g.W, grows(rows) * g.Wo) && (rows % g.sh == 0 || rows == g.H)) {
+                plan.planes_per_wg = 1;
+                plan.rows_per_wg = (int)rows;
+                plan.strips = ceil_div(g.H, rows);
+                blocks = planes * plan.strips;
+                x_floats = part(xrows(rows) * g.W);
+                gy_floats = part(grows(rows) * g.Wo);
+                ok = true;
+            }
+        }
+        if (ok && blocks <= 0x7fffffffLL && (long long)plan.planes_per_wg * plane_in < (1 << 30)) {
+            if (g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2)
+                return launch_bwd_slab<MODE, 3, 3, 2, 2>(src, ddst, dsrc, g, plan, x_floats, gy_floats, blocks, st);
+            if (g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2)
+                return launch_bwd_slab<MODE, 2, 2, 2, 2>(src, ddst, dsrc, g, plan, x_floats, gy_floats, blocks, st);
+            return launch_bwd_slab<MODE, 0, 0, 0, 0>(src, ddst, dsrc, g, plan, x_floats, gy_floats, blocks, st);
         }
     }
     return launch_bwd_generic<MODE>(src, ddst, dsrc, g, 0, st);

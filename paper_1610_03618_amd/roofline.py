@@ -28,6 +28,19 @@ def softmax_bytes(N: int, classes: int) -> int:
     return 2 * 4 * N * classes
 
 
+def pool_backward_bytes(N: int, C: int, H: int, W: int, kh: int, kw: int, sh: int, sw: int,
+                        ph: int = 0, pw: int = 0, needs_input: bool = True) -> int:
+    """Read the incoming gradient (and, for the maximum, the forward input), write every input gradient."""
+    Ho, Wo = pooled_extent(H, kh, sh, ph), pooled_extent(W, kw, sw, pw)
+    Hc = min(H, (Ho - 1) * sh + kh - ph)
+    Wc = min(W, (Wo - 1) * sw + kw - pw)
+    return 4 * N * C * (H * W + Ho * Wo + (Hc * Wc if needs_input else 0))
+
+
+def softmax_backward_bytes(N: int, classes: int) -> int:
+    return 3 * 4 * N * classes
+
+
 
 
 # HBM bytes per launch seen by the L2 <-> fabric counters (rocprofv3 --pmc FETCH_SIZE, then
