@@ -263,7 +263,7 @@ const char* cnnmem_status_string(int status) {
     }
 }
 
-int cnnmem_version(void) { return 100; }   // 0.1.0
+int cnnmem_version(void) { return 200; }   // 0.2.0: storage orders, 16-bit storage, backward passes
 
 unsigned cnnmem_debug_fastdiv(unsigned n, unsigned d) {
     return fd_div(n, make_fastdiv(d));

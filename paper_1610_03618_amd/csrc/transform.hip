@@ -33,7 +33,7 @@ extern __shared__ float4 dyn_tile[];                // 16-byte aligned dynamic L
 template <int TR, int TS, int THREADS>
 __global__ __launch_bounds__(THREADS) void transpose_vec4_kernel(
     const float* __restrict__ src, float* __restrict__ dst, long long R, long long S,
-    uint32_t tiles_s) {
+    uint32_t tiles_s, int xcd_order) {
     static_assert(TR % 4 == 0 && TS % 4 == 0, "tile sides are multiples of 4");
     static_assert((TR * TS / 16) % THREADS == 0, "whole number of 4x4 blocks per lane");
     constexpr int P = TR + 4;                       // LDS pitch in floats (keeps float4 alignment)
@@ -44,7 +44,7 @@ __global__ __launch_bounds__(THREADS) void transpose_vec4_kernel(
 
     float* tile = reinterpret_cast<float*>(dyn_tile);   // TS * P floats, sized by the launch
 
-    const uint32_t tile_id = blockIdx.x;
+    const uint32_t tile_id = xcd_order ? xcd_contiguous_tile(blockIdx.x, gridDim.x) : blockIdx.x;
     const long long r0 = (long long)(tile_id / tiles_s) * TR;
     const long long s0 = (long long)(tile_id % tiles_s) * TS;
     const int tid = threadIdx.x;
@@ -99,14 +99,14 @@ __global__ __launch_bounds__(THREADS) void transpose_vec4_kernel(
 // 4x4-block kernel; same LDS layout.
 template <int TR, int TS>
 __global__ __launch_bounds__(TR * TS / 4) void transpose_u1_kernel(
-    const float* __restrict__ src, float* __restrict__ dst, long long R, long long S, uint32_t tiles_s) {
-    constexpr int THREADS = TR * TS / 4;
+    const float* __restrict__ src, float* __restrict__ dst, long long R, long long S, uint32_t tiles_s,
+    int xcd_order) {
     constexpr int P = TR + 4;
     constexpr int NC4 = TS / 4;                     // float4 per source row of the tile
     constexpr int NBR = TR / 4;                     // float4 per destination row of the tile
     __shared__ __attribute__((aligned(16))) float tile[TS * P];
 
-    const uint32_t tile_id = blockIdx.x;
+    const uint32_t tile_id = xcd_order ? xcd_contiguous_tile(blockIdx.x, gridDim.x) : blockIdx.x;
     const long long r0 = (long long)(tile_id / tiles_s) * TR;
     const long long s0 = (long long)(tile_id % tiles_s) * TS;
     const int tid = threadIdx.x;
@@ -186,7 +186,7 @@ int launch_vec4(const float* src, float* dst, long long R, long long S, hipStrea
             return CNNMEM_ERR_RUNTIME;
     }
     hipLaunchKernelGGL((transpose_vec4_kernel<TR, TS, THREADS>), dim3((unsigned)tiles), dim3(THREADS), lds_bytes, st,
-                       src, dst, R, S, (uint32_t)tiles_s);
+                       src, dst, R, S, (uint32_t)tiles_s, env_int("CNNMEM_TRANSFORM_XCD", 0));
     return launch_status();
 }
 
@@ -196,7 +196,7 @@ int launch_u1(const float* src, float* dst, long long R, long long S, hipStream_
     const long long tiles = tiles_r * tiles_s;
     if (tiles > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
     hipLaunchKernelGGL((transpose_u1_kernel<TR, TS>), dim3((unsigned)tiles), dim3(TR * TS / 4), 0, st,
-                       src, dst, R, S, (uint32_t)tiles_s);
+                       src, dst, R, S, (uint32_t)tiles_s, env_int("CNNMEM_TRANSFORM_XCD", 0));
     return launch_status();
 }
 
