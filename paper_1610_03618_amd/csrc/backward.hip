@@ -20,6 +20,13 @@ namespace {
 constexpr int kThreads = 256;
 constexpr float kNegInf = kRowNegInf;
 
+// Pins a loaded value in registers.  A load whose only use is one arm of a select gets moved under a
+// branch by the compiler, and a branch per load means a full wait per load; after this the value
+// has an unconditional use, so the loads stay where they are written, back to back.
+__device__ __forceinline__ void keep(float4& v) {
+    asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w));
+}
+
 // windows (along one axis) that contain input coordinate x: lo <= i <= hi
 __device__ __forceinline__ void window_range(int x, int k, int s, int p, int n_out, int& lo, int& hi) {
     const int a = x + p - k + 1;                    // first window start that still reaches x, times s
@@ -175,12 +182,25 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_chwn_cell_kernel(
 #pragma unroll
         for (int b = 0; b < NW; ++b) {
             const int i = i0 + a, j = j0 + b;
-            const bool ok = i >= 0 && i < g.Ho && j >= 0 && j < g.Wo;
             const int ic = i < 0 ? 0 : (i < g.Ho ? i : g.Ho - 1), jc = j < 0 ? 0 : (j < g.Wo ? j : g.Wo - 1);
-            float4 v = *reinterpret_cast<const float4*>(gplane + ((size_t)ic * g.Wo + jc) * N);
-            if (!ok) v = make_float4(0.f, 0.f, 0.f, 0.f);
-            gy[a][b] = v;
+            gy[a][b] = *reinterpret_cast<const float4*>(gplane + ((size_t)ic * g.Wo + jc) * N);
         }
+
+    // called once every load of the lane has been issued: pins the gradients (see keep) and zeroes
+    // those of windows outside the output
+    auto settle_gradients = [&]() {
+#pragma unroll
+        for (int a = 0; a < NW; ++a)
+#pragma unroll
+            for (int b = 0; b < NW; ++b) keep(gy[a][b]);
+#pragma unroll
+        for (int a = 0; a < NW; ++a)
+#pragma unroll
+            for (int b = 0; b < NW; ++b) {
+                const int i = i0 + a, j = j0 + b;
+                if (!(i >= 0 && i < g.Ho && j >= 0 && j < g.Wo)) gy[a][b] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+    };
 
     float4 dx[S][S];
 #pragma unroll
@@ -189,6 +209,7 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_chwn_cell_kernel(
         for (int ex = 0; ex < S; ++ex) dx[ey][ex] = make_float4(0.f, 0.f, 0.f, 0.f);
 
     if (MODE == CNNMEM_POOL_AVG) {
+        settle_gradients();
 #pragma unroll
         for (int a = 0; a < NW; ++a)
 #pragma unroll
@@ -226,6 +247,11 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_chwn_cell_kernel(
                 xv[y][x] = *reinterpret_cast<const float4*>(plane + ((size_t)rc * g.W + qc) * N);
             }
         }
+        settle_gradients();
+#pragma unroll
+        for (int y = 0; y < RR; ++y)
+#pragma unroll
+            for (int x = 0; x < RR; ++x) keep(xv[y][x]);
 #pragma unroll
         for (int a = 0; a < NW; ++a)
 #pragma unroll
