@@ -14,21 +14,40 @@ SOURCES = ["api.hip", "transform.hip", "permute.hip", "pool.hip", "softmax.hip",
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-fvisibility=hidden", "-fno-gpu-rdc",
     # packed fp32 VALU forms are kept out of the generated code on the test machines
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
 ]
+BUILD_DIR = os.path.join(HERE, "_build")
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every HIP source into ``paper_1610_03618_amd/libcnnmem.so``."""
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    cmd = [HIPCC] + FLAGS + ["-I", INCLUDE, "-I", CSRC] + srcs + ["-o", LIB_PATH]
+def build(verbose: bool = False, jobs: int = 8) -> str:
+    """Compile every HIP source (in parallel) and link ``paper_1610_03618_amd/libcnnmem.so``."""
+    os.makedirs(BUILD_DIR, exist_ok=True)
+    pending = []
+    for name in SOURCES:
+        obj = os.path.join(BUILD_DIR, os.path.splitext(name)[0] + ".o")
+        cmd = [HIPCC] + FLAGS + ["-I", INCLUDE, "-I", CSRC, "-c", os.path.join(CSRC, name), "-o", obj]
+        pending.append((cmd, obj))
+    objs, running = [], []
+    for cmd, obj in pending:
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        running.append((subprocess.Popen(cmd), cmd))
+        objs.append(obj)
+        if len(running) >= jobs:
+            proc, c = running.pop(0)
+            if proc.wait() != 0:
+                raise subprocess.CalledProcessError(proc.returncode, c)
+    for proc, c in running:
+        if proc.wait() != 0:
+            raise subprocess.CalledProcessError(proc.returncode, c)
+    link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc"] + objs + ["-o", LIB_PATH]
     if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+        print(" ".join(link), flush=True)
+    subprocess.run(link, check=True)
     return LIB_PATH
 
 
