@@ -65,7 +65,7 @@ CNNMEM_API int cnnmem_transform(const float *src, float *dst, int N, int C, int 
  *                accesses).
  *   dims, perm : host, four ints each, read before the call returns.
  * Errors: INVALID_ARG for null pointers, extents <= 0 or a perm that is not a
- * permutation of 0..3; UNSUPPORTED beyond 2^31 - 1 tiles or items in one launch.
+ * permutation of 0..3; UNSUPPORTED beyond 2^31 - 1 tiles in one launch (far above any HBM).
  */
 CNNMEM_API int cnnmem_permute(const float *src, float *dst, const int *dims, const int *perm, void *hip_stream);
 

@@ -438,26 +438,38 @@ int launch_permute(const float* src, float* dst, const int* dims, const int* per
     ds[k - 1] = 1;
     for (int i = k - 2; i >= 0; --i) ds[i] = ds[i + 1] * e[i + 1];
     if (pm[k - 1] == k - 1) {
-        // the fastest axis stays: gather its runs
+        // the fastest axis stays: gather its runs.  The kernel addresses elements with 32 bits;
+        // larger tensors go slice by slice along the destination's slowest axis.
         const long long L = d[k - 1];
-        if (total >= 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
-        RowPlan p;
         // outer destination axes, padded at the slow end to three
         long long oe[3] = {1, 1, 1}, ot[3] = {0, 0, 0};
         for (int i = 0; i < k - 1; ++i) {
             oe[3 - (k - 1) + i] = e[i];
             ot[3 - (k - 1) + i] = ss[pm[i]];
         }
-        p.t0 = ot[0]; p.t1 = ot[1]; p.t2 = ot[2];
-        p.L = (uint32_t)L;
-        p.total = (uint32_t)total;
-        const FastDiv d_L = make_fastdiv((uint32_t)L), d_e2 = make_fastdiv((uint32_t)oe[2]),
-                      d_e1 = make_fastdiv((uint32_t)oe[1]);
-        const dim3 grid((unsigned)ceil_div64(ceil_div64(total, 4), kThreads)), block(kThreads);
-        if (aligned16(dst))
-            hipLaunchKernelGGL((permute_rows_kernel<true>), grid, block, 0, st, src, dst, p, d_L, d_e2, d_e1);
-        else
-            hipLaunchKernelGGL((permute_rows_kernel<false>), grid, block, 0, st, src, dst, p, d_L, d_e2, d_e1);
+        const int slow = 3 - (k - 1);                   // index of the slowest real outer axis
+        const long long slice = total / oe[slow];       // elements per entry of that axis
+        const long long limit = 0x7fffffffLL;
+        if (slice >= limit) return CNNMEM_ERR_UNSUPPORTED;
+        const long long per_launch = total < limit ? oe[slow] : limit / slice;
+        const FastDiv d_L = make_fastdiv((uint32_t)L);
+        for (long long first = 0; first < oe[slow]; first += per_launch) {
+            const long long count = oe[slow] - first < per_launch ? oe[slow] - first : per_launch;
+            long long ce[3] = {oe[0], oe[1], oe[2]};
+            ce[slow] = count;
+            RowPlan p;
+            p.t0 = ot[0]; p.t1 = ot[1]; p.t2 = ot[2];
+            p.L = (uint32_t)L;
+            p.total = (uint32_t)(count * slice);
+            const FastDiv d_e2 = make_fastdiv((uint32_t)ce[2]), d_e1 = make_fastdiv((uint32_t)ce[1]);
+            const float* sp = src + (size_t)first * (size_t)ot[slow];
+            float* dp = dst + (size_t)first * (size_t)slice;
+            const dim3 grid((unsigned)ceil_div64(ceil_div64(count * slice, 4), kThreads)), block(kThreads);
+            if (aligned16(dp))
+                hipLaunchKernelGGL((permute_rows_kernel<true>), grid, block, 0, st, sp, dp, p, d_L, d_e2, d_e1);
+            else
+                hipLaunchKernelGGL((permute_rows_kernel<false>), grid, block, 0, st, sp, dp, p, d_L, d_e2, d_e1);
+        }
         return launch_status();
     }
 

@@ -93,3 +93,59 @@ def test_softmax_beyond_2g_elements_sampled_rows():
     assert np.all(np.abs(got - want) <= np.maximum(2e-6 * want, 1e-7))
     sums = p.sum(dim=1, dtype=torch.float64)
     assert float((sums - 1.0).abs().max()) <= 1e-5
+
+
+def _letter_index(layout: str, ext: dict, coord: dict) -> int:
+    """Linear index of a coordinate in a spelled layout (slowest axis first): plain positional arithmetic."""
+    idx = 0
+    for letter in layout:
+        idx = idx * ext[letter] + coord[letter]
+    return idx
+
+
+@pytest.mark.parametrize("dst_layout", ["NHWC", "HWCN", "CNHW"])
+def test_relayout_beyond_2g_elements_sampled(dst_layout):
+    """Strided tile kernel (NHWC, HWCN) and row-move kernel (CNHW, several launches) with 64-bit offsets."""
+    if _free_gib() < 24:
+        pytest.skip("needs ~20 GiB of free device memory")
+    N, C, H, W = 96, 340, 257, 257                           # 2 155 839 360 elements
+    total = N * C * H * W
+    assert total > 2**31
+    src = (torch.arange(total, dtype=torch.int64, device="cuda") & 0x7FFFFFFF).to(torch.int32).view(torch.float32)
+    dst = torch.zeros(total, dtype=torch.float32, device="cuda")
+    st = cm.cnnmem_relayout(src, dst, N, C, H, W, "NCHW", dst_layout)
+    assert st == 0
+    ext = dict(N=N, C=C, H=H, W=W)
+    rng = np.random.default_rng(9)
+    pts = np.stack([rng.integers(0, d, size=4000) for d in (N, C, H, W)], axis=1)
+    pts[:4] = [[0, 0, 0, 0], [N - 1, C - 1, H - 1, W - 1], [N - 1, 0, H - 1, 0], [0, C - 1, 0, W - 1]]
+    si = np.array([_letter_index("NCHW", ext, dict(zip("NCHW", map(int, p)))) for p in pts], dtype=np.int64)
+    di = np.array([_letter_index(dst_layout, ext, dict(zip("NCHW", map(int, p)))) for p in pts], dtype=np.int64)
+    assert di.max() > 2**31
+    got = dst.view(torch.int32)[torch.from_numpy(di).cuda()].cpu().numpy()
+    np.testing.assert_array_equal(got, (si & 0x7FFFFFFF).astype(np.int32))
+    back = torch.empty(total, dtype=torch.float32, device="cuda")
+    assert cm.cnnmem_relayout(dst, back, N, C, H, W, dst_layout, "NCHW") == 0
+    probe = torch.arange(0, total, 1000003, device="cuda")
+    assert torch.equal(back.view(torch.int32)[probe], src.view(torch.int32)[probe])
+    assert torch.equal(back.view(torch.int32)[-4096:], src.view(torch.int32)[-4096:])
+
+
+def test_transform16_beyond_2g_elements_sampled():
+    if _free_gib() < 14:
+        pytest.skip("needs ~10 GiB of free device memory")
+    N, C, H, W = 128, 1000, 100, 170                        # 2 176 000 000 16-bit words
+    total = N * C * H * W
+    src = (torch.arange(total, dtype=torch.int64, device="cuda") % 65521).to(torch.int16)
+    dst = torch.empty(total, dtype=torch.int16, device="cuda")
+    st = cm.library().cnnmem_transform_dtype(src.data_ptr(), dst.data_ptr(), N, C, H, W, NCHW, CHWN, cm.F16,
+                                             torch.cuda.current_stream().cuda_stream or None)
+    assert st == 0
+    rng = np.random.default_rng(10)
+    pts = np.stack([rng.integers(0, d, size=4000) for d in (N, C, H, W)], axis=1)
+    pts[:4] = [[0, 0, 0, 0], [N - 1, C - 1, H - 1, W - 1], [N - 1, 0, 0, 0], [0, C - 1, H - 1, W - 1]]
+    si = np.array([oracle.index(NCHW, N, C, H, W, *map(int, p)) for p in pts], dtype=np.int64)
+    di = torch.tensor([oracle.index(CHWN, N, C, H, W, *map(int, p)) for p in pts], device="cuda")
+    assert int(di.max()) > 2**31
+    got = dst[di].cpu().numpy().astype(np.int64) & 0xFFFF
+    np.testing.assert_array_equal(got, si % 65521)
