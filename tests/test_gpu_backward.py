@@ -20,6 +20,9 @@ CASES = [  # N, C, H, W, k, s, p
     (8, 5, 14, 14, 2, 2, 0), (8, 3, 13, 13, 3, 1, 1), (8, 2, 17, 19, 3, 2, 1), (6, 3, 15, 15, 3, 2, 0),
     (4, 3, 30, 24, 2, 2, 0), (8, 2, 9, 9, 5, 3, 2), (3, 2, 7, 5, 2, 1, 0), (4, 2, 20, 20, 9, 4, 3),
     (4, 2, 12, 12, 4, 4, 0), (8, 2, 11, 11, 2, 3, 0),
+    # planes larger than the LDS budget: strips of input rows (cells and single elements), with and without padding
+    (4, 3, 150, 150, 3, 2, 0), (4, 2, 224, 224, 3, 2, 1), (4, 2, 300, 40, 5, 3, 2), (4, 2, 111, 113, 3, 2, 0),
+    (4, 1, 130, 130, 2, 2, 0), (8, 2, 97, 200, 3, 1, 1),
 ]
 
 

@@ -104,7 +104,8 @@ P_CASES = [  # N, C, H, W, k, s, p
     (16, 8, 32, 32, 3, 2, 0), (8, 4, 55, 55, 3, 2, 0), (8, 3, 27, 27, 3, 2, 0), (16, 6, 28, 28, 2, 2, 0),
     (8, 5, 14, 14, 2, 2, 0), (8, 3, 13, 13, 3, 1, 1), (8, 2, 17, 19, 3, 2, 1), (6, 3, 15, 15, 3, 2, 0),
     (8, 2, 64, 64, 2, 2, 0), (4, 3, 30, 24, 2, 2, 0), (8, 2, 9, 9, 5, 3, 2), (24, 2, 150, 150, 3, 2, 0),
-    (8, 1, 224, 224, 2, 2, 0), (3, 2, 7, 5, 2, 1, 0),
+    (8, 1, 224, 224, 2, 2, 0), (3, 2, 7, 5, 2, 1, 0), (4, 2, 224, 224, 3, 2, 1), (4, 2, 300, 40, 5, 3, 2),
+    (8, 2, 129, 131, 3, 2, 0),
 ]
 
 
