@@ -126,6 +126,26 @@ def test_pool16_matches_oracle(case, dtype):
         check_rounded(bits_of(got), want, 0.999, (case, layout, "avg"))
 
 
+@pytest.mark.parametrize("dtype", DTYPES, ids=[IDS[d] for d in DTYPES])
+def test_pool16_max_orders_every_finite_pattern(dtype):
+    """Subnormals, the largest finite values and infinities: the maximum of random bit patterns
+    (NaNs and the negative zero excluded) is the oracle's, bit for bit, in every kernel."""
+    rng = np.random.default_rng(1616)
+    N, C, H, W = 8, 6, 24, 24
+    bits = rng.integers(0, 65536, size=(N, C, H, W)).astype(np.uint16)
+    exp_mask, frac_mask = (0x7c00, 0x03ff) if dtype == cm.F16 else (0x7f80, 0x007f)
+    nan = ((bits & exp_mask) == exp_mask) & ((bits & frac_mask) != 0)
+    bits[nan | (bits == 0x8000)] = 0x0001                              # the smallest subnormal instead
+    xd = torch.from_numpy(bits.view(np.int16)).cuda().view(TORCH[dtype])
+    xcb = oracle.transform16(bits, N, C, H, W, 0, 1)
+    xcd = cm.transform(xd, N, C, H, W, cm.NCHW, cm.CHWN)
+    for (k, s) in [(2, 2), (3, 2), (3, 1)]:
+        for layout, hb, dev in ((cm.NCHW, bits, xd), (cm.CHWN, xcb, xcd)):
+            want = oracle.pool16(hb, N, C, H, W, layout, 0, k, k, s, s, 0, 0, dtype)
+            got = cm.pool(dev, N, C, H, W, layout, cm.POOL_MAX, k, k, s, s)
+            assert np.array_equal(bits_of(got), want), (k, s, layout)
+
+
 def test_pool16_misaligned_views_take_the_generic_kernel():
     N, C, H, W, k, s = 8, 3, 12, 12, 3, 2
     rng = np.random.default_rng(77)
