@@ -129,6 +129,11 @@ CNNMEM_API int cnnmem_pool_dtype(const void *src, void *dst, int N, int C, int H
                                  int kh, int kw, int sh, int sw, int ph, int pw, int dtype, void *hip_stream);
 CNNMEM_API int cnnmem_softmax_dtype(const void *logits, void *probs, int N, int classes, int dtype,
                                     void *hip_stream);
+/* cnnmem_permute / cnnmem_relayout on tensors of `dtype` (words move bit for bit). */
+CNNMEM_API int cnnmem_permute_dtype(const void *src, void *dst, const int *dims, const int *perm, int dtype,
+                                    void *hip_stream);
+CNNMEM_API int cnnmem_relayout_dtype(const void *src, void *dst, int N, int C, int H, int W, const char *src_layout,
+                                     const char *dst_layout, int dtype, void *hip_stream);
 
 /*
  * Pooled output extent (host only, no GPU work):

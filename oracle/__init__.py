@@ -69,6 +69,8 @@ def _load():
         lib.cnnmem_ref_pool_backward.restype = i
         lib.cnnmem_ref_softmax_backward.argtypes = [fp, fp, fp, i, i]
         lib.cnnmem_ref_softmax_backward.restype = i
+        lib.cnnmem_ref_permute16.argtypes = [fp, fp, ip, ip]
+        lib.cnnmem_ref_permute16.restype = i
         lib.cnnmem_ref_index.argtypes = [i] * 9
         lib.cnnmem_ref_index.restype = ctypes.c_ulonglong
         for name in ("cnnmem_ref_transform", "cnnmem_ref_pool_out_dims", "cnnmem_ref_pool",
@@ -267,3 +269,13 @@ def softmax16(logits: np.ndarray, dtype=F16) -> np.ndarray:
     probs = np.empty_like(logits)
     _check(_load().cnnmem_ref_softmax16(logits.ctypes.data, probs.ctypes.data, N, classes, dtype), "softmax16")
     return probs
+
+
+def permute16(src: np.ndarray, dims, perm) -> np.ndarray:
+    """Axis permutation of a tensor of 16-bit words (bit patterns move untouched)."""
+    src = _u16(src)
+    assert src.size == int(np.prod(dims)) and len(dims) == 4 and len(perm) == 4
+    dst = np.empty(tuple(dims[p] for p in perm), dtype=np.uint16)
+    _check(_load().cnnmem_ref_permute16(src.ctypes.data, dst.ctypes.data, (ctypes.c_int * 4)(*dims),
+                                        (ctypes.c_int * 4)(*perm)), "permute16")
+    return dst

@@ -566,3 +566,26 @@ int cnnmem_ref_softmax_backward(const float *probs, const float *dprobs, float *
     }
     return REF_OK;
 }
+
+/* General axis permutation of a tensor of 16-bit words (see cnnmem_ref_permute). */
+int cnnmem_ref_permute16(const uint16_t *src, uint16_t *dst, const int *dims, const int *perm)
+{
+    if (!src || !dst || !dims || !perm) return REF_ERR_INVALID_ARG;
+    int seen[4] = {0, 0, 0, 0};
+    for (int i = 0; i < 4; ++i) {
+        if (dims[i] <= 0 || perm[i] < 0 || perm[i] > 3 || seen[perm[i]]) return REF_ERR_INVALID_ARG;
+        seen[perm[i]] = 1;
+    }
+    size_t ss[4];
+    ss[3] = 1;
+    for (int a = 2; a >= 0; --a) ss[a] = ss[a + 1] * (size_t)dims[a + 1];
+    const int e0 = dims[perm[0]], e1 = dims[perm[1]], e2 = dims[perm[2]], e3 = dims[perm[3]];
+    const size_t t0 = ss[perm[0]], t1 = ss[perm[1]], t2 = ss[perm[2]], t3 = ss[perm[3]];
+#pragma omp parallel for schedule(static)
+    for (int i0 = 0; i0 < e0; ++i0)
+        for (int i1 = 0; i1 < e1; ++i1)
+            for (int i2 = 0; i2 < e2; ++i2)
+                for (int i3 = 0; i3 < e3; ++i3)
+                    dst[(((size_t)i0 * e1 + i1) * e2 + i2) * e3 + i3] = src[i0 * t0 + i1 * t1 + i2 * t2 + i3 * t3];
+    return REF_OK;
+}

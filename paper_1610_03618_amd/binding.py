@@ -61,6 +61,10 @@ def library() -> ctypes.CDLL:
         lib.cnnmem_debug_canonical_permutation.argtypes = [ctypes.POINTER(i), ctypes.POINTER(i), ctypes.POINTER(i),
                                                            ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(i)]
         lib.cnnmem_debug_canonical_permutation.restype = i
+        lib.cnnmem_permute_dtype.argtypes = [p, p, ctypes.POINTER(i), ctypes.POINTER(i), i, p]
+        lib.cnnmem_permute_dtype.restype = i
+        lib.cnnmem_relayout_dtype.argtypes = [p, p, i, i, i, i, ctypes.c_char_p, ctypes.c_char_p, i, p]
+        lib.cnnmem_relayout_dtype.restype = i
         lib.cnnmem_pool_backward.argtypes = [p, p, p] + [i] * 12 + [p]
         lib.cnnmem_pool_backward.restype = i
         lib.cnnmem_softmax_backward.argtypes = [p, p, p, i, i, p]
@@ -139,6 +143,16 @@ def cnnmem_permute(src, dst, dims, perm, stream=None) -> int:
 def cnnmem_relayout(src, dst, N, C, H, W, src_layout: str, dst_layout: str, stream=None) -> int:
     return library().cnnmem_relayout(_ptr(src), _ptr(dst), N, C, H, W, src_layout.encode(), dst_layout.encode(),
                                      _stream(stream))
+
+
+def cnnmem_permute_dtype(src, dst, dims, perm, dtype, stream=None) -> int:
+    return library().cnnmem_permute_dtype(_ptr(src, dtype), _ptr(dst, dtype), (ctypes.c_int * 4)(*dims),
+                                          (ctypes.c_int * 4)(*perm), dtype, _stream(stream))
+
+
+def cnnmem_relayout_dtype(src, dst, N, C, H, W, src_layout: str, dst_layout: str, dtype, stream=None) -> int:
+    return library().cnnmem_relayout_dtype(_ptr(src, dtype), _ptr(dst, dtype), N, C, H, W, src_layout.encode(),
+                                           dst_layout.encode(), dtype, _stream(stream))
 
 
 def cnnmem_debug_canonical_permutation(dims, perm):
@@ -242,8 +256,8 @@ def transform(src: torch.Tensor, N, C, H, W, src_layout, dst_layout, out=None, s
 
 def permute(src: torch.Tensor, dims, perm, out=None, stream=None) -> torch.Tensor:
     if out is None:
-        out = torch.empty(tuple(dims[a] for a in perm), dtype=torch.float32, device=src.device)
-    st = cnnmem_permute(src, out, dims, perm, stream)
+        out = torch.empty(tuple(dims[a] for a in perm), dtype=src.dtype, device=src.device)
+    st = cnnmem_permute_dtype(src, out, dims, perm, dtype_of(src), stream)
     if st:
         raise CnnmemError(st, "cnnmem_permute")
     return out
@@ -253,8 +267,8 @@ def relayout(src: torch.Tensor, N, C, H, W, src_layout: str, dst_layout: str, ou
     if out is None:
         ext = dict(N=N, C=C, H=H, W=W)
         shape = tuple(ext.get(l, 0) for l in dst_layout) if len(dst_layout) == 4 else (N * C * H * W,)
-        out = torch.empty(shape if all(shape) else (N * C * H * W,), dtype=torch.float32, device=src.device)
-    st = cnnmem_relayout(src, out, N, C, H, W, src_layout, dst_layout, stream)
+        out = torch.empty(shape if all(shape) else (N * C * H * W,), dtype=src.dtype, device=src.device)
+    st = cnnmem_relayout_dtype(src, out, N, C, H, W, src_layout, dst_layout, dtype_of(src), stream)
     if st:
         raise CnnmemError(st, "cnnmem_relayout")
     return out

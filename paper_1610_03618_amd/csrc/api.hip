@@ -55,8 +55,31 @@ int cnnmem_permute(const float* src, float* dst, const int* dims, const int* per
     return launch_permute(src, dst, dims, perm, static_cast<hipStream_t>(hip_stream));
 }
 
+int cnnmem_permute_dtype(const void* src, void* dst, const int* dims, const int* perm, int dtype, void* hip_stream) {
+    if (dtype == CNNMEM_F32)
+        return cnnmem_permute(static_cast<const float*>(src), static_cast<float*>(dst), dims, perm, hip_stream);
+    if (dtype != CNNMEM_F16 && dtype != CNNMEM_BF16) return CNNMEM_ERR_INVALID_ARG;
+    if (!src || !dst || !dims || !perm) return CNNMEM_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 1u) return CNNMEM_ERR_INVALID_ARG;
+    bool seen[4] = {false, false, false, false};
+    long long total = 1;
+    const long long limit = 1LL << 46;
+    for (int i = 0; i < 4; ++i) {
+        if (dims[i] <= 0 || perm[i] < 0 || perm[i] > 3 || seen[perm[i]]) return CNNMEM_ERR_INVALID_ARG;
+        seen[perm[i]] = true;
+        if (total > limit / dims[i]) return CNNMEM_ERR_UNSUPPORTED;
+        total *= dims[i];
+    }
+    return launch_permute16(src, dst, dims, perm, static_cast<hipStream_t>(hip_stream));
+}
+
 int cnnmem_relayout(const float* src, float* dst, int N, int C, int H, int W, const char* src_layout,
                     const char* dst_layout, void* hip_stream) {
+    return cnnmem_relayout_dtype(src, dst, N, C, H, W, src_layout, dst_layout, CNNMEM_F32, hip_stream);
+}
+
+int cnnmem_relayout_dtype(const void* src, void* dst, int N, int C, int H, int W, const char* src_layout,
+                          const char* dst_layout, int dtype, void* hip_stream) {
     if (!src || !dst || N <= 0 || C <= 0 || H <= 0 || W <= 0 || !src_layout || !dst_layout)
         return CNNMEM_ERR_INVALID_ARG;
     // a layout is the four letters N, C, H, W, each once, slowest axis first
@@ -79,7 +102,7 @@ int cnnmem_relayout(const float* src, float* dst, int N, int C, int H, int W, co
         perm[i] = where_in_src[l];
     }
     if (dst_layout[4] != 0) return CNNMEM_ERR_INVALID_ARG;
-    return cnnmem_permute(src, dst, dims, perm, hip_stream);
+    return cnnmem_permute_dtype(src, dst, dims, perm, dtype, hip_stream);
 }
 
 int cnnmem_pool_out_dims(int H, int W, int kh, int kw, int sh, int sw, int ph, int pw, int* Ho, int* Wo) {

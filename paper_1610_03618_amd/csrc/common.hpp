@@ -143,6 +143,21 @@ int launch_copy(const float* src, float* dst, long long n, hipStream_t st);
 int launch_transpose2d_any(const float* src, float* dst, long long R, long long S, hipStream_t st);
 // General 4-D axis permutation: dims = source extents (slowest first), destination axis i = source axis perm[i].
 int launch_permute(const float* src, float* dst, const int* dims, const int* perm, hipStream_t st);
+// What a 4-D permutation comes down to once it is in canonical form (host only; extents and
+// strides in elements, independent of the element size).
+struct PermutePlan {
+    enum Kind { kCopy, kTranspose2d, kRows, kTiles } kind;
+    long long total;                        // all elements
+    // kTranspose2d, kTiles: R along the destination's fastest axis, S along the source's
+    long long R, S;
+    long long ss_r, ds_s;                   // kTiles: source stride of r, destination stride of s
+    long long nb0, nb1, sb0, sb1, db0, db1; // kTiles: batch extents and strides on both sides
+    int xcd_order;                          // kTiles: keep neighbouring tiles on one XCD
+    // kRows: run length, extents and source strides of the (up to three) outer destination axes
+    long long L, oe[3], ot[3];
+    int slow;                               // index of the slowest real outer axis
+};
+PermutePlan plan_permutation(const int* dims, const int* perm);
 // Canonical form of a permutation: extent-1 axes dropped, axes that stay neighbours merged (host only).
 void canonical_permutation(const int* dims, const int* perm, int* rank, long long* cdims, int* cperm);
 
@@ -173,6 +188,7 @@ int launch_softmax_backward(const float* probs, const float* dprobs, float* dlog
 // 16-bit storage (dtype CNNMEM_F16 / CNNMEM_BF16); the transform sees the tensor as an [N][M] / [M][N] matrix
 int launch_transform16(const void* src, void* dst, long long N, long long M, int src_layout, int dst_layout,
                        hipStream_t st);
+int launch_permute16(const void* src, void* dst, const int* dims, const int* perm, hipStream_t st);
 int launch_pool16(const void* src, void* dst, const PoolGeom& g, int layout, int dtype, hipStream_t st);
 int launch_softmax16(const void* logits, void* probs, int N, int classes, int dtype, hipStream_t st);
 

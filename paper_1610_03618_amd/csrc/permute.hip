@@ -421,15 +421,16 @@ void canonical_permutation(const int* dims, const int* perm, int* rank, long lon
     *rank = groups;
 }
 
-int launch_permute(const float* src, float* dst, const int* dims, const int* perm, hipStream_t st) {
+PermutePlan plan_permutation(const int* dims, const int* perm) {
+    PermutePlan pl = {};
     int k;
     long long d[4];
     int pm[4];
     canonical_permutation(dims, perm, &k, d, pm);
-    long long total = 1;
-    for (int i = 0; i < 4; ++i) total *= dims[i];
-    if (k <= 1) return launch_copy(src, dst, total, st);
-    if (k == 2) return launch_transpose2d(src, dst, d[0], d[1], st);
+    pl.total = 1;
+    for (int i = 0; i < 4; ++i) pl.total *= dims[i];
+    if (k <= 1) { pl.kind = PermutePlan::kCopy; return pl; }
+    if (k == 2) { pl.kind = PermutePlan::kTranspose2d; pl.R = d[0]; pl.S = d[1]; return pl; }
 
     long long ss[4], ds[4], e[4];                   // source strides by source axis; destination strides / extents by position
     ss[k - 1] = 1;
@@ -438,31 +439,67 @@ int launch_permute(const float* src, float* dst, const int* dims, const int* per
     ds[k - 1] = 1;
     for (int i = k - 2; i >= 0; --i) ds[i] = ds[i + 1] * e[i + 1];
     if (pm[k - 1] == k - 1) {
-        // the fastest axis stays: gather its runs.  The kernel addresses elements with 32 bits;
-        // larger tensors go slice by slice along the destination's slowest axis.
-        const long long L = d[k - 1];
-        // outer destination axes, padded at the slow end to three
-        long long oe[3] = {1, 1, 1}, ot[3] = {0, 0, 0};
+        // the fastest axis stays: its runs are gathered; outer destination axes padded at the slow end to three
+        pl.kind = PermutePlan::kRows;
+        pl.L = d[k - 1];
+        for (int i = 0; i < 3; ++i) { pl.oe[i] = 1; pl.ot[i] = 0; }
         for (int i = 0; i < k - 1; ++i) {
-            oe[3 - (k - 1) + i] = e[i];
-            ot[3 - (k - 1) + i] = ss[pm[i]];
+            pl.oe[3 - (k - 1) + i] = e[i];
+            pl.ot[3 - (k - 1) + i] = ss[pm[i]];
         }
-        const int slow = 3 - (k - 1);                   // index of the slowest real outer axis
-        const long long slice = total / oe[slow];       // elements per entry of that axis
+        pl.slow = 3 - (k - 1);
+        return pl;
+    }
+    // the fastest axis changes: tiles over (destination's fastest axis r, source's fastest axis s)
+    pl.kind = PermutePlan::kTiles;
+    const int ar = pm[k - 1];                       // source axis that is fastest in the destination
+    int pos_s = 0;                                  // destination position of the source's fastest axis
+    for (int i = 0; i < k; ++i)
+        if (pm[i] == k - 1) pos_s = i;
+    pl.R = d[ar];
+    pl.S = d[k - 1];
+    pl.ss_r = ss[ar];
+    pl.ds_s = ds[pos_s];
+    pl.nb0 = pl.nb1 = 1;
+    pl.sb0 = pl.sb1 = pl.db0 = pl.db1 = 0;
+    // When every batch axis is slower than both tile axes on both sides, each batch entry is a
+    // contiguous block and tiles run in plain order.  Otherwise a batch axis sits between the
+    // tile axes in memory (NCHW <-> HWCN: the channel axis), the segments of neighbouring
+    // tiles interleave, and keeping neighbours on one XCD measured 5-10 points better.
+    pl.xcd_order = 0;
+    int nbatch = 0;
+    for (int i = 0; i < k; ++i) {                   // remaining axes, in destination order
+        if (i == k - 1 || i == pos_s) continue;
+        if (i > pos_s || pm[i] > ar) pl.xcd_order = 1;
+        if (nbatch == 0 && k == 4) { pl.nb0 = e[i]; pl.sb0 = ss[pm[i]]; pl.db0 = ds[i]; }
+        else { pl.nb1 = e[i]; pl.sb1 = ss[pm[i]]; pl.db1 = ds[i]; }
+        ++nbatch;
+    }
+    return pl;
+}
+
+int launch_permute(const float* src, float* dst, const int* dims, const int* perm, hipStream_t st) {
+    const PermutePlan pl = plan_permutation(dims, perm);
+    if (pl.kind == PermutePlan::kCopy) return launch_copy(src, dst, pl.total, st);
+    if (pl.kind == PermutePlan::kTranspose2d) return launch_transpose2d(src, dst, pl.R, pl.S, st);
+    if (pl.kind == PermutePlan::kRows) {
+        // The kernel addresses elements with 32 bits; larger tensors go slice by slice along the
+        // destination's slowest axis.
+        const long long slice = pl.total / pl.oe[pl.slow];      // elements per entry of that axis
         const long long limit = 0x7fffffffLL;
         if (slice >= limit) return CNNMEM_ERR_UNSUPPORTED;
-        const long long per_launch = total < limit ? oe[slow] : limit / slice;
-        const FastDiv d_L = make_fastdiv((uint32_t)L);
-        for (long long first = 0; first < oe[slow]; first += per_launch) {
-            const long long count = oe[slow] - first < per_launch ? oe[slow] - first : per_launch;
-            long long ce[3] = {oe[0], oe[1], oe[2]};
-            ce[slow] = count;
+        const long long per_launch = pl.total < limit ? pl.oe[pl.slow] : limit / slice;
+        const FastDiv d_L = make_fastdiv((uint32_t)pl.L);
+        for (long long first = 0; first < pl.oe[pl.slow]; first += per_launch) {
+            const long long count = pl.oe[pl.slow] - first < per_launch ? pl.oe[pl.slow] - first : per_launch;
+            long long ce[3] = {pl.oe[0], pl.oe[1], pl.oe[2]};
+            ce[pl.slow] = count;
             RowPlan p;
-            p.t0 = ot[0]; p.t1 = ot[1]; p.t2 = ot[2];
-            p.L = (uint32_t)L;
+            p.t0 = pl.ot[0]; p.t1 = pl.ot[1]; p.t2 = pl.ot[2];
+            p.L = (uint32_t)pl.L;
             p.total = (uint32_t)(count * slice);
             const FastDiv d_e2 = make_fastdiv((uint32_t)ce[2]), d_e1 = make_fastdiv((uint32_t)ce[1]);
-            const float* sp = src + (size_t)first * (size_t)ot[slow];
+            const float* sp = src + (size_t)first * (size_t)pl.ot[pl.slow];
             float* dp = dst + (size_t)first * (size_t)slice;
             const dim3 grid((unsigned)ceil_div64(ceil_div64(count * slice, 4), kThreads)), block(kThreads);
             if (aligned16(dp))
@@ -472,33 +509,11 @@ int launch_permute(const float* src, float* dst, const int* dims, const int* per
         }
         return launch_status();
     }
-
-    // the fastest axis changes: tiles over (destination's fastest axis r, source's fastest axis s)
-    const int ar = pm[k - 1];                       // source axis that is fastest in the destination
-    int pos_s = 0;                                  // destination position of the source's fastest axis
-    for (int i = 0; i < k; ++i)
-        if (pm[i] == k - 1) pos_s = i;
     TilePlan p;
-    p.R = d[ar];
-    p.S = d[k - 1];
-    p.ss_r = ss[ar];
-    p.ds_s = ds[pos_s];
-    long long nb[2] = {1, 1};
-    p.sb0 = p.sb1 = p.db0 = p.db1 = 0;
-    // When every batch axis is slower than both tile axes on both sides, each batch entry is a
-    // contiguous block and tiles run in plain order.  Otherwise a batch axis sits between the
-    // tile axes in memory (NCHW <-> HWCN: the channel axis), the segments of neighbouring
-    // tiles interleave, and keeping neighbours on one XCD measured 5-10 points better.
-    p.xcd_order = 0;
-    int nbatch = 0;
-    for (int i = 0; i < k; ++i) {                   // remaining axes, in destination order
-        if (i == k - 1 || i == pos_s) continue;
-        if (i > pos_s || pm[i] > ar) p.xcd_order = 1;
-        if (nbatch == 0 && k == 4) { nb[0] = e[i]; p.sb0 = ss[pm[i]]; p.db0 = ds[i]; }
-        else { nb[1] = e[i]; p.sb1 = ss[pm[i]]; p.db1 = ds[i]; }
-        ++nbatch;
-    }
-    return launch_tile_shape(src, dst, p, nb[0], nb[1], st);
+    p.R = pl.R; p.S = pl.S; p.ss_r = pl.ss_r; p.ds_s = pl.ds_s;
+    p.sb0 = pl.sb0; p.sb1 = pl.sb1; p.db0 = pl.db0; p.db1 = pl.db1;
+    p.xcd_order = pl.xcd_order;
+    return launch_tile_shape(src, dst, p, pl.nb0, pl.nb1, st);
 }
 
 }  // namespace cnnmem

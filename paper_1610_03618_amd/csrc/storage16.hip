@@ -47,6 +47,33 @@ __device__ __forceinline__ void st8_stream(uint16_t* p, u32x2 v) {
     __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(p));
 }
 
+// Eight consecutive 16-bit words at any 2-byte aligned address of a dword-aligned buffer.  On a
+// dword boundary this is one 128-bit access; one word off, the load takes the enclosing aligned
+// 128 bits plus the eighth word and shifts, the store writes word, three dwords, word.
+__device__ __forceinline__ u32x4 load8_any(const uint16_t* p) {
+    if ((reinterpret_cast<uintptr_t>(p) & 2u) == 0) return ld16u_stream(p);
+    const u32x4 d = ld16u_stream(p - 1);            // words p-1 .. p+6
+    const uint32_t last = p[7];
+    u32x4 o;
+    o.x = (d.x >> 16) | (d.y << 16);
+    o.y = (d.y >> 16) | (d.z << 16);
+    o.z = (d.z >> 16) | (d.w << 16);
+    o.w = (d.w >> 16) | (last << 16);
+    return o;
+}
+__device__ __forceinline__ void store8_any(uint16_t* q, const u32x4& o) {
+    if ((reinterpret_cast<uintptr_t>(q) & 2u) == 0) {
+        st16u_stream(q, o);
+        return;
+    }
+    q[0] = (uint16_t)o.x;
+    uint32_t* d = reinterpret_cast<uint32_t*>(q + 1);
+    d[0] = (o.x >> 16) | (o.y << 16);
+    d[1] = (o.y >> 16) | (o.z << 16);
+    d[2] = (o.z >> 16) | (o.w << 16);
+    q[7] = (uint16_t)(o.w >> 16);
+}
+
 // ---- the two storage formats -------------------------------------------------
 struct Half {                                       // IEEE binary16
     // Both conversions are single instructions written as inline asm on purpose.  Given the
@@ -250,6 +277,267 @@ int launch_transpose16(const uint16_t* src, uint16_t* dst, long long R, long lon
     hipLaunchKernelGGL(transpose16_scalar_kernel, dim3((unsigned)(tiles_r * tiles_s)), dim3(kThreads), 0, st, src, dst,
                        R, S, (uint32_t)tiles_s);
     return launch_status();
+}
+
+// ---- any storage order of 16-bit tensors (Section I: 24 orders) --------------------------
+// The strided, batched forms of the two kernels above, driven by the same canonical plan as
+// the fp32 permutation.
+
+struct Tile16Plan {
+    long long R, S, ss_r, ds_s, sb0, sb1, db0, db1;
+    uint32_t tiles_s, tiles_plane;
+};
+
+// S >= 8, R >= 2, dword-aligned buffers.  ANY = false: R and S even, so every stride is even and
+// rows start on dword boundaries on both sides.  ANY = true: odd extents as well (rows start on
+// either half of a dword: load8_any / store8_any; the last row of an odd R pairs with itself).
+template <int TR, int TS, bool ANY>
+__global__ __launch_bounds__(kThreads) void permute16_tile_kernel(
+    const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, Tile16Plan p, FastDiv d_plane, FastDiv d_tiles_s,
+    FastDiv d_nb1) {
+    static_assert(TR % 16 == 0 && TS % 8 == 0 && (TR * TS / 16) % kThreads == 0, "tile shape");
+    constexpr int PD = TR / 2 + 1;
+    constexpr int NC8 = TS / 8;
+    constexpr int NB8 = TR / 8;
+    constexpr int LOADS = (TR * TS / 16) / kThreads;
+    constexpr int STORES = (TS * NB8) / kThreads;
+    __shared__ uint32_t tile[(TS + 1) * PD];
+
+    const uint32_t batch = fd_div(blockIdx.x, d_plane);
+    const uint32_t in_plane = blockIdx.x - batch * p.tiles_plane;
+    const uint32_t tr = fd_div(in_plane, d_tiles_s);
+    const uint32_t ts = in_plane - tr * p.tiles_s;
+    const uint32_t b0 = fd_div(batch, d_nb1);
+    const uint32_t b1 = batch - b0 * d_nb1.d;
+    const long long r0 = (long long)tr * TR, s0 = (long long)ts * TS;
+    src += (size_t)b0 * (size_t)p.sb0 + (size_t)b1 * (size_t)p.sb1;
+    dst += (size_t)b0 * (size_t)p.db0 + (size_t)b1 * (size_t)p.db1;
+    const int tid = threadIdx.x;
+
+    u32x4 a[LOADS], b[LOADS];
+    int col[LOADS];
+#pragma unroll
+    for (int it = 0; it < LOADS; ++it) {
+        const int w = tid + it * kThreads;
+        const int c8 = w % NC8, rp = w / NC8;
+        long long r = r0 + 2 * rp, s = s0 + 8 * c8;
+        s = s + 8 <= p.S ? s : p.S - 8;
+        col[it] = (int)(s - s0);                    // >= -7 (even extents: even, >= -6)
+        if (ANY) {
+            r = r < p.R ? r : p.R - 1;
+            const long long r1 = r + 1 < p.R ? r + 1 : p.R - 1;
+            a[it] = load8_any(src + (size_t)r * (size_t)p.ss_r + (size_t)s);
+            b[it] = load8_any(src + (size_t)r1 * (size_t)p.ss_r + (size_t)s);
+        } else {
+            r = r < p.R ? r : p.R - 2;
+            const uint16_t* q = src + (size_t)r * (size_t)p.ss_r + (size_t)s;
+            a[it] = ld16u_stream(q);
+            b[it] = ld16u_stream(q + p.ss_r);
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < LOADS; ++it) {
+        const int rp = (tid + it * kThreads) / NC8;
+        const uint32_t lo[4] = {a[it].x, a[it].y, a[it].z, a[it].w};
+        const uint32_t hi[4] = {b[it].x, b[it].y, b[it].z, b[it].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = col[it] + 2 * j;          // with odd extents c may be -1: only column c + 1 is in the tile
+            const int row0 = c >= 0 ? c : TS, row1 = c + 1 >= 0 ? c + 1 : TS;
+            tile[row0 * PD + rp] = (lo[j] & 0xffffu) | (hi[j] << 16);
+            tile[row1 * PD + rp] = (lo[j] >> 16) | (hi[j] & 0xffff0000u);
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < STORES; ++it) {
+        const int f = tid + it * kThreads;
+        const int b8 = f % NB8, sl = f / NB8;
+        const uint32_t* t = tile + sl * PD + 4 * b8;
+        u32x4 o;
+        o.x = t[0]; o.y = t[1]; o.z = t[2]; o.w = t[3];
+        const long long s = s0 + sl, r = r0 + 8 * b8;
+        if (s < p.S) {
+            uint16_t* q = dst + (size_t)s * (size_t)p.ds_s + (size_t)r;
+            if (r + 8 <= p.R) {
+                if (ANY) store8_any(q, o);
+                else st16u_stream(q, o);
+            } else if (ANY) {
+                const uint32_t w[4] = {o.x, o.y, o.z, o.w};
+                for (int j = 0; j < 8; ++j)
+                    if (r + j < p.R) q[j] = (uint16_t)(w[j >> 1] >> (16 * (j & 1)));
+            } else {
+                const uint32_t w[4] = {o.x, o.y, o.z, o.w};
+                for (int j = 0; j < 4; ++j)
+                    if (r + 2 * j < p.R) *reinterpret_cast<uint32_t*>(q + 2 * j) = w[j];
+            }
+        }
+    }
+}
+
+// Any extents, strides and alignment: word by word through a TR x TS tile (4096 words; stretched
+// along the long side when the other has only a few entries, e.g. three feature maps).
+template <int TR, int TS>
+__global__ __launch_bounds__(kThreads) void permute16_tile_scalar_kernel(
+    const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, Tile16Plan p, FastDiv d_plane, FastDiv d_tiles_s,
+    FastDiv d_nb1) {
+    static_assert(TR * TS == 4096, "4096 words per tile");
+    constexpr int P = TS + 2;
+    __shared__ uint16_t tile[TR * P];
+    const uint32_t batch = fd_div(blockIdx.x, d_plane);
+    const uint32_t in_plane = blockIdx.x - batch * p.tiles_plane;
+    const uint32_t tr = fd_div(in_plane, d_tiles_s);
+    const uint32_t ts = in_plane - tr * p.tiles_s;
+    const uint32_t b0 = fd_div(batch, d_nb1);
+    const uint32_t b1 = batch - b0 * d_nb1.d;
+    const long long r0 = (long long)tr * TR, s0 = (long long)ts * TS;
+    src += (size_t)b0 * (size_t)p.sb0 + (size_t)b1 * (size_t)p.sb1;
+    dst += (size_t)b0 * (size_t)p.db0 + (size_t)b1 * (size_t)p.db1;
+#pragma unroll
+    for (int k = 0; k < 4096 / kThreads; ++k) {
+        const int e = threadIdx.x + k * kThreads;
+        const int sl = e % TS, rl = e / TS;
+        const long long r = r0 + rl, s = s0 + sl;
+        if (r < p.R && s < p.S) tile[rl * P + sl] = src[(size_t)r * (size_t)p.ss_r + (size_t)s];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 4096 / kThreads; ++k) {
+        const int e = threadIdx.x + k * kThreads;
+        const int rl = e % TR, sl = e / TR;
+        const long long s = s0 + sl, r = r0 + rl;
+        if (r < p.R && s < p.S) dst[(size_t)s * (size_t)p.ds_s + (size_t)r] = tile[rl * P + sl];
+    }
+}
+
+template <int TR, int TS>
+int launch_p16_scalar(const uint16_t* src, uint16_t* dst, Tile16Plan p, long long nb0, long long nb1, hipStream_t st) {
+    const long long tiles_r = ceil_div64(p.R, TR), tiles_s = ceil_div64(p.S, TS);
+    const long long plane = tiles_r * tiles_s;
+    if (plane >= 0x7fffffffLL || nb0 * nb1 >= 0x7fffffffLL || plane * nb0 * nb1 >= 0x7fffffffLL)
+        return CNNMEM_ERR_UNSUPPORTED;
+    p.tiles_s = (uint32_t)tiles_s;
+    p.tiles_plane = (uint32_t)plane;
+    hipLaunchKernelGGL((permute16_tile_scalar_kernel<TR, TS>), dim3((unsigned)(plane * nb0 * nb1)), dim3(kThreads), 0, st,
+                       src, dst, p, make_fastdiv((uint32_t)plane), make_fastdiv((uint32_t)tiles_s),
+                       make_fastdiv((uint32_t)nb1));
+    return launch_status();
+}
+
+struct Row16Plan {
+    long long t0, t1, t2;
+    uint32_t L, total;
+};
+
+// The fastest axis stays: a lane owns 8 consecutive destination words.  VEC: both buffers are
+// dword aligned; 8 words inside one run are one 128-bit load wherever the run happens to start
+// (load8_any), and the destination, being linear, is always on a dword boundary.
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void permute16_rows_kernel(
+    const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, Row16Plan p, FastDiv d_L, FastDiv d_e2, FastDiv d_e1) {
+    const uint32_t e = 8u * (blockIdx.x * kThreads + threadIdx.x);
+    if (e >= p.total) return;
+    auto run_source = [&](uint32_t run) {
+        const uint32_t q = fd_div(run, d_e2);
+        const uint32_t o2 = run - q * d_e2.d;
+        const uint32_t o0 = fd_div(q, d_e1);
+        const uint32_t o1 = q - o0 * d_e1.d;
+        return (size_t)o0 * (size_t)p.t0 + (size_t)o1 * (size_t)p.t1 + (size_t)o2 * (size_t)p.t2;
+    };
+    const uint32_t run = fd_div(e, d_L);
+    const uint32_t in_run = e - run * p.L;
+    if (VEC && in_run + 8 <= p.L) {
+        st16u_stream(dst + e, load8_any(src + run_source(run) + in_run));
+        return;
+    }
+    for (uint32_t j = 0; j < 8 && e + j < p.total; ++j) {
+        const uint32_t rj = fd_div(e + j, d_L);
+        dst[e + j] = src[run_source(rj) + (e + j - rj * p.L)];
+    }
+}
+
+template <int TR, int TS>
+int launch_p16_tile(const uint16_t* src, uint16_t* dst, Tile16Plan p, long long nb0, long long nb1, bool any,
+                    hipStream_t st) {
+    const long long tiles_r = ceil_div64(p.R, TR), tiles_s = ceil_div64(p.S, TS);
+    const long long plane = tiles_r * tiles_s;
+    if (plane >= 0x7fffffffLL || nb0 * nb1 >= 0x7fffffffLL || plane * nb0 * nb1 >= 0x7fffffffLL)
+        return CNNMEM_ERR_UNSUPPORTED;
+    p.tiles_s = (uint32_t)tiles_s;
+    p.tiles_plane = (uint32_t)plane;
+    const dim3 grid((unsigned)(plane * nb0 * nb1)), block(kThreads);
+    const FastDiv d_plane = make_fastdiv((uint32_t)plane), d_ts = make_fastdiv((uint32_t)tiles_s),
+                  d_nb1 = make_fastdiv((uint32_t)nb1);
+    if (any)
+        hipLaunchKernelGGL((permute16_tile_kernel<TR, TS, true>), grid, block, 0, st, src, dst, p, d_plane, d_ts, d_nb1);
+    else
+        hipLaunchKernelGGL((permute16_tile_kernel<TR, TS, false>), grid, block, 0, st, src, dst, p, d_plane, d_ts, d_nb1);
+    return launch_status();
+}
+
+int launch_permute16_impl(const uint16_t* src, uint16_t* dst, const int* dims, const int* perm, hipStream_t st) {
+    const PermutePlan pl = plan_permutation(dims, perm);
+    const bool dword_ok = ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 3u) == 0;
+    if (pl.kind == PermutePlan::kCopy) {
+        const long long blocks = ceil_div64(ceil_div64(pl.total, 8), kThreads);
+        if (blocks > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(copy16_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, src, dst, (size_t)pl.total);
+        return launch_status();
+    }
+    if (pl.kind == PermutePlan::kTranspose2d) return launch_transpose16(src, dst, pl.R, pl.S, st);
+    if (pl.kind == PermutePlan::kRows) {
+        const long long slice = pl.total / pl.oe[pl.slow];
+        const long long limit = 0x7fffffffLL;
+        if (slice >= limit) return CNNMEM_ERR_UNSUPPORTED;
+        const long long per_launch = pl.total < limit ? pl.oe[pl.slow] : limit / slice;
+        // slices start a multiple of 8 words into the destination when they are not the first one only if
+        // the slice length is even; an odd slice length keeps the word-by-word kernel for the later slices
+        const bool vec = dword_ok && (pl.total < limit || slice % 2 == 0);
+        for (long long first = 0; first < pl.oe[pl.slow]; first += per_launch) {
+            const long long count = pl.oe[pl.slow] - first < per_launch ? pl.oe[pl.slow] - first : per_launch;
+            long long ce[3] = {pl.oe[0], pl.oe[1], pl.oe[2]};
+            ce[pl.slow] = count;
+            Row16Plan p;
+            p.t0 = pl.ot[0]; p.t1 = pl.ot[1]; p.t2 = pl.ot[2];
+            p.L = (uint32_t)pl.L;
+            p.total = (uint32_t)(count * slice);
+            const uint16_t* sp = src + (size_t)first * (size_t)pl.ot[pl.slow];
+            uint16_t* dp = dst + (size_t)first * (size_t)slice;
+            const dim3 grid((unsigned)ceil_div64(ceil_div64(count * slice, 8), kThreads)), block(kThreads);
+            if (vec)
+                hipLaunchKernelGGL((permute16_rows_kernel<true>), grid, block, 0, st, sp, dp, p,
+                                   make_fastdiv((uint32_t)pl.L), make_fastdiv((uint32_t)ce[2]),
+                                   make_fastdiv((uint32_t)ce[1]));
+            else
+                hipLaunchKernelGGL((permute16_rows_kernel<false>), grid, block, 0, st, sp, dp, p,
+                                   make_fastdiv((uint32_t)pl.L), make_fastdiv((uint32_t)ce[2]),
+                                   make_fastdiv((uint32_t)ce[1]));
+        }
+        return launch_status();
+    }
+    Tile16Plan p;
+    p.R = pl.R; p.S = pl.S; p.ss_r = pl.ss_r; p.ds_s = pl.ds_s;
+    p.sb0 = pl.sb0; p.sb1 = pl.sb1; p.db0 = pl.db0; p.db1 = pl.db1;
+    p.tiles_s = p.tiles_plane = 0;
+    if (dword_ok && p.S >= 8 && p.R > 4) {
+        // even extents: every stride is a multiple of S (source side) or R (destination side), hence even
+        const bool any = p.R % 2 != 0 || p.S % 2 != 0;
+        if (p.R <= 16) return launch_p16_tile<16, 256>(src, dst, p, pl.nb0, pl.nb1, any, st);
+        if (p.R <= 32) return launch_p16_tile<32, 128>(src, dst, p, pl.nb0, pl.nb1, any, st);
+        if (p.S <= 16) return launch_p16_tile<256, 16>(src, dst, p, pl.nb0, pl.nb1, any, st);
+        if (p.S <= 32) return launch_p16_tile<128, 32>(src, dst, p, pl.nb0, pl.nb1, any, st);
+        // rows that are not whole 128-byte lines (64 words) get the long side of the tile, as for fp32
+        const bool ragged_dst = p.R % 64 != 0, ragged_src = p.S % 64 != 0;
+        if (ragged_dst && p.R >= 256) return launch_p16_tile<256, 32>(src, dst, p, pl.nb0, pl.nb1, any, st);
+        if (ragged_src && p.S >= 256) return launch_p16_tile<32, 256>(src, dst, p, pl.nb0, pl.nb1, any, st);
+        if (p.R >= 128 && p.S >= 128) return launch_p16_tile<128, 128>(src, dst, p, pl.nb0, pl.nb1, any, st);
+        return launch_p16_tile<64, 64>(src, dst, p, pl.nb0, pl.nb1, any, st);
+    }
+    if (p.S <= 4) return launch_p16_scalar<1024, 4>(src, dst, p, pl.nb0, pl.nb1, st);
+    if (p.R <= 4) return launch_p16_scalar<4, 1024>(src, dst, p, pl.nb0, pl.nb1, st);
+    if (p.S <= 16) return launch_p16_scalar<256, 16>(src, dst, p, pl.nb0, pl.nb1, st);
+    if (p.R <= 16) return launch_p16_scalar<16, 256>(src, dst, p, pl.nb0, pl.nb1, st);
+    return launch_p16_scalar<64, 64>(src, dst, p, pl.nb0, pl.nb1, st);
 }
 
 // =============================================================================
@@ -788,6 +1076,10 @@ int launch_transform16(const void* src, void* dst, long long N, long long M, int
     }
     if (src_layout == CNNMEM_NCHW) return launch_transpose16(s, d, N, M, st);
     return launch_transpose16(s, d, M, N, st);
+}
+
+int launch_permute16(const void* src, void* dst, const int* dims, const int* perm, hipStream_t st) {
+    return launch_permute16_impl(static_cast<const uint16_t*>(src), static_cast<uint16_t*>(dst), dims, perm, st);
 }
 
 int launch_pool16(const void* src, void* dst, const PoolGeom& g, int layout, int dtype, hipStream_t st) {

@@ -252,3 +252,48 @@ def test_config5_softmax16_full_size(dtype):
     zb, zd = to16(wl.make_logits(s, wl.rng_for(5, 0)), dtype)
     want = oracle.softmax16(zb, dtype)
     check_rounded(bits_of(cm.softmax(zd)), want, 0.99, "config 5")
+
+
+# ---- any storage order, 16-bit words ------------------------------------------------
+
+import itertools
+
+P16_SHAPES = [(8, 16, 20, 24), (5, 12, 70, 36), (3, 7, 9, 130), (2, 3, 129, 67), (4, 68, 6, 72), (1, 96, 7, 7),
+              (4, 1, 33, 5), (6, 4, 1, 260), (2, 300, 2, 4), (1, 1, 1, 9), (3, 3, 3, 3), (2, 130, 34, 18)]
+
+
+@pytest.mark.parametrize("dims", P16_SHAPES, ids=["x".join(map(str, s)) for s in P16_SHAPES])
+def test_permute16_every_permutation_matches_oracle(dims):
+    rng = np.random.default_rng(sum(dims) + 16)
+    x = rng.integers(0, 65536, size=dims).astype(np.uint16)
+    d = torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+    for perm in itertools.permutations(range(4)):
+        want = oracle.permute16(x, dims, perm)
+        got = cm.permute(d, dims, perm)
+        assert tuple(got.shape) == want.shape
+        assert np.array_equal(bits_of(got), want), (dims, perm)
+
+
+def test_relayout16_named_orders_full_size_and_misaligned():
+    t = wl.config(2).transforms[0]                       # 128 x 96 x 55 x 55: odd image extents
+    N, C, H, W = t.N, t.C, t.H, t.W
+    canon = np.random.default_rng(2).integers(0, 65536, size=(N, C, H, W)).astype(np.uint16)
+    d = torch.from_numpy(canon.view(np.int16)).cuda().view(torch.float16)
+    for dst, perm in [("NHWC", (0, 2, 3, 1)), ("HWCN", (2, 3, 1, 0)), ("CNHW", (1, 0, 2, 3))]:
+        want = oracle.permute16(canon, (N, C, H, W), perm)
+        got = cm.relayout(d, N, C, H, W, "NCHW", dst)
+        assert np.array_equal(bits_of(got), want), dst
+        back = cm.relayout(got, N, C, H, W, dst, "NCHW")
+        assert np.array_equal(bits_of(back), canon), dst
+    # buffers that are only 2-byte aligned take the word-by-word kernels
+    dims, n = (3, 8, 36, 20), 3 * 8 * 36 * 20
+    x = np.random.default_rng(3).integers(0, 65536, size=dims).astype(np.uint16)
+    for so, do in [(1, 0), (0, 1), (3, 3)]:
+        sbuf = torch.zeros(n + 8, dtype=torch.float16, device="cuda")
+        sbuf[so:so + n] = torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16).reshape(-1)
+        for perm in [(0, 2, 3, 1), (3, 2, 1, 0), (1, 0, 2, 3), (2, 0, 1, 3)]:
+            dbuf = torch.zeros(n + 8, dtype=torch.float16, device="cuda")
+            assert cm.cnnmem_permute_dtype(sbuf[so:], dbuf[do:], dims, perm, cm.F16) == 0
+            got = bits_of(dbuf)
+            assert np.array_equal(got[do:do + n], oracle.permute16(x, dims, perm).ravel()), (so, do, perm)
+            assert not got[:do].any() and not got[do + n:].any()

@@ -190,3 +190,16 @@ def test_softmax16_hand_rows(dtype):
     out = oracle.softmax16(z, dtype)
     assert out[0, 0] == one
     assert out[0, 1] == (0 if dtype == F16 else oracle.narrow16(np.exp(-60.0) / (1 + np.exp(-60.0)), dtype))
+
+
+def test_permute16_is_numpy_transpose_for_every_permutation():
+    import itertools
+    rng = np.random.default_rng(29)
+    dims = (3, 4, 5, 6)
+    x = rng.integers(0, 65536, size=dims).astype(np.uint16)
+    for perm in itertools.permutations(range(4)):
+        got = oracle.permute16(x, dims, perm)
+        assert np.array_equal(got, x.transpose(perm)), perm
+    # hand-worked: 1x2x1x3 [c][w] = [[0,1,2],[3,4,5]] with the last two real axes swapped -> [[0,3],[1,4],[2,5]]
+    y = oracle.permute16(np.arange(6, dtype=np.uint16).reshape(1, 2, 1, 3), (1, 2, 1, 3), (0, 2, 3, 1))
+    assert y.ravel().tolist() == [0, 3, 1, 4, 2, 5]
