@@ -126,6 +126,26 @@ def tune_pool(N: int, C: int, H: int, W: int, layout: int, mode: int, k: int, s:
     return best, history
 
 
+def load_table(path: str) -> Dict[tuple, dict]:
+    """Reads a table written by ``--out`` and keys it by shape:
+    (N, C, H, W, k, s, p, layout, mode) -> dict of :class:`PoolTuning` fields."""
+    with open(path) as f:
+        raw = json.load(f)
+    table = {}
+    for entry in raw.values():
+        sh = entry["shape"]
+        key = (sh["N"], sh["C"], sh["H"], sh["W"], sh["k"], sh["s"], sh["p"], sh["layout"], sh["mode"])
+        table[key] = dict(entry["tuning"])
+    return table
+
+
+def lookup(table: Dict[tuple, dict], N: int, C: int, H: int, W: int, k: int, s: int, p: int, layout: int,
+           mode: int) -> Optional[dict]:
+    """The cached tuning of a layer, or None (= library defaults) when the shape was never tuned.
+    Pass the result as ``tuning=`` to :func:`paper_1610_03618_amd.pool`."""
+    return table.get((N, C, H, W, k, s, p, layout, mode))
+
+
 def _table1_layers():
     from . import workloads as wl
     return [(name, N, C, hw, hw, k, s) for (name, N, hw, k, C, s) in wl.TABLE1_POOLS]

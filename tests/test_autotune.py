@@ -40,3 +40,22 @@ def test_tune_pool_returns_a_valid_tuning_that_changes_no_result(layout):
     want = oracle.pool(src, N, C, H, W, layout, 0, k, k, s, s)
     got = cm.pool(torch.from_numpy(src).cuda(), N, C, H, W, layout, cm.POOL_MAX, k, k, s, s, tuning=best)
     np.testing.assert_array_equal(got.cpu().numpy(), want)
+
+
+def test_tuning_table_round_trip(tmp_path):
+    """The shape -> tuning table the tool writes can be read back and looked up by shape."""
+    import json
+    from paper_1610_03618_amd import autotune
+    written = {
+        "PL5 ...": dict(shape=dict(N=128, C=96, H=55, W=55, k=3, s=2, p=0, layout=1, mode=0),
+                        tuning=dict(rows_per_lane=3, cols_per_lane=1, workgroups_per_cu=3), gbps=5190.0),
+        "PL1 ...": dict(shape=dict(N=128, C=16, H=28, W=28, k=2, s=2, p=0, layout=0, mode=0),
+                        tuning=dict(nchw_kernel=2, slab_lanes=1024, workgroups_per_cu=6), gbps=622.0),
+    }
+    path = tmp_path / "table.json"
+    path.write_text(json.dumps(written))
+    table = autotune.load_table(str(path))
+    assert autotune.lookup(table, 128, 96, 55, 55, 3, 2, 0, 1, 0) == dict(rows_per_lane=3, cols_per_lane=1,
+                                                                            workgroups_per_cu=3)
+    assert autotune.lookup(table, 128, 16, 28, 28, 2, 2, 0, 0, 0)["slab_lanes"] == 1024
+    assert autotune.lookup(table, 64, 16, 28, 28, 2, 2, 0, 0, 0) is None
