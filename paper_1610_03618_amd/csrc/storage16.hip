@@ -202,6 +202,77 @@ __global__ __launch_bounds__(kThreads) void transpose16_kernel(
     }
 }
 
+// The same transpose with 8 x 8 register blocks: a lane loads 8 words of eight consecutive
+// source rows (eight 128-bit loads in flight), transposes the block in registers and parks eight
+// 128-bit vectors, one per destination row, in an LDS tile that is already in destination
+// order; after the barrier it reads 128 bits of a destination row back and stores them.  Four
+// times fewer LDS instructions per byte than the pair-packing kernel.  LDS rows are stored
+// j-major (destination row s = 8*c + j at j*(TS/8) + c) with a pitch of an odd number of 16-byte
+// units, so the eight lanes that write one column of blocks hit distinct bank groups.
+template <int TR, int TS, bool ANY>
+__global__ __launch_bounds__(kThreads) void transpose16_block_kernel(
+    const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, long long R, long long S, uint32_t tiles_s) {
+    static_assert(TR % 8 == 0 && TS % 8 == 0 && TR * TS == 64 * kThreads, "one 8x8 block per lane");
+    constexpr int NC8 = TS / 8;                     // blocks along s
+    constexpr int NB8 = TR / 8;                     // 128-bit vectors per destination row of the tile
+    constexpr int PV = NB8 + 1 + (NB8 % 2);         // LDS pitch in 16-byte units, odd
+    __shared__ u32x4 tile[TS * PV];
+
+    const long long r0 = (long long)(blockIdx.x / tiles_s) * TR;
+    const long long s0 = (long long)(blockIdx.x % tiles_s) * TS;
+    const int tid = threadIdx.x;
+    const int c8 = tid % NC8, rb = tid / NC8;
+
+    long long s = s0 + 8 * c8;
+    s = s + 8 <= S ? s : S - 8;                     // S >= 8 (launcher); the shifted block is filed under its true columns
+    const int col = (int)(s - s0);                  // >= -7
+    u32x4 a[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        long long r = r0 + 8 * rb + i;
+        r = r < R ? r : R - 1;                      // rows past R re-read the last one and are never written out
+        const uint16_t* q = src + (size_t)r * (size_t)S + (size_t)s;
+        a[i] = ANY ? load8_any(q) : ld16u_stream(q);
+    }
+    // 8 x 8 transpose: o[j] = column j of the block = words (row 0 .. row 7)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        uint32_t w[4];
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const uint32_t lo = j < 2 ? a[2 * m].x : j < 4 ? a[2 * m].y : j < 6 ? a[2 * m].z : a[2 * m].w;
+            const uint32_t hi = j < 2 ? a[2 * m + 1].x : j < 4 ? a[2 * m + 1].y : j < 6 ? a[2 * m + 1].z : a[2 * m + 1].w;
+            w[m] = (j & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
+        }
+        const int c = col + j;                      // tile column of this vector; left of the tile: spare slot
+        u32x4 o;
+        o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3];
+        const int row = c >= 0 ? (c & 7) * NC8 + (c >> 3) : 0;
+        const int slot = c >= 0 ? rb : NB8;         // column NB8 of a row is padding, never read
+        tile[row * PV + slot] = o;
+    }
+    __syncthreads();
+    // TS destination rows x NB8 vectors = TS * NB8 = 8 * kThreads stores
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+        const int f = tid + it * kThreads;
+        const int b8 = f % NB8, sl = f / NB8;
+        const u32x4 o = tile[((sl & 7) * NC8 + (sl >> 3)) * PV + b8];
+        const long long sd = s0 + sl, r = r0 + 8 * b8;
+        if (sd < S) {
+            uint16_t* q = dst + (size_t)sd * (size_t)R + (size_t)r;
+            if (r + 8 <= R) {
+                if (ANY) store8_any(q, o);
+                else st16u_stream(q, o);
+            } else {
+                const uint32_t w[4] = {o.x, o.y, o.z, o.w};
+                for (int j = 0; j < 8; ++j)
+                    if (r + j < R) q[j] = (uint16_t)(w[j >> 1] >> (16 * (j & 1)));
+            }
+        }
+    }
+}
+
 // Any R, S: word by word through a 64 x 64 tile.
 __global__ __launch_bounds__(kThreads) void transpose16_scalar_kernel(
     const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, long long R, long long S, uint32_t tiles_s) {
@@ -239,6 +310,18 @@ __global__ __launch_bounds__(kThreads) void copy16_kernel(const uint16_t* __rest
 }
 
 template <int TR, int TS>
+int launch_t16_block(const uint16_t* src, uint16_t* dst, long long R, long long S, bool any, hipStream_t st) {
+    const long long tiles_r = ceil_div64(R, TR), tiles_s = ceil_div64(S, TS);
+    if (tiles_r * tiles_s > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)(tiles_r * tiles_s)), block(kThreads);
+    if (any)
+        hipLaunchKernelGGL((transpose16_block_kernel<TR, TS, true>), grid, block, 0, st, src, dst, R, S, (uint32_t)tiles_s);
+    else
+        hipLaunchKernelGGL((transpose16_block_kernel<TR, TS, false>), grid, block, 0, st, src, dst, R, S, (uint32_t)tiles_s);
+    return launch_status();
+}
+
+template <int TR, int TS>
 int launch_t16(const uint16_t* src, uint16_t* dst, long long R, long long S, hipStream_t st) {
     const long long tiles_r = ceil_div64(R, TR), tiles_s = ceil_div64(S, TS);
     if (tiles_r * tiles_s > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
@@ -249,8 +332,35 @@ int launch_t16(const uint16_t* src, uint16_t* dst, long long R, long long S, hip
 
 int launch_transpose16(const uint16_t* src, uint16_t* dst, long long R, long long S, hipStream_t st) {
     const bool dword_ok = ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 3u) == 0;
+    const int forced = env_int("CNNMEM_TRANSFORM16_TILE", -1);
+    const bool odd = R % 2 != 0 || S % 2 != 0;
+    if (dword_ok && S >= 8 && (forced >= 10 || (odd && forced < 0))) {
+        // 8 x 8 register blocks.  On even extents they measure the same as the pair-packing kernel
+        // below (both sit at ~85 % of a copy of the same bytes), so that one stays the default;
+        // odd extents need the shifted 128-bit accesses, which only this kernel has.
+        const bool any = odd;
+        int shape = forced;
+        if (shape < 0) {
+            if (R <= 8) shape = 16;
+            else if (R <= 16) shape = 15;
+            else if (R <= 32) shape = 13;
+            else if (R <= 64) shape = 11;
+            else if (S <= 32) shape = 14;
+            else if (S <= 64) shape = 12;
+            else shape = 10;
+        }
+        switch (shape) {
+            case 11: return launch_t16_block<64, 256>(src, dst, R, S, any, st);
+            case 12: return launch_t16_block<256, 64>(src, dst, R, S, any, st);
+            case 13: return launch_t16_block<32, 512>(src, dst, R, S, any, st);
+            case 14: return launch_t16_block<512, 32>(src, dst, R, S, any, st);
+            case 15: return launch_t16_block<16, 1024>(src, dst, R, S, any, st);
+            case 16: return launch_t16_block<8, 2048>(src, dst, R, S, any, st);
+            default: return launch_t16_block<128, 128>(src, dst, R, S, any, st);
+        }
+    }
     if (dword_ok && R % 2 == 0 && S % 2 == 0 && S >= 8 && R >= 2) {
-        int shape = env_int("CNNMEM_TRANSFORM16_TILE", -1);
+        int shape = forced;
         if (shape < 0) {
             if (R <= 16) shape = 3;
             else if (R <= 32) shape = 2;

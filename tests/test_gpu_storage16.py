@@ -66,9 +66,11 @@ def test_transform16_matches_oracle(shape):
     assert np.array_equal(bits_of(same), x)
 
 
-@pytest.mark.parametrize("tile", list(range(10)))
-def test_transform16_every_tile_shape(tile):
-    N, C, H, W = 150, 6, 11, 14          # 150 x 924: even extents, ragged in every tile shape
+@pytest.mark.parametrize("odd", [False, True], ids=["even", "odd"])
+@pytest.mark.parametrize("tile", list(range(17)))
+def test_transform16_every_tile_shape(tile, odd):
+    # 150 x 924: even extents, ragged in every tile shape; 151 x 1001: odd extents (shifted accesses / word tiles)
+    N, C, H, W = (151, 7, 11, 13) if odd else (150, 6, 11, 14)
     rng = np.random.default_rng(tile)
     x = rng.integers(0, 65536, size=(N, C, H, W)).astype(np.uint16)
     d = torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
