@@ -151,3 +151,15 @@ def test_dtype_entry_points_validate_like_the_fp32_ones(dtype):
     assert cm.cnnmem_pool_dtype(None, FAKE, 2, 2, 4, 4, cm.NCHW, cm.POOL_MAX, 2, 2, 2, 2, 0, 0, dtype, stream=0) == INVALID
     assert cm.cnnmem_softmax_dtype(FAKE, FAKE + 4096, 2, 0, dtype, stream=0) == INVALID
     assert cm.cnnmem_softmax_dtype(FAKE + 1, FAKE + 4096, 2, 10, dtype, stream=0) == INVALID
+
+
+def test_headers_compile_as_plain_c(tmp_path):
+    """The ABI headers are plain C: no torch, no HIP, no C++."""
+    import subprocess
+    src = tmp_path / "use_headers.c"
+    src.write_text('#include "cnnmem.h"\n#include "cnnmem_debug.h"\n'
+                   'int main(void) { cnnmem_pool_tuning t = {0, 0, 0, 0, 0}; cnnmem_layer l = {CNNMEM_LAYER_POOL, 1, 1};\n'
+                   '  (void)t; (void)l; return CNNMEM_F16 + CNNMEM_POOL_AVG + CNNMEM_CHWN > 0 ? 0 : 1; }\n')
+    include = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", include, "-c", str(src),
+                    "-o", str(tmp_path / "use_headers.o")], check=True)
