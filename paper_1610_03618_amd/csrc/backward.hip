@@ -357,7 +357,7 @@ template <int MODE, int KH, int KW, int SH, int SW>
 __global__ __launch_bounds__(kBwdThreads) void pool_bwd_nchw_slab_kernel(
     const float* __restrict__ src, const float* __restrict__ ddst, float* __restrict__ dsrc, PoolGeom g,
     BwdSlabPlan plan, int x_floats, int gy_floats, FastDiv div_w, FastDiv div_plane_in, FastDiv div_wo,
-    FastDiv div_plane_out) {
+    FastDiv div_plane_out, FastDiv div_cells_w, FastDiv div_cells_plane) {
     constexpr int VEC = kBwdSlabFloats / 4 / kBwdThreads + 1;
     float* slab = reinterpret_cast<float*>(bwd_dyn_lds);
     const int kh = KH ? KH : g.kh, kw = KW ? KW : g.kw, sh = SH ? SH : g.sh, sw = SW ? SW : g.sw;
@@ -422,6 +422,20 @@ __global__ __launch_bounds__(kBwdThreads) void pool_bwd_nchw_slab_kernel(
             const float* xs = slab + (x_base + (long long)pl * plane_in);
             float best = kNegInf;
             int where = -1;
+            if (KH != 0 && g.ph == 0 && g.pw == 0) {
+                // compile-time window without padding: every tap is inside the image
+                const int base = (i * sh) * g.W + j * sw;
+                best = xs[base];
+                where = base;
+#pragma unroll
+                for (int y = 0; y < (KH ? KH : 1); ++y)
+#pragma unroll
+                    for (int x = 0; x < (KW ? KW : 1); ++x) {
+                        if (y == 0 && x == 0) continue;
+                        const float val = xs[base + y * g.W + x];
+                        if (val > best) { best = val; where = base + y * g.W + x; }
+                    }
+            } else
             for (int y = 0; y < kh; ++y) {
                 const int r = i * sh - g.ph + y;
                 if (r < 0 || r >= g.H) continue;
@@ -452,10 +466,10 @@ __global__ __launch_bounds__(kBwdThreads) void pool_bwd_nchw_slab_kernel(
         const int n_cells = planes * cell_rows * cells_w;
         const int ci0 = h0 / S;
         for (int v = threadIdx.x; v < n_cells; v += kBwdThreads) {
-            const int per_plane = cell_rows * cells_w;
-            const int pl = planes > 1 ? v / per_plane : 0;
-            const int rem = v - pl * per_plane;
-            const int cil = rem / cells_w;
+            // per_plane = cells of a whole plane (planes > 1 implies whole planes)
+            const int pl = planes > 1 ? (int)fd_div((uint32_t)v, div_cells_plane) : 0;
+            const int rem = v - pl * (int)div_cells_plane.d;
+            const int cil = (int)fd_div((uint32_t)rem, div_cells_w);
             const int cj = rem - cil * cells_w;
             const int ci = ci0 + cil;
             const long long gofs = gy_base + (long long)pl * plane_out;
@@ -615,7 +629,8 @@ int launch_bwd_slab(const float* src, const float* ddst, float* dsrc, const Pool
     hipLaunchKernelGGL((pool_bwd_nchw_slab_kernel<MODE, KH, KW, SH, SW>), dim3((unsigned)blocks), dim3(kBwdThreads), lds,
                        st, src, ddst, dsrc, g, plan, x_floats, gy_floats, make_fastdiv((uint32_t)g.W),
                        make_fastdiv((uint32_t)(g.H * g.W)), make_fastdiv((uint32_t)g.Wo),
-                       make_fastdiv((uint32_t)(g.Ho * g.Wo)));
+                       make_fastdiv((uint32_t)(g.Ho * g.Wo)), make_fastdiv((uint32_t)ceil_div(g.W, g.sw)),
+                       make_fastdiv((uint32_t)(ceil_div(g.W, g.sw) * ceil_div(g.H, g.sh))));
     return launch_status();
 }
 
@@ -669,10 +684,27 @@ int dispatch_pool_backward(const float* src, const float* ddst, float* dsrc, con
             cap = kBwdSlabFloats;                   // a whole plane does not fit the preferred size: take the large one
         auto fits = [&](long long xf, long long gf) { return part(xf) + part(gf) * (kMax ? 2 : 1) <= cap; };
         if (fits(plane_in, plane_out)) {
+            // Planes per workgroup: among the counts that fit (up to 48 KB when the caller did not
+            // ask otherwise) and leave at least 2048 workgroups, the one that keeps the 512 lanes
+            // busiest over the phases (windows, cells or elements, 128-bit loads and stores).
+            const int env_cap = env_int("CNNMEM_BWD_SLAB_FLOATS", 0);
+            const long long roomy = env_cap > 0 ? cap : (cap > 12288 ? cap : 12288);
+            auto fits_roomy = [&](long long q) {
+                return part(q * plane_in) + part(q * plane_out) * (kMax ? 2 : 1) <= roomy;
+            };
+            auto busy = [&](long long work) {
+                const long long rounds = ceil_div64(work, kBwdThreads);
+                return (double)work / (double)(rounds * kBwdThreads);
+            };
+            const long long cells = (long long)ceil_div(g.H, g.sh) * ceil_div(g.W, g.sw);
             long long p = 1;
-            while (fits((p + 1) * plane_in, (p + 1) * plane_out)) ++p;
-            const long long min_blocks = 2048;
-            if (planes / p < min_blocks) p = planes / min_blocks > 0 ? planes / min_blocks : 1;
+            double best = -1.0;
+            for (long long q = 1; fits_roomy(q) && q <= planes; ++q) {
+                if (q > 1 && planes / q < 2048) break;
+                double score = busy(q * cells) * busy(q * plane_in / 4 + 1);
+                if (kMax) score *= busy(q * plane_out);
+                if (score > best + 0.02) { best = score; p = q; }     // prefer the smaller count on near ties
+            }
             plan.planes_per_wg = (int)p;
             plan.rows_per_wg = g.H;
             plan.strips = 1;
