@@ -57,6 +57,16 @@ __device__ __forceinline__ float row_reduce(float v, float* slots, int wave, int
     return v;
 }
 
+// Reduction over a group of G = 4 .. 32 neighbouring lanes (G a power of two, groups aligned
+// to G): every lane of the group ends up with the group's result.  All 64 lanes of the
+// wavefront must take part.
+template <class Op, int G>
+__device__ __forceinline__ float group_reduce(float v) {
+#pragma unroll
+    for (int off = G / 2; off >= 1; off >>= 1) v = Op::apply(v, __shfl_xor(v, off, G));
+    return v;
+}
+
 // exp(d) for d <= 0, about 1 ulp: 2^t with t = d*log2(e) rounded once, then a
 // first-order correction for the rounding error of that product.  Arguments
 // below -120 give exactly 0 (they are below the smallest fp32 denormal anyway).

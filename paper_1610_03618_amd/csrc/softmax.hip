@@ -106,34 +106,106 @@ __global__ __launch_bounds__(TPR < 256 ? 256 : TPR) void softmax_rows_kernel(
     if (live && is_edge) st1_stream(y + edge_idx, e * inv);
 }
 
-// Rows of fewer than 8 categories: one lane per row, everything in registers.
+// Rows of fewer than 4 categories: one lane per row, everything in registers.
 __global__ __launch_bounds__(256) void softmax_tiny_kernel(const float* logits, float* probs, int N, int classes) {
     const long long row = (long long)blockIdx.x * 256 + threadIdx.x;
     if (row >= N) return;
     const float* x = logits + (size_t)row * classes;
     float* y = probs + (size_t)row * classes;
-    float v[7];
+    float v[3];
     float m = kNegInf;
 #pragma unroll
-    for (int c = 0; c < 7; ++c) {
+    for (int c = 0; c < 3; ++c) {
         v[c] = c < classes ? x[c] : kNegInf;
         m = fmaxf(m, v[c]);
     }
     float s = 0.f;
 #pragma unroll
-    for (int c = 0; c < 7; ++c) {
+    for (int c = 0; c < 3; ++c) {
         v[c] = exp_nonpos(v[c] - m);
         s += v[c];
     }
     const float inv = 1.0f / s;
 #pragma unroll
-    for (int c = 0; c < 7; ++c)
+    for (int c = 0; c < 3; ++c)
         if (c < classes) y[c] = v[c] * inv;
 }
 
-// Rows too long for registers (or buffers that are not 16-byte aligned): one
-// 1024-lane workgroup per row, dword accesses, three sweeps over the row (max,
-// sum of exponentials, normalised values); the later sweeps mostly hit in L2.
+// Short rows (4 .. 159 categories; works up to 512): a whole wavefront per row would idle most lanes, so a
+// row gets G = 4 .. 32 lanes and a workgroup 256 / G rows.  Rows start at any dword, hence
+// 128-bit accesses at dword alignment; a row's last, partial float4 is loaded as the row's last
+// four words and shifted into place, so every load is unconditional.
+template <int G, int ITEMS>
+__global__ __launch_bounds__(256) void softmax_short_kernel(const float* logits, float* probs, int N, int classes) {
+    constexpr int ROWS = 256 / G;
+    const int lane = threadIdx.x % G;
+    const long long row_raw = (long long)blockIdx.x * ROWS + threadIdx.x / G;
+    const bool live = row_raw < N;
+    const long long row = live ? row_raw : (long long)N - 1;       // idle groups shadow the last row
+    const float* x = logits + (size_t)row * (size_t)classes;
+    float* y = probs + (size_t)row * (size_t)classes;
+
+    float t[ITEMS][4];
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+        const int e0 = 4 * (lane + k * G);
+        const int ec = e0 + 4 <= classes ? e0 : classes - 4;        // classes >= 4; may be far left of e0
+        const float4 v = ld4u_stream(x + (ec > 0 ? ec : 0));
+        const float a[4] = {v.x, v.y, v.z, v.w};
+        const int d = e0 - ec;                                      // 0 for whole slots, 1..3 in the last one, >= 4 past the row
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float val = kNegInf;
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (j + d == u) val = a[u];
+            t[k][j] = val;
+        }
+    }
+    float m = kNegInf;
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) m = fmaxf(fmaxf(m, fmaxf(t[k][0], t[k][1])), fmaxf(t[k][2], t[k][3]));
+    m = group_reduce<MaxOp, G>(m);
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) t[k][j] = exp_nonpos(t[k][j] - m);
+        s += (t[k][0] + t[k][1]) + (t[k][2] + t[k][3]);
+    }
+    s = group_reduce<SumOp, G>(s);
+    const float inv = 1.0f / s;
+    if (!live) return;
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+        const int e0 = 4 * (lane + k * G);
+        if (e0 + 4 <= classes) {
+            st4u_stream(y + e0, make_float4(t[k][0] * inv, t[k][1] * inv, t[k][2] * inv, t[k][3] * inv));
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (e0 + j < classes) y[e0 + j] = t[k][j] * inv;
+        }
+    }
+}
+
+template <int G>
+int launch_short(int items, const float* logits, float* probs, int N, int classes, hipStream_t st) {
+    const dim3 grid((unsigned)ceil_div64(N, 256 / G)), block(256);
+    switch (items) {
+        case 1: hipLaunchKernelGGL((softmax_short_kernel<G, 1>), grid, block, 0, st, logits, probs, N, classes); break;
+        case 2: hipLaunchKernelGGL((softmax_short_kernel<G, 2>), grid, block, 0, st, logits, probs, N, classes); break;
+        case 3: hipLaunchKernelGGL((softmax_short_kernel<G, 3>), grid, block, 0, st, logits, probs, N, classes); break;
+        default: hipLaunchKernelGGL((softmax_short_kernel<G, 4>), grid, block, 0, st, logits, probs, N, classes); break;
+    }
+    return launch_status();
+}
+
+// Rows too long for registers, or buffers whose 16-byte phases differ: one 1024-lane workgroup
+// per row, two sweeps of 128-bit accesses at dword alignment (so no head / tail bookkeeping).
+// Sweep 1 keeps a running maximum and a running sum of exponentials per lane, rescaling the sum
+// whenever the maximum grows (the "online" form of steps 1-4); sweep 2 reads the row again, by
+// then mostly from L2, and writes the normalised values.  In place is allowed: a word is read
+// by the lane that writes it, just before.
 __global__ __launch_bounds__(1024) void softmax_stream_kernel(const float* logits, float* probs,
                                                               int classes) {
     constexpr int TPR = 1024;
@@ -143,15 +215,36 @@ __global__ __launch_bounds__(1024) void softmax_stream_kernel(const float* logit
     const size_t row_off = (size_t)blockIdx.x * (size_t)classes;
     const float* x = logits + row_off;
     float* y = probs + row_off;
+    const int nvec = classes >> 2;                  // whole float4 of the row; the last 0..3 words go one by one
+    const int tail0 = nvec << 2;
 
-    float m = kNegInf;
-    for (int c = tid; c < classes; c += TPR) m = fmaxf(m, x[c]);
-    m = row_reduce<MaxOp, TPR>(m, slots, wave, 0);
-    float s = 0.f;
-    for (int c = tid; c < classes; c += TPR) s += exp_nonpos(x[c] - m);
-    s = row_reduce<SumOp, TPR>(s, slots, wave, 0);
-    const float inv = 1.0f / s;
-    for (int c = tid; c < classes; c += TPR) y[c] = exp_nonpos(x[c] - m) * inv;
+    float m = kNegInf, s = 0.f;
+    for (int q = tid; q < nvec; q += TPR) {
+        const float4 v = ld4u_stream(x + 4 * q);
+        const float vm = fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w));
+        if (vm > m) {                               // rare after the first few vectors
+            s *= exp_nonpos(m - vm);                // m = -inf at first: exp gives 0, s stays 0
+            m = vm;
+        }
+        s += (exp_nonpos(v.x - m) + exp_nonpos(v.y - m)) + (exp_nonpos(v.z - m) + exp_nonpos(v.w - m));
+    }
+    if (tid < classes - tail0) {
+        const float v = x[tail0 + tid];
+        if (v > m) { s *= exp_nonpos(m - v); m = v; }
+        s += exp_nonpos(v - m);
+    }
+    // combine the lanes: rescale every lane's sum to the row maximum, then add
+    const float row_m = row_reduce<MaxOp, TPR>(m, slots, wave, 0);
+    s *= exp_nonpos(m - row_m);                     // lanes that saw nothing: m = -inf, s = 0
+    const float row_s = row_reduce<SumOp, TPR>(s, slots, wave, 0);
+    const float inv = 1.0f / row_s;
+
+    for (int q = tid; q < nvec; q += TPR) {
+        const float4 v = ld4u_stream(x + 4 * q);
+        st4u_stream(y + 4 * q, make_float4(exp_nonpos(v.x - row_m) * inv, exp_nonpos(v.y - row_m) * inv,
+                                           exp_nonpos(v.z - row_m) * inv, exp_nonpos(v.w - row_m) * inv));
+    }
+    if (tid < classes - tail0) y[tail0 + tid] = exp_nonpos(x[tail0 + tid] - row_m) * inv;
 }
 
 template <int TPR, int ITEMS>
@@ -193,10 +286,26 @@ int launch_softmax(const float* logits, float* probs, int N, int classes, hipStr
     // whole-line accesses need both buffers at the same offset inside their 128-byte lines
     const int align = (((pa ^ pb) & 127u) == 0 && classes >= 64 && env_int("CNNMEM_SOFTMAX_ALIGN", 32) == 32) ? 32 : 4;
     const int base_mis = (int)((pa & (uintptr_t)(4 * align - 1)) >> 2);
-    if (classes < 8) {
+    if (classes < 4) {
         hipLaunchKernelGGL(softmax_tiny_kernel, dim3((unsigned)ceil_div64(N, 256)), dim3(256), 0, st, logits, probs,
                            N, classes);
         return launch_status();
+    }
+    // measured on MI355X: 44 % against 28 % of peak at 64 categories, 56 % against 44 % at 128, but
+    // 52 % against 61 % at 200, where the 64-lane register kernel below takes over
+    const int short_below = env_int("CNNMEM_SOFTMAX_SHORT_BELOW", 160);
+    if (classes < (short_below < 513 ? short_below : 513) && env_int("CNNMEM_SOFTMAX_TPR", 0) == 0) {
+        // G lanes per row, at most four float4 per lane
+        const int slots = (classes + 3) / 4;
+        int g = 4;
+        while (g < 32 && slots > 4 * g) g *= 2;
+        const int items = (slots + g - 1) / g;
+        switch (g) {
+            case 4: return launch_short<4>(items, logits, probs, N, classes, st);
+            case 8: return launch_short<8>(items, logits, probs, N, classes, st);
+            case 16: return launch_short<16>(items, logits, probs, N, classes, st);
+            default: return launch_short<32>(items, logits, probs, N, classes, st);
+        }
     }
     const long long nq = classes / 4;                             // most aligned float4 a row can hold
     int tpr = env_int("CNNMEM_SOFTMAX_TPR", 0);

@@ -298,3 +298,26 @@ def test_non_default_stream():
     want = oracle.softmax(z)
     err = np.abs(out.cpu().numpy().astype(np.float64) - want)
     assert np.all(err <= np.maximum(2e-6 * np.abs(want), 1e-7))
+
+
+@pytest.mark.parametrize("shape", [(1000, 4), (777, 5), (300, 10), (129, 31), (64, 63), (50, 100), (33, 159), (17, 160),
+                                   (9, 257), (5, 512), (3, 70001), (2, 131073), (1, 262147)],
+                         ids=lambda s: f"{s[0]}x{s[1]}")
+def test_softmax_short_and_very_long_rows(shape):
+    """Sub-wavefront row groups (4 .. 32 lanes per row) and the two-sweep kernel for rows beyond the register budget."""
+    n, c = shape
+    rng = np.random.default_rng(n + c)
+    z = wl.normal_logits(rng, n, c, 3.0)
+    if c > 10:
+        z = wl.plant_outliers(z, rng)
+    want = oracle.softmax(z).astype(np.float64)
+    got = cm.softmax(torch.from_numpy(z).cuda()).cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - want) <= np.maximum(2e-6 * want, 1e-7)), shape
+    # a view one float into a buffer: rows start at every dword phase
+    buf = torch.zeros(n * c + 4, device="cuda")
+    buf[1:1 + n * c] = torch.from_numpy(z).cuda().reshape(-1)
+    out = torch.zeros(n * c + 4, device="cuda")
+    assert cm.cnnmem_softmax(buf[1:], out[3:], n, c) == 0
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got[3:3 + n * c].reshape(n, c) - want) <= np.maximum(2e-6 * want, 1e-7)), shape
+    assert not got[:3].any() and not got[3 + n * c:].any()
