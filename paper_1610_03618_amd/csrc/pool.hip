@@ -184,6 +184,40 @@ __global__ __launch_bounds__(kThreads) void pool_chwn_vec4_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// CHWN, any window: float4 over four images, one output per lane, the window walked
+// with run-time loops (global 7x7 pooling, 5x5 / stride 3, rectangular windows ...).
+// ---------------------------------------------------------------------------
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void pool_chwn_vec4_any_kernel(
+    const float* __restrict__ src, float* __restrict__ dst, PoolGeom g, uint32_t items, FastDiv div_n4, FastDiv div_wo,
+    FastDiv div_ho) {
+    const uint32_t u = blockIdx.x * kThreads + threadIdx.x;   // ((c*Ho + i)*Wo + j)*N4 + n4
+    if (u >= items) return;
+    uint32_t t = fd_div(u, div_n4);
+    const uint32_t n4 = u - t * div_n4.d;
+    uint32_t t2 = fd_div(t, div_wo);
+    const int j = (int)(t - t2 * div_wo.d);
+    const uint32_t c = fd_div(t2, div_ho);
+    const int i = (int)(t2 - c * div_ho.d);
+    const int N = g.N;
+    // in-image part of the window
+    int r_lo = i * g.sh - g.ph, q_lo = j * g.sw - g.pw;
+    int r_hi = r_lo + g.kh, q_hi = q_lo + g.kw;
+    if (r_lo < 0) r_lo = 0;
+    if (q_lo < 0) q_lo = 0;
+    if (r_hi > g.H) r_hi = g.H;
+    if (q_hi > g.W) q_hi = g.W;
+    const float* plane = src + (size_t)c * g.H * g.W * N + 4 * n4;
+    float4 acc = Acc<MODE>::identity4();
+    for (int r = r_lo; r < r_hi; ++r) {
+        const float* rowp = plane + (size_t)r * g.W * N;
+        for (int q = q_lo; q < q_hi; ++q)
+            acc = Acc<MODE>::op4(acc, *reinterpret_cast<const float4*>(rowp + (size_t)q * N));
+    }
+    st4_stream(dst + 4 * (size_t)u, Acc<MODE>::finish4(acc, (float)(g.kh * g.kw)));
+}
+
+// ---------------------------------------------------------------------------
 // NCHW, 2x2 window, stride 2, no padding, even H: the tensor is a list of
 // N*C*H rows of W floats and output row k is made of input rows 2k and 2k+1.
 // A lane reads one float4 of both rows and writes two outputs: a wavefront's
@@ -430,6 +464,13 @@ int dispatch_chwn(const float* src, float* dst, const PoolGeom& g, const PoolTun
         rc = launch_chwn_window<MODE, 3, 3, 1, 1>(tune.rows_per_lane ? tune.rows_per_lane : 4, ox, src, dst, g, tune, st);
     }
     if (rc != CNNMEM_ERR_UNSUPPORTED) return rc;
+    const long long items = (long long)g.C * g.Ho * g.Wo * (g.N / 4);
+    if (vec && items < 0x7fffffffLL && items > 0) {
+        hipLaunchKernelGGL((pool_chwn_vec4_any_kernel<MODE>), dim3((unsigned)ceil_div64(items, kThreads)), dim3(kThreads),
+                           0, st, src, dst, g, (uint32_t)items, make_fastdiv((uint32_t)(g.N / 4)),
+                           make_fastdiv((uint32_t)g.Wo), make_fastdiv((uint32_t)g.Ho));
+        return launch_status();
+    }
     return launch_generic<MODE>(src, dst, g, 1, st);
 }
 
