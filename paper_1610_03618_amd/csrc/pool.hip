@@ -356,15 +356,22 @@ __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
         const int base = lds0 + pl * plane_in;      // LDS index of this plane's element (0, 0)
         float acc = Acc<MODE>::identity();
         if (KH != 0) {
+            // With padding, a tap outside the image is read from the nearest in-image position, which
+            // lies in the same window (every window keeps a tap): the maximum does not change, the
+            // average drops it by a select.  No branches either way.
 #pragma unroll
             for (int y = 0; y < (KH ? KH : 1); ++y) {
                 const int r = rb + y;
-                if (PADDED && (r < 0 || r >= g.H)) continue;
+                const bool r_in = !PADDED || (r >= 0 && r < g.H);
+                const int rc = !PADDED ? r : (r < 0 ? 0 : (r < g.H ? r : g.H - 1));
 #pragma unroll
                 for (int x = 0; x < (KW ? KW : 1); ++x) {
                     const int q = qb + x;
-                    if (PADDED && (q < 0 || q >= g.W)) continue;
-                    acc = Acc<MODE>::op(acc, slab[base + r * g.W + q]);
+                    const bool in = r_in && (!PADDED || (q >= 0 && q < g.W));
+                    const int qc = !PADDED ? q : (q < 0 ? 0 : (q < g.W ? q : g.W - 1));
+                    const float v = slab[base + rc * g.W + qc];
+                    if (MODE == CNNMEM_POOL_MAX) acc = fmaxf(acc, v);
+                    else acc += in ? v : 0.f;
                 }
             }
         } else {
@@ -558,6 +565,8 @@ int dispatch_nchw(const float* src, float* dst, const PoolGeom& g, const PoolTun
                 return launch_slab<MODE, 3, 3, 2, 2>(src, dst, g, plan, blocks, tune, st);
             if (g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2)
                 return launch_slab<MODE, 2, 2, 2, 2>(src, dst, g, plan, blocks, tune, st);
+            if (g.kh == 3 && g.kw == 3 && g.sh == 1 && g.sw == 1)
+                return launch_slab<MODE, 3, 3, 1, 1>(src, dst, g, plan, blocks, tune, st);
             return launch_slab<MODE, 0, 0, 0, 0>(src, dst, g, plan, blocks, tune, st);
         }
     }
