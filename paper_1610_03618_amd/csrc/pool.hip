@@ -258,10 +258,14 @@ struct SlabPlan {
     long long total_planes;
 };
 
-template <int MODE, int KH, int KW, int SH, int SW, bool PADDED, int THREADS>
+// OY > 1 (compile-time windows only): a lane owns OY vertically adjacent outputs.  Each of the (OY-1)*SH + KH input
+// rows they touch is reduced along W once and that row result serves every output whose window holds the row (the
+// CHWN kernel's reuse, taken from LDS here); lanes stay adjacent along W, so the LDS reads stay conflict-free.
+// div_blk divides by the number of row blocks per plane, ceil(rows_out / OY).
+template <int MODE, int KH, int KW, int SH, int SW, int OY, bool PADDED, int THREADS>
 __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
     const float* __restrict__ src, float* __restrict__ dst, PoolGeom g, SlabPlan plan,
-    FastDiv div_wo, FastDiv div_plane_out, int rt_kh, int rt_kw, int rt_sh, int rt_sw) {
+    FastDiv div_wo, FastDiv div_plane_out, FastDiv div_blk, int rt_kh, int rt_kw, int rt_sh, int rt_sw) {
     constexpr int kSlabThreads = THREADS;
     constexpr int kSlabVecPerLane = kSlabFloats / 4 / THREADS + 1;   // float4 per lane, worst case
     __shared__ __attribute__((aligned(16))) float slab[kSlabFloats + 8];
@@ -341,6 +345,59 @@ __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
     const int lds0 = (int)((long long)((size_t)p0 * plane_in) - (long long)a_lo);
     // Lane -> output assignment is shifted so that every wavefront's 256-byte
     // store starts on a 128-byte line of dst (no line is written in two pieces).
+    if constexpr (OY > 1 && KH != 0) {
+        constexpr int ROWS = (OY - 1) * SH + KH;
+        const int nblk = (int)div_blk.d;             // row blocks per plane
+        const int n_items = planes * nblk * g.Wo;
+        const int r_last = r_hi - 1;                 // rows of the slab: [r_lo, r_hi)
+        for (int it = (int)threadIdx.x; it < n_items; it += kSlabThreads) {
+            const int pb = (int)fd_div((uint32_t)it, div_wo);      // plane * nblk + block
+            const int j = it - pb * g.Wo;
+            const int pl = (int)fd_div((uint32_t)pb, div_blk);
+            const int blk = pb - pl * nblk;
+            const int il0 = blk * OY;                               // first output row of the lane, strip-local
+            const int rb = (i0 + il0) * SH - g.ph;
+            const int qb = j * SW - g.pw;
+            const int base = lds0 + pl * plane_in;
+            // Rows and columns are clamped into the slab: a clamped tap of a real output lies in the same
+            // window (so the maximum is unchanged; the average drops it by a select), and the rows of outputs
+            // past the strip's end only feed results that are never stored.
+            int qc[KW];
+            bool q_in[KW];
+#pragma unroll
+            for (int x = 0; x < KW; ++x) {
+                const int q = qb + x;
+                q_in[x] = !PADDED || (q >= 0 && q < g.W);
+                qc[x] = !PADDED ? q : (q < 0 ? 0 : (q < g.W ? q : g.W - 1));
+            }
+            float hr[ROWS];
+#pragma unroll
+            for (int y = 0; y < ROWS; ++y) {
+                const int r = rb + y;
+                int rc = r < r_last ? r : r_last;
+                if (PADDED) rc = rc > r_lo ? rc : r_lo;
+                const float* row = slab + base + rc * g.W;
+                float acc = Acc<MODE>::identity();
+#pragma unroll
+                for (int x = 0; x < KW; ++x) {
+                    const float v = row[qc[x]];
+                    if (MODE == CNNMEM_POOL_MAX) acc = fmaxf(acc, v);
+                    else acc += q_in[x] ? v : 0.f;
+                }
+                if (MODE != CNNMEM_POOL_MAX && PADDED && (r < 0 || r >= g.H)) acc = 0.f;
+                hr[y] = acc;
+            }
+            float* out = dst + out0 + (size_t)(pl * rows_out + il0) * g.Wo + j;
+#pragma unroll
+            for (int k = 0; k < OY; ++k) {
+                float acc = hr[k * SH];
+#pragma unroll
+                for (int y = 1; y < KH; ++y) acc = Acc<MODE>::op(acc, hr[k * SH + y]);
+                if (il0 + k < rows_out) st1_stream(out + (size_t)k * g.Wo, Acc<MODE>::finish(acc, (float)(KH * KW)));
+            }
+        }
+        return;
+    }
     const int lead = (int)(((reinterpret_cast<uintptr_t>(dst) >> 2) + out0) & 31);
     for (int o = (int)threadIdx.x - lead; o < n_out; o += kSlabThreads) {
         if (o < 0) continue;
@@ -481,29 +538,31 @@ int dispatch_chwn(const float* src, float* dst, const PoolGeom& g, const PoolTun
     return launch_generic<MODE>(src, dst, g, 1, st);
 }
 
-template <int MODE, int KH, int KW, int SH, int SW, int THREADS>
+template <int MODE, int KH, int KW, int SH, int SW, int OY, int THREADS>
 int launch_slab_threads(const float* src, float* dst, const PoolGeom& g, const SlabPlan& plan, long long blocks,
                         hipStream_t st) {
     const FastDiv dwo = make_fastdiv((uint32_t)g.Wo);
     const FastDiv dpo = make_fastdiv((uint32_t)(g.Ho * g.Wo));
+    const int rows_out = plan.strips == 1 ? g.Ho : plan.rows_per_wg;
+    const FastDiv dblk = make_fastdiv((uint32_t)ceil_div(rows_out, OY));
     if (g.ph > 0 || g.pw > 0 || KH == 0)
-        hipLaunchKernelGGL((pool_nchw_slab_kernel<MODE, KH, KW, SH, SW, true, THREADS>), dim3((unsigned)blocks),
-                           dim3(THREADS), 0, st, src, dst, g, plan, dwo, dpo, g.kh, g.kw, g.sh, g.sw);
+        hipLaunchKernelGGL((pool_nchw_slab_kernel<MODE, KH, KW, SH, SW, OY, true, THREADS>), dim3((unsigned)blocks),
+                           dim3(THREADS), 0, st, src, dst, g, plan, dwo, dpo, dblk, g.kh, g.kw, g.sh, g.sw);
     else
-        hipLaunchKernelGGL((pool_nchw_slab_kernel<MODE, KH, KW, SH, SW, false, THREADS>), dim3((unsigned)blocks),
-                           dim3(THREADS), 0, st, src, dst, g, plan, dwo, dpo, g.kh, g.kw, g.sh, g.sw);
+        hipLaunchKernelGGL((pool_nchw_slab_kernel<MODE, KH, KW, SH, SW, OY, false, THREADS>), dim3((unsigned)blocks),
+                           dim3(THREADS), 0, st, src, dst, g, plan, dwo, dpo, dblk, g.kh, g.kw, g.sh, g.sw);
     return launch_status();
 }
 
-template <int MODE, int KH, int KW, int SH, int SW>
+template <int MODE, int KH, int KW, int SH, int SW, int OY = 1>
 int launch_slab(const float* src, float* dst, const PoolGeom& g, const SlabPlan& plan, long long blocks,
                 const PoolTuning& tune, hipStream_t st) {
     // lanes per slab: more lanes = fewer 128-bit loads in flight per lane for the same 32 KB;
     // 512 measured best (68 % of peak against 64 % with 256 and 49 % with 1024)
     const int threads = tune.slab_lanes ? tune.slab_lanes : 512;
-    if (threads >= 1024) return launch_slab_threads<MODE, KH, KW, SH, SW, 1024>(src, dst, g, plan, blocks, st);
-    if (threads >= 512) return launch_slab_threads<MODE, KH, KW, SH, SW, 512>(src, dst, g, plan, blocks, st);
-    return launch_slab_threads<MODE, KH, KW, SH, SW, 256>(src, dst, g, plan, blocks, st);
+    if (threads >= 1024) return launch_slab_threads<MODE, KH, KW, SH, SW, OY, 1024>(src, dst, g, plan, blocks, st);
+    if (threads >= 512) return launch_slab_threads<MODE, KH, KW, SH, SW, OY, 512>(src, dst, g, plan, blocks, st);
+    return launch_slab_threads<MODE, KH, KW, SH, SW, OY, 256>(src, dst, g, plan, blocks, st);
 }
 
 template <int MODE>
@@ -561,12 +620,25 @@ int dispatch_nchw(const float* src, float* dst, const PoolGeom& g, const PoolTun
             }
         }
         if (ok && blocks <= 0x7fffffffLL) {
-            if (g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2)
+            // Rows per lane.  Several rows share row results and, with padding, the clamping arithmetic, but
+            // break the workgroup's contiguous output run into row pieces: measured better only with padding
+            // (3x3/s1/p1 64x256x56x56: 43 -> 57 % max, 34 -> 55 % avg; 3x3/s2/p1 avg 63 -> 70 %) and worse
+            // without (3x3/s1: 68 -> 49 %; 3x3/s2: 75 -> 70 %).
+            const bool padded = g.ph > 0 || g.pw > 0;
+            int oy = env_int("CNNMEM_SLAB_ROWS", 0);
+            if (oy == 0) oy = !padded ? 1 : (g.sh == 1 ? 4 : (MODE == CNNMEM_POOL_AVG ? 2 : 1));
+            if (g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2) {
+                if (oy == 3) return launch_slab<MODE, 3, 3, 2, 2, 3>(src, dst, g, plan, blocks, tune, st);
+                if (oy == 2) return launch_slab<MODE, 3, 3, 2, 2, 2>(src, dst, g, plan, blocks, tune, st);
                 return launch_slab<MODE, 3, 3, 2, 2>(src, dst, g, plan, blocks, tune, st);
+            }
+            if (g.kh == 3 && g.kw == 3 && g.sh == 1 && g.sw == 1) {
+                if (oy == 1) return launch_slab<MODE, 3, 3, 1, 1>(src, dst, g, plan, blocks, tune, st);
+                if (oy == 2) return launch_slab<MODE, 3, 3, 1, 1, 2>(src, dst, g, plan, blocks, tune, st);
+                return launch_slab<MODE, 3, 3, 1, 1, 4>(src, dst, g, plan, blocks, tune, st);
+            }
             if (g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2)
                 return launch_slab<MODE, 2, 2, 2, 2>(src, dst, g, plan, blocks, tune, st);
-            if (g.kh == 3 && g.kw == 3 && g.sh == 1 && g.sw == 1)
-                return launch_slab<MODE, 3, 3, 1, 1>(src, dst, g, plan, blocks, tune, st);
             return launch_slab<MODE, 0, 0, 0, 0>(src, dst, g, plan, blocks, tune, st);
         }
     }

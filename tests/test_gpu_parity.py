@@ -185,6 +185,19 @@ def test_pool_nchw_every_kernel_choice(tuning):
     check_pool(x, 8, 4, 16, 16, (2, 2, 2, 2, 0, 0), layouts=(CHWN,), tuning=tuning)
 
 
+@pytest.mark.parametrize("rows", [0, 1, 2, 3, 4])
+def test_pool_nchw_slab_rows_per_lane(rows, monkeypatch):
+    """The LDS kernel's several-outputs-per-lane variants (padding clamps, ragged row blocks, strips with halo)."""
+    monkeypatch.setenv("CNNMEM_SLAB_ROWS", str(rows))
+    rng = np.random.default_rng(40 + rows)
+    for shape, geom in [((3, 5, 13, 17), (3, 3, 1, 1, 1, 1)), ((2, 3, 57, 57), (3, 3, 1, 1, 0, 0)),
+                        ((1, 2, 130, 131), (3, 3, 1, 1, 1, 1)), ((3, 5, 13, 17), (3, 3, 2, 2, 1, 1)),
+                        ((2, 3, 57, 57), (3, 3, 2, 2, 0, 0)), ((1, 2, 230, 131), (3, 3, 2, 2, 1, 1)),
+                        ((2, 2, 9, 300), (3, 3, 1, 1, 1, 0)), ((2, 2, 300, 9), (3, 3, 2, 2, 0, 1))]:
+        x = rng.standard_normal(shape, dtype=np.float32)
+        check_pool(x, *shape, geom, layouts=(NCHW,))
+
+
 def test_pool_misaligned_views():
     N, C, H, W = 8, 3, 9, 9
     geom = (3, 3, 2, 2, 0, 0)
