@@ -145,11 +145,20 @@ __global__ __launch_bounds__(THREADS) void permute_tile_kernel(
 
 constexpr int kThin = 1024;     // entries of the long axis per workgroup
 
+// The block's kThin * T words sit in LDS in the order of its contiguous side, as 128-bit slots;
+// slot f lives at f + f/8.  Eight neighbouring lanes that each own T consecutive slots (stride T),
+// and eight lanes that walk consecutive slots, then both touch eight different 16-byte bank groups
+// for every T <= 8; with words T apart and no padding, T = 8 put all lanes of a wavefront on two banks.
+__device__ __forceinline__ int thin_slot(int f) { return f + (f >> 3); }
+__device__ __forceinline__ int thin_word(int i) { return 4 * thin_slot(i >> 2) + (i & 3); }
+constexpr int thin_lds_words(int T) { return 4 * (kThin / 4 * T + kThin / 32 * T); }
+__device__ __forceinline__ float component(const float4& v, int c) { return c == 0 ? v.x : c == 1 ? v.y : c == 2 ? v.z : v.w; }
+
 // Destination rows are thin: dst[s][r], r < T, rows back to back (ds_s == T).
 template <int T>
 __global__ __launch_bounds__(kThreads) void permute_thin_dst_kernel(
     const float* __restrict__ src, float* __restrict__ dst, TilePlan p, FastDiv d_plane, FastDiv d_nb1) {
-    __shared__ __attribute__((aligned(16))) float tile[kThin * T + 4 * T];   // + room for words left of the tile
+    __shared__ __attribute__((aligned(16))) float tile[thin_lds_words(T)];
     const uint32_t batch = fd_div(blockIdx.x, d_plane);
     const uint32_t ts = blockIdx.x - batch * p.tiles_plane;
     const uint32_t b0 = fd_div(batch, d_nb1);
@@ -160,20 +169,35 @@ __global__ __launch_bounds__(kThreads) void permute_thin_dst_kernel(
     const int ns = (int)(p.S - s0 < kThin ? p.S - s0 : kThin);
     const int tid = threadIdx.x;
 
-    // T source rows of kThin words: one float4 per lane per row, clamped like the tile kernel
+    // T source rows of kThin words: one float4 per lane per row; the lanes at the end of the last
+    // block re-read the row's last four words instead (S >= 4: launcher)
     long long s = s0 + 4 * tid;
-    s = s + 4 <= p.S ? s : p.S - 4;                     // S >= 4 (launcher)
+    s = s + 4 <= p.S ? s : p.S - 4;
     const int col = (int)(s - s0);                      // -3 .. kThin - 4
     float4 v[T];
 #pragma unroll
     for (int r = 0; r < T; ++r) v[r] = ld4u_stream(src + (size_t)r * (size_t)p.ss_r + (size_t)s);
-    float* t0 = tile + 4 * T;                           // tile[(c) * T + r], c may be -3..-1
+    if (col == 4 * tid) {
+        // four columns x T rows = 4T consecutive destination words = T whole slots
+        float w[4 * T];
 #pragma unroll
-    for (int r = 0; r < T; ++r) {
-        t0[(col + 0) * T + r] = v[r].x;
-        t0[(col + 1) * T + r] = v[r].y;
-        t0[(col + 2) * T + r] = v[r].z;
-        t0[(col + 3) * T + r] = v[r].w;
+        for (int r = 0; r < T; ++r) {
+            w[0 * T + r] = v[r].x;
+            w[1 * T + r] = v[r].y;
+            w[2 * T + r] = v[r].z;
+            w[3 * T + r] = v[r].w;
+        }
+#pragma unroll
+        for (int k = 0; k < T; ++k)
+            *reinterpret_cast<float4*>(tile + 4 * thin_slot(tid * T + k)) =
+                make_float4(w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3]);
+    } else {
+        // shifted lanes: word by word; columns left of the block belong to the previous one
+#pragma unroll
+        for (int r = 0; r < T; ++r)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (col + c >= 0) tile[thin_word((col + c) * T + r)] = component(v[r], c);
     }
     __syncthreads();
     // the block's ns * T destination words are contiguous
@@ -181,9 +205,9 @@ __global__ __launch_bounds__(kThreads) void permute_thin_dst_kernel(
     const int total = ns * T;
     for (int i = 4 * tid; i < total; i += 4 * kThreads) {
         if (i + 4 <= total) {
-            st4u_stream(out + i, make_float4(t0[i], t0[i + 1], t0[i + 2], t0[i + 3]));
+            st4u_stream(out + i, *reinterpret_cast<const float4*>(tile + 4 * thin_slot(i >> 2)));
         } else {
-            for (int j = i; j < total; ++j) st1_stream(out + j, t0[j]);
+            for (int j = i; j < total; ++j) st1_stream(out + j, tile[thin_word(j)]);
         }
     }
 }
@@ -192,7 +216,7 @@ __global__ __launch_bounds__(kThreads) void permute_thin_dst_kernel(
 template <int T>
 __global__ __launch_bounds__(kThreads) void permute_thin_src_kernel(
     const float* __restrict__ src, float* __restrict__ dst, TilePlan p, FastDiv d_plane, FastDiv d_nb1) {
-    __shared__ __attribute__((aligned(16))) float tile[kThin * T + 4];
+    __shared__ __attribute__((aligned(16))) float tile[thin_lds_words(T)];
     const uint32_t batch = fd_div(blockIdx.x, d_plane);
     const uint32_t tr = blockIdx.x - batch * p.tiles_plane;
     const uint32_t b0 = fd_div(batch, d_nb1);
@@ -218,27 +242,38 @@ __global__ __launch_bounds__(kThreads) void permute_thin_src_kernel(
         at[k] = i;
         v[k] = ld4u_stream(in + i);
     }
-    float* t0 = tile + 4;
 #pragma unroll
     for (int k = 0; k < T; ++k) {
-        // words in front of the block (at[k] < 0) fall into the 4 spare words before t0
-        t0[at[k] + 0] = v[k].x;
-        t0[at[k] + 1] = v[k].y;
-        t0[at[k] + 2] = v[k].z;
-        t0[at[k] + 3] = v[k].w;
+        if (at[k] == 4 * (tid + k * kThreads)) {
+            *reinterpret_cast<float4*>(tile + 4 * thin_slot(tid + k * kThreads)) = v[k];
+        } else {
+            // shifted lanes: word by word; words in front of the block belong to the previous one
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (at[k] + c >= 0) tile[thin_word(at[k] + c)] = component(v[k], c);
+        }
     }
     __syncthreads();
-    // T destination rows of nr words
+    // T destination rows of nr words; a lane's four rows x T columns are T whole slots
+    const int r = 4 * tid;
+    if (r + 4 <= nr) {
+        float w[4 * T];
 #pragma unroll
-    for (int sidx = 0; sidx < T; ++sidx) {
-        const int r = 4 * tid;
-        float* q = dst + (size_t)sidx * (size_t)p.ds_s + (size_t)(r0 + r);
-        if (r + 4 <= nr) {
-            st4u_stream(q, make_float4(t0[(r + 0) * T + sidx], t0[(r + 1) * T + sidx], t0[(r + 2) * T + sidx],
-                                       t0[(r + 3) * T + sidx]));
-        } else {
-            for (int j = r; j < nr; ++j) st1_stream(q + (j - r), t0[j * T + sidx]);
+        for (int k = 0; k < T; ++k) {
+            const float4 q = *reinterpret_cast<const float4*>(tile + 4 * thin_slot(tid * T + k));
+            w[4 * k] = q.x;
+            w[4 * k + 1] = q.y;
+            w[4 * k + 2] = q.z;
+            w[4 * k + 3] = q.w;
         }
+#pragma unroll
+        for (int sidx = 0; sidx < T; ++sidx)
+            st4u_stream(dst + (size_t)sidx * (size_t)p.ds_s + (size_t)(r0 + r),
+                        make_float4(w[0 * T + sidx], w[1 * T + sidx], w[2 * T + sidx], w[3 * T + sidx]));
+    } else {
+        for (int sidx = 0; sidx < T; ++sidx)
+            for (int j = r; j < nr; ++j)
+                st1_stream(dst + (size_t)sidx * (size_t)p.ds_s + (size_t)(r0 + j), tile[thin_word(j * T + sidx)]);
     }
 }
 

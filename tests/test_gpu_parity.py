@@ -45,6 +45,10 @@ TRANSFORM_SHAPES = [
     (32, 6, 10, 10), (8, 16, 9, 4), (256, 2, 17, 4), (100, 4, 5, 9), (132, 3, 11, 4),   # vector paths, ragged tiles
     (5, 7, 3, 3), (3, 2, 55, 55), (127, 1, 9, 7), (16, 3, 5, 5), (66, 1, 1, 129),       # scalar path
     (20, 8, 6, 2), (12, 4, 4, 4),
+    (1, 3, 17, 19), (1, 64, 8, 8),                                                      # one image: a copy
+    (2, 3, 37, 61), (3, 5, 21, 33), (4, 16, 28, 28), (5, 1, 1, 1025), (6, 2, 50, 50),   # 2..8 images: thin-plane kernels,
+    (7, 3, 19, 23), (8, 8, 32, 32), (8, 1, 1, 3), (4, 1, 1, 1), (2, 1, 1, 2),           # several blocks, ragged ends
+    (100, 4, 16, 16), (96, 8, 8, 8), (72, 64, 4, 4),                                     # 65..127 images: 128-wide tiles
 ]
 
 
