@@ -389,8 +389,8 @@ int launch_tile_shape(const float* src, float* dst, const TilePlan& p, long long
         else if (p.R <= 32) shape = ragged_src && p.S >= 256 ? 8 : 1;
         else if (p.S <= 16) shape = 4;
         else if (p.S <= 32) shape = ragged_dst && p.R >= 256 ? 11 : 2;
-        else if (ragged_dst && !ragged_src && p.R >= 256) shape = 11;
-        else if (ragged_src && !ragged_dst && p.S >= 256) shape = 8;
+        else if (ragged_dst && !ragged_src && p.R > 128) shape = 11;   // 13x13 and 14x14 planes included
+        else if (ragged_src && !ragged_dst && p.S > 128) shape = 8;
         else shape = 0;
     }
     switch (shape) {

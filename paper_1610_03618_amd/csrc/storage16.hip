@@ -330,7 +330,201 @@ int launch_t16(const uint16_t* src, uint16_t* dst, long long R, long long S, hip
     return launch_status();
 }
 
+struct Tile16Plan {
+    long long R, S, ss_r, ds_s, sb0, sb1, db0, db1;
+    uint32_t tiles_s, tiles_plane;
+};
+
+// ---- thin planes: one tile axis has 2..8 entries (batches of 2..8 images, RGB input) ----------
+// A workgroup takes all T entries of the thin axis and kThin16 entries of the long one.  On the side
+// where the thin axis is fastest that block is one contiguous run and moves as a linear 128-bit stream;
+// in LDS it is kept in that order as 128-bit slots, slot f at f + f/8 (a lane's eight entries of the
+// long axis times T are T whole slots; the padding spreads neighbouring lanes over all bank groups).
+constexpr int kThin16 = 2048;
+__device__ __forceinline__ int thin16_slot(int f) { return f + (f >> 3); }
+__device__ __forceinline__ int thin16_word(int i) { return 8 * thin16_slot(i >> 3) + (i & 7); }
+constexpr int thin16_lds_words(int T) { return 8 * (kThin16 / 8 * T + kThin16 / 64 * T); }
+__device__ __forceinline__ uint32_t word_of(const u32x4& v, int c) {        // c-th 16-bit word of eight
+    const uint32_t d = c < 2 ? v.x : c < 4 ? v.y : c < 6 ? v.z : v.w;
+    return (c & 1) ? d >> 16 : d & 0xffffu;
+}
+
+// Destination rows are thin: dst[s][r], r < T, rows back to back (ds_s == T).  S >= 8.
+template <int T>
+__global__ __launch_bounds__(kThreads) void permute16_thin_dst_kernel(
+    const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, Tile16Plan p, FastDiv d_plane, FastDiv d_nb1) {
+    __shared__ __attribute__((aligned(16))) uint16_t tile[thin16_lds_words(T)];
+    const uint32_t batch = fd_div(blockIdx.x, d_plane);
+    const uint32_t ts = blockIdx.x - batch * p.tiles_plane;
+    const uint32_t b0 = fd_div(batch, d_nb1);
+    const uint32_t b1 = batch - b0 * d_nb1.d;
+    src += (size_t)b0 * (size_t)p.sb0 + (size_t)b1 * (size_t)p.sb1;
+    dst += (size_t)b0 * (size_t)p.db0 + (size_t)b1 * (size_t)p.db1;
+    const long long s0 = (long long)ts * kThin16;
+    const int ns = (int)(p.S - s0 < kThin16 ? p.S - s0 : kThin16);
+    const int tid = threadIdx.x;
+
+    long long s = s0 + 8 * tid;
+    s = s + 8 <= p.S ? s : p.S - 8;                     // lanes past the end re-read the row's last eight words
+    const int col = (int)(s - s0);                      // -7 .. kThin16 - 8
+    u32x4 v[T];
+#pragma unroll
+    for (int r = 0; r < T; ++r) v[r] = load8_any(src + (size_t)r * (size_t)p.ss_r + (size_t)s);
+    if (col == 8 * tid) {
+        // eight columns x T rows = 8T consecutive destination words = T whole slots; word h of them is
+        // column h / T of row h % T
+#pragma unroll
+        for (int k = 0; k < T; ++k) {
+            uint32_t d[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int lo = 8 * k + 2 * j, hi = lo + 1;
+                d[j] = word_of(v[lo % T], lo / T) | (word_of(v[hi % T], hi / T) << 16);
+            }
+            u32x4 o;
+            o.x = d[0]; o.y = d[1]; o.z = d[2]; o.w = d[3];
+            *reinterpret_cast<u32x4*>(tile + 8 * thin16_slot(tid * T + k)) = o;
+        }
+    } else {
+        // shifted lanes: word by word; columns left of the block belong to the previous one
+#pragma unroll
+        for (int r = 0; r < T; ++r)
+#pragma unroll
+            for (int c = 0; c < 8; ++c)
+                if (col + c >= 0) tile[thin16_word((col + c) * T + r)] = (uint16_t)word_of(v[r], c);
+    }
+    __syncthreads();
+    uint16_t* out = dst + (size_t)s0 * T;               // the block's ns * T destination words are contiguous
+    const int total = ns * T;
+    for (int i = 8 * tid; i < total; i += 8 * kThreads) {
+        if (i + 8 <= total) {
+            store8_any(out + i, *reinterpret_cast<const u32x4*>(tile + 8 * thin16_slot(i >> 3)));
+        } else {
+            for (int j = i; j < total; ++j) out[j] = tile[thin16_word(j)];
+        }
+    }
+}
+
+// Source rows are thin: src[r][s], s < T, rows back to back (ss_r == T).  R * T >= 8.
+template <int T>
+__global__ __launch_bounds__(kThreads) void permute16_thin_src_kernel(
+    const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, Tile16Plan p, FastDiv d_plane, FastDiv d_nb1) {
+    __shared__ __attribute__((aligned(16))) uint16_t tile[thin16_lds_words(T)];
+    const uint32_t batch = fd_div(blockIdx.x, d_plane);
+    const uint32_t tr = blockIdx.x - batch * p.tiles_plane;
+    const uint32_t b0 = fd_div(batch, d_nb1);
+    const uint32_t b1 = batch - b0 * d_nb1.d;
+    src += (size_t)b0 * (size_t)p.sb0 + (size_t)b1 * (size_t)p.sb1;
+    dst += (size_t)b0 * (size_t)p.db0 + (size_t)b1 * (size_t)p.db1;
+    const long long r0 = (long long)tr * kThin16;
+    const int nr = (int)(p.R - r0 < kThin16 ? p.R - r0 : kThin16);
+    const int tid = threadIdx.x;
+
+    // the block's nr * T source words are contiguous: a linear stream, the last vector shifted back so
+    // that it ends with the block (or, in a tiny first block, starts with the plane)
+    const uint16_t* in = src + (size_t)r0 * T;
+    const int total = nr * T;
+    const long long before = r0 * T;
+    u32x4 v[T];
+    int at[T];
+#pragma unroll
+    for (int k = 0; k < T; ++k) {
+        int i = 8 * (tid + k * kThreads);
+        i = i + 8 <= total ? i : total - 8;
+        if ((long long)i + before < 0) i = (int)-before;
+        at[k] = i;
+        v[k] = load8_any(in + i);
+    }
+#pragma unroll
+    for (int k = 0; k < T; ++k) {
+        if (at[k] == 8 * (tid + k * kThreads)) {
+            *reinterpret_cast<u32x4*>(tile + 8 * thin16_slot(tid + k * kThreads)) = v[k];
+        } else {
+#pragma unroll
+            for (int c = 0; c < 8; ++c)
+                if (at[k] + c >= 0) tile[thin16_word(at[k] + c)] = (uint16_t)word_of(v[k], c);
+        }
+    }
+    __syncthreads();
+    // T destination rows of nr words; a lane's eight rows x T columns are T whole slots, word h of them
+    // is row h / T, column h % T
+    const int r = 8 * tid;
+    if (r + 8 <= nr) {
+        u32x4 q[T];
+#pragma unroll
+        for (int k = 0; k < T; ++k) q[k] = *reinterpret_cast<const u32x4*>(tile + 8 * thin16_slot(tid * T + k));
+#pragma unroll
+        for (int sidx = 0; sidx < T; ++sidx) {
+            uint32_t d[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int lo = (2 * j) * T + sidx, hi = (2 * j + 1) * T + sidx;
+                d[j] = word_of(q[lo / 8], lo % 8) | (word_of(q[hi / 8], hi % 8) << 16);
+            }
+            u32x4 o;
+            o.x = d[0]; o.y = d[1]; o.z = d[2]; o.w = d[3];
+            store8_any(dst + (size_t)sidx * (size_t)p.ds_s + (size_t)(r0 + r), o);
+        }
+    } else {
+        for (int sidx = 0; sidx < T; ++sidx)
+            for (int j = r; j < nr; ++j)
+                dst[(size_t)sidx * (size_t)p.ds_s + (size_t)(r0 + j)] = tile[thin16_word(j * T + sidx)];
+    }
+}
+
+template <int T>
+int launch_thin16(bool thin_dst, const uint16_t* src, uint16_t* dst, Tile16Plan p, long long nb0, long long nb1,
+                  hipStream_t st) {
+    const long long plane = ceil_div64(thin_dst ? p.S : p.R, kThin16);
+    if (plane >= 0x7fffffffLL || nb0 * nb1 >= 0x7fffffffLL || plane * nb0 * nb1 >= 0x7fffffffLL)
+        return CNNMEM_ERR_UNSUPPORTED;
+    p.tiles_plane = (uint32_t)plane;
+    p.tiles_s = thin_dst ? (uint32_t)plane : 1;
+    const FastDiv d_plane = make_fastdiv((uint32_t)plane), d_nb1 = make_fastdiv((uint32_t)nb1);
+    const dim3 grid((unsigned)(plane * nb0 * nb1)), block(kThreads);
+    if (thin_dst)
+        hipLaunchKernelGGL((permute16_thin_dst_kernel<T>), grid, block, 0, st, src, dst, p, d_plane, d_nb1);
+    else
+        hipLaunchKernelGGL((permute16_thin_src_kernel<T>), grid, block, 0, st, src, dst, p, d_plane, d_nb1);
+    return launch_status();
+}
+
+// CNNMEM_ERR_UNSUPPORTED when the plane is not thin (the caller then takes the tile kernels).
+int launch_thin16_any(const uint16_t* src, uint16_t* dst, const Tile16Plan& p, long long nb0, long long nb1,
+                      hipStream_t st) {
+    const bool dword_ok = ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 3u) == 0;
+    if (!dword_ok || env_int("CNNMEM_THIN16", 1) == 0) return CNNMEM_ERR_UNSUPPORTED;
+    bool thin_dst;
+    int T;
+    if (p.R >= 2 && p.R <= 8 && p.ds_s == p.R && p.S >= 8) { thin_dst = true; T = (int)p.R; }
+    else if (p.S >= 2 && p.S <= 8 && p.ss_r == p.S && p.R * p.S >= 8) { thin_dst = false; T = (int)p.S; }
+    else return CNNMEM_ERR_UNSUPPORTED;
+    switch (T) {
+        case 2: return launch_thin16<2>(thin_dst, src, dst, p, nb0, nb1, st);
+        case 3: return launch_thin16<3>(thin_dst, src, dst, p, nb0, nb1, st);
+        case 4: return launch_thin16<4>(thin_dst, src, dst, p, nb0, nb1, st);
+        case 5: return launch_thin16<5>(thin_dst, src, dst, p, nb0, nb1, st);
+        case 6: return launch_thin16<6>(thin_dst, src, dst, p, nb0, nb1, st);
+        case 7: return launch_thin16<7>(thin_dst, src, dst, p, nb0, nb1, st);
+        default: return launch_thin16<8>(thin_dst, src, dst, p, nb0, nb1, st);
+    }
+}
+
 int launch_transpose16(const uint16_t* src, uint16_t* dst, long long R, long long S, hipStream_t st) {
+    if (R == 1 || S == 1) {                             // a vector: nothing moves
+        const long long blocks = ceil_div64(ceil_div64(R * S, 8), kThreads);
+        if (blocks > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(copy16_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, src, dst, (size_t)(R * S));
+        return launch_status();
+    }
+    if (env_int("CNNMEM_TRANSFORM16_TILE", -1) < 0) {
+        Tile16Plan tp;
+        tp.R = R; tp.S = S; tp.ss_r = S; tp.ds_s = R;
+        tp.sb0 = tp.sb1 = tp.db0 = tp.db1 = 0;
+        tp.tiles_s = tp.tiles_plane = 0;
+        const int rc = launch_thin16_any(src, dst, tp, 1, 1, st);
+        if (rc != CNNMEM_ERR_UNSUPPORTED) return rc;
+    }
     const bool dword_ok = ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 3u) == 0;
     const int forced = env_int("CNNMEM_TRANSFORM16_TILE", -1);
     const bool odd = R % 2 != 0 || S % 2 != 0;
@@ -366,7 +560,7 @@ int launch_transpose16(const uint16_t* src, uint16_t* dst, long long R, long lon
             else if (R <= 32) shape = 2;
             else if (S <= 16) shape = 5;
             else if (S <= 32) shape = 4;
-            else if (R >= 128 && S >= 128) shape = 1;
+            else if (R > 64 && S > 64) shape = 1;       // 65..127 images: one 128-wide tile spans the batch
             else shape = 0;
         }
         switch (shape) {
@@ -393,10 +587,6 @@ int launch_transpose16(const uint16_t* src, uint16_t* dst, long long R, long lon
 // The strided, batched forms of the two kernels above, driven by the same canonical plan as
 // the fp32 permutation.
 
-struct Tile16Plan {
-    long long R, S, ss_r, ds_s, sb0, sb1, db0, db1;
-    uint32_t tiles_s, tiles_plane;
-};
 
 // S >= 8, R >= 2, dword-aligned buffers.  ANY = false: R and S even, so every stride is even and
 // rows start on dword boundaries on both sides.  ANY = true: odd extents as well (rows start on
@@ -629,6 +819,10 @@ int launch_permute16_impl(const uint16_t* src, uint16_t* dst, const int* dims, c
     p.R = pl.R; p.S = pl.S; p.ss_r = pl.ss_r; p.ds_s = pl.ds_s;
     p.sb0 = pl.sb0; p.sb1 = pl.sb1; p.db0 = pl.db0; p.db1 = pl.db1;
     p.tiles_s = p.tiles_plane = 0;
+    {
+        const int rc = launch_thin16_any(src, dst, p, pl.nb0, pl.nb1, st);
+        if (rc != CNNMEM_ERR_UNSUPPORTED) return rc;
+    }
     if (dword_ok && p.S >= 8 && p.R > 4) {
         // even extents: every stride is a multiple of S (source side) or R (destination side), hence even
         const bool any = p.R % 2 != 0 || p.S % 2 != 0;

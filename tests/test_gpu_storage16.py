@@ -48,7 +48,11 @@ def check_rounded(got: np.ndarray, want: np.ndarray, min_equal: float, what):
 # ---- transform -------------------------------------------------------------------
 
 T_SHAPES = [(16, 64, 32, 32), (6, 7, 9, 10), (3, 5, 7, 11), (128, 3, 9, 10), (2, 96, 13, 13), (130, 2, 33, 4),
-            (1, 8, 8, 8), (64, 1, 1, 1), (8, 1, 1, 7), (34, 4, 5, 6), (256, 16, 6, 6)]
+            (1, 8, 8, 8), (64, 1, 1, 1), (8, 1, 1, 7), (34, 4, 5, 6), (256, 16, 6, 6),
+            # 2..8 images: thin-plane kernels (several blocks, ragged and odd ends, blocks of fewer than 8 columns)
+            (2, 3, 37, 61), (3, 5, 21, 33), (4, 16, 28, 28), (5, 1, 1, 2049), (6, 2, 50, 50), (7, 3, 19, 23),
+            (8, 8, 32, 32), (8, 1, 1, 9), (4, 1, 1, 8), (2, 1, 1, 4), (3, 1, 1, 4099), (1, 3, 17, 19),
+            (100, 4, 16, 16), (96, 8, 8, 8)]
 
 
 @pytest.mark.parametrize("shape", T_SHAPES, ids=["x".join(map(str, s)) for s in T_SHAPES])
@@ -274,6 +278,20 @@ def test_permute16_every_permutation_matches_oracle(dims):
         got = cm.permute(d, dims, perm)
         assert tuple(got.shape) == want.shape
         assert np.array_equal(bits_of(got), want), (dims, perm)
+
+
+@pytest.mark.parametrize("T", [2, 3, 4, 5, 6, 7, 8])
+def test_relayout16_thin_axes_both_directions(T):
+    """Two to eight feature maps in 16-bit storage: the thin-plane kernels inside a batch of planes."""
+    for (N, H, W) in [(2, 37, 61), (1, 50, 50), (3, 1, 2049), (2, 1, 5)]:
+        rng = np.random.default_rng(T * 100 + H)
+        x = rng.integers(0, 65536, size=(N, T, H, W)).astype(np.uint16)
+        d = torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16)
+        nhwc = cm.relayout(d, N, T, H, W, "NCHW", "NHWC")
+        want = oracle.permute16(x, (N, T, H, W), (0, 2, 3, 1))
+        assert np.array_equal(bits_of(nhwc).reshape(-1), want.reshape(-1)), (T, N, H, W)
+        back = cm.relayout(nhwc, N, T, H, W, "NHWC", "NCHW")
+        assert np.array_equal(bits_of(back).reshape(-1), x.reshape(-1)), (T, N, H, W)
 
 
 def test_relayout16_named_orders_full_size_and_misaligned():
