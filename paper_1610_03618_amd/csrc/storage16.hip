@@ -1000,10 +1000,14 @@ struct Slab16Plan {
     long long total_planes;
 };
 
-template <class E, int MODE, int KH, int KW, int SH, int SW>
+// OY > 1 (compile-time windows only): a lane owns a block of 2 x OY outputs.  Each of the (OY-1)*SH + KH
+// input rows they touch is read once (SW + KW columns) and reduced along W once per output column; that
+// row result serves every output row whose window holds it.  div_blk divides by the row blocks per plane
+// (ceil(rows_out / OY)), div_pair by the column pairs per row (ceil(Wo / 2)).
+template <class E, int MODE, int KH, int KW, int SH, int SW, int OY, bool PADDED>
 __global__ __launch_bounds__(kSlabThreads) void pool16_nchw_slab_kernel(
     const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, PoolGeom g, Slab16Plan plan, FastDiv div_wo,
-    FastDiv div_plane_out) {
+    FastDiv div_plane_out, FastDiv div_blk, FastDiv div_pair) {
     constexpr int VEC = kSlabWords / 8 / kSlabThreads + 1;      // 128-bit loads per lane, worst case
     __shared__ __attribute__((aligned(16))) uint16_t slab[kSlabWords + 16];
     const int kh = KH ? KH : g.kh, kw = KW ? KW : g.kw, sh = SH ? SH : g.sh, sw = SW ? SW : g.sw;
@@ -1068,6 +1072,80 @@ __global__ __launch_bounds__(kSlabThreads) void pool16_nchw_slab_kernel(
     const int n_out = planes * rows_out * g.Wo;
     const size_t out0 = (size_t)p0 * plane_out + (size_t)i0 * g.Wo;
     const int lds0 = (int)((long long)((size_t)p0 * plane_in) - (long long)a_lo);
+    if constexpr (OY > 1 && KH != 0) {
+        constexpr int ROWS = (OY - 1) * SH + KH;
+        constexpr int COLS = SW + KW;                // columns under two neighbouring windows
+        const int nblk = (int)div_blk.d, npair = (int)div_pair.d;
+        const int n_items = planes * nblk * npair;
+        const int r_last = r_hi - 1;                 // rows of the slab: [r_lo, r_hi)
+        const size_t dst_word = reinterpret_cast<uintptr_t>(dst) >> 1;
+        for (int it = (int)threadIdx.x; it < n_items; it += kSlabThreads) {
+            const int pb = (int)fd_div((uint32_t)it, div_pair);    // plane * nblk + block
+            const int j = 2 * (it - pb * npair);
+            const int pl = (int)fd_div((uint32_t)pb, div_blk);
+            const int il0 = (pb - pl * nblk) * OY;                  // first output row of the lane, strip-local
+            const int rb = (i0 + il0) * SH - g.ph;
+            const int qb = j * SW - g.pw;
+            const int base = lds0 + pl * plane_in;
+            // Rows and columns are clamped into the slab.  A clamped tap of a real output lies in the same
+            // window (the maximum is unchanged, the average drops it by a select); rows and columns of
+            // outputs past the strip's or the row's end only feed results that are never stored.
+            int qc[COLS];
+            bool q_in[COLS];
+#pragma unroll
+            for (int x = 0; x < COLS; ++x) {
+                const int q = qb + x;
+                q_in[x] = !PADDED || (q >= 0 && q < g.W);
+                int c = q < g.W ? q : g.W - 1;
+                if (PADDED) c = c > 0 ? c : 0;
+                qc[x] = c;
+            }
+            float hr[2][ROWS];
+#pragma unroll
+            for (int y = 0; y < ROWS; ++y) {
+                const int r = rb + y;
+                int rc = r < r_last ? r : r_last;
+                if (PADDED) rc = rc > r_lo ? rc : r_lo;
+                const uint16_t* row = slab + base + rc * g.W;
+                float t[COLS];
+#pragma unroll
+                for (int x = 0; x < COLS; ++x) {
+                    t[x] = E::widen(row[qc[x]]);
+                    if (MODE != CNNMEM_POOL_MAX && PADDED) t[x] = q_in[x] ? t[x] : 0.f;
+                }
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    float acc = t[h * SW];
+#pragma unroll
+                    for (int x = 1; x < KW; ++x) acc = Acc<MODE>::op(acc, t[h * SW + x]);
+                    if (MODE != CNNMEM_POOL_MAX && PADDED && (r < 0 || r >= g.H)) acc = 0.f;
+                    hr[h][y] = acc;
+                }
+            }
+            const size_t o_first = out0 + (size_t)(pl * rows_out + il0) * g.Wo + j;
+#pragma unroll
+            for (int k = 0; k < OY; ++k) {
+                float a0 = hr[0][k * SH], a1 = hr[1][k * SH];
+#pragma unroll
+                for (int y = 1; y < KH; ++y) {
+                    a0 = Acc<MODE>::op(a0, hr[0][k * SH + y]);
+                    a1 = Acc<MODE>::op(a1, hr[1][k * SH + y]);
+                }
+                if (il0 + k >= rows_out) continue;
+                const uint32_t b0 = E::narrow(Acc<MODE>::finish(a0, (float)(KH * KW)));
+                const uint32_t b1 = E::narrow(Acc<MODE>::finish(a1, (float)(KH * KW)));
+                const size_t a = o_first + (size_t)k * g.Wo;
+                const bool second = j + 1 < g.Wo;
+                if (second && ((dst_word + a) & 1) == 0) {
+                    *reinterpret_cast<uint32_t*>(dst + a) = b0 | (b1 << 16);
+                } else {
+                    dst[a] = (uint16_t)b0;
+                    if (second) dst[a + 1] = (uint16_t)b1;
+                }
+            }
+        }
+        return;
+    }
     // a lane computes two neighbouring outputs and stores them as one dword; the pairs are laid so that
     // dwords (and each wavefront's 256-byte store) are aligned in dst
     const int lead = (int)(((reinterpret_cast<uintptr_t>(dst) >> 1) + out0) & 63);
@@ -1087,13 +1165,34 @@ __global__ __launch_bounds__(kSlabThreads) void pool16_nchw_slab_kernel(
             const int rb = (i0 + il) * sh - g.ph, qb = j * sw - g.pw;
             const int base = lds0 + pl * plane_in;
             float acc = Acc<MODE>::identity();
-            for (int y = 0; y < kh; ++y) {
-                const int r = rb + y;
-                if (r < 0 || r >= g.H) continue;
-                for (int x = 0; x < kw; ++x) {
-                    const int q = qb + x;
-                    if (q < 0 || q >= g.W) continue;
-                    acc = Acc<MODE>::op(acc, E::widen(slab[base + r * g.W + q]));
+            if (KH != 0) {
+                // compile-time window, no branches: with padding a tap outside the image is read from the
+                // nearest in-image position, which lies in the same window (the maximum does not change,
+                // the average drops it by a select)
+#pragma unroll
+                for (int y = 0; y < (KH ? KH : 1); ++y) {
+                    const int r = rb + y;
+                    const bool r_in = !PADDED || (r >= 0 && r < g.H);
+                    const int rc = !PADDED ? r : (r < 0 ? 0 : (r < g.H ? r : g.H - 1));
+#pragma unroll
+                    for (int x = 0; x < (KW ? KW : 1); ++x) {
+                        const int q = qb + x;
+                        const bool in = r_in && (!PADDED || (q >= 0 && q < g.W));
+                        const int qc = !PADDED ? q : (q < 0 ? 0 : (q < g.W ? q : g.W - 1));
+                        const float t = E::widen(slab[base + rc * g.W + qc]);
+                        if (MODE == CNNMEM_POOL_MAX) acc = fmaxf(acc, t);
+                        else acc += in ? t : 0.f;
+                    }
+                }
+            } else {
+                for (int y = 0; y < kh; ++y) {
+                    const int r = rb + y;
+                    if (r < 0 || r >= g.H) continue;
+                    for (int x = 0; x < kw; ++x) {
+                        const int q = qb + x;
+                        if (q < 0 || q >= g.W) continue;
+                        acc = Acc<MODE>::op(acc, E::widen(slab[base + r * g.W + q]));
+                    }
                 }
             }
             bits[half] = E::narrow(Acc<MODE>::finish(acc, (float)(kh * kw)));
@@ -1131,12 +1230,18 @@ int launch_pool16_chwn(const uint16_t* src, uint16_t* dst, const PoolGeom& g, hi
     return launch_status();
 }
 
-template <class E, int MODE, int KH, int KW, int SH, int SW>
+template <class E, int MODE, int KH, int KW, int SH, int SW, int OY = 1>
 int launch_pool16_slab(const uint16_t* src, uint16_t* dst, const PoolGeom& g, const Slab16Plan& plan, long long blocks,
                        hipStream_t st) {
     const FastDiv dwo = make_fastdiv((uint32_t)g.Wo), dpo = make_fastdiv((uint32_t)(g.Ho * g.Wo));
-    hipLaunchKernelGGL((pool16_nchw_slab_kernel<E, MODE, KH, KW, SH, SW>), dim3((unsigned)blocks), dim3(kSlabThreads),
-                       0, st, src, dst, g, plan, dwo, dpo);
+    const int rows_out = plan.strips == 1 ? g.Ho : plan.rows_per_wg;
+    const FastDiv dblk = make_fastdiv((uint32_t)ceil_div(rows_out, OY)), dpair = make_fastdiv((uint32_t)((g.Wo + 1) / 2));
+    if (g.ph > 0 || g.pw > 0 || KH == 0)
+        hipLaunchKernelGGL((pool16_nchw_slab_kernel<E, MODE, KH, KW, SH, SW, OY, true>), dim3((unsigned)blocks),
+                           dim3(kSlabThreads), 0, st, src, dst, g, plan, dwo, dpo, dblk, dpair);
+    else
+        hipLaunchKernelGGL((pool16_nchw_slab_kernel<E, MODE, KH, KW, SH, SW, OY, false>), dim3((unsigned)blocks),
+                           dim3(kSlabThreads), 0, st, src, dst, g, plan, dwo, dpo, dblk, dpair);
     return launch_status();
 }
 
@@ -1198,10 +1303,24 @@ int dispatch_pool16(const uint16_t* src, uint16_t* dst, const PoolGeom& g, int l
             }
         }
         if (ok && blocks <= 0x7fffffffLL) {
-            if (g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2)
+            // Rows per lane (0 = default).  With 2-byte elements the per-tap work (16-bit LDS read, widening,
+            // clamps) weighs twice as much against the bytes moved as in fp32, so sharing row results pays
+            // even without padding: 3x3/s1 on 64x256x56x56 39 -> 52 % of peak (p1: 21 -> 52 %), 3x3/s2/p1 on
+            // 256x64x112x112 53 -> 69 %, 3x3/s2 on 256x96x55x55 59 -> 61 %.
+            int oy = env_int("CNNMEM_SLAB16_ROWS", 0);
+            if (oy == 0) oy = g.sh == 1 ? 4 : (g.ph > 0 || g.pw > 0 ? 3 : 2);
+            if (g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2) {
+                if (oy == 2) return launch_pool16_slab<E, MODE, 3, 3, 2, 2, 2>(src, dst, g, plan, blocks, st);
+                if (oy == 3) return launch_pool16_slab<E, MODE, 3, 3, 2, 2, 3>(src, dst, g, plan, blocks, st);
                 return launch_pool16_slab<E, MODE, 3, 3, 2, 2>(src, dst, g, plan, blocks, st);
+            }
             if (g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2)
                 return launch_pool16_slab<E, MODE, 2, 2, 2, 2>(src, dst, g, plan, blocks, st);
+            if (g.kh == 3 && g.kw == 3 && g.sh == 1 && g.sw == 1) {
+                if (oy == 2) return launch_pool16_slab<E, MODE, 3, 3, 1, 1, 2>(src, dst, g, plan, blocks, st);
+                if (oy == 4) return launch_pool16_slab<E, MODE, 3, 3, 1, 1, 4>(src, dst, g, plan, blocks, st);
+                return launch_pool16_slab<E, MODE, 3, 3, 1, 1>(src, dst, g, plan, blocks, st);
+            }
             return launch_pool16_slab<E, MODE, 0, 0, 0, 0>(src, dst, g, plan, blocks, st);
         }
     }

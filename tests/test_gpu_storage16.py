@@ -152,6 +152,24 @@ def test_pool16_max_orders_every_finite_pattern(dtype):
             assert np.array_equal(bits_of(got), want), (k, s, layout)
 
 
+@pytest.mark.parametrize("rows", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("dtype", DTYPES, ids=[IDS[d] for d in DTYPES])
+def test_pool16_nchw_slab_rows_per_lane(rows, dtype, monkeypatch):
+    """The LDS kernel's 2 x OY output blocks: padding clamps, odd Wo (unaligned pairs), ragged row blocks, strips."""
+    monkeypatch.setenv("CNNMEM_SLAB16_ROWS", str(rows))
+    for case in [(3, 5, 13, 17, 3, 1, 1), (2, 3, 57, 57, 3, 1, 0), (1, 2, 150, 131, 3, 1, 1), (3, 5, 13, 17, 3, 2, 1),
+                 (2, 3, 57, 57, 3, 2, 0), (1, 2, 260, 131, 3, 2, 1), (2, 2, 9, 300, 3, 1, 1), (2, 2, 300, 9, 3, 2, 1)]:
+        N, C, H, W, k, s, p = case
+        rng = np.random.default_rng(sum(case) + rows)
+        xb, xd = to16(wl.relu_normal(rng, (N, C, H, W)) + np.float32(0.25), dtype)
+        want = oracle.pool16(xb, N, C, H, W, cm.NCHW, 0, k, k, s, s, p, p, dtype)
+        got = cm.pool(xd, N, C, H, W, cm.NCHW, cm.POOL_MAX, k, k, s, s, p, p)
+        assert np.array_equal(bits_of(got), want), (case, "max")
+        want = oracle.pool16(xb, N, C, H, W, cm.NCHW, 1, k, k, s, s, p, p, dtype)
+        got = cm.pool(xd, N, C, H, W, cm.NCHW, cm.POOL_AVG, k, k, s, s, p, p)
+        check_rounded(bits_of(got), want, 0.999, (case, "avg"))
+
+
 def test_pool16_misaligned_views_take_the_generic_kernel():
     N, C, H, W, k, s = 8, 3, 12, 12, 3, 2
     rng = np.random.default_rng(77)
