@@ -891,6 +891,45 @@ __global__ __launch_bounds__(kThreads) void pool16_generic_kernel(
     }
 }
 
+// CHWN, any window: eight images per lane (one 128-bit access), one output per lane, the in-image part
+// of the window walked with run-time loops (global 7x7 pooling, 5x5 / stride 3, rectangular windows).
+template <class E, int MODE>
+__global__ __launch_bounds__(kThreads) void pool16_chwn_any_kernel(
+    const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, PoolGeom g, uint32_t items, FastDiv div_n8,
+    FastDiv div_wo, FastDiv div_ho) {
+    const uint32_t u = blockIdx.x * kThreads + threadIdx.x;   // ((c*Ho + i)*Wo + j)*N8 + n8
+    if (u >= items) return;
+    const uint32_t t = fd_div(u, div_n8);
+    const uint32_t n8 = u - t * div_n8.d;
+    const uint32_t t2 = fd_div(t, div_wo);
+    const int j = (int)(t - t2 * div_wo.d);
+    const uint32_t c = fd_div(t2, div_ho);
+    const int i = (int)(t2 - c * div_ho.d);
+    const int N = g.N;
+    int r_lo = i * g.sh - g.ph, q_lo = j * g.sw - g.pw;
+    int r_hi = r_lo + g.kh, q_hi = q_lo + g.kw;
+    if (r_lo < 0) r_lo = 0;
+    if (q_lo < 0) q_lo = 0;
+    if (r_hi > g.H) r_hi = g.H;
+    if (q_hi > g.W) q_hi = g.W;
+    const uint16_t* plane = src + (size_t)c * g.H * g.W * N + 8 * n8;
+    float acc[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc[k] = Acc<MODE>::identity();
+    for (int r = r_lo; r < r_hi; ++r) {
+        const uint16_t* rowp = plane + (size_t)r * g.W * N;
+        for (int q = q_lo; q < q_hi; ++q) {
+            float v[8];
+            unpack8<E>(ld16_cached(rowp + (size_t)q * N), v);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) acc[k] = Acc<MODE>::op(acc[k], v[k]);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc[k] = Acc<MODE>::finish(acc[k], (float)(g.kh * g.kw));
+    st16_stream(dst + 8 * (size_t)u, pack8<E>(acc));
+}
+
 // CHWN: a lane owns 8 consecutive images of one output column and walks down OY
 // output rows; each input row it touches is reduced horizontally once and that row
 // result is reused by every output row whose window contains it (Section V.A's
@@ -1256,6 +1295,13 @@ int dispatch_pool16(const uint16_t* src, uint16_t* dst, const PoolGeom& g, int l
                 return launch_pool16_chwn<E, MODE, 2, 2, 2, 2, 1>(src, dst, g, st);
             if (g.kh == 3 && g.kw == 3 && g.sh == 1 && g.sw == 1)
                 return launch_pool16_chwn<E, MODE, 3, 3, 1, 1, 3>(src, dst, g, st);
+        }
+        const long long items = (long long)g.C * g.Ho * g.Wo * (g.N / 8);
+        if (a16 && g.N % 8 == 0 && items < 0x7fffffffLL && items > 0) {
+            hipLaunchKernelGGL((pool16_chwn_any_kernel<E, MODE>), dim3((unsigned)ceil_div64(items, kThreads)),
+                               dim3(kThreads), 0, st, src, dst, g, (uint32_t)items, make_fastdiv((uint32_t)(g.N / 8)),
+                               make_fastdiv((uint32_t)g.Wo), make_fastdiv((uint32_t)g.Ho));
+            return launch_status();
         }
         return launch_pool16_generic<E, MODE>(src, dst, g, 1, st);
     }

@@ -111,7 +111,7 @@ P_CASES = [  # N, C, H, W, k, s, p
     (8, 5, 14, 14, 2, 2, 0), (8, 3, 13, 13, 3, 1, 1), (8, 2, 17, 19, 3, 2, 1), (6, 3, 15, 15, 3, 2, 0),
     (8, 2, 64, 64, 2, 2, 0), (4, 3, 30, 24, 2, 2, 0), (8, 2, 9, 9, 5, 3, 2), (24, 2, 150, 150, 3, 2, 0),
     (8, 1, 224, 224, 2, 2, 0), (3, 2, 7, 5, 2, 1, 0), (4, 2, 224, 224, 3, 2, 1), (4, 2, 300, 40, 5, 3, 2),
-    (8, 2, 129, 131, 3, 2, 0),
+    (8, 2, 129, 131, 3, 2, 0), (16, 3, 7, 7, 7, 7, 0), (8, 2, 20, 21, 4, 3, 1), (24, 2, 33, 35, 5, 3, 2),
 ]
 
 
