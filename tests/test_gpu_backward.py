@@ -23,6 +23,9 @@ CASES = [  # N, C, H, W, k, s, p
     # planes larger than the LDS budget: strips of input rows (cells and single elements), with and without padding
     (4, 3, 150, 150, 3, 2, 0), (4, 2, 224, 224, 3, 2, 1), (4, 2, 300, 40, 5, 3, 2), (4, 2, 111, 113, 3, 2, 0),
     (4, 1, 130, 130, 2, 2, 0), (8, 2, 97, 200, 3, 1, 1),
+    # batches that are multiples of 32: the CHWN patch kernel (ragged patches, one-cell images, several chunks)
+    (32, 3, 27, 27, 3, 2, 0), (64, 2, 55, 55, 3, 2, 0), (32, 2, 13, 13, 3, 2, 0), (32, 1, 5, 5, 3, 2, 0),
+    (32, 2, 64, 70, 3, 2, 0), (96, 1, 3, 3, 3, 2, 0), (32, 1, 9, 40, 3, 2, 0),
 ]
 
 
