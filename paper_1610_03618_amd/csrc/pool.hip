@@ -211,6 +211,7 @@ __global__ __launch_bounds__(kThreads) void pool_chwn_vec4_any_kernel(
     float4 acc = Acc<MODE>::identity4();
     for (int r = r_lo; r < r_hi; ++r) {
         const float* rowp = plane + (size_t)r * g.W * N;
+#pragma unroll 4
         for (int q = q_lo; q < q_hi; ++q)
             acc = Acc<MODE>::op4(acc, *reinterpret_cast<const float4*>(rowp + (size_t)q * N));
     }
