@@ -314,9 +314,11 @@ __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
     // condition) and simply do not park it.  The up to three floats of a ragged
     // tensor end are then fetched one by one by the lane that owns them.
     const size_t a_last = (total_in - 4) & ~(size_t)3;
+    // (a round wholly past the slab is skipped by the whole workgroup: small planes leave most rounds empty)
     float4 v[kSlabVecPerLane];
 #pragma unroll
     for (int k = 0; k < kSlabVecPerLane; ++k) {
+        if (k * kSlabThreads >= nvec) break;
         const int q = threadIdx.x + k * kSlabThreads;
         size_t a = a_lo + 4 * (size_t)(q < nvec ? q : 0);
         a = a <= a_last ? a : a_last;

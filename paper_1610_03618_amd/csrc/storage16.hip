@@ -1087,6 +1087,7 @@ __global__ __launch_bounds__(kSlabThreads) void pool16_nchw_slab_kernel(
     u32x4 v[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
+        if (k * kSlabThreads >= nvec) break;        // uniform: small planes leave most rounds empty
         const int q = threadIdx.x + k * kSlabThreads;
         size_t a = a_lo + 8 * (size_t)(q < nvec ? q : 0);
         a = a <= a_last ? a : a_last;
