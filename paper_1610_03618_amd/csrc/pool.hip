@@ -179,7 +179,7 @@ __global__ __launch_bounds__(kThreads) void pool_chwn_vec4_kernel(
 #pragma unroll
         for (int ox = 0; ox < OX; ++ox)
             if (i < g.Ho && j0 + ox < g.Wo)
-                st4_stream(outp + ((size_t)i * g.Wo + ox) * N, Acc<MODE>::finish4(acc[oy][ox], (float)(KH * KW)));
+                st4_through(outp + ((size_t)i * g.Wo + ox) * N, Acc<MODE>::finish4(acc[oy][ox], (float)(KH * KW)));
     }
 }
 
@@ -243,7 +243,7 @@ __global__ __launch_bounds__(kThreads) void pool_nchw_2x2s2_kernel(
         o0 = ((a.x + a.y) + (b.x + b.y)) * 0.25f;
         o1 = ((a.z + a.w) + (b.z + b.w)) * 0.25f;
     }
-    st2_stream(dst + (size_t)I * 2, o0, o1);
+    st2_through(dst + (size_t)I * 2, o0, o1);
 }
 
 // ---------------------------------------------------------------------------
