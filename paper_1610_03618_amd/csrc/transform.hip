@@ -165,7 +165,7 @@ __global__ __launch_bounds__(kThreads) void copy_vec4_kernel(const float* __rest
                                                              float* __restrict__ dst, size_t n4,
                                                              size_t first) {
     const size_t i = first + (size_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i < n4) st4_stream(dst + 4 * i, ld4_stream(src + 4 * i));
+    if (i < n4) st4_through(dst + 4 * i, ld4_stream(src + 4 * i));
 }
 
 __global__ __launch_bounds__(kThreads) void copy_scalar_kernel(const float* __restrict__ src,
