@@ -167,6 +167,15 @@ __device__ __forceinline__ void st4_through(float* p, const float4& a) {
     st4_stream(p, a);
 #endif
 }
+// the same at any 4-byte aligned address
+__device__ __forceinline__ void st4u_through(float* p, const float4& a) {
+#if CNNMEM_STORE_SC1 && CNNMEM_STREAM_NT
+    const v4f_t v = {a.x, a.y, a.z, a.w};
+    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v));
+#else
+    st4u_stream(p, a);
+#endif
+}
 __device__ __forceinline__ void st2_through(float* p, float a, float b) {
 #if CNNMEM_STORE_SC1 && CNNMEM_STREAM_NT
     const v2f_t v = {a, b};

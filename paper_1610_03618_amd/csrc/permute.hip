@@ -205,7 +205,7 @@ __global__ __launch_bounds__(kThreads) void permute_thin_dst_kernel(
     const int total = ns * T;
     for (int i = 4 * tid; i < total; i += 4 * kThreads) {
         if (i + 4 <= total) {
-            st4u_stream(out + i, *reinterpret_cast<const float4*>(tile + 4 * thin_slot(i >> 2)));
+            st4u_through(out + i, *reinterpret_cast<const float4*>(tile + 4 * thin_slot(i >> 2)));
         } else {
             for (int j = i; j < total; ++j) st1_stream(out + j, tile[thin_word(j)]);
         }
@@ -268,7 +268,7 @@ __global__ __launch_bounds__(kThreads) void permute_thin_src_kernel(
         }
 #pragma unroll
         for (int sidx = 0; sidx < T; ++sidx)
-            st4u_stream(dst + (size_t)sidx * (size_t)p.ds_s + (size_t)(r0 + r),
+            st4u_through(dst + (size_t)sidx * (size_t)p.ds_s + (size_t)(r0 + r),
                         make_float4(w[0 * T + sidx], w[1 * T + sidx], w[2 * T + sidx], w[3 * T + sidx]));
     } else {
         for (int sidx = 0; sidx < T; ++sidx)

@@ -89,7 +89,7 @@ __global__ __launch_bounds__(THREADS) void transpose_vec4_kernel(
         const long long s = s0 + sl;
         const long long r = r0 + 4 * br;
         if (s < S && r < R)
-            st4_stream(dst + (size_t)s * (size_t)R + (size_t)r, o);
+            st4_through(dst + (size_t)s * (size_t)R + (size_t)r, o);
     }
 }
 
