@@ -47,11 +47,11 @@ def softmax_backward_bytes(N: int, classes: int) -> int:
 # WRITE_SIZE, scaled by what the same counters read for a plain copy of known size), keyed by
 # the benchmark's launch names.  Filled from the committed profile summaries; None = not measured.
 MEASURED_TRAFFIC = {
-    "transform_nchw_to_chwn": 297289896,
-    "transform_chwn_to_nchw": 297303668,
-    "pool_max_nchw": 1027310443,
-    "pool_max_chwn": 1027321192,
-    "pool_avg_nchw": 1027306732,
-    "pool_avg_chwn": 1027320040,
-    "softmax": 716973707,
+    "transform_nchw_to_chwn": 297379839,
+    "transform_chwn_to_nchw": 297399252,
+    "pool_max_nchw": 1027518422,
+    "pool_max_chwn": 1027533780,
+    "pool_avg_nchw": 1027514327,
+    "pool_avg_chwn": 1027533780,
+    "softmax": 717155210,
 }
