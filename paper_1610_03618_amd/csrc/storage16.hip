@@ -918,7 +918,6 @@ __global__ __launch_bounds__(kThreads) void pool16_chwn_any_kernel(
     for (int k = 0; k < 8; ++k) acc[k] = Acc<MODE>::identity();
     for (int r = r_lo; r < r_hi; ++r) {
         const uint16_t* rowp = plane + (size_t)r * g.W * N;
-#pragma unroll 4
         for (int q = q_lo; q < q_hi; ++q) {
             float v[8];
             unpack8<E>(ld16_cached(rowp + (size_t)q * N), v);
