@@ -149,3 +149,48 @@ def test_transform16_beyond_2g_elements_sampled():
     assert int(di.max()) > 2**31
     got = dst[di].cpu().numpy().astype(np.int64) & 0xFFFF
     np.testing.assert_array_equal(got, si % 65521)
+
+
+@pytest.mark.parametrize("layout,k", [(NCHW, 2), (CHWN, 2), (NCHW, 3), (CHWN, 3)])
+def test_pool_backward_beyond_2g_elements_sampled(layout, k):
+    """Every backward kernel family (row pairs, cells, LDS slab, LDS patches) with 64-bit offsets: sampled input
+    gradients against the oracle run on the small region that holds every window touching the sample."""
+    if _free_gib() < 26:
+        pytest.skip("needs ~22 GiB of free device memory")
+    N, C, H, W, s = 64, 64, 736, 736, 2                     # 2 218 786 816 input elements
+    assert N * C * H * W > 2**31
+    Ho, Wo = oracle.pool_out_dims(H, W, k, k, s, s, 0, 0)
+    g = torch.Generator(device="cuda").manual_seed(21 + k)
+    x = torch.empty(N * C * H * W, dtype=torch.float32, device="cuda")
+    x.uniform_(0.0, 1.0, generator=g)
+    x.mul_(8).floor_().div_(8)                               # few distinct values: plenty of tied windows
+    dy = torch.empty(N * C * Ho * Wo, dtype=torch.float32, device="cuda")
+    dy.normal_(generator=g)
+    rng = np.random.default_rng(9 + k)
+    pts = np.stack([rng.integers(0, d, size=300) for d in (N, C, H, W)], axis=1)
+    pts[:4] = [[0, 0, 0, 0], [N - 1, C - 1, H - 1, W - 1], [N - 1, C - 1, 0, W - 1], [0, C - 1, H - 1, 0]]
+    for mode in (MAX, AVG):
+        dx = torch.full((N * C * H * W,), 7.0, dtype=torch.float32, device="cuda")
+        assert cm.cnnmem_pool_backward(x if mode == MAX else None, dy, dx, N, C, H, W, layout, mode,
+                                       k, k, s, s, 0, 0) == 0
+        for (n, c, h, w) in pts:
+            n, c, h, w = int(n), int(c), int(h), int(w)
+            # windows (along each axis) that contain the sample, clipped to the output
+            i_lo, i_hi = max(0, -(-(h - k + 1) // s)), min(Ho - 1, h // s)
+            j_lo, j_hi = max(0, -(-(w - k + 1) // s)), min(Wo - 1, w // s)
+            got = float(dx[oracle.index(layout, N, C, H, W, n, c, h, w)])
+            if i_lo > i_hi or j_lo > j_hi:                   # last row / column that no window covers
+                assert got == 0.0
+                continue
+            r0, q0 = i_lo * s, j_lo * s
+            R, Q = (i_hi - i_lo) * s + k, (j_hi - j_lo) * s + k
+            idx = np.array([oracle.index(layout, N, C, H, W, n, c, r0 + a, q0 + b) for a in range(R) for b in range(Q)],
+                           dtype=np.int64)
+            gidx = np.array([oracle.index(layout, N, C, Ho, Wo, n, c, i, j)
+                             for i in range(i_lo, i_hi + 1) for j in range(j_lo, j_hi + 1)], dtype=np.int64)
+            region = x[torch.from_numpy(idx).cuda()].cpu().numpy().reshape(1, 1, R, Q)
+            grads = dy[torch.from_numpy(gidx).cuda()].cpu().numpy().reshape(1, 1, i_hi - i_lo + 1, j_hi - j_lo + 1)
+            want = oracle.pool_backward(region, grads, 1, 1, R, Q, NCHW, mode, k, k, s, s, 0, 0)[0, 0, h - r0, w - q0]
+            bound = 1e-6 * float(np.abs(grads).sum()) + 1e-30
+            assert abs(got - float(want)) <= bound, (layout, k, mode, n, c, h, w, got, float(want))
+        del dx
