@@ -39,6 +39,8 @@ WORKLOADS = {
                "tensor and an RGB input batch (Section I, IV.A)",
     "backward": "backward passes: pooling 2x2/s2 on 64x64x224x224 and 3x3/s2 on 128x96x55x55 (both layouts, max and "
                 "avg), softmax on 4096x21841",
+    "shapes": "layer shapes beyond the paper's networks: small and awkward batches, padded / stride-1 / 5x5 / global "
+              "pooling, very short and very long softmax rows; with --compare-torch also PyTorch's own kernel per launch",
     "layout_policy": "the three AlexNet pooling layers of config 3 under both layout policies: pool where the "
                      "data is (NCHW) against transform + pool in CHWN + transform back (Section IV.B, IV.D)",
 }
@@ -50,6 +52,8 @@ WORKLOAD_TEXT = {
     "layouts": "storage-order changes among NCHW / NHWC / CHWN / HWCN on 128x96x55x55, 64x64x112x112 and 64x3x224x224",
     "backward": "backward of max/avg pooling (64x64x224x224 2x2/s2, 128x96x55x55 3x3/s2; NCHW and CHWN) and of softmax (4096x21841)",
     "layout_policy": "config 3 (AlexNet, N=128) max-pool 3x3/s2 x3: NCHW in place vs NCHW->CHWN + pool + CHWN->NCHW",
+    "shapes": "general shapes: transform at batches 1..100, pooling 3x3/s2/p1, 3x3/s1/p1, 5x5/s3/p2, global 7x7 (NCHW and "
+              "CHWN, max and avg), softmax 1048576x10 and 512x128256",
 }
 
 
@@ -69,6 +73,8 @@ def parse_args():
                          "cost, which dominates workloads of very small tensors)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the warm-cache and same-bytes-copy yardsticks measured after the timed region")
+    ap.add_argument("--compare-torch", action="store_true",
+                    help="workload 'shapes': also time PyTorch's own kernel for the same operation (context only)")
     ap.add_argument("--verbose", action="store_true")
     return ap.parse_args()
 
@@ -220,6 +226,94 @@ def build_softmax_sweep_ops(torch, cm, wl, rl, only):
                       (lambda zs, ps, n, c: lambda i: cm.cnnmem_softmax(zs[i], ps[i], n, c))(zs, ps, n, c), ns))
     torch.cuda.synchronize()
     return ops, {}
+
+
+SHAPES_TRANSFORM = [(1, 64, 224, 224), (4, 64, 224, 224), (8, 64, 112, 112), (32, 512, 28, 28), (100, 64, 57, 57)]
+SHAPES_POOL = [  # N, C, H, W, window, stride, pad
+    (256, 64, 112, 112, 3, 2, 1),       # ResNet stem
+    (64, 256, 56, 56, 3, 1, 1),         # Inception branch
+    (64, 64, 150, 150, 5, 3, 2),
+    (128, 2048, 7, 7, 7, 7, 0),         # global pooling
+]
+SHAPES_SOFTMAX = [(1048576, 10), (512, 128256)]
+
+
+def build_shapes_ops(torch, cm, wl, rl, only):
+    """Layer shapes outside the paper's networks (Section III.A lists LeNet, Cifar, AlexNet, ZFNet, VGG)."""
+    import torch.nn.functional as F
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device="cuda").manual_seed(1617)
+    ops = []
+
+    def add(name, kind, nbytes, units, unit_name, launch, ns, torch_launch):
+        if only and name not in only:
+            return
+        op = Op(name, kind, nbytes, units, unit_name, launch, ns)
+        op.torch_launch = torch_launch
+        ops.append(op)
+
+    for (N, C, H, W) in SHAPES_TRANSFORM:
+        n = N * C * H * W
+        ns = _nsets_for(8 * n)
+        a = [torch.randn((N, C, H, W), device=dev, generator=gen) for _ in range(ns)]
+        b = [torch.empty((C, H, W, N), dtype=torch.float32, device=dev) for _ in range(ns)]
+        c = [torch.empty((N, C, H, W), dtype=torch.float32, device=dev) for _ in range(ns)]
+        for i in range(ns):
+            cm.transform(a[i], N, C, H, W, cm.NCHW, cm.CHWN, out=b[i])
+        tag = f"{N}x{C}x{H}x{W}"
+        add(f"transform_nchw_to_chwn_{tag}", "transform", rl.transform_bytes(N, C, H, W), n, "elements",
+            (lambda a, b, N, C, H, W: lambda i: cm.cnnmem_transform(a[i], b[i], N, C, H, W, cm.NCHW, cm.CHWN))(a, b, N, C, H, W),
+            ns, (lambda a, b: lambda i: b[i].copy_(a[i].permute(1, 2, 3, 0)))(a, b))
+        add(f"transform_chwn_to_nchw_{tag}", "transform", rl.transform_bytes(N, C, H, W), n, "elements",
+            (lambda b, c, N, C, H, W: lambda i: cm.cnnmem_transform(b[i], c[i], N, C, H, W, cm.CHWN, cm.NCHW))(b, c, N, C, H, W),
+            ns, (lambda b, c: lambda i: c[i].copy_(b[i].permute(3, 0, 1, 2)))(b, c))
+    for (N, C, H, W, k, s, p) in SHAPES_POOL:
+        st, Ho, Wo = cm.cnnmem_pool_out_dims(H, W, k, k, s, s, p, p)
+        n_in, n_out = N * C * H * W, N * C * Ho * Wo
+        ns = _nsets_for(4 * (n_in + n_out))
+        x = [torch.randn((N, C, H, W), device=dev, generator=gen).relu_() for _ in range(ns)]
+        xc = [cm.transform(t, N, C, H, W, cm.NCHW, cm.CHWN) for t in x]
+        y = [torch.empty(n_out, dtype=torch.float32, device=dev) for _ in range(ns)]
+        pb = rl.pool_bytes(N, C, H, W, k, k, s, s, p, p)
+        tag = f"{N}x{C}x{H}x{W}_k{k}s{s}p{p}"
+        for mode, mname in ((cm.POOL_MAX, "max"), (cm.POOL_AVG, "avg")):
+            tl = ((lambda x, k, s, p: lambda i: F.max_pool2d(x[i], k, s, p))(x, k, s, p) if mode == cm.POOL_MAX else
+                  (lambda x, k, s, p: lambda i: F.avg_pool2d(x[i], k, s, p))(x, k, s, p))
+            for layout, src, lname in ((cm.NCHW, x, "nchw"), (cm.CHWN, xc, "chwn")):
+                add(f"pool_{mname}_{lname}_{tag}", "pool", pb, n_in, "input elements",
+                    (lambda src, y, N, C, H, W, layout, mode, k, s, p:
+                     lambda i: cm.cnnmem_pool(src[i], y[i], N, C, H, W, layout, mode, k, k, s, s, p, p))(
+                         src, y, N, C, H, W, layout, mode, k, s, p), ns, tl if layout == cm.NCHW else None)
+    for (n, c) in SHAPES_SOFTMAX:
+        ns = _nsets_for(8 * n * c)
+        zs = [torch.randn((n, c), device=dev, generator=gen) * 3 for _ in range(ns)]
+        ps = [torch.empty_like(zs[0]) for _ in range(ns)]
+        add(f"softmax_{n}x{c}", "softmax", rl.softmax_bytes(n, c), n * c, "elements",
+            (lambda zs, ps, n, c: lambda i: cm.cnnmem_softmax(zs[i], ps[i], n, c))(zs, ps, n, c), ns,
+            (lambda zs: lambda i: torch.softmax(zs[i], dim=1))(zs))
+    torch.cuda.synchronize()
+    return ops, {}
+
+
+def measure_torch(torch, ops, iters=20):
+    """PyTorch's own kernel for the same operation, as context: median of `iters` launches on rotating inputs."""
+    out = {}
+    for op in ops:
+        fn = getattr(op, "torch_launch", None)
+        if fn is None:
+            continue
+        for i in range(3):
+            fn(i % op.nsets)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(ev):
+            a.record()
+            fn(i % op.nsets)
+            b.record()
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in ev)
+        out[op.name] = ms[len(ms) // 2]
+    return out
 
 
 def build_layouts_ops(torch, cm, wl, rl, only):
@@ -459,7 +553,7 @@ def main():
     only = set(filter(None, args.only.split(",")))
     builders = {"largest": build_ops, "table1": build_table1_ops, "softmax_sweep": build_softmax_sweep_ops,
                 "layout_policy": build_layout_policy_ops, "layouts": build_layouts_ops,
-                "backward": build_backward_ops}
+                "backward": build_backward_ops, "shapes": build_shapes_ops}
     if args.workload == "largest":
         ops, host_inputs = build_ops(torch, cm, wl, rl, only, args.dtype)
     else:
@@ -479,7 +573,10 @@ def main():
         if events is not None:
             events[0].record()
         for k, op in enumerate(ops):
-            st = op.launch(step % op.nsets)
+            # launch k of a step takes buffer set step + k: launches that share tensors (both pooling modes
+            # on one input, a transform and its inverse) never touch a set the previous launch just used,
+            # so the last-level cache cannot serve one launch with what its neighbour left there
+            st = op.launch((step + k) % op.nsets)
             if events is not None:
                 events[k + 1].record()
             if st != 0:
@@ -522,6 +619,7 @@ def main():
                       "value": round(sum(op.alg_bytes for op in ops) / gwall / 1e9, 1), "unit": "GB/s"}
 
     extras = {} if args.no_extras else measure_extras(torch, cm, ops)
+    torch_ms = measure_torch(torch, ops) if args.compare_torch else {}
     step_bytes = sum(op.alg_bytes for op in ops)
     ms_per_step = wall / args.steps * 1e3
     value = step_bytes / (wall / args.steps) / 1e9
@@ -539,6 +637,8 @@ def main():
             kernels[-1]["warm_median_ms"] = round(warm_ms, 5)
             kernels[-1]["copy_same_bytes_median_ms"] = round(copy_ms, 5)
             kernels[-1]["frac_of_copy"] = round(copy_ms / med_ms, 4)
+        if op.name in torch_ms:
+            kernels[-1]["torch_median_ms"] = round(torch_ms[op.name], 5)
     dominant = max(kernels, key=lambda k: k["avg_ms"])
     roofline = {"bound": "hbm", "kernel": dominant["name"], "achieved": dominant["achieved"],
                 "peak": rl.PEAK_HBM_GBPS, "unit": "GB/s", "frac": dominant["frac"],
