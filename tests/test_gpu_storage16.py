@@ -191,7 +191,9 @@ def test_pool16_misaligned_views_take_the_generic_kernel():
 # ---- softmax ---------------------------------------------------------------------
 
 S_SHAPES = [(7, 1), (5, 10), (33, 31), (33, 32), (40, 100), (128, 1000), (64, 1001), (9, 4096), (6, 21841),
-            (3, 70001), (300, 257), (17, 8200)]
+            (3, 70001), (300, 257), (17, 8200),
+            # 32768 < categories <= 65536: the long-row kernel that keeps only 16-bit words in registers
+            (5, 50257), (3, 65536), (4, 40000), (2, 33001), (3, 65535)]
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=[IDS[d] for d in DTYPES])
