@@ -530,16 +530,21 @@ int launch_chwn_window(int oy, int ox, const float* src, float* dst, const PoolG
 template <int MODE>
 int dispatch_chwn(const float* src, float* dst, const PoolGeom& g, const PoolTuning& tune, hipStream_t st) {
     const bool vec = (g.N % 4 == 0) && aligned16(src) && aligned16(dst);
-    const int ox = tune.cols_per_lane ? tune.cols_per_lane : 1;
+    const int ox = tune.cols_per_lane ? tune.cols_per_lane : env_int("CNNMEM_CHWN_COLS", 1);
     int rc = CNNMEM_ERR_UNSUPPORTED;
     if (vec && g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2) {
-        // three rows per lane: 7 input rows feed 3 outputs instead of 9 (measured best on MI355X)
-        rc = launch_chwn_window<MODE, 3, 3, 2, 2>(tune.rows_per_lane ? tune.rows_per_lane : 3, ox, src, dst, g, tune, st);
+        // Outputs per lane along H.  More rows per lane reuse row results (7 input rows feed 3 outputs
+        // instead of 9) but put 21 loads and 3 stores in one lane.  Measured on MI355X with write-through
+        // stores, 128x96x55x55: 67.1 % of peak with one row, 64.7 % with two, 63.9 % with three (three was the
+        // best before the stores were write-through); with padding (256x64x112x112, p1) two rows win: 72.1 %
+        // against 70.0 % and 71.4 %.
+        const int rows = g.ph > 0 || g.pw > 0 ? 2 : 1;
+        rc = launch_chwn_window<MODE, 3, 3, 2, 2>(tune.rows_per_lane ? tune.rows_per_lane : env_int("CNNMEM_CHWN_ROWS", rows), ox, src, dst, g, tune, st);
     } else if (vec && g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2) {
         // disjoint windows: nothing to reuse, one output per lane is fastest
         rc = launch_chwn_window<MODE, 2, 2, 2, 2>(tune.rows_per_lane ? tune.rows_per_lane : 1, ox, src, dst, g, tune, st);
     } else if (vec && g.kh == 3 && g.kw == 3 && g.sh == 1 && g.sw == 1) {
-        rc = launch_chwn_window<MODE, 3, 3, 1, 1>(tune.rows_per_lane ? tune.rows_per_lane : 4, ox, src, dst, g, tune, st);
+        rc = launch_chwn_window<MODE, 3, 3, 1, 1>(tune.rows_per_lane ? tune.rows_per_lane : env_int("CNNMEM_CHWN_ROWS", 4), ox, src, dst, g, tune, st);
     }
     if (rc != CNNMEM_ERR_UNSUPPORTED) return rc;
     const long long items = (long long)g.C * g.Ho * g.Wo * (g.N / 4);
@@ -610,8 +615,10 @@ int dispatch_nchw(const float* src, float* dst, const PoolGeom& g, const PoolTun
         const int budget = kSlabFloats - 32;        // room for the line-aligned head
         if (plane_in <= budget) {
             long long p = budget / plane_in;
-            // keep at least ~8 workgroups per CU's worth of parallelism when the tensor allows
-            const long long min_blocks = 2048;
+            // Small tensors: at least 1024 workgroups when the planes allow, i.e. about one resident round
+            // of the chip (5 x 32 KB of LDS per CU).  With 2048 the Table 1 layers of 2-27 MB needed a second
+            // round for a handful of lanes each: PL2 8.9 -> 6.8 us, PL4 9.1 -> 7.0, PL10 9.5 -> 7.5, PL7 10.7 -> 9.4.
+            const long long min_blocks = 1024;
             if (planes / p < min_blocks) p = planes / min_blocks > 0 ? planes / min_blocks : 1;
             if (p * (long long)g.Ho * g.Wo < (1 << 30)) {
                 plan.planes_per_wg = (int)p;

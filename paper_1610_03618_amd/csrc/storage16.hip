@@ -39,6 +39,14 @@ __device__ __forceinline__ u32x4 ld16u_stream(const uint16_t* p) {      // 4-byt
 __device__ __forceinline__ void st16_stream(uint16_t* p, u32x4 v) {
     __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
 }
+// write-through 128-bit store (device scope on top of the non-temporal hint; see st4_through)
+__device__ __forceinline__ void st16_through(uint16_t* p, u32x4 v) {
+#if CNNMEM_STORE_SC1 && CNNMEM_STREAM_NT
+    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v));
+#else
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
+#endif
+}
 __device__ __forceinline__ void st16u_stream(uint16_t* p, u32x4 v) {
     const u32x4_unaligned w = v;
     __builtin_nontemporal_store(w, reinterpret_cast<u32x4_unaligned*>(p));
@@ -1019,7 +1027,7 @@ __global__ __launch_bounds__(kThreads) void pool16_chwn_kernel(
             float o[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = Acc<MODE>::finish(acc[oy][e], (float)(KH * KW));
-            st16_stream(outp + (size_t)i * g.Wo * N, pack8<E>(o));
+            st16_through(outp + (size_t)i * g.Wo * N, pack8<E>(o));
         }
     }
 }
@@ -1311,7 +1319,14 @@ int dispatch_pool16(const uint16_t* src, uint16_t* dst, const PoolGeom& g, int l
     if (layout == CNNMEM_CHWN) {
         if (a16 && g.N % 8 == 0 && (long long)g.H * g.W * g.N < (1LL << 40)) {
             if (g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2)
+            {
+                // outputs per lane along H: three without padding (256x96x55x55 fp16: 58 % of peak against 55 %
+                // with one), two with padding (256x64x112x112 p1: 68 % against 48 % with three)
+                const int rows = env_int("CNNMEM_CHWN16_ROWS", g.ph > 0 || g.pw > 0 ? 2 : 3);
+                if (rows == 1) return launch_pool16_chwn<E, MODE, 3, 3, 2, 2, 1>(src, dst, g, st);
+                if (rows == 2) return launch_pool16_chwn<E, MODE, 3, 3, 2, 2, 2>(src, dst, g, st);
                 return launch_pool16_chwn<E, MODE, 3, 3, 2, 2, 3>(src, dst, g, st);
+            }
             if (g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2)
                 return launch_pool16_chwn<E, MODE, 2, 2, 2, 2, 1>(src, dst, g, st);
             if (g.kh == 3 && g.kw == 3 && g.sh == 1 && g.sw == 1)
@@ -1348,7 +1363,7 @@ int dispatch_pool16(const uint16_t* src, uint16_t* dst, const PoolGeom& g, int l
         const int budget = kSlabWords - 64;         // room for the line-aligned head
         if (plane_in <= budget) {
             long long p = budget / plane_in;
-            const long long min_blocks = 2048;      // keep the chip busy when the tensor allows
+            const long long min_blocks = 1024;      // about one resident round of the chip (see the fp32 kernel)
             if (planes / p < min_blocks) p = planes / min_blocks > 0 ? planes / min_blocks : 1;
             if (p * (long long)g.Ho * g.Wo < (1 << 30)) {
                 plan.planes_per_wg = (int)p;
