@@ -467,11 +467,12 @@ __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
 // 256-lane workgroups per CU keeps 64-128 KB in flight and loses 2-3 points.
 // Asking for dynamic LDS that the kernel never touches caps the workgroups per CU
 // (160 KB of LDS per CU).  Smaller tensors want all the parallelism they can get,
-// so by default the throttle only applies from 512 MB of input.
+// so by default the throttle only applies from 384 MB of input (measured: it gains 2-4 points at 411 MB and
+// 822 MB of input and loses 2-5 at 206 MB and below).
 //   requested: the caller's tuning (0 = this default rule, -1 = never, 1..8 = that many)
 inline size_t throttle_lds(int requested, long long in_bytes, int default_workgroups_per_cu) {
     int wpc = requested;
-    if (wpc == 0) wpc = in_bytes >= (512LL << 20) ? default_workgroups_per_cu : -1;
+    if (wpc == 0) wpc = in_bytes >= (384LL << 20) ? default_workgroups_per_cu : -1;
     if (wpc < 0 || wpc >= 8) return 0;
     const size_t bytes = (size_t)(160 * 1024 / wpc) - 1024;
     return bytes > 65536 ? 65536 : bytes;           // 64 KB needs no opt-in and already means two per CU
@@ -597,8 +598,9 @@ int dispatch_nchw(const float* src, float* dst, const PoolGeom& g, const PoolTun
         if (items < 0x7fffffffLL) {
             const FastDiv d = make_fastdiv((uint32_t)per_row);
             const unsigned blocks = (unsigned)ceil_div64(items, kThreads);
-            // 32 B in flight per lane: best at 6 workgroups per CU on large tensors
-            const size_t lds = throttle_lds(tune.workgroups_per_cu, 4LL * planes * g.H * g.W, 6);
+            // 32 B in flight per lane: best at 5 workgroups per CU on large tensors (64x64x224x224 with
+            // write-through stores: 82.7 % of peak at 5, 80.4 % at 6, 78.7 % at 4, 76.0 % uncapped)
+            const size_t lds = throttle_lds(tune.workgroups_per_cu, 4LL * planes * g.H * g.W, 5);
             hipLaunchKernelGGL((pool_nchw_2x2s2_kernel<MODE>), dim3(blocks), dim3(kThreads), lds, st, src, dst,
                                (uint32_t)items, (uint32_t)g.W, d);
             return launch_status();
