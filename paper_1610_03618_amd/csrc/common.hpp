@@ -185,6 +185,22 @@ __device__ __forceinline__ void st2_through(float* p, float a, float b) {
 #endif
 }
 
+// Occupancy throttle.  On tensors of hundreds of MB, HBM throughput on MI355X is
+// best with about 48-64 KB of loads in flight per CU; a full complement of eight
+// 256-lane workgroups per CU keeps 64-128 KB in flight and loses 2-3 points.
+// Asking for dynamic LDS that the kernel never touches caps the workgroups per CU
+// (160 KB of LDS per CU).  Smaller tensors want all the parallelism they can get,
+// so by default the throttle only applies from 384 MB of input (measured: it gains 2-4 points at 411 MB and
+// 822 MB of input and loses 2-5 at 206 MB and below).
+//   requested: the caller's tuning (0 = this default rule, -1 = never, 1..8 = that many)
+inline size_t throttle_lds(int requested, long long in_bytes, int default_workgroups_per_cu) {
+    int wpc = requested;
+    if (wpc == 0) wpc = in_bytes >= (384LL << 20) ? default_workgroups_per_cu : -1;
+    if (wpc < 0 || wpc >= 8) return 0;
+    const size_t bytes = (size_t)(160 * 1024 / wpc) - 1024;
+    return bytes > 65536 ? 65536 : bytes;           // 64 KB needs no opt-in and already means two per CU
+}
+
 // ---- launchers implemented in the .hip files (host side, C++ linkage, hidden) ----
 int launch_transpose2d(const float* src, float* dst, long long R, long long S, hipStream_t st);
 int launch_copy(const float* src, float* dst, long long n, hipStream_t st);

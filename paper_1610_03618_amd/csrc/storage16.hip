@@ -1289,12 +1289,16 @@ int launch_pool16_chwn(const uint16_t* src, uint16_t* dst, const PoolGeom& g, hi
     const long long blocks = bx * by * g.C;
     if (row_items >= 0x7fffffffLL || blocks > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
     const FastDiv dn8 = make_fastdiv((uint32_t)(g.N / 8));
+    // occupancy cap for disjoint windows on large tensors, as for fp32: 64x64x224x224 fp16 73.4 % of peak
+    // uncapped, 76.6-76.9 % at 3-5 workgroups per CU (CNNMEM_POOL16_WPC: -1 = never, 1..8 = that many)
+    const bool light = OY == 1 && KH <= SH && KW <= SW;
+    const size_t lds = light ? throttle_lds(env_int("CNNMEM_POOL16_WPC", 0), 2LL * g.N * g.C * g.H * g.W, 4) : 0;
     if (g.ph > 0 || g.pw > 0)
         hipLaunchKernelGGL((pool16_chwn_kernel<E, MODE, KH, KW, SH, SW, OY, true>), dim3((unsigned)blocks),
-                           dim3(kThreads), 0, st, src, dst, g, (uint32_t)row_items, (uint32_t)bx, (uint32_t)by, dn8);
+                           dim3(kThreads), lds, st, src, dst, g, (uint32_t)row_items, (uint32_t)bx, (uint32_t)by, dn8);
     else
         hipLaunchKernelGGL((pool16_chwn_kernel<E, MODE, KH, KW, SH, SW, OY, false>), dim3((unsigned)blocks),
-                           dim3(kThreads), 0, st, src, dst, g, (uint32_t)row_items, (uint32_t)bx, (uint32_t)by, dn8);
+                           dim3(kThreads), lds, st, src, dst, g, (uint32_t)row_items, (uint32_t)bx, (uint32_t)by, dn8);
     return launch_status();
 }
 
@@ -1348,8 +1352,10 @@ int dispatch_pool16(const uint16_t* src, uint16_t* dst, const PoolGeom& g, int l
         const long long items = planes * g.Ho * per_row;
         if (items < 0x7fffffffLL) {
             const FastDiv d = make_fastdiv((uint32_t)per_row);
+            // the row-pair kernel is best uncapped in 16 bits (77.3 % of peak; 71.7 % at 4, 76.6 % at 5)
+            const size_t lds = throttle_lds(env_int("CNNMEM_POOL16_WPC", -1), 2LL * planes * g.H * g.W, 5);
             hipLaunchKernelGGL((pool16_nchw_2x2s2_kernel<E, MODE>), dim3((unsigned)ceil_div64(items, kThreads)),
-                               dim3(kThreads), 0, st, src, dst, (uint32_t)items, (uint32_t)g.W, d);
+                               dim3(kThreads), lds, st, src, dst, (uint32_t)items, (uint32_t)g.W, d);
             return launch_status();
         }
     }
