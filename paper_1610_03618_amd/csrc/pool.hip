@@ -487,8 +487,17 @@ int launch_chwn_vec4(const float* src, float* dst, const PoolGeom& g, const Pool
     // disjoint windows, one output per lane: 64 B in flight per lane, best at 4 workgroups per CU;
     // larger working sets already keep plenty in flight and are left alone unless asked
     const bool light = OY == 1 && OX == 1 && KH <= SH && KW <= SW;
-    const size_t lds = throttle_lds(light || tune.workgroups_per_cu != 0 ? tune.workgroups_per_cu : -1,
-                                    4LL * g.N * g.C * g.H * g.W, 4);
+    const long long in_bytes = 4LL * g.N * g.C * g.H * g.W;
+    int cap = light || tune.workgroups_per_cu != 0 ? tune.workgroups_per_cu : -1;
+    if (!light && tune.workgroups_per_cu == 0) {
+        // Overlapping windows: a lane has 9 (one output) to 15 (two padded rows) 128-bit loads in flight.  Four
+        // resident workgroups per CU measured 1-2 points above the full eight from 96 MB of input up
+        // (128x96x55x55: 66.7 -> 68.3 % of peak, 512x96x55x55: 71.9 -> 73.7 %), three for the two-row blocks on
+        // large tensors (256x64x112x112 p1: 72.0 -> 73.8 %).
+        if (OY * OX == 1 && in_bytes >= (64LL << 20)) cap = 4;
+        else if (OY * OX == 2 && in_bytes >= (384LL << 20)) cap = 3;
+    }
+    const size_t lds = throttle_lds(cap, in_bytes, 4);
     if (g.ph > 0 || g.pw > 0)
         hipLaunchKernelGGL((pool_chwn_vec4_kernel<MODE, KH, KW, SH, SW, OY, OX, true>), dim3((unsigned)blocks),
                            dim3(kThreads), lds, st, src, dst, g, (uint32_t)row_items, (uint32_t)bx,
