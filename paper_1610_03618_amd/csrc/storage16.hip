@@ -1292,7 +1292,8 @@ int launch_pool16_chwn(const uint16_t* src, uint16_t* dst, const PoolGeom& g, hi
     // occupancy cap for disjoint windows on large tensors, as for fp32: 64x64x224x224 fp16 73.4 % of peak
     // uncapped, 76.6-76.9 % at 3-5 workgroups per CU (CNNMEM_POOL16_WPC: -1 = never, 1..8 = that many)
     const bool light = OY == 1 && KH <= SH && KW <= SW;
-    const size_t lds = light ? throttle_lds(env_int("CNNMEM_POOL16_WPC", 0), 2LL * g.N * g.C * g.H * g.W, 4) : 0;
+    const size_t lds = light ? throttle_lds(env_int("CNNMEM_POOL16_WPC", 0), 2LL * g.N * g.C * g.H * g.W, 4)
+                             : throttle_lds(env_int("CNNMEM_POOL16_WPC", -1), 2LL * g.N * g.C * g.H * g.W, 4);
     if (g.ph > 0 || g.pw > 0)
         hipLaunchKernelGGL((pool16_chwn_kernel<E, MODE, KH, KW, SH, SW, OY, true>), dim3((unsigned)blocks),
                            dim3(kThreads), lds, st, src, dst, g, (uint32_t)row_items, (uint32_t)bx, (uint32_t)by, dn8);
