@@ -496,6 +496,7 @@ int launch_chwn_vec4(const float* src, float* dst, const PoolGeom& g, const Pool
         // large tensors (256x64x112x112 p1: 72.0 -> 73.8 %).
         if (OY * OX == 1 && in_bytes >= (64LL << 20)) cap = 4;
         else if (OY * OX == 2 && in_bytes >= (384LL << 20)) cap = 3;
+        else if (OY * OX >= 3 && in_bytes >= (64LL << 20)) cap = 5;    // 3x3/s1, four rows: 59.8 -> 62.2 % at 206 MB
     }
     const size_t lds = throttle_lds(cap, in_bytes, 4);
     if (g.ph > 0 || g.pw > 0)
