@@ -168,7 +168,8 @@ __device__ __forceinline__ u32x4 pack8(const float* f) {
 // row-wise reads over the banks.
 template <int TR, int TS>
 __global__ __launch_bounds__(kThreads) void transpose16_kernel(
-    const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, long long R, long long S, uint32_t tiles_s) {
+    const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, long long R, long long S, uint32_t tiles_s,
+    int xcd_order) {
     static_assert(TR % 16 == 0 && TS % 8 == 0 && (TR * TS / 16) % kThreads == 0, "tile shape");
     constexpr int PD = TR / 2 + 1;                  // LDS pitch in dwords
     constexpr int NC8 = TS / 8;
@@ -177,8 +178,11 @@ __global__ __launch_bounds__(kThreads) void transpose16_kernel(
     constexpr int STORES = (TS * NB8) / kThreads;
     __shared__ uint32_t tile[(TS + 1) * PD];        // one spare row for words left of the tile
 
-    const long long r0 = (long long)(blockIdx.x / tiles_s) * TR;
-    const long long s0 = (long long)(blockIdx.x % tiles_s) * TS;
+    // xcd_order: neighbouring tiles run on one XCD, so a cache line that two of them share (rows that are not a
+    // whole number of lines) is fetched from memory once and found in that XCD's L2 the second time
+    const uint32_t t = xcd_order ? xcd_contiguous_tile(blockIdx.x, gridDim.x) : blockIdx.x;
+    const long long r0 = (long long)(t / tiles_s) * TR;
+    const long long s0 = (long long)(t % tiles_s) * TS;
     const int tid = threadIdx.x;
 
     u32x4 a[LOADS], b[LOADS];
@@ -354,13 +358,18 @@ int launch_t16(const uint16_t* src, uint16_t* dst, long long R, long long S, hip
     const long long tiles_r = ceil_div64(R, TR), tiles_s = ceil_div64(S, TS);
     if (tiles_r * tiles_s > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
     hipLaunchKernelGGL((transpose16_kernel<TR, TS>), dim3((unsigned)(tiles_r * tiles_s)), dim3(kThreads), 0, st, src,
-                       dst, R, S, (uint32_t)tiles_s);
+                       dst, R, S, (uint32_t)tiles_s,
+                       // source rows that are not whole 128-byte lines: neighbouring tiles share lines (counters showed
+                       // 1.25x the tensor fetched from memory); 256x96x55x55 NCHW -> CHWN 61.8 -> 65.7 % of peak.  With
+                       // line-aligned source rows the plain order is 1-3 points better.
+                       env_int("CNNMEM_TRANSFORM16_XCD", (S * 2) % 128 != 0 ? 1 : 0));
     return launch_status();
 }
 
 struct Tile16Plan {
     long long R, S, ss_r, ds_s, sb0, sb1, db0, db1;
     uint32_t tiles_s, tiles_plane;
+    int xcd_order = 0;          // tile kernel: neighbouring tiles on one XCD
 };
 
 // ---- thin planes: one tile axis has 2..8 entries (batches of 2..8 images, RGB input) ----------
@@ -631,8 +640,9 @@ __global__ __launch_bounds__(kThreads) void permute16_tile_kernel(
     constexpr int STORES = (TS * NB8) / kThreads;
     __shared__ uint32_t tile[(TS + 1) * PD];
 
-    const uint32_t batch = fd_div(blockIdx.x, d_plane);
-    const uint32_t in_plane = blockIdx.x - batch * p.tiles_plane;
+    const uint32_t lin = p.xcd_order ? xcd_contiguous_tile(blockIdx.x, gridDim.x) : blockIdx.x;
+    const uint32_t batch = fd_div(lin, d_plane);
+    const uint32_t in_plane = lin - batch * p.tiles_plane;
     const uint32_t tr = fd_div(in_plane, d_tiles_s);
     const uint32_t ts = in_plane - tr * p.tiles_s;
     const uint32_t b0 = fd_div(batch, d_nb1);
@@ -793,6 +803,7 @@ int launch_p16_tile(const uint16_t* src, uint16_t* dst, Tile16Plan p, long long 
         return CNNMEM_ERR_UNSUPPORTED;
     p.tiles_s = (uint32_t)tiles_s;
     p.tiles_plane = (uint32_t)plane;
+    p.xcd_order = env_int("CNNMEM_PERMUTE16_XCD", p.xcd_order);
     const dim3 grid((unsigned)(plane * nb0 * nb1)), block(kThreads);
     const FastDiv d_plane = make_fastdiv((uint32_t)plane), d_ts = make_fastdiv((uint32_t)tiles_s),
                   d_nb1 = make_fastdiv((uint32_t)nb1);
@@ -847,6 +858,14 @@ int launch_permute16_impl(const uint16_t* src, uint16_t* dst, const int* dims, c
     p.R = pl.R; p.S = pl.S; p.ss_r = pl.ss_r; p.ds_s = pl.ds_s;
     p.sb0 = pl.sb0; p.sb1 = pl.sb1; p.db0 = pl.db0; p.db1 = pl.db1;
     p.tiles_s = p.tiles_plane = 0;
+    // Neighbouring tiles on one XCD (a line two tiles share is then an L2 hit) when a batch axis lies between
+    // the tile axes, as for fp32; when the source rows are short and not whole 128-byte lines (NHWC -> NCHW
+    // with 96 channels: 192-byte rows); and when only the destination rows are not whole lines (NHWC -> NCHW of
+    // 27 x 27 planes with 256 channels).  Measured in fp16: 128x96x55x55 NHWC -> NCHW 38.5 -> 46.1 % of peak,
+    // NCHW -> HWCN 38.2 -> 41.7 %, HWCN -> NCHW 31.7 -> 43.0 %; 128x256x27x27 NHWC -> NCHW 36.4 -> 43.6 %.
+    // Long misaligned source rows (NCHW -> NHWC) lose 1-3 points with it and keep the plain order.
+    const bool src_ragged = (p.S * 2) % 128 != 0, dst_ragged = (p.R * 2) % 128 != 0;
+    p.xcd_order = pl.xcd_order || (src_ragged && p.S < 256) || (dst_ragged && !src_ragged) ? 1 : 0;
     {
         const int rc = launch_thin16_any(src, dst, p, pl.nb0, pl.nb1, st);
         if (rc != CNNMEM_ERR_UNSUPPORTED) return rc;
