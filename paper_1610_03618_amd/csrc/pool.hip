@@ -184,38 +184,55 @@ __global__ __launch_bounds__(kThreads) void pool_chwn_vec4_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// CHWN, any window: float4 over four images, one output per lane, the window walked
-// with run-time loops (global 7x7 pooling, 5x5 / stride 3, rectangular windows ...).
+// CHWN, any window: float4 over four images, the window walked with run-time loops
+// (global 7x7 pooling, 5x5 / stride 3, rectangular windows ...).
 // ---------------------------------------------------------------------------
-template <int MODE>
+// OY vertically adjacent outputs per lane: each input row under them is read and reduced along W once and
+// serves every output whose window holds it.  With one output per lane the rows that two windows share were
+// fetched from HBM twice (counters: 1.75x the tensor for 5x5 / stride 3): the workgroups of neighbouring
+// output rows run at the same time, but each streams 64 KB and the shared rows have left L2 by the time the
+// neighbour asks for them.
+template <int MODE, int OY>
 __global__ __launch_bounds__(kThreads) void pool_chwn_vec4_any_kernel(
     const float* __restrict__ src, float* __restrict__ dst, PoolGeom g, uint32_t items, FastDiv div_n4, FastDiv div_wo,
-    FastDiv div_ho) {
-    const uint32_t u = blockIdx.x * kThreads + threadIdx.x;   // ((c*Ho + i)*Wo + j)*N4 + n4
+    FastDiv div_hb) {
+    // neighbouring workgroups run on one XCD, so columns that neighbouring lanes' windows share are L2 hits
+    const uint32_t u = xcd_contiguous_tile(blockIdx.x, gridDim.x) * kThreads + threadIdx.x;   // ((c*HB + ib)*Wo + j)*N4 + n4
     if (u >= items) return;
     uint32_t t = fd_div(u, div_n4);
     const uint32_t n4 = u - t * div_n4.d;
     uint32_t t2 = fd_div(t, div_wo);
     const int j = (int)(t - t2 * div_wo.d);
-    const uint32_t c = fd_div(t2, div_ho);
-    const int i = (int)(t2 - c * div_ho.d);
+    const uint32_t c = fd_div(t2, div_hb);
+    const int i0 = (int)(t2 - c * div_hb.d) * OY;              // first output row of the lane
     const int N = g.N;
-    // in-image part of the window
-    int r_lo = i * g.sh - g.ph, q_lo = j * g.sw - g.pw;
-    int r_hi = r_lo + g.kh, q_hi = q_lo + g.kw;
-    if (r_lo < 0) r_lo = 0;
+    int q_lo = j * g.sw - g.pw, q_hi = q_lo + g.kw;
     if (q_lo < 0) q_lo = 0;
-    if (r_hi > g.H) r_hi = g.H;
     if (q_hi > g.W) q_hi = g.W;
+    const int i_last = i0 + OY - 1 < g.Ho - 1 ? i0 + OY - 1 : g.Ho - 1;
+    int r_lo = i0 * g.sh - g.ph, r_hi = i_last * g.sh - g.ph + g.kh;
+    if (r_lo < 0) r_lo = 0;
+    if (r_hi > g.H) r_hi = g.H;
     const float* plane = src + (size_t)c * g.H * g.W * N + 4 * n4;
-    float4 acc = Acc<MODE>::identity4();
+    float4 acc[OY];
+#pragma unroll
+    for (int k = 0; k < OY; ++k) acc[k] = Acc<MODE>::identity4();
     for (int r = r_lo; r < r_hi; ++r) {
         const float* rowp = plane + (size_t)r * g.W * N;
+        float4 h = Acc<MODE>::identity4();
 #pragma unroll 4
         for (int q = q_lo; q < q_hi; ++q)
-            acc = Acc<MODE>::op4(acc, *reinterpret_cast<const float4*>(rowp + (size_t)q * N));
+            h = Acc<MODE>::op4(h, *reinterpret_cast<const float4*>(rowp + (size_t)q * N));
+#pragma unroll
+        for (int k = 0; k < OY; ++k) {
+            const int top = (i0 + k) * g.sh - g.ph;            // first row of output k's window
+            if (OY == 1 || (r >= top && r < top + g.kh)) acc[k] = Acc<MODE>::op4(acc[k], h);
+        }
     }
-    st4_stream(dst + 4 * (size_t)u, Acc<MODE>::finish4(acc, (float)(g.kh * g.kw)));
+    float* out = dst + (((size_t)c * g.Ho + i0) * g.Wo + j) * N + 4 * n4;
+#pragma unroll
+    for (int k = 0; k < OY; ++k)
+        if (i0 + k < g.Ho) st4_stream(out + (size_t)k * g.Wo * N, Acc<MODE>::finish4(acc[k], (float)(g.kh * g.kw)));
 }
 
 // ---------------------------------------------------------------------------
@@ -542,11 +559,25 @@ int dispatch_chwn(const float* src, float* dst, const PoolGeom& g, const PoolTun
         rc = launch_chwn_window<MODE, 3, 3, 1, 1>(tune.rows_per_lane ? tune.rows_per_lane : env_int("CNNMEM_CHWN_ROWS", 4), ox, src, dst, g, tune, st);
     }
     if (rc != CNNMEM_ERR_UNSUPPORTED) return rc;
-    const long long items = (long long)g.C * g.Ho * g.Wo * (g.N / 4);
+    // Output rows per lane, measured on MI355X (% of peak with 1 / 2 / 3 rows): 5x5/s1 24 / 33 / 37, 5x5/s2
+    // 45 / 50 / 51, 5x5/s3 52 / 55 / 55, 4x4/s2 52 / 51 / 50.  Windows more than twice the stride take three,
+    // windows between one and two strides two, the rest one.
+    int rows = 1;
+    if (g.Ho >= 3 && g.kh > 2 * g.sh) rows = 3;
+    else if (g.Ho >= 2 && g.kh > g.sh && g.kh < 2 * g.sh) rows = 2;
+    const int oy = env_int("CNNMEM_CHWN_ANY_ROWS", rows);
+    const long long hb = ceil_div64(g.Ho, oy == 3 ? 3 : (oy == 2 ? 2 : 1));
+    const long long items = (long long)g.C * hb * g.Wo * (g.N / 4);
     if (vec && items < 0x7fffffffLL && items > 0) {
-        hipLaunchKernelGGL((pool_chwn_vec4_any_kernel<MODE>), dim3((unsigned)ceil_div64(items, kThreads)), dim3(kThreads),
-                           0, st, src, dst, g, (uint32_t)items, make_fastdiv((uint32_t)(g.N / 4)),
-                           make_fastdiv((uint32_t)g.Wo), make_fastdiv((uint32_t)g.Ho));
+        const dim3 grid((unsigned)ceil_div64(items, kThreads)), block(kThreads);
+        const FastDiv dn4 = make_fastdiv((uint32_t)(g.N / 4)), dwo = make_fastdiv((uint32_t)g.Wo),
+                      dhb = make_fastdiv((uint32_t)hb);
+        if (oy == 3)
+            hipLaunchKernelGGL((pool_chwn_vec4_any_kernel<MODE, 3>), grid, block, 0, st, src, dst, g, (uint32_t)items, dn4, dwo, dhb);
+        else if (oy == 2)
+            hipLaunchKernelGGL((pool_chwn_vec4_any_kernel<MODE, 2>), grid, block, 0, st, src, dst, g, (uint32_t)items, dn4, dwo, dhb);
+        else
+            hipLaunchKernelGGL((pool_chwn_vec4_any_kernel<MODE, 1>), grid, block, 0, st, src, dst, g, (uint32_t)items, dn4, dwo, dhb);
         return launch_status();
     }
     return launch_generic<MODE>(src, dst, g, 1, st);

@@ -944,7 +944,8 @@ template <class E, int MODE>
 __global__ __launch_bounds__(kThreads) void pool16_chwn_any_kernel(
     const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, PoolGeom g, uint32_t items, FastDiv div_n8,
     FastDiv div_wo, FastDiv div_ho) {
-    const uint32_t u = blockIdx.x * kThreads + threadIdx.x;   // ((c*Ho + i)*Wo + j)*N8 + n8
+    // neighbouring workgroups on one XCD: output rows that share input rows find them in L2
+    const uint32_t u = xcd_contiguous_tile(blockIdx.x, gridDim.x) * kThreads + threadIdx.x;   // ((c*Ho + i)*Wo + j)*N8 + n8
     if (u >= items) return;
     const uint32_t t = fd_div(u, div_n8);
     const uint32_t n8 = u - t * div_n8.d;

@@ -165,6 +165,20 @@ def test_pool_matches_oracle(shape, geom):
     check_pool(x, N, C, H, W, geom)
 
 
+@pytest.mark.parametrize("rows", [1, 2, 3])
+def test_pool_chwn_any_window_rows_per_lane(rows, monkeypatch):
+    """The run-time-window CHWN kernel with 1..3 output rows per lane: ragged row blocks, padding, rectangular
+    windows, windows as large as the image."""
+    monkeypatch.setenv("CNNMEM_CHWN_ANY_ROWS", str(rows))
+    rng = np.random.default_rng(60 + rows)
+    for shape, geom in [((8, 3, 17, 19), (5, 5, 3, 3, 2, 2)), ((4, 2, 20, 21), (5, 5, 2, 2, 2, 2)),
+                        ((8, 2, 11, 13), (5, 5, 1, 1, 2, 2)), ((4, 3, 16, 16), (4, 4, 2, 2, 1, 1)),
+                        ((8, 2, 7, 7), (7, 7, 7, 7, 0, 0)), ((4, 2, 9, 30), (5, 3, 1, 2, 2, 1)),
+                        ((4, 2, 30, 9), (3, 5, 2, 1, 1, 2)), ((12, 1, 10, 10), (4, 4, 3, 3, 2, 2))]:
+        x = rng.standard_normal(shape, dtype=np.float32)
+        check_pool(x, *shape, geom, layouts=(CHWN,))
+
+
 @pytest.mark.parametrize("oy", [1, 2, 3, 4])
 @pytest.mark.parametrize("ox", [1, 2])
 def test_pool_chwn_every_working_set_shape(oy, ox):
