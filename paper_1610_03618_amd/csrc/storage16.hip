@@ -118,8 +118,36 @@ struct Half {                                       // IEEE binary16
         return h & 0xffffu;
     }
     static __device__ __forceinline__ uint32_t pack2(float lo, float hi) { return narrow(lo) | (narrow(hi) << 16); }
+    // The maximum of two pairs without widening them: exact, subnormals included (16-bit subnormals are
+    // never flushed), and it writes the whole destination register.
+    static constexpr bool kPairMax = true;
+    static constexpr uint32_t kNegInfPair = 0xfc00fc00u;
+    // v[0..7] += the eight halves of w, in fp32: the mixed-precision fused multiply-add widens one half of
+    // a register exactly, multiplies by 1 and adds with a single rounding, i.e. the fp32 sum, in one
+    // instruction per value instead of three (mask or shift, widen, add).  It honours subnormals.
+    static __device__ __forceinline__ void add8(float* v, const u32x4& w) {
+        const uint32_t d[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            asm("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "+v"(v[2 * k]) : "v"(d[k]));
+            asm("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "+v"(v[2 * k + 1]) : "v"(d[k]));
+        }
+    }
+    static __device__ __forceinline__ uint32_t max2(uint32_t a, uint32_t b) {
+        uint32_t r;
+        asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+        return r;
+    }
 };
 struct BFloat {                                     // upper half of binary32
+    static constexpr bool kPairMax = false;         // no packed bfloat16 arithmetic on this target
+    static constexpr uint32_t kNegInfPair = 0xff80ff80u;
+    static __device__ __forceinline__ void add8(float* v, const u32x4& w) {
+        v[0] += widen(w.x & 0xffffu); v[1] += widen(w.x >> 16);
+        v[2] += widen(w.y & 0xffffu); v[3] += widen(w.y >> 16);
+        v[4] += widen(w.z & 0xffffu); v[5] += widen(w.z >> 16);
+        v[6] += widen(w.w & 0xffffu); v[7] += widen(w.w >> 16);
+    }
     static __device__ __forceinline__ float widen(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
     static __device__ __forceinline__ uint32_t narrow(float x) {
         const uint32_t u = __float_as_uint(x);
@@ -894,15 +922,79 @@ int launch_permute16_impl(const uint16_t* src, uint16_t* dst, const int* dims, c
 // =============================================================================
 // Pooling (Equation 2; Section IV.B, V.A)
 // =============================================================================
+// fmaxf() on a value that comes straight from memory costs two instructions: the compiler first quiets a
+// possible signalling NaN (v_max_f32 x, x, x).  With eight widened values per 128-bit load that doubled the
+// arithmetic of maximum pooling and made it slower than the average (256x64x112x112 3x3/s2/p1 CHWN fp16:
+// 48 % of peak against 56 %).  The instruction itself returns the other operand for a quiet NaN and a quiet
+// NaN for a signalling one, which is all that is wanted here.
+__device__ __forceinline__ float max_plain(float a, float b) {
+    float r;
+    asm("v_max_f32_e32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
 template <int MODE>
 struct Acc {
     static __device__ __forceinline__ float identity() { return MODE == CNNMEM_POOL_MAX ? kNegInf : 0.f; }
     static __device__ __forceinline__ float op(float a, float b) {
-        return MODE == CNNMEM_POOL_MAX ? fmaxf(a, b) : a + b;
+        return MODE == CNNMEM_POOL_MAX ? max_plain(a, b) : a + b;
     }
     static __device__ __forceinline__ float finish(float a, float divisor) {
         return MODE == CNNMEM_POOL_MAX ? a : a / divisor;
     }
+};
+
+// The eight accumulators of a lane that owns eight images (one 128-bit word group).  In general they are
+// fp32 values; for the maximum of binary16 data they stay packed, because the packed maximum is exact and
+// takes 4 instructions per tap instead of 24 (mask or shift, widen, maximum for each of 8 values).
+template <class E, int MODE, bool PAIRS = (MODE == CNNMEM_POOL_MAX && E::kPairMax)>
+struct Lane8 {
+    float v[8];
+    __device__ __forceinline__ void clear() {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = Acc<MODE>::identity();
+    }
+    __device__ __forceinline__ void tap(const u32x4& w) {
+        if (MODE == CNNMEM_POOL_AVG) {
+            E::add8(v, w);
+        } else {
+            float t[8];
+            unpack8<E>(w, t);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = Acc<MODE>::op(v[e], t[e]);
+        }
+    }
+    __device__ __forceinline__ void tap_if(const u32x4& w, bool ok) {     // a tap in the padding counts as the identity
+        constexpr uint32_t id = MODE == CNNMEM_POOL_MAX ? E::kNegInfPair : 0u;
+        u32x4 m;
+        m.x = ok ? w.x : id; m.y = ok ? w.y : id; m.z = ok ? w.z : id; m.w = ok ? w.w : id;
+        tap(m);
+    }
+    __device__ __forceinline__ void merge(const Lane8& o) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = Acc<MODE>::op(v[e], o.v[e]);
+    }
+    __device__ __forceinline__ u32x4 result(float divisor) const {
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = Acc<MODE>::finish(v[e], divisor);
+        return pack8<E>(o);
+    }
+};
+template <class E, int MODE>
+struct Lane8<E, MODE, true> {
+    u32x4 w;
+    __device__ __forceinline__ void clear() { w.x = w.y = w.z = w.w = E::kNegInfPair; }
+    __device__ __forceinline__ void tap(const u32x4& t) {
+        w.x = E::max2(w.x, t.x); w.y = E::max2(w.y, t.y); w.z = E::max2(w.z, t.z); w.w = E::max2(w.w, t.w);
+    }
+    __device__ __forceinline__ void tap_if(const u32x4& t, bool ok) {
+        u32x4 m;
+        m.x = ok ? t.x : E::kNegInfPair; m.y = ok ? t.y : E::kNegInfPair;
+        m.z = ok ? t.z : E::kNegInfPair; m.w = ok ? t.w : E::kNegInfPair;
+        tap(m);
+    }
+    __device__ __forceinline__ void merge(const Lane8& o) { tap(o.w); }
+    __device__ __forceinline__ u32x4 result(float) const { return w; }
 };
 
 // Fallback: one lane per output, any layout through strides.
@@ -938,44 +1030,56 @@ __global__ __launch_bounds__(kThreads) void pool16_generic_kernel(
     }
 }
 
-// CHWN, any window: eight images per lane (one 128-bit access), one output per lane, the in-image part
-// of the window walked with run-time loops (global 7x7 pooling, 5x5 / stride 3, rectangular windows).
-template <class E, int MODE>
+// CHWN, any window: eight images per lane (one 128-bit access), the in-image part of the window walked with
+// run-time loops (global 7x7 pooling, 5x5 / stride 3, rectangular windows).  A lane owns OY vertically adjacent
+// outputs: each input row under them is read and reduced along W once and serves every output whose window
+// holds it, instead of being fetched again by the lanes of the neighbouring output rows.
+template <class E, int MODE, int OY>
 __global__ __launch_bounds__(kThreads) void pool16_chwn_any_kernel(
     const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, PoolGeom g, uint32_t items, FastDiv div_n8,
-    FastDiv div_wo, FastDiv div_ho) {
+    FastDiv div_wo, FastDiv div_hb) {
     // neighbouring workgroups on one XCD: output rows that share input rows find them in L2
-    const uint32_t u = xcd_contiguous_tile(blockIdx.x, gridDim.x) * kThreads + threadIdx.x;   // ((c*Ho + i)*Wo + j)*N8 + n8
+    const uint32_t u = xcd_contiguous_tile(blockIdx.x, gridDim.x) * kThreads + threadIdx.x;   // ((c*HB + ib)*Wo + j)*N8 + n8
     if (u >= items) return;
     const uint32_t t = fd_div(u, div_n8);
     const uint32_t n8 = u - t * div_n8.d;
     const uint32_t t2 = fd_div(t, div_wo);
     const int j = (int)(t - t2 * div_wo.d);
-    const uint32_t c = fd_div(t2, div_ho);
-    const int i = (int)(t2 - c * div_ho.d);
+    const uint32_t c = fd_div(t2, div_hb);
+    const int i0 = (int)(t2 - c * div_hb.d) * OY;              // first output row of the lane
     const int N = g.N;
-    int r_lo = i * g.sh - g.ph, q_lo = j * g.sw - g.pw;
-    int r_hi = r_lo + g.kh, q_hi = q_lo + g.kw;
-    if (r_lo < 0) r_lo = 0;
+    int q_lo = j * g.sw - g.pw, q_hi = q_lo + g.kw;
     if (q_lo < 0) q_lo = 0;
-    if (r_hi > g.H) r_hi = g.H;
     if (q_hi > g.W) q_hi = g.W;
+    const int i_last = i0 + OY - 1 < g.Ho - 1 ? i0 + OY - 1 : g.Ho - 1;
+    int r_lo = i0 * g.sh - g.ph, r_hi = i_last * g.sh - g.ph + g.kh;
+    if (r_lo < 0) r_lo = 0;
+    if (r_hi > g.H) r_hi = g.H;
     const uint16_t* plane = src + (size_t)c * g.H * g.W * N + 8 * n8;
-    float acc[8];
+    Lane8<E, MODE> acc[OY];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) acc[k] = Acc<MODE>::identity();
+    for (int o = 0; o < OY; ++o) acc[o].clear();
     for (int r = r_lo; r < r_hi; ++r) {
         const uint16_t* rowp = plane + (size_t)r * g.W * N;
-        for (int q = q_lo; q < q_hi; ++q) {
-            float v[8];
-            unpack8<E>(ld16_cached(rowp + (size_t)q * N), v);
+        Lane8<E, MODE> h;
+        h.clear();
+        int q = q_lo;
+        for (; q + 4 <= q_hi; q += 4) {                         // four loads in flight before the first is used
+            const u32x4 w0 = ld16_cached(rowp + (size_t)q * N), w1 = ld16_cached(rowp + (size_t)(q + 1) * N),
+                        w2 = ld16_cached(rowp + (size_t)(q + 2) * N), w3 = ld16_cached(rowp + (size_t)(q + 3) * N);
+            h.tap(w0); h.tap(w1); h.tap(w2); h.tap(w3);
+        }
+        for (; q < q_hi; ++q) h.tap(ld16_cached(rowp + (size_t)q * N));
 #pragma unroll
-            for (int k = 0; k < 8; ++k) acc[k] = Acc<MODE>::op(acc[k], v[k]);
+        for (int o = 0; o < OY; ++o) {
+            const int top = (i0 + o) * g.sh - g.ph;            // first row of output o's window
+            if (OY == 1 || (r >= top && r < top + g.kh)) acc[o].merge(h);
         }
     }
+    uint16_t* out = dst + (((size_t)c * g.Ho + i0) * g.Wo + j) * N + 8 * n8;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) acc[k] = Acc<MODE>::finish(acc[k], (float)(g.kh * g.kw));
-    st16_stream(dst + 8 * (size_t)u, pack8<E>(acc));
+    for (int o = 0; o < OY; ++o)
+        if (i0 + o < g.Ho) st16_stream(out + (size_t)o * g.Wo * N, acc[o].result((float)(g.kh * g.kw)));
 }
 
 // CHWN: a lane owns 8 consecutive images of one output column and walks down OY
@@ -999,11 +1103,9 @@ __global__ __launch_bounds__(kThreads) void pool16_chwn_kernel(
     const int i0 = (int)by * OY;
     const int N = g.N;
 
-    float acc[OY][8];
+    Lane8<E, MODE> acc[OY];
 #pragma unroll
-    for (int oy = 0; oy < OY; ++oy)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[oy][e] = Acc<MODE>::identity();
+    for (int oy = 0; oy < OY; ++oy) acc[oy].clear();
 
     const int q0 = (int)j * SW - g.pw;
     const int r_base = i0 * SH - g.ph;
@@ -1015,40 +1117,26 @@ __global__ __launch_bounds__(kThreads) void pool16_chwn_kernel(
         const bool row_ok = !PADDED || (r >= 0 && r < g.H);
         const int rc = r < 0 ? 0 : (r < g.H ? r : g.H - 1);
         const uint16_t* rowp = plane + (size_t)rc * g.W * N;
-        float h[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) h[e] = Acc<MODE>::identity();
+        Lane8<E, MODE> h;
+        h.clear();
 #pragma unroll
         for (int x = 0; x < KW; ++x) {
             const int q = q0 + x;
             const bool ok = row_ok && (!PADDED || (q >= 0 && q < g.W));
             const int qc = q < 0 ? 0 : (q < g.W ? q : g.W - 1);
             const u32x4 w = kStream ? ld16_stream(rowp + (size_t)qc * N) : ld16_cached(rowp + (size_t)qc * N);
-            float t[8];
-            unpack8<E>(w, t);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                if (PADDED && !ok) t[e] = Acc<MODE>::identity();
-                h[e] = Acc<MODE>::op(h[e], t[e]);
-            }
+            if (PADDED) h.tap_if(w, ok);
+            else h.tap(w);
         }
 #pragma unroll
         for (int oy = 0; oy < OY; ++oy)
-            if (rr >= oy * SH && rr < oy * SH + KH) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[oy][e] = Acc<MODE>::op(acc[oy][e], h[e]);
-            }
+            if (rr >= oy * SH && rr < oy * SH + KH) acc[oy].merge(h);
     }
     uint16_t* outp = dst + ((size_t)c * g.Ho * g.Wo + j) * N + 8 * n8;
 #pragma unroll
     for (int oy = 0; oy < OY; ++oy) {
         const int i = i0 + oy;
-        if (i < g.Ho) {
-            float o[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = Acc<MODE>::finish(acc[oy][e], (float)(KH * KW));
-            st16_through(outp + (size_t)i * g.Wo * N, pack8<E>(o));
-        }
+        if (i < g.Ho) st16_through(outp + (size_t)i * g.Wo * N, acc[oy].result((float)(KH * KW)));
     }
 }
 
@@ -1357,11 +1445,24 @@ int dispatch_pool16(const uint16_t* src, uint16_t* dst, const PoolGeom& g, int l
             if (g.kh == 3 && g.kw == 3 && g.sh == 1 && g.sw == 1)
                 return launch_pool16_chwn<E, MODE, 3, 3, 1, 1, 3>(src, dst, g, st);
         }
-        const long long items = (long long)g.C * g.Ho * g.Wo * (g.N / 8);
+        // output rows per lane as in the 32-bit kernel: three when the window is taller than two strides, two
+        // when it is between one and two strides, else one
+        int rows = 1;
+        if (g.Ho >= 3 && g.kh > 2 * g.sh) rows = 3;
+        else if (g.Ho >= 2 && g.kh > g.sh && g.kh < 2 * g.sh) rows = 2;
+        const int oy = env_int("CNNMEM_CHWN16_ANY_ROWS", rows);
+        const long long hb = ceil_div64(g.Ho, oy == 3 ? 3 : (oy == 2 ? 2 : 1));
+        const long long items = (long long)g.C * hb * g.Wo * (g.N / 8);
         if (a16 && g.N % 8 == 0 && items < 0x7fffffffLL && items > 0) {
-            hipLaunchKernelGGL((pool16_chwn_any_kernel<E, MODE>), dim3((unsigned)ceil_div64(items, kThreads)),
-                               dim3(kThreads), 0, st, src, dst, g, (uint32_t)items, make_fastdiv((uint32_t)(g.N / 8)),
-                               make_fastdiv((uint32_t)g.Wo), make_fastdiv((uint32_t)g.Ho));
+            const dim3 grid((unsigned)ceil_div64(items, kThreads)), block(kThreads);
+            const FastDiv dn8 = make_fastdiv((uint32_t)(g.N / 8)), dwo = make_fastdiv((uint32_t)g.Wo),
+                          dhb = make_fastdiv((uint32_t)hb);
+            if (oy == 3)
+                hipLaunchKernelGGL((pool16_chwn_any_kernel<E, MODE, 3>), grid, block, 0, st, src, dst, g, (uint32_t)items, dn8, dwo, dhb);
+            else if (oy == 2)
+                hipLaunchKernelGGL((pool16_chwn_any_kernel<E, MODE, 2>), grid, block, 0, st, src, dst, g, (uint32_t)items, dn8, dwo, dhb);
+            else
+                hipLaunchKernelGGL((pool16_chwn_any_kernel<E, MODE, 1>), grid, block, 0, st, src, dst, g, (uint32_t)items, dn8, dwo, dhb);
             return launch_status();
         }
         return launch_pool16_generic<E, MODE>(src, dst, g, 1, st);

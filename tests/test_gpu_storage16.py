@@ -170,6 +170,28 @@ def test_pool16_nchw_slab_rows_per_lane(rows, dtype, monkeypatch):
         check_rounded(bits_of(got), want, 0.999, (case, "avg"))
 
 
+@pytest.mark.parametrize("rows", [1, 2, 3])
+@pytest.mark.parametrize("dtype", DTYPES, ids=[IDS[d] for d in DTYPES])
+def test_pool16_chwn_any_window_rows_per_lane(rows, dtype, monkeypatch):
+    """The run-time-window CHWN kernel with 1..3 output rows per lane: ragged row blocks, padding, rectangular
+    windows, a window as large as the image."""
+    monkeypatch.setenv("CNNMEM_CHWN16_ANY_ROWS", str(rows))
+    for case in [(8, 3, 17, 19, 5, 5, 3, 3, 2, 2), (16, 2, 20, 21, 5, 5, 2, 2, 2, 2), (8, 2, 11, 13, 5, 5, 1, 1, 2, 2),
+                 (8, 3, 16, 16, 4, 4, 2, 2, 1, 1), (8, 2, 7, 7, 7, 7, 7, 7, 0, 0), (8, 2, 9, 30, 5, 3, 1, 2, 2, 1),
+                 (8, 2, 30, 9, 3, 5, 2, 1, 1, 2), (24, 1, 10, 10, 4, 4, 3, 3, 2, 2)]:
+        N, C, H, W, kh, kw, sh, sw, ph, pw = case
+        rng = np.random.default_rng(sum(case) + rows)
+        xb, _ = to16(wl.relu_normal(rng, (N, C, H, W)) + np.float32(0.25), dtype)
+        xcb = oracle.transform16(xb, N, C, H, W, 0, 1)
+        xcd = torch.from_numpy(xcb.view(np.int16)).cuda().view(TORCH[dtype])
+        want = oracle.pool16(xcb, N, C, H, W, cm.CHWN, 0, kh, kw, sh, sw, ph, pw, dtype)
+        got = cm.pool(xcd, N, C, H, W, cm.CHWN, cm.POOL_MAX, kh, kw, sh, sw, ph, pw)
+        assert np.array_equal(bits_of(got), want), (case, "max")
+        want = oracle.pool16(xcb, N, C, H, W, cm.CHWN, 1, kh, kw, sh, sw, ph, pw, dtype)
+        got = cm.pool(xcd, N, C, H, W, cm.CHWN, cm.POOL_AVG, kh, kw, sh, sw, ph, pw)
+        check_rounded(bits_of(got), want, 0.999, (case, "avg"))
+
+
 def test_pool16_misaligned_views_take_the_generic_kernel():
     N, C, H, W, k, s = 8, 3, 12, 12, 3, 2
     rng = np.random.default_rng(77)
