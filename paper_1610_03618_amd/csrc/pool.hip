@@ -452,25 +452,15 @@ __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
                 }
             }
         } else {
-            // run-time window: clamped, branch-free taps for the maximum (5x5/s3/p2: 46 -> 59 % of peak);
-            // the average, which would need a select per tap, is faster skipping them (50 % against 45 %)
-            for (int y = 0; y < kh; ++y) {
-                const int r = rb + y;
-                if (MODE == CNNMEM_POOL_MAX) {
-                    const int row = base + (r < 0 ? 0 : (r < g.H ? r : g.H - 1)) * g.W;
+            // run-time window: the in-image part of the window, loop bounds clipped once, no test or
+            // select per tap (5x5/s3/p2 on 64x64x150x150: average 49 -> 60 % of peak against skipping
+            // taps one by one)
+            const int r_lo = rb < 0 ? 0 : rb, r_hi = rb + kh < g.H ? rb + kh : g.H;
+            const int q_lo = qb < 0 ? 0 : qb, q_hi = qb + kw < g.W ? qb + kw : g.W;
+            for (int r = r_lo; r < r_hi; ++r) {
+                const int row = base + r * g.W;
 #pragma unroll 4
-                    for (int x = 0; x < kw; ++x) {
-                        const int q = qb + x;
-                        acc = fmaxf(acc, slab[row + (q < 0 ? 0 : (q < g.W ? q : g.W - 1))]);
-                    }
-                } else {
-                    if (r < 0 || r >= g.H) continue;
-                    for (int x = 0; x < kw; ++x) {
-                        const int q = qb + x;
-                        if (q < 0 || q >= g.W) continue;
-                        acc += slab[base + r * g.W + q];
-                    }
-                }
+                for (int q = q_lo; q < q_hi; ++q) acc = Acc<MODE>::op(acc, slab[row + q]);
             }
         }
         st1_stream(dst + out0 + o, Acc<MODE>::finish(acc, (float)(kh * kw)));

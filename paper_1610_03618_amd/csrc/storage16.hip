@@ -938,8 +938,21 @@ struct Acc {
     static __device__ __forceinline__ float op(float a, float b) {
         return MODE == CNNMEM_POOL_MAX ? max_plain(a, b) : a + b;
     }
+    // Equation 2's division by the window area.  A correctly rounded fp32 division is about ten instructions
+    // per output, as much as the taps of a 3x3 window now that those are one instruction each.  The
+    // reciprocal is formed once per lane (at compile time for the fixed windows); one residual step on the
+    // product then gives the correctly rounded quotient again (q = a r, e = a - q d exactly by fma,
+    // q + e r), which matters: with 16-bit data the exact average often lies exactly on a rounding tie of
+    // the storage format (window sums are small integers in units of the data's last place), and the bare
+    // product a * (1/15) landed on the wrong side of 0.9 % of them.  The fix-up instruction restores the
+    // quotient of infinities and NaNs.
     static __device__ __forceinline__ float finish(float a, float divisor) {
-        return MODE == CNNMEM_POOL_MAX ? a : a / divisor;
+        if (MODE == CNNMEM_POOL_MAX) return a;
+        const float r = 1.0f / divisor;
+        float q = a * r;
+        const float e = __builtin_fmaf(-q, divisor, a);
+        q = __builtin_fmaf(e, r, q);
+        return __builtin_amdgcn_div_fixupf(q, divisor, a);
     }
 };
 
@@ -1361,14 +1374,18 @@ __global__ __launch_bounds__(kSlabThreads) void pool16_nchw_slab_kernel(
                     }
                 }
             } else {
-                for (int y = 0; y < kh; ++y) {
-                    const int r = rb + y;
-                    if (r < 0 || r >= g.H) continue;
-                    for (int x = 0; x < kw; ++x) {
-                        const int q = qb + x;
-                        if (q < 0 || q >= g.W) continue;
-                        acc = Acc<MODE>::op(acc, E::widen(slab[base + r * g.W + q]));
+                // run-time window: the in-image part of the window, loop bounds clipped once (no test per tap)
+                const int r_lo = rb < 0 ? 0 : rb, r_hi = rb + kh < g.H ? rb + kh : g.H;
+                const int q_lo = qb < 0 ? 0 : qb, q_hi = qb + kw < g.W ? qb + kw : g.W;
+                for (int r = r_lo; r < r_hi; ++r) {
+                    const int row = base + r * g.W;
+                    int q = q_lo;
+                    for (; q + 4 <= q_hi; q += 4) {
+                        const float t0 = E::widen(slab[row + q]), t1 = E::widen(slab[row + q + 1]),
+                                    t2 = E::widen(slab[row + q + 2]), t3 = E::widen(slab[row + q + 3]);
+                        acc = Acc<MODE>::op(Acc<MODE>::op(acc, t0), Acc<MODE>::op(t1, Acc<MODE>::op(t2, t3)));
                     }
+                    for (; q < q_hi; ++q) acc = Acc<MODE>::op(acc, E::widen(slab[row + q]));
                 }
             }
             bits[half] = E::narrow(Acc<MODE>::finish(acc, (float)(kh * kw)));
