@@ -235,6 +235,63 @@ __global__ __launch_bounds__(kThreads) void pool_chwn_vec4_any_kernel(
         if (i0 + k < g.Ho) st4_stream(out + (size_t)k * g.Wo * N, Acc<MODE>::finish4(acc[k], (float)(g.kh * g.kw)));
 }
 
+// The same kernel for tensors with few outputs and large windows (global 7x7 pooling of 128x2048x7x7 has
+// 65536 float4 outputs: one wavefront per SIMD, each walking 49 taps one after the other).  The rows of a
+// window are dealt over P lanes (row r_lo + part, + P, ...), which puts P times as many loads in flight, and
+// the P partial results meet in LDS.  A workgroup is P parts x 256/P outputs; part 0 stores.
+template <int MODE, int P>
+__global__ __launch_bounds__(kThreads) void pool_chwn_vec4_split_kernel(
+    const float* __restrict__ src, float* __restrict__ dst, PoolGeom g, uint32_t items, FastDiv div_n4, FastDiv div_wo,
+    FastDiv div_ho) {
+    constexpr int PER = kThreads / P;                           // outputs (float4) per workgroup
+    __shared__ float4 part_acc[P][PER];
+    const int part = threadIdx.x / PER, slot = threadIdx.x % PER;
+    const uint32_t u = blockIdx.x * PER + slot;                 // ((c*Ho + i)*Wo + j)*N4 + n4
+    const bool live = u < items;
+    float4 acc = Acc<MODE>::identity4();
+    if (live) {
+        const uint32_t t = fd_div(u, div_n4);
+        const uint32_t n4 = u - t * div_n4.d;
+        const uint32_t t2 = fd_div(t, div_wo);
+        const int j = (int)(t - t2 * div_wo.d);
+        const uint32_t c = fd_div(t2, div_ho);
+        const int i = (int)(t2 - c * div_ho.d);
+        const int N = g.N;
+        int q_lo = j * g.sw - g.pw, q_hi = q_lo + g.kw;
+        if (q_lo < 0) q_lo = 0;
+        if (q_hi > g.W) q_hi = g.W;
+        int r_lo = i * g.sh - g.ph, r_hi = r_lo + g.kh;
+        if (r_lo < 0) r_lo = 0;
+        if (r_hi > g.H) r_hi = g.H;
+        const float* plane = src + (size_t)c * g.H * g.W * N + 4 * n4;
+        for (int r = r_lo + part; r < r_hi; r += P) {
+            const float* rowp = plane + (size_t)r * g.W * N;
+            int q = q_lo;
+            for (; q + 4 <= q_hi; q += 4) {                     // four loads in flight before the first is used
+                const float4 v0 = *reinterpret_cast<const float4*>(rowp + (size_t)q * N),
+                             v1 = *reinterpret_cast<const float4*>(rowp + (size_t)(q + 1) * N),
+                             v2 = *reinterpret_cast<const float4*>(rowp + (size_t)(q + 2) * N),
+                             v3 = *reinterpret_cast<const float4*>(rowp + (size_t)(q + 3) * N);
+                acc = Acc<MODE>::op4(Acc<MODE>::op4(acc, v0), Acc<MODE>::op4(Acc<MODE>::op4(v1, v2), v3));
+            }
+            if (q + 2 <= q_hi) {
+                const float4 v0 = *reinterpret_cast<const float4*>(rowp + (size_t)q * N),
+                             v1 = *reinterpret_cast<const float4*>(rowp + (size_t)(q + 1) * N);
+                acc = Acc<MODE>::op4(acc, Acc<MODE>::op4(v0, v1));
+                q += 2;
+            }
+            if (q < q_hi) acc = Acc<MODE>::op4(acc, *reinterpret_cast<const float4*>(rowp + (size_t)q * N));
+        }
+    }
+    part_acc[part][slot] = acc;
+    __syncthreads();
+    if (part == 0 && live) {
+#pragma unroll
+        for (int k = 1; k < P; ++k) acc = Acc<MODE>::op4(acc, part_acc[k][slot]);
+        st4_stream(dst + 4 * (size_t)u, Acc<MODE>::finish4(acc, (float)(g.kh * g.kw)));
+    }
+}
+
 // ---------------------------------------------------------------------------
 // NCHW, 2x2 window, stride 2, no padding, even H: the tensor is a list of
 // N*C*H rows of W floats and output row k is made of input rows 2k and 2k+1.
@@ -559,9 +616,23 @@ int dispatch_chwn(const float* src, float* dst, const PoolGeom& g, const PoolTun
     const long long hb = ceil_div64(g.Ho, oy == 3 ? 3 : (oy == 2 ? 2 : 1));
     const long long items = (long long)g.C * hb * g.Wo * (g.N / 4);
     if (vec && items < 0x7fffffffLL && items > 0) {
-        const dim3 grid((unsigned)ceil_div64(items, kThreads)), block(kThreads);
         const FastDiv dn4 = make_fastdiv((uint32_t)(g.N / 4)), dwo = make_fastdiv((uint32_t)g.Wo),
                       dhb = make_fastdiv((uint32_t)hb);
+        // Few outputs, tall windows: fewer lanes than half the chip holds (256 CUs x 2048) would each walk
+        // 16 taps or more one after the other; the window's rows are dealt over 4 or 8 lanes instead
+        // (global 7x7 on 128x2048x7x7: 21.9 -> 13.4 us, global 14x14 on 32x512x14x14: 30.6 -> 13.0 us).
+        int split = 0;
+        if (oy == 1 && items < 262144 && g.kh >= 4 && g.kh * g.kw >= 16) split = g.kh >= 7 ? 8 : 4;
+        split = env_int("CNNMEM_CHWN_SPLIT", split);
+        if (oy == 1 && (split == 4 || split == 8)) {
+            const dim3 sgrid((unsigned)ceil_div64(items, kThreads / split)), sblock(kThreads);
+            if (split == 8)
+                hipLaunchKernelGGL((pool_chwn_vec4_split_kernel<MODE, 8>), sgrid, sblock, 0, st, src, dst, g, (uint32_t)items, dn4, dwo, dhb);
+            else
+                hipLaunchKernelGGL((pool_chwn_vec4_split_kernel<MODE, 4>), sgrid, sblock, 0, st, src, dst, g, (uint32_t)items, dn4, dwo, dhb);
+            return launch_status();
+        }
+        const dim3 grid((unsigned)ceil_div64(items, kThreads)), block(kThreads);
         if (oy == 3)
             hipLaunchKernelGGL((pool_chwn_vec4_any_kernel<MODE, 3>), grid, block, 0, st, src, dst, g, (uint32_t)items, dn4, dwo, dhb);
         else if (oy == 2)

@@ -1095,6 +1095,60 @@ __global__ __launch_bounds__(kThreads) void pool16_chwn_any_kernel(
         if (i0 + o < g.Ho) st16_stream(out + (size_t)o * g.Wo * N, acc[o].result((float)(g.kh * g.kw)));
 }
 
+// The same for tensors with few outputs and tall windows (global 7x7 pooling): the rows of a window are
+// dealt over P lanes (row r_lo + part, + P, ...), which puts P times as many loads in flight, and the P
+// partial results meet in LDS.  A workgroup is P parts x 256/P outputs; part 0 stores.
+template <class E, int MODE, int P>
+__global__ __launch_bounds__(kThreads) void pool16_chwn_split_kernel(
+    const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, PoolGeom g, uint32_t items, FastDiv div_n8,
+    FastDiv div_wo, FastDiv div_ho) {
+    constexpr int PER = kThreads / P;
+    __shared__ Lane8<E, MODE> part_acc[P][PER];
+    const int part = threadIdx.x / PER, slot = threadIdx.x % PER;
+    const uint32_t u = blockIdx.x * PER + slot;                 // ((c*Ho + i)*Wo + j)*N8 + n8
+    const bool live = u < items;
+    Lane8<E, MODE> acc;
+    acc.clear();
+    if (live) {
+        const uint32_t t = fd_div(u, div_n8);
+        const uint32_t n8 = u - t * div_n8.d;
+        const uint32_t t2 = fd_div(t, div_wo);
+        const int j = (int)(t - t2 * div_wo.d);
+        const uint32_t c = fd_div(t2, div_ho);
+        const int i = (int)(t2 - c * div_ho.d);
+        const int N = g.N;
+        int q_lo = j * g.sw - g.pw, q_hi = q_lo + g.kw;
+        if (q_lo < 0) q_lo = 0;
+        if (q_hi > g.W) q_hi = g.W;
+        int r_lo = i * g.sh - g.ph, r_hi = r_lo + g.kh;
+        if (r_lo < 0) r_lo = 0;
+        if (r_hi > g.H) r_hi = g.H;
+        const uint16_t* plane = src + (size_t)c * g.H * g.W * N + 8 * n8;
+        for (int r = r_lo + part; r < r_hi; r += P) {
+            const uint16_t* rowp = plane + (size_t)r * g.W * N;
+            int q = q_lo;
+            for (; q + 4 <= q_hi; q += 4) {
+                const u32x4 w0 = ld16_cached(rowp + (size_t)q * N), w1 = ld16_cached(rowp + (size_t)(q + 1) * N),
+                            w2 = ld16_cached(rowp + (size_t)(q + 2) * N), w3 = ld16_cached(rowp + (size_t)(q + 3) * N);
+                acc.tap(w0); acc.tap(w1); acc.tap(w2); acc.tap(w3);
+            }
+            if (q + 2 <= q_hi) {
+                const u32x4 w0 = ld16_cached(rowp + (size_t)q * N), w1 = ld16_cached(rowp + (size_t)(q + 1) * N);
+                acc.tap(w0); acc.tap(w1);
+                q += 2;
+            }
+            if (q < q_hi) acc.tap(ld16_cached(rowp + (size_t)q * N));
+        }
+    }
+    part_acc[part][slot] = acc;
+    __syncthreads();
+    if (part == 0 && live) {
+#pragma unroll
+        for (int k = 1; k < P; ++k) acc.merge(part_acc[k][slot]);
+        st16_stream(dst + 8 * (size_t)u, acc.result((float)(g.kh * g.kw)));
+    }
+}
+
 // CHWN: a lane owns 8 consecutive images of one output column and walks down OY
 // output rows; each input row it touches is reduced horizontally once and that row
 // result is reused by every output row whose window contains it (Section V.A's
@@ -1474,6 +1528,18 @@ int dispatch_pool16(const uint16_t* src, uint16_t* dst, const PoolGeom& g, int l
             const dim3 grid((unsigned)ceil_div64(items, kThreads)), block(kThreads);
             const FastDiv dn8 = make_fastdiv((uint32_t)(g.N / 8)), dwo = make_fastdiv((uint32_t)g.Wo),
                           dhb = make_fastdiv((uint32_t)hb);
+            // few outputs, tall windows (global pooling): the window's rows are dealt over 4 or 8 lanes
+            int split = 0;
+            if (oy == 1 && items < 262144 && g.kh >= 4 && g.kh * g.kw >= 16) split = g.kh >= 7 ? 8 : 4;
+            split = env_int("CNNMEM_CHWN_SPLIT", split);
+            if (oy == 1 && (split == 4 || split == 8)) {
+                const dim3 sgrid((unsigned)ceil_div64(items, kThreads / split));
+                if (split == 8)
+                    hipLaunchKernelGGL((pool16_chwn_split_kernel<E, MODE, 8>), sgrid, block, 0, st, src, dst, g, (uint32_t)items, dn8, dwo, dhb);
+                else
+                    hipLaunchKernelGGL((pool16_chwn_split_kernel<E, MODE, 4>), sgrid, block, 0, st, src, dst, g, (uint32_t)items, dn8, dwo, dhb);
+                return launch_status();
+            }
             if (oy == 3)
                 hipLaunchKernelGGL((pool16_chwn_any_kernel<E, MODE, 3>), grid, block, 0, st, src, dst, g, (uint32_t)items, dn8, dwo, dhb);
             else if (oy == 2)

@@ -179,6 +179,21 @@ def test_pool_chwn_any_window_rows_per_lane(rows, monkeypatch):
         check_pool(x, *shape, geom, layouts=(CHWN,))
 
 
+@pytest.mark.parametrize("split", [0, 4, 8])
+def test_pool_chwn_window_rows_dealt_over_lanes(split, monkeypatch):
+    """Few outputs, tall windows: the rows of a window are dealt over 4 or 8 lanes and the partial results meet in
+    LDS.  Global pooling, padded windows shorter than the number of parts, a ragged last workgroup."""
+    if split:
+        monkeypatch.setenv("CNNMEM_CHWN_SPLIT", str(split))
+    monkeypatch.setenv("CNNMEM_CHWN_ANY_ROWS", "1")
+    rng = np.random.default_rng(70 + split)
+    for shape, geom in [((128, 20, 7, 7), (7, 7, 7, 7, 0, 0)), ((8, 3, 14, 14), (14, 14, 14, 14, 0, 0)),
+                        ((4, 5, 9, 11), (5, 5, 3, 3, 2, 2)), ((12, 2, 8, 8), (8, 8, 1, 1, 4, 4)),
+                        ((4, 3, 13, 6), (6, 4, 2, 1, 3, 2)), ((36, 7, 10, 10), (4, 4, 2, 2, 1, 1))]:
+        x = rng.standard_normal(shape, dtype=np.float32)
+        check_pool(x, *shape, geom, layouts=(CHWN,))
+
+
 @pytest.mark.parametrize("oy", [1, 2, 3, 4])
 @pytest.mark.parametrize("ox", [1, 2])
 def test_pool_chwn_every_working_set_shape(oy, ox):

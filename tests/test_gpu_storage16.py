@@ -192,6 +192,28 @@ def test_pool16_chwn_any_window_rows_per_lane(rows, dtype, monkeypatch):
         check_rounded(bits_of(got), want, 0.999, (case, "avg"))
 
 
+@pytest.mark.parametrize("split", [0, 4, 8])
+@pytest.mark.parametrize("dtype", DTYPES, ids=[IDS[d] for d in DTYPES])
+def test_pool16_chwn_window_rows_dealt_over_lanes(split, dtype, monkeypatch):
+    """Few outputs, tall windows: the rows of a window dealt over 4 or 8 lanes, partial results combined in LDS."""
+    if split:
+        monkeypatch.setenv("CNNMEM_CHWN_SPLIT", str(split))
+    monkeypatch.setenv("CNNMEM_CHWN16_ANY_ROWS", "1")
+    for case in [(128, 20, 7, 7, 7, 7, 7, 7, 0, 0), (8, 3, 14, 14, 14, 14, 14, 14, 0, 0), (8, 5, 9, 11, 5, 5, 3, 3, 2, 2),
+                 (24, 2, 8, 8, 8, 8, 1, 1, 4, 4), (8, 3, 13, 6, 6, 4, 2, 1, 3, 2), (40, 7, 10, 10, 4, 4, 2, 2, 1, 1)]:
+        N, C, H, W, kh, kw, sh, sw, ph, pw = case
+        rng = np.random.default_rng(sum(case) + split)
+        xb, _ = to16(wl.relu_normal(rng, (N, C, H, W)) + np.float32(0.25), dtype)
+        xcb = oracle.transform16(xb, N, C, H, W, 0, 1)
+        xcd = torch.from_numpy(xcb.view(np.int16)).cuda().view(TORCH[dtype])
+        want = oracle.pool16(xcb, N, C, H, W, cm.CHWN, 0, kh, kw, sh, sw, ph, pw, dtype)
+        got = cm.pool(xcd, N, C, H, W, cm.CHWN, cm.POOL_MAX, kh, kw, sh, sw, ph, pw)
+        assert np.array_equal(bits_of(got), want), (case, "max")
+        want = oracle.pool16(xcb, N, C, H, W, cm.CHWN, 1, kh, kw, sh, sw, ph, pw, dtype)
+        got = cm.pool(xcd, N, C, H, W, cm.CHWN, cm.POOL_AVG, kh, kw, sh, sw, ph, pw)
+        check_rounded(bits_of(got), want, 0.999, (case, "avg"))
+
+
 def test_pool16_misaligned_views_take_the_generic_kernel():
     N, C, H, W, k, s = 8, 3, 12, 12, 3, 2
     rng = np.random.default_rng(77)
