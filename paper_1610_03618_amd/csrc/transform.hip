@@ -225,6 +225,12 @@ int launch_transpose2d(const float* src, float* dst, long long R, long long S, h
             // on 100x64x57x57: 36 -> 65 % and 50 -> 63 % against two 64-wide tiles with the second mostly idle)
             else if (R > 64 && S >= 4 * R) shape = 7;      // few long source rows (NCHW -> CHWN)
             else if (S > 64 && R >= 4 * S) shape = 8;      // many short source rows (CHWN -> NCHW)
+            // 48..64 images: the same one-float-per-access LDS tile as shape 8, 64 wide (CHWN -> NCHW on
+            // 64x256x56x56: 66.6 -> 71.0 % of peak, 64x64x224x224 65.8 -> 68.3 %, 48x128x56x56 61.1 -> 62.8 %;
+            // 40 images lose, 55 x 55 planes are level), and a 128-long tile side along the long source rows
+            // (NCHW -> CHWN: 69.6 -> 70.7 %)
+            else if (S >= 48 && S <= 64 && R >= 4 * S) shape = 10;
+            else if (R == 64 && S >= 4 * R) shape = 6;
             else shape = 0;
         }
         switch (shape) {
