@@ -390,27 +390,46 @@ __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
     const size_t a_last = (total_in - 4) & ~(size_t)3;
     // (a round wholly past the slab is skipped by the whole workgroup: small planes leave most rounds empty)
     float4 v[kSlabVecPerLane];
+    if (a_lo + 4 * (size_t)(nvec - 1) <= a_last) {
+        // Every workgroup but the one at the tensor's end: no float4 of the slab can cross the end, so the
+        // lane's address is a uniform base plus a 32-bit offset and needs no 64-bit clamp (the 64-bit
+        // compares and selects of the general form below were a third of the kernel's vector instructions).
+        const float* sbase = src + a_lo;
 #pragma unroll
-    for (int k = 0; k < kSlabVecPerLane; ++k) {
-        if (k * kSlabThreads >= nvec) break;
-        const int q = threadIdx.x + k * kSlabThreads;
-        size_t a = a_lo + 4 * (size_t)(q < nvec ? q : 0);
-        a = a <= a_last ? a : a_last;
-        v[k] = ld4_stream(src + a);
-    }
+        for (int k = 0; k < kSlabVecPerLane; ++k) {
+            if (k * kSlabThreads >= nvec) break;
+            const uint32_t q = threadIdx.x + k * kSlabThreads;
+            v[k] = ld4_stream(sbase + 4u * (q < (uint32_t)nvec ? q : 0u));
+        }
 #pragma unroll
-    for (int k = 0; k < kSlabVecPerLane; ++k) {
-        const int q = threadIdx.x + k * kSlabThreads;
-        const size_t a = a_lo + 4 * (size_t)q;
-        if (q < nvec && a <= a_last) *reinterpret_cast<float4*>(slab + 4 * q) = v[k];
-    }
+        for (int k = 0; k < kSlabVecPerLane; ++k) {
+            if (k * kSlabThreads >= nvec) break;
+            const uint32_t q = threadIdx.x + k * kSlabThreads;
+            if (q < (uint32_t)nvec) *reinterpret_cast<float4*>(slab + 4 * q) = v[k];
+        }
+    } else {
 #pragma unroll
-    for (int k = 0; k < kSlabVecPerLane; ++k) {
-        const int q = threadIdx.x + k * kSlabThreads;
-        const size_t a = a_lo + 4 * (size_t)q;
-        if (q < nvec && a > a_last) {               // ragged end of the tensor (at most one lane, once)
-            for (int j = 0; j < 4; ++j)
-                if (a + j < total_in) slab[4 * q + j] = src[a + j];
+        for (int k = 0; k < kSlabVecPerLane; ++k) {
+            if (k * kSlabThreads >= nvec) break;
+            const int q = threadIdx.x + k * kSlabThreads;
+            size_t a = a_lo + 4 * (size_t)(q < nvec ? q : 0);
+            a = a <= a_last ? a : a_last;
+            v[k] = ld4_stream(src + a);
+        }
+#pragma unroll
+        for (int k = 0; k < kSlabVecPerLane; ++k) {
+            if (k * kSlabThreads >= nvec) break;
+            const int q = threadIdx.x + k * kSlabThreads;
+            const size_t a = a_lo + 4 * (size_t)q;
+            if (q < nvec && a <= a_last) *reinterpret_cast<float4*>(slab + 4 * q) = v[k];
+        }
+        for (int k = 0; k < kSlabVecPerLane; ++k) {
+            const int q = threadIdx.x + k * kSlabThreads;
+            const size_t a = a_lo + 4 * (size_t)q;
+            if (q < nvec && a > a_last) {           // ragged end of the tensor (at most one lane, once)
+                for (int j = 0; j < 4; ++j)
+                    if (a + j < total_in) slab[4 * q + j] = src[a + j];
+            }
         }
     }
     __syncthreads();

@@ -1291,27 +1291,45 @@ __global__ __launch_bounds__(kSlabThreads) void pool16_nchw_slab_kernel(
     // cross its end, re-read the last complete vector (total_in >= 8 is a dispatch condition)
     const size_t a_last = (total_in - 8) & ~(size_t)7;
     u32x4 v[VEC];
+    if (a_lo + 8 * (size_t)(nvec - 1) <= a_last) {
+        // every workgroup but the one at the tensor's end: no vector of the slab can cross the end, so a
+        // lane's address is a uniform base plus a 32-bit offset, without the 64-bit clamp of the general form
+        const uint16_t* sbase = src + a_lo;
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) {
-        if (k * kSlabThreads >= nvec) break;        // uniform: small planes leave most rounds empty
-        const int q = threadIdx.x + k * kSlabThreads;
-        size_t a = a_lo + 8 * (size_t)(q < nvec ? q : 0);
-        a = a <= a_last ? a : a_last;
-        v[k] = ld16_stream(src + a);
-    }
+        for (int k = 0; k < VEC; ++k) {
+            if (k * kSlabThreads >= nvec) break;    // uniform: small planes leave most rounds empty
+            const uint32_t q = threadIdx.x + k * kSlabThreads;
+            v[k] = ld16_stream(sbase + 8u * (q < (uint32_t)nvec ? q : 0u));
+        }
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) {
-        const int q = threadIdx.x + k * kSlabThreads;
-        const size_t a = a_lo + 8 * (size_t)q;
-        if (q < nvec && a <= a_last) *reinterpret_cast<u32x4*>(slab + 8 * q) = v[k];
-    }
+        for (int k = 0; k < VEC; ++k) {
+            if (k * kSlabThreads >= nvec) break;
+            const uint32_t q = threadIdx.x + k * kSlabThreads;
+            if (q < (uint32_t)nvec) *reinterpret_cast<u32x4*>(slab + 8 * q) = v[k];
+        }
+    } else {
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) {
-        const int q = threadIdx.x + k * kSlabThreads;
-        const size_t a = a_lo + 8 * (size_t)q;
-        if (q < nvec && a > a_last) {               // ragged end of the tensor (at most one lane, once)
-            for (int j = 0; j < 8; ++j)
-                if (a + j < total_in) slab[8 * q + j] = src[a + j];
+        for (int k = 0; k < VEC; ++k) {
+            if (k * kSlabThreads >= nvec) break;
+            const int q = threadIdx.x + k * kSlabThreads;
+            size_t a = a_lo + 8 * (size_t)(q < nvec ? q : 0);
+            a = a <= a_last ? a : a_last;
+            v[k] = ld16_stream(src + a);
+        }
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            if (k * kSlabThreads >= nvec) break;
+            const int q = threadIdx.x + k * kSlabThreads;
+            const size_t a = a_lo + 8 * (size_t)q;
+            if (q < nvec && a <= a_last) *reinterpret_cast<u32x4*>(slab + 8 * q) = v[k];
+        }
+        for (int k = 0; k < VEC; ++k) {
+            const int q = threadIdx.x + k * kSlabThreads;
+            const size_t a = a_lo + 8 * (size_t)q;
+            if (q < nvec && a > a_last) {           // ragged end of the tensor (at most one lane, once)
+                for (int j = 0; j < 8; ++j)
+                    if (a + j < total_in) slab[8 * q + j] = src[a + j];
+            }
         }
     }
     __syncthreads();
@@ -1336,15 +1354,21 @@ __global__ __launch_bounds__(kSlabThreads) void pool16_nchw_slab_kernel(
             const int base = lds0 + pl * plane_in;
             // Rows and columns are clamped into the slab.  A clamped tap of a real output lies in the same
             // window (the maximum is unchanged, the average drops it by a select); rows and columns of
-            // outputs past the strip's or the row's end only feed results that are never stored.
+            // outputs past the strip's or the row's end only feed results that are never stored.  Without
+            // padding the columns of a real output need no clamp, and those of the missing second output of
+            // a ragged pair run at most SW words past the row (the slab array has 16 spare words): the
+            // taps of a row are then at constant offsets from one address.
             int qc[COLS];
             bool q_in[COLS];
 #pragma unroll
             for (int x = 0; x < COLS; ++x) {
                 const int q = qb + x;
                 q_in[x] = !PADDED || (q >= 0 && q < g.W);
-                int c = q < g.W ? q : g.W - 1;
-                if (PADDED) c = c > 0 ? c : 0;
+                int c = q;
+                if (PADDED) {
+                    c = q < g.W ? q : g.W - 1;
+                    c = c > 0 ? c : 0;
+                }
                 qc[x] = c;
             }
             float hr[2][ROWS];
