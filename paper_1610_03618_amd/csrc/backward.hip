@@ -460,6 +460,24 @@ __device__ __forceinline__ size_t stream_to_lds(const float* __restrict__ p, siz
     // rounds of kBwdThreads vectors; a round past the end of the part is skipped by the whole
     // workgroup (uniform), inside a round every load is unconditional
     float4 v[VEC];
+    if (a_lo + 4 * (size_t)(nvec - 1) <= a_last) {
+        // every workgroup but the one at the tensor's end: no float4 can cross the end; uniform base plus a
+        // 32-bit lane offset instead of 64-bit compares and selects per load
+        const float* base = p + a_lo;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            if (k * kBwdThreads >= nvec) break;
+            const uint32_t q = threadIdx.x + k * kBwdThreads;
+            v[k] = ld4_stream(base + 4u * (q < (uint32_t)nvec ? q : 0u));
+        }
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            if (k * kBwdThreads >= nvec) break;
+            const uint32_t q = threadIdx.x + k * kBwdThreads;
+            if (q < (uint32_t)nvec) *reinterpret_cast<float4*>(dst_lds + 4 * q) = v[k];
+        }
+        return a_lo;
+    }
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
         if (k * kBwdThreads >= nvec) break;
@@ -468,7 +486,6 @@ __device__ __forceinline__ size_t stream_to_lds(const float* __restrict__ p, siz
         a = a <= a_last ? a : a_last;
         v[k] = ld4_stream(p + a);
     }
-#pragma unroll
     for (int k = 0; k < VEC; ++k) {
         if (k * kBwdThreads >= nvec) break;
         const int q = threadIdx.x + k * kBwdThreads;
