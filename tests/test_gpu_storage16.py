@@ -145,7 +145,7 @@ def test_pool16_max_orders_every_finite_pattern(dtype):
     xd = torch.from_numpy(bits.view(np.int16)).cuda().view(TORCH[dtype])
     xcb = oracle.transform16(bits, N, C, H, W, 0, 1)
     xcd = cm.transform(xd, N, C, H, W, cm.NCHW, cm.CHWN)
-    for (k, s) in [(2, 2), (3, 2), (3, 1)]:
+    for (k, s) in [(2, 2), (3, 2), (3, 1), (5, 3), (4, 2), (24, 24)]:      # the last three: run-time-window kernels
         for layout, hb, dev in ((cm.NCHW, bits, xd), (cm.CHWN, xcb, xcd)):
             want = oracle.pool16(hb, N, C, H, W, layout, 0, k, k, s, s, 0, 0, dtype)
             got = cm.pool(dev, N, C, H, W, layout, cm.POOL_MAX, k, k, s, s)
