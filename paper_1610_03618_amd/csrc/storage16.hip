@@ -1371,6 +1371,50 @@ __global__ __launch_bounds__(kSlabThreads) void pool16_nchw_slab_kernel(
                 }
                 qc[x] = c;
             }
+            const size_t o_first = out0 + (size_t)(pl * rows_out + il0) * g.Wo + j;
+            if constexpr (MODE == CNNMEM_POOL_MAX && E::kPairMax) {
+                // binary16 maximum: the taps of the two outputs are paired in one register (tap x of the
+                // left output with tap x of the right one, SW columns on) and reduced with the packed
+                // maximum, so a row costs 2 KW - 1 instructions instead of COLS widenings and 2 (KW - 1)
+                // maxima, and the result already is the dword to store.  Clamped taps repeat a tap of the
+                // same window, which a maximum ignores.
+                uint32_t hp[ROWS];
+#pragma unroll
+                for (int y = 0; y < ROWS; ++y) {
+                    const int r = rb + y;
+                    int rc = r < r_last ? r : r_last;
+                    if (PADDED) rc = rc > r_lo ? rc : r_lo;
+                    // Odd columns are read through a second index the compiler cannot relate to the first:
+                    // left alone it fuses neighbouring words into 64-bit LDS reads at 2-byte alignment, which
+                    // ran a quarter slower than five 16-bit reads.
+                    const int row = base + rc * g.W;
+                    int row_odd = row + 1;
+                    if (!PADDED) asm("" : "+v"(row_odd));      // clamped columns are not fused anyway
+                    uint32_t t[COLS];
+#pragma unroll
+                    for (int x = 0; x < COLS; ++x) t[x] = (x & 1) ? slab[row_odd + qc[x] - 1] : slab[row + qc[x]];
+                    uint32_t acc = t[0] | (t[SW] << 16);
+#pragma unroll
+                    for (int x = 1; x < KW; ++x) acc = E::max2(acc, t[x] | (t[SW + x] << 16));
+                    hp[y] = acc;
+                }
+#pragma unroll
+                for (int k = 0; k < OY; ++k) {
+                    uint32_t pair = hp[k * SH];
+#pragma unroll
+                    for (int y = 1; y < KH; ++y) pair = E::max2(pair, hp[k * SH + y]);
+                    if (il0 + k >= rows_out) continue;
+                    const size_t a = o_first + (size_t)k * g.Wo;
+                    const bool second = j + 1 < g.Wo;
+                    if (second && ((dst_word + a) & 1) == 0) {
+                        *reinterpret_cast<uint32_t*>(dst + a) = pair;
+                    } else {
+                        dst[a] = (uint16_t)pair;
+                        if (second) dst[a + 1] = (uint16_t)(pair >> 16);
+                    }
+                }
+                continue;
+            }
             float hr[2][ROWS];
 #pragma unroll
             for (int y = 0; y < ROWS; ++y) {
@@ -1393,7 +1437,6 @@ __global__ __launch_bounds__(kSlabThreads) void pool16_nchw_slab_kernel(
                     hr[h][y] = acc;
                 }
             }
-            const size_t o_first = out0 + (size_t)(pl * rows_out + il0) * g.Wo + j;
 #pragma unroll
             for (int k = 0; k < OY; ++k) {
                 float a0 = hr[0][k * SH], a1 = hr[1][k * SH];
