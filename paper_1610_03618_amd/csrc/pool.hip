@@ -141,7 +141,7 @@ __global__ __launch_bounds__(kThreads) void pool_chwn_vec4_kernel(
     constexpr bool kStream = (KH <= SH) && (KW <= SW);
     // Every load is unconditional (a branch per row would make the compiler wait
     // for each row before asking for the next): taps outside the image are read
-    // from a clamped, valid address and replaced by the identity.  Without padding
+    // from a clamped, valid address.  Without padding
     // the only rows past H and columns past W belong to outputs beyond Ho x Wo,
     // which are never stored, so clamping alone is enough there.
 #pragma unroll
@@ -160,7 +160,17 @@ __global__ __launch_bounds__(kThreads) void pool_chwn_vec4_kernel(
             const int qc = q < 0 ? 0 : (q < g.W ? q : g.W - 1);
             float4 t = kStream ? ld4_stream(rowp + (size_t)qc * N)
                                : *reinterpret_cast<const float4*>(rowp + (size_t)qc * N);
-            if (PADDED && !ok) t = Acc<MODE>::identity4();
+            // A tap in the padding was read from the nearest in-image position, which lies in every window
+            // that holds the tap: the maximum needs nothing more.  The average clears it with a bit mask,
+            // not with `if (!ok) t = 0`: the compiler turns that into a branch around the load and waits for
+            // each load before issuing the next (3x3/s2/p1 had 53 branches and one load in flight).
+            if (PADDED && MODE != CNNMEM_POOL_MAX) {
+                const uint32_t keep = ok ? 0xffffffffu : 0u;
+                t.x = __uint_as_float(__float_as_uint(t.x) & keep);
+                t.y = __uint_as_float(__float_as_uint(t.y) & keep);
+                t.z = __uint_as_float(__float_as_uint(t.z) & keep);
+                t.w = __uint_as_float(__float_as_uint(t.w) & keep);
+            }
 #pragma unroll
             for (int ox = 0; ox < OX; ++ox)
                 if (x >= ox * SW && x < ox * SW + KW) h[ox] = Acc<MODE>::op4(h[ox], t);
@@ -573,12 +583,10 @@ int launch_chwn_vec4(const float* src, float* dst, const PoolGeom& g, const Pool
     const long long in_bytes = 4LL * g.N * g.C * g.H * g.W;
     int cap = light || tune.workgroups_per_cu != 0 ? tune.workgroups_per_cu : -1;
     if (!light && tune.workgroups_per_cu == 0) {
-        // Overlapping windows: a lane has 9 (one output) to 15 (two padded rows) 128-bit loads in flight.  Four
+        // Overlapping windows: a lane has 9 (one output) to 15 (two rows) 128-bit loads in flight.  Four
         // resident workgroups per CU measured 1-2 points above the full eight from 96 MB of input up
-        // (128x96x55x55: 66.7 -> 68.3 % of peak, 512x96x55x55: 71.9 -> 73.7 %), three for the two-row blocks on
-        // large tensors (256x64x112x112 p1: 72.0 -> 73.8 %).
+        // (128x96x55x55: 66.7 -> 68.3 % of peak, 512x96x55x55: 71.9 -> 73.7 %); two-row blocks are best uncapped.
         if (OY * OX == 1 && in_bytes >= (64LL << 20)) cap = 4;
-        else if (OY * OX == 2 && in_bytes >= (384LL << 20)) cap = 3;
         else if (OY * OX >= 3 && in_bytes >= (64LL << 20)) cap = 5;    // 3x3/s1, four rows: 59.8 -> 62.2 % at 206 MB
     }
     const size_t lds = throttle_lds(cap, in_bytes, 4);
@@ -614,9 +622,9 @@ int dispatch_chwn(const float* src, float* dst, const PoolGeom& g, const PoolTun
         // Outputs per lane along H.  More rows per lane reuse row results (7 input rows feed 3 outputs
         // instead of 9) but put 21 loads and 3 stores in one lane.  Measured on MI355X with write-through
         // stores, 128x96x55x55: 67.1 % of peak with one row, 64.7 % with two, 63.9 % with three (three was the
-        // best before the stores were write-through); with padding (256x64x112x112, p1) two rows win: 72.1 %
-        // against 70.0 % and 71.4 %.
-        const int rows = g.ph > 0 || g.pw > 0 ? 2 : 1;
+        // best before the stores were write-through).  The same holds with padding since the padded taps
+        // stopped being branches (256x64x112x112 p1: 74.2 % with one row, 71.8 % with two, 71.4 % with three).
+        const int rows = 1;
         rc = launch_chwn_window<MODE, 3, 3, 2, 2>(tune.rows_per_lane ? tune.rows_per_lane : env_int("CNNMEM_CHWN_ROWS", rows), ox, src, dst, g, tune, st);
     } else if (vec && g.kh == 2 && g.kw == 2 && g.sh == 2 && g.sw == 2) {
         // disjoint windows: nothing to reuse, one output per lane is fastest
