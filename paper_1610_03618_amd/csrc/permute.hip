@@ -117,11 +117,20 @@ __global__ __launch_bounds__(THREADS) void permute_tile_kernel(
         }
     }
     __syncthreads();
+    // every LDS read first, then the stores (the branches of the ragged end would keep read, wait and store of
+    // each iteration together)
+    constexpr int STORE_ITERS = (TS * NBR) / THREADS;
+    float4 ov[STORE_ITERS];
 #pragma unroll
-    for (int it = 0; it < (TS * NBR) / THREADS; ++it) {
+    for (int it = 0; it < STORE_ITERS; ++it) {
+        const int f = tid + it * THREADS;
+        ov[it] = *reinterpret_cast<const float4*>(tile + lds_row<TS>(f / NBR) * P + 4 * (f % NBR));
+    }
+#pragma unroll
+    for (int it = 0; it < STORE_ITERS; ++it) {
         const int f = tid + it * THREADS;
         const int br = f % NBR, sl = f / NBR;
-        const float4 o = *reinterpret_cast<const float4*>(tile + lds_row<TS>(sl) * P + 4 * br);
+        const float4 o = ov[it];
         const long long s = s0 + sl, r = r0 + 4 * br;
         if (s < p.S) {
             float* q = dst + (size_t)s * (size_t)p.ds_s + (size_t)r;

@@ -241,13 +241,20 @@ __global__ __launch_bounds__(kThreads) void transpose16_kernel(
         }
     }
     __syncthreads();
+    // every LDS read first, then the stores: the branches of the ragged end otherwise keep each iteration's
+    // read, wait and store in a block of their own, STORES LDS round trips in a row
+    u32x4 ov[STORES];
+#pragma unroll
+    for (int it = 0; it < STORES; ++it) {
+        const int f = tid + it * kThreads;
+        const uint32_t* t = tile + (f / NB8) * PD + 4 * (f % NB8);
+        ov[it].x = t[0]; ov[it].y = t[1]; ov[it].z = t[2]; ov[it].w = t[3];
+    }
 #pragma unroll
     for (int it = 0; it < STORES; ++it) {
         const int f = tid + it * kThreads;
         const int b8 = f % NB8, sl = f / NB8;
-        const uint32_t* t = tile + sl * PD + 4 * b8;
-        u32x4 o;
-        o.x = t[0]; o.y = t[1]; o.z = t[2]; o.w = t[3];
+        const u32x4 o = ov[it];
         const long long s = s0 + sl, r = r0 + 8 * b8;
         if (s < S) {
             uint16_t* q = dst + (size_t)s * (size_t)R + (size_t)r;
@@ -312,12 +319,20 @@ __global__ __launch_bounds__(kThreads) void transpose16_block_kernel(
         tile[row * PV + slot] = o;
     }
     __syncthreads();
-    // TS destination rows x NB8 vectors = TS * NB8 = 8 * kThreads stores
+    // TS destination rows x NB8 vectors = TS * NB8 = 8 * kThreads stores; every LDS read first (the branches
+    // of the store paths would otherwise keep read, wait and store of each iteration together)
+    u32x4 ov[8];
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+        const int f = tid + it * kThreads;
+        const int sl = f / NB8;
+        ov[it] = tile[((sl & 7) * NC8 + (sl >> 3)) * PV + f % NB8];
+    }
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
         const int f = tid + it * kThreads;
         const int b8 = f % NB8, sl = f / NB8;
-        const u32x4 o = tile[((sl & 7) * NC8 + (sl >> 3)) * PV + b8];
+        const u32x4 o = ov[it];
         const long long sd = s0 + sl, r = r0 + 8 * b8;
         if (sd < S) {
             uint16_t* q = dst + (size_t)sd * (size_t)R + (size_t)r;
@@ -719,13 +734,18 @@ __global__ __launch_bounds__(kThreads) void permute16_tile_kernel(
         }
     }
     __syncthreads();
+    u32x4 ov[STORES];                               // every LDS read first, then the stores (see transpose16_kernel)
+#pragma unroll
+    for (int it = 0; it < STORES; ++it) {
+        const int f = tid + it * kThreads;
+        const uint32_t* t = tile + (f / NB8) * PD + 4 * (f % NB8);
+        ov[it].x = t[0]; ov[it].y = t[1]; ov[it].z = t[2]; ov[it].w = t[3];
+    }
 #pragma unroll
     for (int it = 0; it < STORES; ++it) {
         const int f = tid + it * kThreads;
         const int b8 = f % NB8, sl = f / NB8;
-        const uint32_t* t = tile + sl * PD + 4 * b8;
-        u32x4 o;
-        o.x = t[0]; o.y = t[1]; o.z = t[2]; o.w = t[3];
+        const u32x4 o = ov[it];
         const long long s = s0 + sl, r = r0 + 8 * b8;
         if (s < p.S) {
             uint16_t* q = dst + (size_t)s * (size_t)p.ds_s + (size_t)r;

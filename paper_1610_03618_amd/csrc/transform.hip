@@ -80,16 +80,23 @@ __global__ __launch_bounds__(THREADS) void transpose_vec4_kernel(
         *reinterpret_cast<float4*>(base + lds_row<TS>(4 * bs + 3) * P) = make_float4(a.w, bq.w, c.w, d.w);
     }
     __syncthreads();
+    // every LDS read first, then the stores: the compiler keeps LDS reads behind the inline-asm store that
+    // precedes them in program order, so read / wait / store would repeat STORE_ITERS times
+    float4 o[STORE_ITERS];
+#pragma unroll
+    for (int it = 0; it < STORE_ITERS; ++it) {
+        const int f = tid + it * THREADS;
+        o[it] = *reinterpret_cast<const float4*>(tile + lds_row<TS>(f / NBR) * P + 4 * (f % NBR));
+    }
 #pragma unroll
     for (int it = 0; it < STORE_ITERS; ++it) {
         const int f = tid + it * THREADS;
         const int br = f % NBR;
         const int sl = f / NBR;
-        const float4 o = *reinterpret_cast<const float4*>(tile + lds_row<TS>(sl) * P + 4 * br);
         const long long s = s0 + sl;
         const long long r = r0 + 4 * br;
         if (s < S && r < R)
-            st4_through(dst + (size_t)s * (size_t)R + (size_t)r, o);
+            st4_through(dst + (size_t)s * (size_t)R + (size_t)r, o[it]);
     }
 }
 
