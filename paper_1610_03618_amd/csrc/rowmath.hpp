@@ -40,13 +40,15 @@ __device__ __forceinline__ float wave_reduce(float v) {
 }
 
 // Reduction over the TPR lanes that share a row.  `slots` has one float per
-// wavefront of the workgroup; `first_wave` is the row's first wavefront.
-template <class Op, int TPR>
+// wavefront of the workgroup; `first_wave` is the row's first wavefront.  FRESH: nothing has used `slots`
+// before in this kernel (each reduction has an array of its own), which saves the barrier that otherwise
+// separates this use from the previous one: two barriers per row instead of four.
+template <class Op, int TPR, bool FRESH = false>
 __device__ __forceinline__ float row_reduce(float v, float* slots, int wave, int first_wave) {
     v = wave_reduce<Op>(v);
     if constexpr (TPR > kWave) {
         constexpr int WAVES = TPR / kWave;
-        __syncthreads();                            // previous use of slots is over
+        if constexpr (!FRESH) __syncthreads();      // previous use of slots is over
         if ((threadIdx.x & (kWave - 1)) == 0) slots[wave] = v;
         __syncthreads();
         float r = slots[first_wave];

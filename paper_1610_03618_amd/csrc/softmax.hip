@@ -39,7 +39,7 @@ __global__ __launch_bounds__(TPR < 256 ? 256 : TPR) void softmax_rows_kernel(
     const float* logits, float* probs, int N, int classes, int base_mis, int align) {
     constexpr int BLOCK = TPR < 256 ? 256 : TPR;
     constexpr int ROWS = BLOCK / TPR;
-    __shared__ float slots[BLOCK / kWave];
+    __shared__ float slots[BLOCK / kWave], slots_sum[BLOCK / kWave];
 
     const int tid = threadIdx.x;
     const int wave = tid / kWave;
@@ -80,7 +80,7 @@ __global__ __launch_bounds__(TPR < 256 ? 256 : TPR) void softmax_rows_kernel(
         if (lane + k * TPR >= nbody) v[k] = make_float4(kNegInf, kNegInf, kNegInf, kNegInf);
         m = fmaxf(fmaxf(m, fmaxf(v[k].x, v[k].y)), fmaxf(v[k].z, v[k].w));
     }
-    m = row_reduce<MaxOp, TPR>(m, slots, wave, first_wave);
+    m = row_reduce<MaxOp, TPR, true>(m, slots, wave, first_wave);
 
     // steps 2-4: shift, exponentiate, sum (masked slots hold -inf and give 0)
     e = exp_nonpos(e - m);
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(TPR < 256 ? 256 : TPR) void softmax_rows_kernel(
         v[k].w = exp_nonpos(v[k].w - m);
         s += (v[k].x + v[k].y) + (v[k].z + v[k].w);
     }
-    s = row_reduce<SumOp, TPR>(s, slots, wave, first_wave);
+    s = row_reduce<SumOp, TPR, true>(s, slots_sum, wave, first_wave);
 
     // step 5: normalise
     const float inv = 1.0f / s;
