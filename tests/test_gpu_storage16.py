@@ -152,6 +152,29 @@ def test_pool16_max_orders_every_finite_pattern(dtype):
             assert np.array_equal(bits_of(got), want), (k, s, layout)
 
 
+@pytest.mark.parametrize("dtype", DTYPES, ids=[IDS[d] for d in DTYPES])
+def test_pool16_average_of_infinities_and_exact_ties(dtype):
+    """The average divides by a reciprocal with one residual step and a fix-up: windows that hold an infinity give
+    that infinity, and window sums that are exact multiples of the area (averages exactly representable, many of
+    them on rounding ties of the storage format) come out bit-exact."""
+    rng = np.random.default_rng(77)
+    N, C, H, W = 8, 4, 21, 23
+    small = rng.integers(0, 64, size=(N, C, H, W)).astype(np.float32) / np.float32(8.0)    # multiples of 1/8
+    xb, _ = to16(small, dtype)
+    inf16 = np.uint16(0x7c00 if dtype == cm.F16 else 0x7f80)
+    xb = xb.copy()
+    xb[0, 0, 3, 4] = inf16
+    xb[1, 2, 10, 11] = inf16 | np.uint16(0x8000)
+    xd = torch.from_numpy(xb.view(np.int16)).cuda().view(TORCH[dtype])
+    xcb = oracle.transform16(xb, N, C, H, W, 0, 1)
+    xcd = torch.from_numpy(xcb.view(np.int16)).cuda().view(TORCH[dtype])
+    for (kh, kw, s, p) in [(3, 3, 2, 0), (3, 3, 1, 1), (5, 3, 2, 1), (2, 2, 2, 0), (21, 23, 21, 0)]:
+        for layout, hb, dev in ((cm.NCHW, xb, xd), (cm.CHWN, xcb, xcd)):
+            want = oracle.pool16(hb, N, C, H, W, layout, 1, kh, kw, s, s, p, p, dtype)
+            got = bits_of(cm.pool(dev, N, C, H, W, layout, cm.POOL_AVG, kh, kw, s, s, p, p))
+            assert np.array_equal(got, want), (kh, kw, s, p, layout, int((got != want).sum()))
+
+
 @pytest.mark.parametrize("rows", [0, 1, 2, 3, 4])
 @pytest.mark.parametrize("dtype", DTYPES, ids=[IDS[d] for d in DTYPES])
 def test_pool16_nchw_slab_rows_per_lane(rows, dtype, monkeypatch):
