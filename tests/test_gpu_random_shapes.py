@@ -96,6 +96,58 @@ def test_pool_forward_and_backward(seed):
                 assert np.all(np.abs(got - want) <= bound), (what, layout, mode, float(np.abs(got - want).max()))
 
 
+@pytest.mark.parametrize("seed", SEEDS[:8])
+def test_pool_rectangular_windows(seed):
+    """Windows up to 7 x 7 with different extents, strides and padding per axis (the run-time-window kernels: several
+    output rows per lane, window rows dealt over lanes, clipped loops), fp32 and fp16, forward and backward."""
+    rng = np.random.default_rng(5000 + seed)
+    for trial in range(3):
+        N, C, H, W = draw_tensor(rng, big=False)
+        for _ in range(100):
+            kh, kw = int(rng.integers(1, 8)), int(rng.integers(1, 8))
+            sh, sw = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+            ph, pw = int(rng.integers(0, kh // 2 + 1)), int(rng.integers(0, kw // 2 + 1))
+            if H + 2 * ph >= kh and W + 2 * pw >= kw and (kh, kw) != (sh, sw):
+                break
+        else:
+            kh = kw = sh = sw = 1
+            ph = pw = 0
+        what = (N, C, H, W, kh, kw, sh, sw, ph, pw)
+        Ho, Wo = oracle.pool_out_dims(H, W, kh, kw, sh, sw, ph, pw)
+        x = wl.relu_normal(rng, (N, C, H, W)) + np.float32(0.25)
+        dy = rng.standard_normal((N, C, Ho, Wo), dtype=np.float32)
+        xc = oracle.transform(x, N, C, H, W, 0, 1)
+        dyc = oracle.transform(dy, N, C, Ho, Wo, 0, 1)
+        tol = 1e-6 * oracle.pool(np.abs(x), N, C, H, W, 0, 1, kh, kw, sh, sw, ph, pw).astype(np.float64)
+        tolc = oracle.transform(tol.astype(np.float32), N, C, Ho, Wo, 0, 1).astype(np.float64) * (1 + 1e-6)
+        xh = torch.from_numpy(x).cuda().half()
+        xhb = xh.view(torch.int16).cpu().numpy().view(np.uint16)
+        xhc = cm.transform(xh, N, C, H, W, cm.NCHW, cm.CHWN)
+        xhcb = oracle.transform16(xhb, N, C, H, W, 0, 1)
+        for layout, hx, hdy, t, d16, b16 in ((cm.NCHW, x, dy, tol, xh, xhb), (cm.CHWN, xc, dyc, tolc, xhc, xhcb)):
+            dx = torch.from_numpy(hx).cuda()
+            want = oracle.pool(hx, N, C, H, W, layout, 0, kh, kw, sh, sw, ph, pw)
+            got = cm.pool(dx, N, C, H, W, layout, cm.POOL_MAX, kh, kw, sh, sw, ph, pw).cpu().numpy()
+            assert np.array_equal(bits32(got), bits32(want)), (what, layout, "max")
+            want = oracle.pool(hx, N, C, H, W, layout, 1, kh, kw, sh, sw, ph, pw)
+            got = cm.pool(dx, N, C, H, W, layout, cm.POOL_AVG, kh, kw, sh, sw, ph, pw).cpu().numpy()
+            err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+            assert np.all(err <= t + 1e-45), (what, layout, "avg", float(err.max()))
+            want = oracle.pool16(b16, N, C, H, W, layout, 0, kh, kw, sh, sw, ph, pw, cm.F16)
+            out = cm.pool(d16, N, C, H, W, layout, cm.POOL_MAX, kh, kw, sh, sw, ph, pw)
+            assert np.array_equal(out.view(torch.int16).cpu().numpy().view(np.uint16), want), (what, layout, "max16")
+            want = oracle.pool16(b16, N, C, H, W, layout, 1, kh, kw, sh, sw, ph, pw, cm.F16)
+            out = cm.pool(d16, N, C, H, W, layout, cm.POOL_AVG, kh, kw, sh, sw, ph, pw)
+            dist = ulp16(out.view(torch.int16).cpu().numpy().view(np.uint16), want)
+            assert dist.max() <= 1, (what, layout, "avg16", int(dist.max()))
+            for mode in (cm.POOL_MAX, cm.POOL_AVG):
+                want = oracle.pool_backward(hx, hdy, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw).astype(np.float64)
+                bound = 1e-6 * oracle.pool_backward(hx, np.abs(hdy), N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw) + 1e-30
+                got = cm.pool_backward(dx if mode == cm.POOL_MAX else None, torch.from_numpy(hdy).cuda(),
+                                       N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw).cpu().numpy().astype(np.float64)
+                assert np.all(np.abs(got - want) <= bound), (what, layout, mode, float(np.abs(got - want).max()))
+
+
 @pytest.mark.parametrize("seed", SEEDS)
 def test_softmax_forward_and_backward(seed):
     rng = np.random.default_rng(3000 + seed)
