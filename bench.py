@@ -688,6 +688,14 @@ def main():
             t = sum(k["avg_ms"] for k in ks) * 1e-3
             per_kind[kind] = {"achieved": round(b / t / 1e9, 1), "frac": round(b / t / 1e9 / rl.PEAK_HBM_GBPS, 4)}
 
+    per_kind_b2b = {}
+    for kind in ("transform", "pool", "softmax"):
+        ks = [k for k in kernels if k["kind"] == kind and "back_to_back_ms" in k]
+        if ks:
+            b = sum(k["alg_bytes"] for k in ks)
+            t = sum(k["back_to_back_ms"] for k in ks) * 1e-3
+            per_kind_b2b[kind] = {"achieved": round(b / t / 1e9, 1), "frac": round(b / t / 1e9 / rl.PEAK_HBM_GBPS, 4)}
+
     out = {
         "metric": "achieved HBM GB/s (and % of peak) per layer: transform, pool, softmax",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -698,6 +706,7 @@ def main():
                    "launches_per_step": len(ops), "alg_bytes_per_step": step_bytes,
                    "cache_control": "rotating buffer sets, each larger than the 256 MB last-level cache"},
         "per_layer": per_kind,
+        "per_layer_back_to_back": per_kind_b2b,
         "roofline": roofline,
         "kernels": kernels,
     }
