@@ -171,7 +171,7 @@ CNNMEM_API int cnnmem_pool(const float *src, float *dst, int N, int C, int H, in
  * serves the call are ignored.  Results never depend on the tuning.
  */
 typedef struct cnnmem_pool_tuning {
-    int rows_per_lane;     /* CHWN: output rows per lane, 1..4                              */
+    int rows_per_lane;     /* CHWN: output rows per lane, 1..4 (run-time windows: at most 3) */
     int cols_per_lane;     /* CHWN: output columns per lane, 1..2                           */
     int workgroups_per_cu; /* cap on resident 256-lane workgroups per CU, 2..8; -1 = no cap */
     int nchw_kernel;       /* NCHW: 1 = row-pair kernel where it applies, 2 = LDS-slab kernel */

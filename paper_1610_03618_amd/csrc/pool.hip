@@ -639,7 +639,9 @@ int dispatch_chwn(const float* src, float* dst, const PoolGeom& g, const PoolTun
     int rows = 1;
     if (g.Ho >= 3 && g.kh > 2 * g.sh) rows = 3;
     else if (g.Ho >= 2 && g.kh > g.sh && g.kh < 2 * g.sh) rows = 2;
-    const int oy = env_int("CNNMEM_CHWN_ANY_ROWS", rows);
+    // the caller's tuning (the auto-tuner's search over outputs per lane along H) reaches this kernel too
+    const int oy = tune.rows_per_lane ? (tune.rows_per_lane > 3 ? 3 : tune.rows_per_lane)
+                                      : env_int("CNNMEM_CHWN_ANY_ROWS", rows);
     const long long hb = ceil_div64(g.Ho, oy == 3 ? 3 : (oy == 2 ? 2 : 1));
     const long long items = (long long)g.C * hb * g.Wo * (g.N / 4);
     if (vec && items < 0x7fffffffLL && items > 0) {

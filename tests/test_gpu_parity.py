@@ -200,7 +200,8 @@ def test_pool_chwn_every_working_set_shape(oy, ox):
     rng = np.random.default_rng(10 * oy + ox)
     for shape, geom in [((8, 3, 27, 27), (3, 3, 2, 2, 0, 0)), ((8, 3, 13, 15), (3, 3, 2, 2, 1, 1)),
                         ((8, 3, 14, 30), (2, 2, 2, 2, 0, 0)), ((4, 2, 12, 11), (3, 3, 1, 1, 1, 1)),
-                        ((16, 2, 9, 7), (2, 2, 2, 2, 1, 1))]:
+                        ((16, 2, 9, 7), (2, 2, 2, 2, 1, 1)), ((8, 2, 17, 16), (5, 5, 3, 3, 2, 2)),
+                        ((4, 3, 12, 14), (4, 6, 2, 1, 1, 3))]:    # the last two: the run-time-window kernel
         x = rng.standard_normal(shape, dtype=np.float32)
         check_pool(x, *shape, geom, layouts=(CHWN,), tuning=dict(rows_per_lane=oy, cols_per_lane=ox))
 
