@@ -309,7 +309,10 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_chwn_cell_kernel(
 // RR - S rows and columns) go from global memory into LDS once, with all loads in flight together, and
 // every lane then takes the taps of its cell's windows from LDS.  Patches that share a halo run on the
 // same XCD, so the halo is an L2 hit.  One lane per (cell, four images): 256 = CR * CQ * NB4.
-template <int K, int S, int CR, int CQ, int NB4>
+// SHARED: the first maximum of every window of the patch is found once, by one lane per (window, four images),
+// and left in LDS as four 8-bit tap indices; the NW x NW cells that share the window read it from there
+// instead of each scanning the window's K x K taps again.
+template <int K, int S, int CR, int CQ, int NB4, bool SHARED>
 __global__ __launch_bounds__(CR * CQ * NB4) void pool_bwd_chwn_patch_kernel(
     const float* __restrict__ src, const float* __restrict__ ddst, float* __restrict__ dsrc, PoolGeom g,
     uint32_t patches_w, uint32_t patches_h, uint32_t chunks, FastDiv div_chunks, FastDiv div_pw, FastDiv div_ph) {
@@ -382,6 +385,35 @@ __global__ __launch_bounds__(CR * CQ * NB4) void pool_bwd_chwn_patch_kernel(
     for (int ey = 0; ey < S; ++ey)
 #pragma unroll
         for (int ex = 0; ex < S; ++ex) dx[ey][ex] = make_float4(0.f, 0.f, 0.f, 0.f);
+    // first maximum of the window whose first tap is at w0, in scan order, per image: index y*K + x
+    auto first_max = [&](const float4* w0, int& kx, int& ky, int& kz, int& kw) {
+        float4 best = w0[0];
+        kx = ky = kz = kw = 0;
+#pragma unroll
+        for (int y = 0; y < K; ++y)
+#pragma unroll
+            for (int x = 0; x < K; ++x) {
+                if (y == 0 && x == 0) continue;
+                const float4 u = w0[(y * PQ + x) * NB4];
+                const int idx = y * K + x;
+                if (u.x > best.x) { best.x = u.x; kx = idx; }
+                if (u.y > best.y) { best.y = u.y; ky = idx; }
+                if (u.z > best.z) { best.z = u.z; kz = idx; }
+                if (u.w > best.w) { best.w = u.w; kw = idx; }
+            }
+    };
+    constexpr int WR = CR + NW - 1, WQ = CQ + NW - 1;          // windows that touch the patch
+    __shared__ uint32_t widx[SHARED ? WR * WQ * NB4 : 1];
+    if constexpr (SHARED) {
+        for (int it = tid; it < WR * WQ * NB4; it += THREADS) {
+            const int win = it / NB4, wn4 = it - win * NB4;
+            const int wy = win / WQ, wx = win - wy * WQ;
+            int kx, ky, kz, kw;
+            first_max(taps + ((S * wy) * PQ + S * wx) * NB4 + wn4, kx, ky, kz, kw);
+            widx[it] = (uint32_t)kx | ((uint32_t)ky << 8) | ((uint32_t)kz << 16) | ((uint32_t)kw << 24);
+        }
+        __syncthreads();
+    }
     // Window by window, taps straight from LDS (holding all RR x RR taps in registers, or finding the
     // maximum first and then its first occurrence, both measured slower: 84 us against 81 us on
     // 128x96x55x55).
@@ -389,22 +421,14 @@ __global__ __launch_bounds__(CR * CQ * NB4) void pool_bwd_chwn_patch_kernel(
     for (int a = 0; a < NW; ++a)
 #pragma unroll
         for (int b = 0; b < NW; ++b) {
-            // first maximum of window (a, b) in scan order, per image: index y*K + x
-            const float4* w0 = taps + ((S * (cy + a)) * PQ + S * (cx + b)) * NB4 + n4;
-            float4 best = w0[0];
-            int kx = 0, ky = 0, kz = 0, kw = 0;
-#pragma unroll
-            for (int y = 0; y < K; ++y)
-#pragma unroll
-                for (int x = 0; x < K; ++x) {
-                    if (y == 0 && x == 0) continue;
-                    const float4 u = w0[(y * PQ + x) * NB4];
-                    const int idx = y * K + x;
-                    if (u.x > best.x) { best.x = u.x; kx = idx; }
-                    if (u.y > best.y) { best.y = u.y; ky = idx; }
-                    if (u.z > best.z) { best.z = u.z; kz = idx; }
-                    if (u.w > best.w) { best.w = u.w; kw = idx; }
-                }
+            int kx, ky, kz, kw;
+            if constexpr (SHARED) {
+                const uint32_t packed = widx[((cy + a) * WQ + (cx + b)) * NB4 + n4];
+                kx = (int)(packed & 0xffu); ky = (int)((packed >> 8) & 0xffu);
+                kz = (int)((packed >> 16) & 0xffu); kw = (int)(packed >> 24);
+            } else {
+                first_max(taps + ((S * (cy + a)) * PQ + S * (cx + b)) * NB4 + n4, kx, ky, kz, kw);
+            }
 #pragma unroll
             for (int ey = 0; ey < S; ++ey)
 #pragma unroll
@@ -790,9 +814,14 @@ int launch_bwd_chwn_patch(const float* src, const float* ddst, float* dsrc, cons
     const long long ph = ceil_div64(cells_h, CR), pw = ceil_div64(cells_w, CQ), chunks = g.N / (4 * NB4);
     const long long blocks = (long long)g.C * ph * pw * chunks;
     if (blocks >= 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((pool_bwd_chwn_patch_kernel<K, S, CR, CQ, NB4>), dim3((unsigned)blocks), dim3(CR * CQ * NB4), 0,
-                       st, src, ddst, dsrc, g, (uint32_t)pw, (uint32_t)ph, (uint32_t)chunks,
-                       make_fastdiv((uint32_t)chunks), make_fastdiv((uint32_t)pw), make_fastdiv((uint32_t)ph));
+    if (env_int("CNNMEM_BWD_PATCH", 2) == 2)
+        hipLaunchKernelGGL((pool_bwd_chwn_patch_kernel<K, S, CR, CQ, NB4, true>), dim3((unsigned)blocks),
+                           dim3(CR * CQ * NB4), 0, st, src, ddst, dsrc, g, (uint32_t)pw, (uint32_t)ph, (uint32_t)chunks,
+                           make_fastdiv((uint32_t)chunks), make_fastdiv((uint32_t)pw), make_fastdiv((uint32_t)ph));
+    else
+        hipLaunchKernelGGL((pool_bwd_chwn_patch_kernel<K, S, CR, CQ, NB4, false>), dim3((unsigned)blocks),
+                           dim3(CR * CQ * NB4), 0, st, src, ddst, dsrc, g, (uint32_t)pw, (uint32_t)ph, (uint32_t)chunks,
+                           make_fastdiv((uint32_t)chunks), make_fastdiv((uint32_t)pw), make_fastdiv((uint32_t)ph));
     return launch_status();
 }
 
