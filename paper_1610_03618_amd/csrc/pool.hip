@@ -577,8 +577,10 @@ int launch_chwn_vec4(const float* src, float* dst, const PoolGeom& g, const Pool
     const uint32_t flat_items = flat ? (uint32_t)all_items : 0;
     if (flat) blocks = ceil_div64(all_items, kThreads);
     const FastDiv d_row = make_fastdiv((uint32_t)row_items), d_by = make_fastdiv((uint32_t)by);
-    // disjoint windows, one output per lane: 64 B in flight per lane, best at 4 workgroups per CU;
-    // larger working sets already keep plenty in flight and are left alone unless asked
+    // disjoint windows, one output per lane: 64 B in flight per lane, best at 4 workgroups per CU for the
+    // maximum and at 3 for the average (five tensors of 411-1644 MB, back to back: the average 1-2 % faster
+    // at 3 than at 4 on every one, the maximum 3-6 % slower); larger working sets already keep plenty in
+    // flight and are left alone unless asked
     const bool light = OY == 1 && OX == 1 && KH <= SH && KW <= SW;
     const long long in_bytes = 4LL * g.N * g.C * g.H * g.W;
     int cap = light || tune.workgroups_per_cu != 0 ? tune.workgroups_per_cu : -1;
@@ -589,7 +591,7 @@ int launch_chwn_vec4(const float* src, float* dst, const PoolGeom& g, const Pool
         if (OY * OX == 1 && in_bytes >= (64LL << 20)) cap = 4;
         else if (OY * OX >= 3 && in_bytes >= (64LL << 20)) cap = 5;    // 3x3/s1, four rows: 59.8 -> 62.2 % at 206 MB
     }
-    const size_t lds = throttle_lds(cap, in_bytes, 4);
+    const size_t lds = throttle_lds(cap, in_bytes, light && MODE == CNNMEM_POOL_AVG ? 3 : 4);
     if (g.ph > 0 || g.pw > 0)
         hipLaunchKernelGGL((pool_chwn_vec4_kernel<MODE, KH, KW, SH, SW, OY, OX, true>), dim3((unsigned)blocks),
                            dim3(kThreads), lds, st, src, dst, g, (uint32_t)row_items, (uint32_t)bx,
