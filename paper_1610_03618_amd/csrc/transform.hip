@@ -198,12 +198,12 @@ int launch_vec4(const float* src, float* dst, long long R, long long S, hipStrea
 }
 
 template <int TR, int TS>
-int launch_u1(const float* src, float* dst, long long R, long long S, hipStream_t st) {
+int launch_u1(const float* src, float* dst, long long R, long long S, hipStream_t st, int xcd_default = 0) {
     const long long tiles_r = ceil_div64(R, TR), tiles_s = ceil_div64(S, TS);
     const long long tiles = tiles_r * tiles_s;
     if (tiles > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
     hipLaunchKernelGGL((transpose_u1_kernel<TR, TS>), dim3((unsigned)tiles), dim3(TR * TS / 4), 0, st,
-                       src, dst, R, S, (uint32_t)tiles_s, env_int("CNNMEM_TRANSFORM_XCD", 0));
+                       src, dst, R, S, (uint32_t)tiles_s, env_int("CNNMEM_TRANSFORM_XCD", xcd_default));
     return launch_status();
 }
 
@@ -230,6 +230,10 @@ int launch_transpose2d(const float* src, float* dst, long long R, long long S, h
             else if (S <= 32) shape = 4;
             // the short side fits one 128-wide tile side (N = 65..128: one tile spans every image; measured
             // on 100x64x57x57: 36 -> 65 % and 50 -> 63 % against two 64-wide tiles with the second mostly idle)
+            // 256 images and more (several tiles along the batch): the one-float4-per-lane tile with neighbouring
+            // tiles on one XCD, measured back to back on 256x96x55x55 107.4 -> 97.4 us, 256x64x56x56 77.1 -> 68.1 us,
+            // 256x512x14x14 38.7 -> 35.8 us, 384x64x28x28 30.1 -> 28.7 us (192 images: level, left as they are)
+            else if (R >= 256 && S >= 4 * R) shape = 12;
             else if (R > 64 && S >= 4 * R) shape = 7;      // few long source rows (NCHW -> CHWN)
             else if (S > 64 && R >= 4 * S) shape = 8;      // many short source rows (CHWN -> NCHW)
             // 48..64 images: the same one-float-per-access LDS tile as shape 8, 64 wide (CHWN -> NCHW on
@@ -249,6 +253,7 @@ int launch_transpose2d(const float* src, float* dst, long long R, long long S, h
             case 6: return launch_vec4<64, 128>(src, dst, R, S, st);
             case 7: return launch_vec4<128, 64, 512>(src, dst, R, S, st);
             case 8: return launch_u1<32, 128>(src, dst, R, S, st);
+            case 12: return launch_u1<32, 128>(src, dst, R, S, st, 1);
             case 9: return launch_u1<128, 32>(src, dst, R, S, st);
             case 10: return launch_u1<64, 64>(src, dst, R, S, st);
             case 11: return launch_vec4<128, 128, 1024>(src, dst, R, S, st);

@@ -45,6 +45,7 @@ TRANSFORM_SHAPES = [
     (32, 6, 10, 10), (8, 16, 9, 4), (256, 2, 17, 4), (100, 4, 5, 9), (132, 3, 11, 4),   # vector paths, ragged tiles
     (5, 7, 3, 3), (3, 2, 55, 55), (127, 1, 9, 7), (16, 3, 5, 5), (66, 1, 1, 129),       # scalar path
     (20, 8, 6, 2), (12, 4, 4, 4),
+    (256, 4, 17, 16), (260, 8, 12, 12), (512, 4, 24, 24),                               # 256 images and more: XCD-ordered tiles
     (1, 3, 17, 19), (1, 64, 8, 8),                                                      # one image: a copy
     (2, 3, 37, 61), (3, 5, 21, 33), (4, 16, 28, 28), (5, 1, 1, 1025), (6, 2, 50, 50),   # 2..8 images: thin-plane kernels,
     (7, 3, 19, 23), (8, 8, 32, 32), (8, 1, 1, 3), (4, 1, 1, 1), (2, 1, 1, 2),           # several blocks, ragged ends
@@ -69,7 +70,7 @@ def test_transform_matches_oracle_bit_for_bit(shape):
     assert same_bits(host(same), x)
 
 
-@pytest.mark.parametrize("tile", list(range(12)))
+@pytest.mark.parametrize("tile", list(range(13)))
 def test_transform_every_tile_shape(tile, monkeypatch):
     monkeypatch.setenv("CNNMEM_TRANSFORM_TILE", str(tile))
     for (N, C, H, W) in [(128, 3, 9, 12), (20, 5, 7, 4), (260, 1, 33, 4)]:
