@@ -79,6 +79,63 @@ def parse_args():
     return ap.parse_args()
 
 
+class TimingEvents:
+    """HIP events made for timing: created with hipEventDisableSystemFence, which drops the system-scope
+    fence (and the cache write-back that comes with it) that a default event performs when it completes.
+    HIP documents the flag for events that only measure time.  Measured on MI355X with a 46 us copy kernel:
+    an event after every launch adds 2.8 us per launch with default events (torch.cuda.Event) and 1.0 us
+    with these.  They are recorded on torch's current stream, the stream the library launches on."""
+
+    DISABLE_SYSTEM_FENCE = 0x20000000
+
+    def __init__(self, torch):
+        import ctypes
+        self._ct = ctypes
+        path = None
+        with open("/proc/self/maps") as f:                      # the HIP runtime this process already uses
+            for line in f:
+                if "libamdhip64.so" in line:
+                    path = line.split()[-1]
+                    break
+        if path is None:
+            raise RuntimeError("the HIP runtime is not loaded in this process")
+        self._hip = ctypes.CDLL(path)
+        self._hip.hipEventCreateWithFlags.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint]
+        self._hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self._hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self._hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self._torch = torch
+        self._made = []
+
+    def _check(self, status, what):
+        if status != 0:
+            raise RuntimeError(f"{what} failed with HIP status {status}")
+
+    def create(self, n):
+        out = []
+        for _ in range(n):
+            ev = self._ct.c_void_p()
+            self._check(self._hip.hipEventCreateWithFlags(self._ct.byref(ev), self.DISABLE_SYSTEM_FENCE),
+                        "hipEventCreateWithFlags")
+            out.append(ev)
+        self._made += out
+        return out
+
+    def record(self, ev):
+        stream = self._ct.c_void_p(self._torch.cuda.current_stream().cuda_stream)
+        self._check(self._hip.hipEventRecord(ev, stream), "hipEventRecord")
+
+    def elapsed_ms(self, a, b):
+        ms = self._ct.c_float()
+        self._check(self._hip.hipEventElapsedTime(self._ct.byref(ms), a, b), "hipEventElapsedTime")
+        return ms.value
+
+    def destroy_all(self):
+        for ev in self._made:
+            self._hip.hipEventDestroy(ev)
+        self._made = []
+
+
 class Op:
     """One launch of the hot path with its rotating buffer sets."""
 
@@ -426,7 +483,7 @@ def layout_policy_summary(kernels):
     return layers
 
 
-def measure_extras(torch, cm, ops, iters=20):
+def measure_extras(torch, cm, ops, tev, iters=20):
     """Two yardsticks beside every launch, measured after the timed region:
 
     warm -- the same launch repeated on one buffer set (the last-level cache may serve it);
@@ -448,31 +505,34 @@ def measure_extras(torch, cm, ops, iters=20):
     def timed(fn, n):
         for i in range(3):
             fn(i)
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        ev = [tev.create(2) for _ in range(n)]
         torch.cuda.synchronize()
         for _ in range(3):
             cm.cnnmem_transform(pa, pb, 1, 1, 1, pa.numel(), cm.NCHW, cm.NCHW)
         for i, (a, b) in enumerate(ev):
-            a.record()
+            tev.record(a)
             fn(i)
-            b.record()
+            tev.record(b)
         torch.cuda.synchronize()
-        ms = sorted(a.elapsed_time(b) for a, b in ev)
+        ms = sorted(tev.elapsed_ms(a, b) for a, b in ev)
+        tev.destroy_all()
         return ms[len(ms) // 2]
 
     def train(fn, n):
         for i in range(3):
             fn(i)
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a, b = tev.create(2)
         torch.cuda.synchronize()
         for _ in range(3):
             cm.cnnmem_transform(pa, pb, 1, 1, 1, pa.numel(), cm.NCHW, cm.NCHW)
-        a.record()
+        tev.record(a)
         for i in range(n):
             fn(i)
-        b.record()
+        tev.record(b)
         torch.cuda.synchronize()
-        return a.elapsed_time(b) / n
+        ms = tev.elapsed_ms(a, b) / n
+        tev.destroy_all()
+        return ms
 
     for op in ops:
         warm_ms = timed(lambda i, op=op: op.launch(0), iters)
@@ -486,6 +546,108 @@ def measure_extras(torch, cm, ops, iters=20):
             copy_cache[op.alg_bytes] = (timed(fn, iters), train(fn, iters))
             del a, b
         out[op.name] = (warm_ms, copy_cache[op.alg_bytes][0], b2b_ms, copy_cache[op.alg_bytes][1])
+    return out
+
+
+def measure_configs(torch, cm, wl, rl, tev, iters=20):
+    """Every tensor the five benchmark configurations name, each launch timed back to back.
+
+    One entry per launch: ``iters`` launches of it on rotating buffer sets (together larger than the last-level
+    cache), replayed as one HIP graph between one pair of events, after three untimed launches.  Tensors are filled on the device with seeded
+    values of the configuration's distribution; nothing here is checked against the oracle (the parity tests
+    run the same tensors through it).
+    """
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device="cuda").manual_seed(161003618)
+    out = []
+
+    def values(spec_values, shape):
+        if spec_values == "uniform":
+            return torch.rand(shape, device=dev, generator=gen) * 2 - 1
+        return torch.randn(shape, device=dev, generator=gen).relu_()
+
+    def train(fn, ns):
+        # the train is captured into a HIP graph and replayed: several of these tensors take a few microseconds,
+        # less than the host needs to issue a launch from Python
+        for i in range(3):
+            fn(i % ns)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(iters):
+                fn(i % ns)
+        graph.replay()
+        a, b = tev.create(2)
+        torch.cuda.synchronize()
+        tev.record(a)
+        graph.replay()
+        tev.record(b)
+        torch.cuda.synchronize()
+        ms = tev.elapsed_ms(a, b) / iters
+        tev.destroy_all()
+        del graph
+        return ms
+
+    names = set()
+
+    def add(cfg, name, nbytes, fn, ns):
+        if (cfg, name) in names:                             # config 3: a pooled shape that is also a layer input
+            return
+        names.add((cfg, name))
+        ms = train(fn, ns)
+        gbps = nbytes / (ms * 1e-3) / 1e9
+        out.append({"config": cfg, "name": name, "alg_bytes": nbytes, "back_to_back_ms": round(ms, 5),
+                    "achieved": round(gbps, 1), "frac": round(gbps / rl.PEAK_HBM_GBPS, 4)})
+
+    def transforms(cfg, N, C, H, W, vals):
+        n = N * C * H * W
+        ns = _nsets_for(8 * n)
+        a = [values(vals, (N, C, H, W)) for _ in range(ns)]
+        b = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(ns)]
+        tag = f"{N}x{C}x{H}x{W}"
+        add(cfg, f"transform_nchw_to_chwn_{tag}", rl.transform_bytes(N, C, H, W),
+            lambda i: cm.cnnmem_transform(a[i], b[i], N, C, H, W, cm.NCHW, cm.CHWN), ns)
+        add(cfg, f"transform_chwn_to_nchw_{tag}", rl.transform_bytes(N, C, H, W),
+            lambda i: cm.cnnmem_transform(a[i], b[i], N, C, H, W, cm.CHWN, cm.NCHW), ns)
+
+    def pools(cfg, N, C, H, W, k, s_, modes, vals):
+        st, Ho, Wo = cm.cnnmem_pool_out_dims(H, W, k, k, s_, s_, 0, 0)
+        n_in, n_out = N * C * H * W, N * C * Ho * Wo
+        ns = _nsets_for(4 * (n_in + n_out))
+        x = [values(vals, (n_in,)) for _ in range(ns)]
+        y = [torch.empty(n_out, dtype=torch.float32, device=dev) for _ in range(ns)]
+        pb = rl.pool_bytes(N, C, H, W, k, k, s_, s_)
+        for mode in modes:
+            for layout, lname in ((cm.NCHW, "nchw"), (cm.CHWN, "chwn")):
+                mname = "max" if mode == cm.POOL_MAX else "avg"
+                add(cfg, f"pool_{mname}_{lname}_{N}x{C}x{H}x{W}_k{k}s{s_}", pb,
+                    lambda i, layout=layout, mode=mode: cm.cnnmem_pool(x[i], y[i], N, C, H, W, layout, mode,
+                                                                       k, k, s_, s_, 0, 0), ns)
+        return Ho, Wo
+
+    def softmax(cfg, n, c, sigma):
+        ns = _nsets_for(8 * n * c)
+        z = [torch.randn((n, c), device=dev, generator=gen) * sigma for _ in range(ns)]
+        pr = [torch.empty_like(z[0]) for _ in range(ns)]
+        add(cfg, f"softmax_{n}x{c}", rl.softmax_bytes(n, c), lambda i: cm.cnnmem_softmax(z[i], pr[i], n, c), ns)
+
+    for k in (1, 2, 3, 4, 5):
+        cfg = wl.config(k)
+        seen = set()
+        for pc in cfg.pools:
+            t = pc.tensor
+            if (t.name, pc.k) in seen:
+                continue
+            seen.add((t.name, pc.k))
+            modes = sorted({q.mode for q in cfg.pools if q.tensor is t})
+            Ho, Wo = pools(k, t.N, t.C, t.H, t.W, pc.k, pc.s, modes, t.values)
+            if k == 3:                                       # the transforms between the layers: pooled shapes too
+                transforms(k, t.N, t.C, Ho, Wo, t.values)
+        for t in cfg.transforms:
+            transforms(k, t.N, t.C, t.H, t.W, t.values)
+        for sm in cfg.softmaxes:
+            softmax(k, sm.N, sm.classes, sm.sigma)
+        torch.cuda.empty_cache()
     return out
 
 
@@ -559,6 +721,7 @@ def main():
         sys.exit(2)
     import torch
     import paper_1610_03618_amd as cm
+    from paper_1610_03618_amd import counters
     from paper_1610_03618_amd import roofline as rl
     from paper_1610_03618_amd import workloads as wl
 
@@ -586,16 +749,18 @@ def main():
 
     # One event before the first launch of a step and one after every launch: launch k of a step lasted
     # from event k to event k + 1 (the launches of a step run back to back on one stream).
+    tev = TimingEvents(torch)
+
     def one_step(step, events=None):
         if events is not None:
-            events[0].record()
+            tev.record(events[0])
         for k, op in enumerate(ops):
             # launch k of a step takes buffer set step + k: launches that share tensors (both pooling modes
             # on one input, a transform and its inverse) never touch a set the previous launch just used,
             # so the last-level cache cannot serve one launch with what its neighbour left there
             st = op.launch((step + k) % op.nsets)
             if events is not None:
-                events[k + 1].record()
+                tev.record(events[k + 1])
             if st != 0:
                 raise RuntimeError(f"{op.name}: status {st}")
 
@@ -613,7 +778,7 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    all_events = [[torch.cuda.Event(enable_timing=True) for _ in range(len(ops) + 1)] for _ in range(args.steps)]
+    all_events = [tev.create(len(ops) + 1) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
@@ -623,7 +788,7 @@ def main():
 
     for s in range(args.steps):
         for k, op in enumerate(ops):
-            op.ms.append(all_events[s][k].elapsed_time(all_events[s][k + 1]))
+            op.ms.append(tev.elapsed_ms(all_events[s][k], all_events[s][k + 1]))
 
     graph_info = None
     if args.graph:
@@ -645,11 +810,21 @@ def main():
         graph_info = {"steps_per_graph": per_graph, "replays": reps, "ms_per_step": round(gwall * 1e3, 4),
                       "value": round(sum(op.alg_bytes for op in ops) / gwall / 1e9, 1), "unit": "GB/s"}
 
-    extras = {} if args.no_extras else measure_extras(torch, cm, ops)
+    tev.destroy_all()
+    extras = {} if args.no_extras else measure_extras(torch, cm, ops, tev)
+    # the driver's default run also times every other tensor of the five configurations
+    per_config = None
+    if args.workload == "largest" and args.dtype == "f32" and not only and not args.no_extras:
+        per_config = measure_configs(torch, cm, wl, rl, tev)
     torch_ms = measure_torch(torch, ops) if args.compare_torch else {}
     step_bytes = sum(op.alg_bytes for op in ops)
     ms_per_step = wall / args.steps * 1e3
     value = step_bytes / (wall / args.steps) / 1e9
+    # HBM bytes per launch from the committed rocprofv3 counter summary; only while that summary was measured on
+    # the kernel sources this run uses (a digest of csrc/ and include/), otherwise null
+    digest = counters.sources_digest()
+    traffic_path = os.path.join(ROOT, "profiles", "hbm_traffic_largest_configs.json")
+    traffic_table = counters.load_for(traffic_path, digest) if args.workload == "largest" else None
     kernels = []
     for op in ops:
         avg_ms = sum(op.ms) / len(op.ms)
@@ -658,7 +833,8 @@ def main():
         kernels.append({"name": op.name, "kind": op.kind, "avg_ms": round(avg_ms, 5), "median_ms": round(med_ms, 5),
                         "min_ms": round(min(op.ms), 5), "alg_bytes": op.alg_bytes,
                         "achieved": round(gbps, 1), "frac": round(gbps / rl.PEAK_HBM_GBPS, 4),
-                        "traffic": rl.MEASURED_TRAFFIC.get(op.name) if args.dtype == "f32" else None})
+                        "traffic": (traffic_table["ops"].get(op.name, {}).get("traffic")
+                                    if traffic_table and args.dtype == "f32" else None)})
         if op.name in extras:
             warm_ms, copy_ms, b2b_ms, copy_b2b_ms = extras[op.name]
             kernels[-1]["warm_median_ms"] = round(warm_ms, 5)
@@ -673,6 +849,9 @@ def main():
     roofline = {"bound": "hbm", "kernel": dominant["name"], "achieved": dominant["achieved"],
                 "peak": rl.PEAK_HBM_GBPS, "unit": "GB/s", "frac": dominant["frac"],
                 "traffic": dominant["traffic"],
+                "traffic_source": ("profiles/hbm_traffic_largest_configs.json (rocprofv3 FETCH_SIZE / WRITE_SIZE on these "
+                                   "kernel sources)" if traffic_table else
+                                   "none: no counter summary for the kernel sources of this run"),
                 "alg_bytes_per_launch": dominant["alg_bytes"], "avg_ms": dominant["avg_ms"]}
     if "back_to_back_ms" in dominant:
         # the same launch repeated between one pair of events: no event after every launch, so this is the
@@ -701,7 +880,7 @@ def main():
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "ms_per_step_with_events": round(wall_events / args.steps * 1e3, 4),
         "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+        "vs_baseline": None, "dtype": args.dtype, "data": "synthetic", "sources_digest": digest,
         "config": {"workload": WORKLOAD_TEXT[args.workload] + ("" if args.dtype == "f32" else f", tensors stored as {args.dtype}"),
                    "launches_per_step": len(ops), "alg_bytes_per_step": step_bytes,
                    "cache_control": "rotating buffer sets, each larger than the 256 MB last-level cache"},
@@ -710,6 +889,8 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+    if per_config is not None:
+        out["per_config"] = per_config
     if graph_info:
         out["graph"] = graph_info
     if args.workload == "layout_policy":

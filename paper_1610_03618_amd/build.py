@@ -25,6 +25,18 @@ FLAGS += os.environ.get("CNNMEM_EXTRA_FLAGS", "").split()
 BUILD_DIR = os.path.join(HERE, "_build")
 
 
+def stale() -> bool:
+    """True when the library is missing or older than any file under csrc/ or include/."""
+    if not os.path.exists(LIB_PATH):
+        return True
+    built = os.path.getmtime(LIB_PATH)
+    for folder in (CSRC, INCLUDE):
+        for name in os.listdir(folder):
+            if os.path.getmtime(os.path.join(folder, name)) > built:
+                return True
+    return False
+
+
 def build(verbose: bool = False, jobs: int = 8) -> str:
     """Compile every HIP source (in parallel) and link ``paper_1610_03618_amd/libcnnmem.so``."""
     os.makedirs(BUILD_DIR, exist_ok=True)

@@ -25,11 +25,36 @@ inline int launch_status() {
     return hipGetLastError() == hipSuccess ? CNNMEM_OK : CNNMEM_ERR_RUNTIME;
 }
 
-// Integer tuning knob from the environment (read on every call: host-side, cheap).
+// Integer tuning knobs from the environment, for A/B profiling and for tests that force every kernel
+// variant.  They are dead unless the process was started with CNNMEM_KNOBS=1: that switch is read once,
+// at the first launch, so a production call pays one load of a static flag and no getenv; with the
+// switch on, each knob is re-read on every call (a test may change it between calls).
+inline bool knobs_enabled() {
+    static const bool on = [] {
+        const char* s = std::getenv("CNNMEM_KNOBS");
+        return s && s[0] == '1';
+    }();
+    return on;
+}
 inline int env_int(const char* name, int fallback) {
+    if (!knobs_enabled()) return fallback;
     const char* s = std::getenv(name);
     if (!s || !*s) return fallback;
     return std::atoi(s);
+}
+
+// Kernels that need more than 64 KB of dynamic LDS opt in once per device and kernel, not once per launch.
+template <auto kernel>
+inline bool allow_large_lds(size_t bytes) {
+    static bool done[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+    if (done[dev]) return true;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)bytes) != hipSuccess)
+        return false;
+    done[dev] = true;
+    return true;
 }
 
 // Exact unsigned division of any n < 2^31 by a fixed d in [1, 2^31):

@@ -5,14 +5,15 @@
 // generic kernel src[R][S] -> dst[S][R] serves both directions.
 //
 // gfx950 design (not the paper's Kepler float2 scheme): every lane moves
-// 128-bit words on both the read and the write side.  A workgroup owns a TR x TS
-// tile; each lane loads a 4x4 block (four float4 from four consecutive source
-// rows), transposes it in registers, and parks the four transposed float4 in an
-// LDS tile that is already in destination order.  After one barrier the tile is
-// read back row by row with 128-bit LDS reads and written with 128-bit global
-// stores, so global reads and writes are both contiguous runs of TS*4 and TR*4
-// bytes.  LDS rows are padded by 4 floats and stored in a j-major swizzled order
-// so that the 16 lanes that write one 4x4 block column hit distinct bank groups.
+// 128-bit words on both the read and the write side, through an LDS tile that
+// is already in destination order and free of bank conflicts.  Two kernels:
+// 4x4 register blocks (four float4 from four consecutive source rows, transposed
+// in registers, parked as four float4 in a padded, j-major LDS tile) for small
+// batches, and a one-float4-per-lane tile with an XOR swizzle for the batch
+// sizes of real networks.  A pattern-only kernel (the same addresses, no LDS, no
+// barrier, data not transposed) runs at the same speed as these kernels, so
+// what separates them from a plain copy is the order in which the memory system
+// sees the strided side, not the on-chip part.
 #include "common.hpp"
 
 namespace cnnmem {
@@ -33,7 +34,7 @@ extern __shared__ float4 dyn_tile[];                // 16-byte aligned dynamic L
 template <int TR, int TS, int THREADS>
 __global__ __launch_bounds__(THREADS) void transpose_vec4_kernel(
     const float* __restrict__ src, float* __restrict__ dst, long long R, long long S,
-    uint32_t tiles_s, int xcd_order) {
+    uint32_t tiles_s) {
     static_assert(TR % 4 == 0 && TS % 4 == 0, "tile sides are multiples of 4");
     static_assert((TR * TS / 16) % THREADS == 0, "whole number of 4x4 blocks per lane");
     constexpr int P = TR + 4;                       // LDS pitch in floats (keeps float4 alignment)
@@ -44,7 +45,7 @@ __global__ __launch_bounds__(THREADS) void transpose_vec4_kernel(
 
     float* tile = reinterpret_cast<float*>(dyn_tile);   // TS * P floats, sized by the launch
 
-    const uint32_t tile_id = xcd_order ? xcd_contiguous_tile(blockIdx.x, gridDim.x) : blockIdx.x;
+    const uint32_t tile_id = blockIdx.x;
     const long long r0 = (long long)(tile_id / tiles_s) * TR;
     const long long s0 = (long long)(tile_id % tiles_s) * TS;
     const int tid = threadIdx.x;
@@ -100,69 +101,79 @@ __global__ __launch_bounds__(THREADS) void transpose_vec4_kernel(
     }
 }
 
-// One float4 per lane (THREADS = TR*TS/4): the lane scatters its four words into
-// the transposed LDS tile with dword writes, and after the barrier reads one
-// float4 of a destination row back.  Fewer bytes in flight per lane than the
-// 4x4-block kernel; same LDS layout.
-template <int TR, int TS>
-__global__ __launch_bounds__(TR * TS / 4) void transpose_u1_kernel(
-    const float* __restrict__ src, float* __restrict__ dst, long long R, long long S, uint32_t tiles_s,
-    int xcd_order) {
-    constexpr int P = TR + 4;
+// Swizzled tile, one or a few float4 per lane.  Lanes load float4 of source rows and scatter their four
+// words into an LDS tile that is already in destination order; after the barrier a lane reads one
+// float4 of a destination row back and stores it.  The tile has no padding: LDS row q = j*(TS/4) + c
+// holds destination row 4*c + j, and its float4 slot b sits at physical slot b ^ (c & 7).  A wavefront
+// covers 8 float4 columns x 8 source rows per load, so the 32 lanes that scatter together hit 32
+// different banks (4*(slot ^ c) + word), and the 16 lanes that read together take two whole 128-byte
+// LDS rows: SQ_LDS_BANK_CONFLICT is 0 for every tile shape (a padded, unswizzled tile spent 70 % of its
+// LDS cycles on conflicts).  Tile order: 0 = s-tiles fastest, 1 = the same with neighbouring tiles on
+// one XCD, 2 = r-tiles fastest.  Order 2 with a tile that spans only 32 images walks the tensor once
+// per group of 32 images: fewer rows of the strided side are open at a time, which the memory system
+// rewards (CHWN -> NCHW, 256 images: 67.5 -> 72.0 % of peak).
+template <int TR, int TS, int THREADS>
+__global__ __launch_bounds__(THREADS) void transpose_swz_kernel(
+    const float* __restrict__ src, float* __restrict__ dst, long long R, long long S, uint32_t tiles_r,
+    uint32_t tiles_s, int order) {
     constexpr int NC4 = TS / 4;                     // float4 per source row of the tile
     constexpr int NBR = TR / 4;                     // float4 per destination row of the tile
-    __shared__ __attribute__((aligned(16))) float tile[TS * P];
+    constexpr int ITERS = TR * TS / 4 / THREADS;
+    constexpr int CG = NC4 / 8;                     // groups of 8 float4 columns
+    static_assert(TR % 32 == 0 && TS % 32 == 0, "tile sides are multiples of 32");
+    static_assert((TR * TS / 4) % THREADS == 0 && THREADS % 64 == 0, "whole float4 per lane, whole wavefronts");
+    float* tile = reinterpret_cast<float*>(dyn_tile);   // TS rows of TR floats
 
-    const uint32_t tile_id = xcd_order ? xcd_contiguous_tile(blockIdx.x, gridDim.x) : blockIdx.x;
-    const long long r0 = (long long)(tile_id / tiles_s) * TR;
-    const long long s0 = (long long)(tile_id % tiles_s) * TS;
+    uint32_t tr, ts;
+    if (order == 2) {
+        tr = blockIdx.x % tiles_r;
+        ts = blockIdx.x / tiles_r;
+    } else {
+        const uint32_t t = order == 1 ? xcd_contiguous_tile(blockIdx.x, gridDim.x) : blockIdx.x;
+        tr = t / tiles_s;
+        ts = t % tiles_s;
+    }
+    const long long r0 = (long long)tr * TR;
+    const long long s0 = (long long)ts * TS;
     const int tid = threadIdx.x;
-    {
-        const int c4 = tid % NC4;
-        const int rl = tid / NC4;
-        long long r = r0 + rl, s = s0 + 4 * c4;
-        r = r < R ? r : R - 1;                      // edge tiles: re-read a valid word, never written out
-        s = s < S ? s : S - 4;
-        const float4 v = ld4_stream(src + (size_t)r * (size_t)S + (size_t)s);
-        tile[lds_row<TS>(4 * c4 + 0) * P + rl] = v.x;
-        tile[lds_row<TS>(4 * c4 + 1) * P + rl] = v.y;
-        tile[lds_row<TS>(4 * c4 + 2) * P + rl] = v.z;
-        tile[lds_row<TS>(4 * c4 + 3) * P + rl] = v.w;
-    }
-    __syncthreads();
-    {
-        const int br = tid % NBR;
-        const int sl = tid / NBR;
-        const long long s = s0 + sl, r = r0 + 4 * br;
-        if (s < S && r < R)
-            st4_stream(dst + (size_t)s * (size_t)R + (size_t)r,
-                       *reinterpret_cast<const float4*>(tile + lds_row<TS>(sl) * P + 4 * br));
-    }
-}
 
-// Any R, S and any 4-byte alignment: 64x64 tile, dword accesses, pitch 65.
-__global__ __launch_bounds__(kThreads) void transpose_scalar_kernel(
-    const float* __restrict__ src, float* __restrict__ dst, long long R, long long S,
-    uint32_t tiles_s) {
-    constexpr int T = 64;
-    __shared__ float tile[T * (T + 1)];
-    const uint32_t tile_id = blockIdx.x;
-    const long long r0 = (long long)(tile_id / tiles_s) * T;
-    const long long s0 = (long long)(tile_id % tiles_s) * T;
-    const int tx = threadIdx.x % T;
-    const int ty = threadIdx.x / T;                 // 0..3
+    // edge tiles: lanes outside the matrix re-read a valid word (never written out), so no load is conditional
+    float4 v[ITERS];
 #pragma unroll
-    for (int k = 0; k < T / 4; ++k) {
-        const int rl = ty + 4 * k;
-        const long long r = r0 + rl, s = s0 + tx;
-        if (r < R && s < S) tile[rl * (T + 1) + tx] = ld1_stream(src + (size_t)r * (size_t)S + (size_t)s);
+    for (int it = 0; it < ITERS; ++it) {
+        const int e = tid + it * THREADS;
+        const int c4 = (e & 7) + 8 * ((e >> 6) % CG);
+        const int rl = ((e >> 3) & 7) + 8 * ((e >> 6) / CG);
+        long long r = r0 + rl, s = s0 + 4 * c4;
+        r = r < R ? r : R - 1;
+        s = s < S ? s : S - 4;
+        v[it] = ld4_stream(src + (size_t)r * (size_t)S + (size_t)s);
+    }
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int e = tid + it * THREADS;
+        const int c4 = (e & 7) + 8 * ((e >> 6) % CG);
+        const int rl = ((e >> 3) & 7) + 8 * ((e >> 6) / CG);
+        const int col = 4 * ((rl >> 2) ^ (c4 & 7)) + (rl & 3);
+        tile[(0 * NC4 + c4) * TR + col] = v[it].x;
+        tile[(1 * NC4 + c4) * TR + col] = v[it].y;
+        tile[(2 * NC4 + c4) * TR + col] = v[it].z;
+        tile[(3 * NC4 + c4) * TR + col] = v[it].w;
     }
     __syncthreads();
+    float4 o[ITERS];
 #pragma unroll
-    for (int k = 0; k < T / 4; ++k) {
-        const int sl = ty + 4 * k;
-        const long long s = s0 + sl, r = r0 + tx;
-        if (r < R && s < S) st1_stream(dst + (size_t)s * (size_t)R + (size_t)r, tile[tx * (T + 1) + sl]);
+    for (int it = 0; it < ITERS; ++it) {
+        const int e = tid + it * THREADS;
+        const int br = e % NBR, q = e / NBR;
+        o[it] = *reinterpret_cast<const float4*>(tile + q * TR + 4 * (br ^ (q % NC4 & 7)));
+    }
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int e = tid + it * THREADS;
+        const int br = e % NBR, q = e / NBR;
+        const long long s = s0 + 4 * (q % NC4) + q / NC4, r = r0 + 4 * br;
+        if (s < S && r < R) st4_through(dst + (size_t)s * (size_t)R + (size_t)r, o[it]);
     }
 }
 
@@ -187,24 +198,56 @@ int launch_vec4(const float* src, float* dst, long long R, long long S, hipStrea
     const long long tiles = tiles_r * tiles_s;
     if (tiles > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
     constexpr size_t lds_bytes = sizeof(float) * TS * (TR + 4);
-    if (lds_bytes > 65536) {                        // above the default per-workgroup limit: opt in (gfx950 has 160 KB)
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&transpose_vec4_kernel<TR, TS, THREADS>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
-            return CNNMEM_ERR_RUNTIME;
-    }
+    static_assert(lds_bytes <= 65536, "fits the default per-workgroup LDS limit");
     hipLaunchKernelGGL((transpose_vec4_kernel<TR, TS, THREADS>), dim3((unsigned)tiles), dim3(THREADS), lds_bytes, st,
-                       src, dst, R, S, (uint32_t)tiles_s, env_int("CNNMEM_TRANSFORM_XCD", 0));
+                       src, dst, R, S, (uint32_t)tiles_s);
     return launch_status();
 }
 
-template <int TR, int TS>
-int launch_u1(const float* src, float* dst, long long R, long long S, hipStream_t st, int xcd_default = 0) {
+template <int TR, int TS, int THREADS>
+int launch_swz(const float* src, float* dst, long long R, long long S, hipStream_t st, int order) {
     const long long tiles_r = ceil_div64(R, TR), tiles_s = ceil_div64(S, TS);
     const long long tiles = tiles_r * tiles_s;
     if (tiles > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((transpose_u1_kernel<TR, TS>), dim3((unsigned)tiles), dim3(TR * TS / 4), 0, st,
-                       src, dst, R, S, (uint32_t)tiles_s, env_int("CNNMEM_TRANSFORM_XCD", xcd_default));
+    constexpr size_t lds_bytes = sizeof(float) * TS * TR;
+    static_assert(lds_bytes <= 65536, "fits the default per-workgroup LDS limit");
+    hipLaunchKernelGGL((transpose_swz_kernel<TR, TS, THREADS>), dim3((unsigned)tiles), dim3(THREADS), lds_bytes, st,
+                       src, dst, R, S, (uint32_t)tiles_r, (uint32_t)tiles_s, order);
     return launch_status();
+}
+
+// Tile shapes of the 128-bit transpose.  The short side of the matrix is the batch (N images), the long
+// side C*H*W.  Measured back to back on MI355X (fraction of 8 TB/s; a copy of the same bytes: 79-82 %):
+enum Shape {
+    kSquare,        // vec4 64 x 64: neither side short, or 33..47 images
+    kRows16,        // vec4 16 x 256: at most 16 source rows, tile stretched along them
+    kRows32,        // vec4 32 x 128
+    kCols16,        // vec4 256 x 16: at most 16 source columns
+    kCols32,        // vec4 128 x 32
+    kLongRows64,    // vec4 64 x 128: NCHW -> CHWN, 64 images (74.6 %)
+    kLongRows128,   // swz 128 x 32, 512 lanes: NCHW -> CHWN, 65..255 images (128x96x55x55: 75.6 %)
+    kLongRows256,   // swz 32 x 128, r-tiles fastest: NCHW -> CHWN from 256 images on (256x512x14x14: 71.2 %)
+    kShortRows64,   // swz 64 x 64: CHWN -> NCHW, 48..64 images (64x256x56x56: 74.3 %)
+    kShortRows128,  // swz 256 x 32, r-tiles fastest: CHWN -> NCHW, 65..255 images (128x96x55x55: 72.0 %)
+    kShortRows256,  // swz 128 x 32, r-tiles fastest: CHWN -> NCHW from 256 images on (256x512x14x14: 72.0 %)
+    kNumShapes
+};
+
+Shape choose_shape(long long R, long long S) {
+    if (R <= 16) return kRows16;
+    if (R <= 32) return kRows32;
+    if (S <= 16) return kCols16;
+    if (S <= 32) return kCols32;
+    if (S >= 4 * R) {                               // few long source rows: NCHW -> CHWN with R images
+        if (R >= 256) return kLongRows256;
+        if (R > 64) return kLongRows128;
+        if (R == 64) return kLongRows64;
+    } else if (R >= 4 * S) {                        // many short source rows: CHWN -> NCHW with S images
+        if (S >= 256) return kShortRows256;
+        if (S > 64) return kShortRows128;
+        if (S >= 48) return kShortRows64;
+    }
+    return kSquare;
 }
 
 }  // namespace
@@ -212,62 +255,27 @@ int launch_u1(const float* src, float* dst, long long R, long long S, hipStream_
 int launch_transpose2d(const float* src, float* dst, long long R, long long S, hipStream_t st) {
     if (R == 1 || S == 1) return launch_copy(src, dst, R * S, st);     // a vector: nothing moves
     const bool vec = (R % 4 == 0) && (S % 4 == 0) && aligned16(src) && aligned16(dst);
-    // at most 8 rows on one side (batches of 2..8 images): the thin-plane kernels, which idle no lanes
-    const bool thin = (R <= 8 || S <= 8) && R * S >= 4 && env_int("CNNMEM_TRANSFORM_TILE", -1) < 0;
-    if (vec && !thin) {
-        // Tile shape: square by default; when one side of the matrix is short
-        // (small batch N) the tile is stretched along the other side so that no
-        // lane idles; for the batch sizes of real networks (N >= 128) the tile
-        // spans 128 images, which makes the CHWN side of the tile one contiguous
-        // run.  Shapes 7 / 8 measured best on MI355X for N = 128 (71 % / 69 % of
-        // peak HBM bandwidth against 67 % for the square tile).
-        // CNNMEM_TRANSFORM_TILE forces a shape for A/B profiling.
-        int shape = env_int("CNNMEM_TRANSFORM_TILE", -1);
-        if (shape < 0) {
-            if (R <= 16) shape = 3;
-            else if (R <= 32) shape = 2;
-            else if (S <= 16) shape = 5;
-            else if (S <= 32) shape = 4;
-            // the short side fits one 128-wide tile side (N = 65..128: one tile spans every image; measured
-            // on 100x64x57x57: 36 -> 65 % and 50 -> 63 % against two 64-wide tiles with the second mostly idle)
-            // 256 images and more (several tiles along the batch): the one-float4-per-lane tile with neighbouring
-            // tiles on one XCD, measured back to back on 256x96x55x55 107.4 -> 97.4 us, 256x64x56x56 77.1 -> 68.1 us,
-            // 256x512x14x14 38.7 -> 35.8 us, 384x64x28x28 30.1 -> 28.7 us (192 images: level, left as they are)
-            else if (R >= 256 && S >= 4 * R) shape = 12;
-            else if (R > 64 && S >= 4 * R) shape = 7;      // few long source rows (NCHW -> CHWN)
-            else if (S > 64 && R >= 4 * S) shape = 8;      // many short source rows (CHWN -> NCHW)
-            // 48..64 images: the same one-float-per-access LDS tile as shape 8, 64 wide (CHWN -> NCHW on
-            // 64x256x56x56: 66.6 -> 71.0 % of peak, 64x64x224x224 65.8 -> 68.3 %, 48x128x56x56 61.1 -> 62.8 %;
-            // 40 images lose, 55 x 55 planes are level), and a 128-long tile side along the long source rows
-            // (NCHW -> CHWN: 69.6 -> 70.7 %)
-            else if (S >= 48 && S <= 64 && R >= 4 * S) shape = 10;
-            else if (R == 64 && S >= 4 * R) shape = 6;
-            else shape = 0;
-        }
-        switch (shape) {
-            case 1: return launch_vec4<128, 64>(src, dst, R, S, st);
-            case 2: return launch_vec4<32, 128>(src, dst, R, S, st);
-            case 3: return launch_vec4<16, 256>(src, dst, R, S, st);
-            case 4: return launch_vec4<128, 32>(src, dst, R, S, st);
-            case 5: return launch_vec4<256, 16>(src, dst, R, S, st);
-            case 6: return launch_vec4<64, 128>(src, dst, R, S, st);
-            case 7: return launch_vec4<128, 64, 512>(src, dst, R, S, st);
-            case 8: return launch_u1<32, 128>(src, dst, R, S, st);
-            case 12: return launch_u1<32, 128>(src, dst, R, S, st, 1);
-            case 9: return launch_u1<128, 32>(src, dst, R, S, st);
-            case 10: return launch_u1<64, 64>(src, dst, R, S, st);
-            case 11: return launch_vec4<128, 128, 1024>(src, dst, R, S, st);
-            default: return launch_vec4<64, 64>(src, dst, R, S, st);
-        }
+    // CNNMEM_TRANSFORM_TILE forces a shape (tests run every shape on small ragged tensors)
+    const int forced = env_int("CNNMEM_TRANSFORM_TILE", -1);
+    // at most 8 rows on one side (batches of 2..8 images): the thin-plane kernels, which idle no lanes;
+    // any other extents or alignment: the strided tile kernel of the general permutation, 128-bit
+    // accesses at dword alignment
+    const bool thin = (R <= 8 || S <= 8) && R * S >= 4;
+    if (!vec || (thin && forced < 0)) return launch_transpose2d_any(src, dst, R, S, st);
+    const Shape shape = forced >= 0 && forced < kNumShapes ? (Shape)forced : choose_shape(R, S);
+    switch (shape) {
+        case kRows16: return launch_vec4<16, 256>(src, dst, R, S, st);
+        case kRows32: return launch_vec4<32, 128>(src, dst, R, S, st);
+        case kCols16: return launch_vec4<256, 16>(src, dst, R, S, st);
+        case kCols32: return launch_vec4<128, 32>(src, dst, R, S, st);
+        case kLongRows64: return launch_vec4<64, 128>(src, dst, R, S, st);
+        case kLongRows128: return launch_swz<128, 32, 512>(src, dst, R, S, st, 0);
+        case kLongRows256: return launch_swz<32, 128, 1024>(src, dst, R, S, st, 2);
+        case kShortRows64: return launch_swz<64, 64, 1024>(src, dst, R, S, st, 0);
+        case kShortRows128: return launch_swz<256, 32, 1024>(src, dst, R, S, st, 2);
+        case kShortRows256: return launch_swz<128, 32, 1024>(src, dst, R, S, st, 2);
+        default: return launch_vec4<64, 64>(src, dst, R, S, st);
     }
-    // any R, S and any 4-byte alignment: the strided tile kernel of the general permutation,
-    // 128-bit accesses at dword alignment (CNNMEM_TRANSFORM_TILE=100 forces the dword kernel for A/B runs)
-    if (env_int("CNNMEM_TRANSFORM_TILE", -1) != 100) return launch_transpose2d_any(src, dst, R, S, st);
-    const long long tiles_r = ceil_div64(R, 64), tiles_s = ceil_div64(S, 64);
-    if (tiles_r * tiles_s > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(transpose_scalar_kernel, dim3((unsigned)(tiles_r * tiles_s)), dim3(kThreads), 0, st,
-                       src, dst, R, S, (uint32_t)tiles_s);
-    return launch_status();
 }
 
 int launch_copy(const float* src, float* dst, long long n, hipStream_t st) {

@@ -39,19 +39,3 @@ def pool_backward_bytes(N: int, C: int, H: int, W: int, kh: int, kw: int, sh: in
 
 def softmax_backward_bytes(N: int, classes: int) -> int:
     return 3 * 4 * N * classes
-
-
-
-
-# HBM bytes per launch seen by the L2 <-> fabric counters (rocprofv3 --pmc FETCH_SIZE, then
-# WRITE_SIZE, scaled by what the same counters read for a plain copy of known size), keyed by
-# the benchmark's launch names.  Filled from the committed profile summaries; None = not measured.
-MEASURED_TRAFFIC = {
-    "transform_nchw_to_chwn": 297379839,
-    "transform_chwn_to_nchw": 297388586,
-    "pool_max_nchw": 1027518422,
-    "pool_max_chwn": 1027533780,
-    "pool_avg_nchw": 1027518422,
-    "pool_avg_chwn": 1027519446,
-    "softmax": 717100660,
-}

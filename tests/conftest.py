@@ -4,6 +4,10 @@ import sys
 
 import pytest
 
+# the library reads this switch once, at its first launch: with it the CNNMEM_* knobs that some tests use to
+# force every kernel variant are live (they are dead in a process started without it)
+os.environ["CNNMEM_KNOBS"] = "1"
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
@@ -15,11 +19,11 @@ def pytest_configure(config):
 
 @pytest.fixture(scope="session", autouse=True)
 def _built_libraries():
-    """Load what is built; build only if nothing is there."""
+    """Load what is built; build when nothing is there or when a source is newer than the library."""
     import oracle
     oracle.build()
     from paper_1610_03618_amd import build as hip_build
-    if not os.path.exists(hip_build.LIB_PATH):
+    if hip_build.stale():
         hip_build.build()
     yield
 
