@@ -41,6 +41,8 @@ WORKLOADS = {
                 "avg), softmax on 4096x21841",
     "shapes": "layer shapes beyond the paper's networks: small and awkward batches, padded / stride-1 / 5x5 / global "
               "pooling, very short and very long softmax rows; with --compare-torch also PyTorch's own kernel per launch",
+    "configs": "every tensor of the five benchmark configurations, one launch each (the default run reports the "
+               "same launches, timed back to back, under per_config)",
     "layout_policy": "the three AlexNet pooling layers of config 3 under both layout policies: pool where the "
                      "data is (NCHW) against transform + pool in CHWN + transform back (Section IV.B, IV.D)",
 }
@@ -51,6 +53,7 @@ WORKLOAD_TEXT = {
     "softmax_sweep": "softmax, batch 32..256 x categories 10..10000 (the range of Fig. 13)",
     "layouts": "storage-order changes among NCHW / NHWC / CHWN / HWCN on 128x96x55x55, 64x64x112x112 and 64x3x224x224",
     "backward": "backward of max/avg pooling (64x64x224x224 2x2/s2, 128x96x55x55 3x3/s2; NCHW and CHWN) and of softmax (4096x21841)",
+    "configs": "all five configurations: pooling in NCHW and CHWN, transforms both ways, softmax, on every tensor they name",
     "layout_policy": "config 3 (AlexNet, N=128) max-pool 3x3/s2 x3: NCHW in place vs NCHW->CHWN + pool + CHWN->NCHW",
     "shapes": "general shapes: transform at batches 1..100, pooling 3x3/s2/p1, 3x3/s1/p1, 5x5/s3/p2, global 7x7 (NCHW and "
               "CHWN, max and avg), softmax 1048576x10 and 512x128256",
@@ -549,33 +552,117 @@ def measure_extras(torch, cm, ops, tev, iters=20):
     return out
 
 
-def measure_configs(torch, cm, wl, rl, tev, iters=20):
-    """Every tensor the five benchmark configurations name, each launch timed back to back.
-
-    One entry per launch: ``iters`` launches of it on rotating buffer sets (together larger than the last-level
-    cache), replayed as one HIP graph between one pair of events, after three untimed launches.  Tensors are filled on the device with seeded
-    values of the configuration's distribution; nothing here is checked against the oracle (the parity tests
-    run the same tensors through it).
-    """
+def build_config_ops(torch, cm, wl, rl, only):
+    """Every tensor the five benchmark configurations name, one launch each: the pooling layers in both layouts
+    (config 4: max and avg), the transforms in both directions (config 3: on the pooled shapes too), the
+    classifiers.  Tensors are filled on the device with seeded values of the configuration's distribution."""
     dev = torch.device("cuda:0")
     gen = torch.Generator(device="cuda").manual_seed(161003618)
-    out = []
+    ops = []
+    names = set()
+    chosen = set(only) - {"copy_calibration"}               # "copy_calibration" alone adds the copy to every launch
 
     def values(spec_values, shape):
         if spec_values == "uniform":
             return torch.rand(shape, device=dev, generator=gen) * 2 - 1
         return torch.randn(shape, device=dev, generator=gen).relu_()
 
-    def train(fn, ns):
-        # the train is captured into a HIP graph and replayed: several of these tensors take a few microseconds,
-        # less than the host needs to issue a launch from Python
+    def wanted(cfg, name):
+        if (cfg, name) in names or (chosen and name not in chosen):   # config 3: a pooled shape that is also an input
+            return False
+        names.add((cfg, name))
+        return True
+
+    def add(cfg, name, kind, nbytes, units, fn, ns):
+        op = Op(name, kind, nbytes, units, "elements", fn, ns)
+        op.config = cfg
+        ops.append(op)
+
+    def transforms(cfg, N, C, H, W, vals):
+        n = N * C * H * W
+        tag = f"{N}x{C}x{H}x{W}"
+        todo = [d for d in ("nchw_to_chwn", "chwn_to_nchw") if wanted(cfg, f"transform_{d}_{tag}")]
+        if not todo:
+            return
+        ns = _nsets_for(8 * n)
+        a = [values(vals, (N, C, H, W)) for _ in range(ns)]
+        b = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(ns)]
+        for d in todo:
+            s_, d_ = (cm.NCHW, cm.CHWN) if d == "nchw_to_chwn" else (cm.CHWN, cm.NCHW)
+            add(cfg, f"transform_{d}_{tag}", "transform", rl.transform_bytes(N, C, H, W), n,
+                lambda i, s_=s_, d_=d_: cm.cnnmem_transform(a[i], b[i], N, C, H, W, s_, d_), ns)
+
+    def pools(cfg, N, C, H, W, k, s_, modes, vals):
+        st, Ho, Wo = cm.cnnmem_pool_out_dims(H, W, k, k, s_, s_, 0, 0)
+        n_in, n_out = N * C * H * W, N * C * Ho * Wo
+        todo = []
+        for mode in modes:
+            for layout, lname in ((cm.NCHW, "nchw"), (cm.CHWN, "chwn")):
+                name = f"pool_{'max' if mode == cm.POOL_MAX else 'avg'}_{lname}_{N}x{C}x{H}x{W}_k{k}s{s_}"
+                if wanted(cfg, name):
+                    todo.append((name, mode, layout))
+        if todo:
+            ns = _nsets_for(4 * (n_in + n_out))
+            x = [values(vals, (n_in,)) for _ in range(ns)]
+            y = [torch.empty(n_out, dtype=torch.float32, device=dev) for _ in range(ns)]
+            pb = rl.pool_bytes(N, C, H, W, k, k, s_, s_)
+            for name, mode, layout in todo:
+                add(cfg, name, "pool", pb, n_in,
+                    lambda i, layout=layout, mode=mode: cm.cnnmem_pool(x[i], y[i], N, C, H, W, layout, mode,
+                                                                       k, k, s_, s_, 0, 0), ns)
+        return Ho, Wo
+
+    def softmax(cfg, n, c, sigma):
+        if not wanted(cfg, f"softmax_{n}x{c}"):
+            return
+        ns = _nsets_for(8 * n * c)
+        z = [torch.randn((n, c), device=dev, generator=gen) * sigma for _ in range(ns)]
+        pr = [torch.empty_like(z[0]) for _ in range(ns)]
+        add(cfg, f"softmax_{n}x{c}", "softmax", rl.softmax_bytes(n, c), n * c,
+            lambda i: cm.cnnmem_softmax(z[i], pr[i], n, c), ns)
+
+    for k in (1, 2, 3, 4, 5):
+        cfg = wl.config(k)
+        seen = set()
+        for pc in cfg.pools:
+            t = pc.tensor
+            if t.name in seen:
+                continue
+            seen.add(t.name)
+            modes = sorted({q.mode for q in cfg.pools if q.tensor is t})
+            Ho, Wo = pools(k, t.N, t.C, t.H, t.W, pc.k, pc.s, modes, t.values)
+            if k == 3:                                       # the transforms between the layers: pooled shapes too
+                transforms(k, t.N, t.C, Ho, Wo, t.values)
+        for t in cfg.transforms:
+            transforms(k, t.N, t.C, t.H, t.W, t.values)
+        for sm in cfg.softmaxes:
+            softmax(k, sm.N, sm.classes, sm.sigma)
+    if "copy_calibration" in only:
+        n = 128 * 96 * 55 * 55
+        ca = [torch.zeros(n, dtype=torch.float32, device=dev) for _ in range(4)]
+        cb = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(4)]
+        add(0, "copy_calibration", "copy", 2 * 4 * n, n,
+            lambda i: cm.cnnmem_transform(ca[i], cb[i], 1, 1, 1, n, cm.NCHW, cm.NCHW), 4)
+    torch.cuda.synchronize()
+    return ops, {}
+
+
+def measure_configs(torch, cm, wl, rl, tev, iters=20):
+    """The launches of ``build_config_ops``, each timed back to back: ``iters`` launches on rotating buffer
+    sets (together larger than the last-level cache), replayed as one HIP graph between one pair of events after
+    three untimed launches.  Several of these tensors take a few microseconds, less than the host needs to
+    issue a launch from Python, hence the graph.  Nothing here is checked against the oracle (the parity tests
+    run the same tensors through it)."""
+    ops, _ = build_config_ops(torch, cm, wl, rl, set())
+    out = []
+    for op in ops:
         for i in range(3):
-            fn(i % ns)
+            op.launch(i % op.nsets)
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             for i in range(iters):
-                fn(i % ns)
+                op.launch(i % op.nsets)
         graph.replay()
         a, b = tev.create(2)
         torch.cuda.synchronize()
@@ -586,68 +673,11 @@ def measure_configs(torch, cm, wl, rl, tev, iters=20):
         ms = tev.elapsed_ms(a, b) / iters
         tev.destroy_all()
         del graph
-        return ms
-
-    names = set()
-
-    def add(cfg, name, nbytes, fn, ns):
-        if (cfg, name) in names:                             # config 3: a pooled shape that is also a layer input
-            return
-        names.add((cfg, name))
-        ms = train(fn, ns)
-        gbps = nbytes / (ms * 1e-3) / 1e9
-        out.append({"config": cfg, "name": name, "alg_bytes": nbytes, "back_to_back_ms": round(ms, 5),
+        gbps = op.alg_bytes / (ms * 1e-3) / 1e9
+        out.append({"config": op.config, "name": op.name, "alg_bytes": op.alg_bytes, "back_to_back_ms": round(ms, 5),
                     "achieved": round(gbps, 1), "frac": round(gbps / rl.PEAK_HBM_GBPS, 4)})
-
-    def transforms(cfg, N, C, H, W, vals):
-        n = N * C * H * W
-        ns = _nsets_for(8 * n)
-        a = [values(vals, (N, C, H, W)) for _ in range(ns)]
-        b = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(ns)]
-        tag = f"{N}x{C}x{H}x{W}"
-        add(cfg, f"transform_nchw_to_chwn_{tag}", rl.transform_bytes(N, C, H, W),
-            lambda i: cm.cnnmem_transform(a[i], b[i], N, C, H, W, cm.NCHW, cm.CHWN), ns)
-        add(cfg, f"transform_chwn_to_nchw_{tag}", rl.transform_bytes(N, C, H, W),
-            lambda i: cm.cnnmem_transform(a[i], b[i], N, C, H, W, cm.CHWN, cm.NCHW), ns)
-
-    def pools(cfg, N, C, H, W, k, s_, modes, vals):
-        st, Ho, Wo = cm.cnnmem_pool_out_dims(H, W, k, k, s_, s_, 0, 0)
-        n_in, n_out = N * C * H * W, N * C * Ho * Wo
-        ns = _nsets_for(4 * (n_in + n_out))
-        x = [values(vals, (n_in,)) for _ in range(ns)]
-        y = [torch.empty(n_out, dtype=torch.float32, device=dev) for _ in range(ns)]
-        pb = rl.pool_bytes(N, C, H, W, k, k, s_, s_)
-        for mode in modes:
-            for layout, lname in ((cm.NCHW, "nchw"), (cm.CHWN, "chwn")):
-                mname = "max" if mode == cm.POOL_MAX else "avg"
-                add(cfg, f"pool_{mname}_{lname}_{N}x{C}x{H}x{W}_k{k}s{s_}", pb,
-                    lambda i, layout=layout, mode=mode: cm.cnnmem_pool(x[i], y[i], N, C, H, W, layout, mode,
-                                                                       k, k, s_, s_, 0, 0), ns)
-        return Ho, Wo
-
-    def softmax(cfg, n, c, sigma):
-        ns = _nsets_for(8 * n * c)
-        z = [torch.randn((n, c), device=dev, generator=gen) * sigma for _ in range(ns)]
-        pr = [torch.empty_like(z[0]) for _ in range(ns)]
-        add(cfg, f"softmax_{n}x{c}", rl.softmax_bytes(n, c), lambda i: cm.cnnmem_softmax(z[i], pr[i], n, c), ns)
-
-    for k in (1, 2, 3, 4, 5):
-        cfg = wl.config(k)
-        seen = set()
-        for pc in cfg.pools:
-            t = pc.tensor
-            if (t.name, pc.k) in seen:
-                continue
-            seen.add((t.name, pc.k))
-            modes = sorted({q.mode for q in cfg.pools if q.tensor is t})
-            Ho, Wo = pools(k, t.N, t.C, t.H, t.W, pc.k, pc.s, modes, t.values)
-            if k == 3:                                       # the transforms between the layers: pooled shapes too
-                transforms(k, t.N, t.C, Ho, Wo, t.values)
-        for t in cfg.transforms:
-            transforms(k, t.N, t.C, t.H, t.W, t.values)
-        for sm in cfg.softmaxes:
-            softmax(k, sm.N, sm.classes, sm.sigma)
-        torch.cuda.empty_cache()
+    del ops
+    torch.cuda.empty_cache()
     return out
 
 
@@ -733,7 +763,7 @@ def main():
     only = set(filter(None, args.only.split(",")))
     builders = {"largest": build_ops, "table1": build_table1_ops, "softmax_sweep": build_softmax_sweep_ops,
                 "layout_policy": build_layout_policy_ops, "layouts": build_layouts_ops,
-                "backward": build_backward_ops, "shapes": build_shapes_ops}
+                "backward": build_backward_ops, "shapes": build_shapes_ops, "configs": build_config_ops}
     if args.workload == "largest":
         ops, host_inputs = build_ops(torch, cm, wl, rl, only, args.dtype)
     else:
@@ -823,8 +853,9 @@ def main():
     # HBM bytes per launch from the committed rocprofv3 counter summary; only while that summary was measured on
     # the kernel sources this run uses (a digest of csrc/ and include/), otherwise null
     digest = counters.sources_digest()
-    traffic_path = os.path.join(ROOT, "profiles", "hbm_traffic_largest_configs.json")
-    traffic_table = counters.load_for(traffic_path, digest) if args.workload == "largest" else None
+    traffic_file = {"largest": "hbm_traffic_largest_configs.json", "configs": "hbm_traffic_all_configs.json"}
+    traffic_path = os.path.join(ROOT, "profiles", traffic_file.get(args.workload, "none"))
+    traffic_table = counters.load_for(traffic_path, digest)
     kernels = []
     for op in ops:
         avg_ms = sum(op.ms) / len(op.ms)
@@ -849,8 +880,8 @@ def main():
     roofline = {"bound": "hbm", "kernel": dominant["name"], "achieved": dominant["achieved"],
                 "peak": rl.PEAK_HBM_GBPS, "unit": "GB/s", "frac": dominant["frac"],
                 "traffic": dominant["traffic"],
-                "traffic_source": ("profiles/hbm_traffic_largest_configs.json (rocprofv3 FETCH_SIZE / WRITE_SIZE on these "
-                                   "kernel sources)" if traffic_table else
+                "traffic_source": (f"profiles/{traffic_file.get(args.workload)} (rocprofv3 FETCH_SIZE / WRITE_SIZE on "
+                                   "these kernel sources)" if traffic_table else
                                    "none: no counter summary for the kernel sources of this run"),
                 "alg_bytes_per_launch": dominant["alg_bytes"], "avg_ms": dominant["avg_ms"]}
     if "back_to_back_ms" in dominant:
