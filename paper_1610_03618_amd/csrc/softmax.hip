@@ -282,28 +282,35 @@ __global__ __launch_bounds__(1024) void softmax_stream_kernel(const float* logit
 }
 
 template <int TPR, int ITEMS>
-int launch_rows(const float* logits, float* probs, int N, int classes, int base_mis, int align,
+int launch_rows(const float* logits, float* probs, int N, int classes, int base_mis, int align, int rows_per_cu,
                 hipStream_t st) {
     constexpr int BLOCK = TPR < 256 ? 256 : TPR;
     constexpr int ROWS = BLOCK / TPR;
     const unsigned blocks = (unsigned)ceil_div64(N, ROWS);
-    hipLaunchKernelGGL((softmax_rows_kernel<TPR, ITEMS>), dim3(blocks), dim3(BLOCK), 0, st, logits, probs, N,
+    // resident workgroups per CU, capped by asking for LDS that the kernel never touches (0 = no cap)
+    const int wpc = env_int("CNNMEM_SOFTMAX_WPC", rows_per_cu);
+    const size_t lds = wpc > 0 ? throttle_lds(wpc, 0, wpc) : 0;
+    hipLaunchKernelGGL((softmax_rows_kernel<TPR, ITEMS>), dim3(blocks), dim3(BLOCK), lds, st, logits, probs, N,
                        classes, base_mis, align);
     return launch_status();
 }
 
 template <int TPR>
 int launch_rows_items(int items, const float* logits, float* probs, int N, int classes, int base_mis,
-                      int align, hipStream_t st) {
+                      int align, int rows_per_cu, hipStream_t st) {
 #define CNNMEM_CASE(I) \
-    if (items <= I) return launch_rows<TPR, I>(logits, probs, N, classes, base_mis, align, st)
+    if (items <= I) return launch_rows<TPR, I>(logits, probs, N, classes, base_mis, align, rows_per_cu, st)
     CNNMEM_CASE(1);
     CNNMEM_CASE(2);
     CNNMEM_CASE(3);
     CNNMEM_CASE(4);
     CNNMEM_CASE(6);
     CNNMEM_CASE(8);
+    CNNMEM_CASE(9);
+    CNNMEM_CASE(10);
+    CNNMEM_CASE(11);
     CNNMEM_CASE(12);
+    CNNMEM_CASE(14);
     CNNMEM_CASE(16);
     CNNMEM_CASE(24);
     CNNMEM_CASE(32);
@@ -328,7 +335,8 @@ int launch_softmax(const float* logits, float* probs, int N, int classes, hipStr
     // measured on MI355X: 44 % against 28 % of peak at 64 categories, 56 % against 44 % at 128, but
     // 52 % against 61 % at 200, where the 64-lane register kernel below takes over
     const int short_below = env_int("CNNMEM_SOFTMAX_SHORT_BELOW", 160);
-    if (classes < (short_below < 513 ? short_below : 513) && env_int("CNNMEM_SOFTMAX_TPR", 0) == 0) {
+    // (rows of fewer than 8 categories always: the register kernel needs one whole float4 after the row's head)
+    if (classes < 8 || (classes < (short_below < 513 ? short_below : 513) && env_int("CNNMEM_SOFTMAX_TPR", 0) == 0)) {
         // G lanes per row, at most four float4 per lane
         const int slots = (classes + 3) / 4;
         int g = 4;
@@ -343,21 +351,29 @@ int launch_softmax(const float* logits, float* probs, int N, int classes, hipStr
     }
     const long long nq = classes / 4;                             // most aligned float4 a row can hold
     int tpr = env_int("CNNMEM_SOFTMAX_TPR", 0);
+    int rows_per_cu = 0;
     if (tpr != 64 && tpr != 128 && tpr != 256 && tpr != 512 && tpr != 1024) {
         // smallest lane group that keeps at most 8 float4 per lane, else 1024
         tpr = 64;
         while (tpr < 1024 && nq > (long long)tpr * 8) tpr *= 2;
+        // Rows of 64-128 KB: two resident rows per CU on few wavefronts.  4096 x 21841 back to back: 1024 lanes
+        // per row (two workgroups fill a CU) 73.5 % of peak; 256 to 640 lanes per row with the CU capped at
+        // two workgroups 75.0-75.3 %; the same lane counts uncapped (three or four rows per CU) 70.5-72 %.
+        if (classes >= 16384 && classes <= 32768) {
+            tpr = 512;
+            rows_per_cu = 2;
+        }
     }
     const long long items = ceil_div64(nq, tpr);
     // 1024 lanes leave 128 VGPRs per lane: beyond 16 float4 the row would spill
     const long long max_items = tpr == 1024 ? 16 : 32;
     if (same_phase && items <= max_items) {
         switch (tpr) {
-            case 64: return launch_rows_items<64>((int)items, logits, probs, N, classes, base_mis, align, st);
-            case 128: return launch_rows_items<128>((int)items, logits, probs, N, classes, base_mis, align, st);
-            case 256: return launch_rows_items<256>((int)items, logits, probs, N, classes, base_mis, align, st);
-            case 512: return launch_rows_items<512>((int)items, logits, probs, N, classes, base_mis, align, st);
-            default: return launch_rows_items<1024>((int)items, logits, probs, N, classes, base_mis, align, st);
+            case 64: return launch_rows_items<64>((int)items, logits, probs, N, classes, base_mis, align, rows_per_cu, st);
+            case 128: return launch_rows_items<128>((int)items, logits, probs, N, classes, base_mis, align, rows_per_cu, st);
+            case 256: return launch_rows_items<256>((int)items, logits, probs, N, classes, base_mis, align, rows_per_cu, st);
+            case 512: return launch_rows_items<512>((int)items, logits, probs, N, classes, base_mis, align, rows_per_cu, st);
+            default: return launch_rows_items<1024>((int)items, logits, probs, N, classes, base_mis, align, rows_per_cu, st);
         }
     }
     // measured on MI355X: 512 x 128256 46 -> 56 % of peak, 2048 x 151936 45 -> 57 %, 1024 x 70001 42 -> 52 %,
