@@ -1,6 +1,7 @@
 /*
  * cnnmem_debug.h -- host-only hooks that let the CPU test-suite exercise the
- * library's index arithmetic without a GPU.  Not needed to use the library.
+ * library's index arithmetic without a GPU.  They are exported by
+ * libcnnmem_testhooks.so, a library of their own: libcnnmem.so does not carry them.
  */
 #ifndef CNNMEM_DEBUG_H
 #define CNNMEM_DEBUG_H
@@ -14,7 +15,7 @@ extern "C" {
 #endif
 
 /* n / d through the multiply-shift divider the kernels use for output-index
- * decoding; exact for 0 <= n < 2^31, 1 <= d < 2^31.  Host only. */
+ * decoding; exact for 0 <= n < 2^31, 1 <= d < 2^31; d = 0 returns 0xffffffff.  Host only. */
 CNNMEM_API unsigned cnnmem_debug_fastdiv(unsigned n, unsigned d);
 
 /* Logical tile that hardware workgroup `block` of an `nblocks`-wide launch

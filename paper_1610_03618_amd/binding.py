@@ -58,9 +58,6 @@ def library() -> ctypes.CDLL:
         lib.cnnmem_permute.restype = i
         lib.cnnmem_relayout.argtypes = [p, p, i, i, i, i, ctypes.c_char_p, ctypes.c_char_p, p]
         lib.cnnmem_relayout.restype = i
-        lib.cnnmem_debug_canonical_permutation.argtypes = [ctypes.POINTER(i), ctypes.POINTER(i), ctypes.POINTER(i),
-                                                           ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(i)]
-        lib.cnnmem_debug_canonical_permutation.restype = i
         lib.cnnmem_permute_dtype.argtypes = [p, p, ctypes.POINTER(i), ctypes.POINTER(i), i, p]
         lib.cnnmem_permute_dtype.restype = i
         lib.cnnmem_relayout_dtype.argtypes = [p, p, i, i, i, i, ctypes.c_char_p, ctypes.c_char_p, i, p]
@@ -90,26 +87,68 @@ def library() -> ctypes.CDLL:
         for name in ("cnnmem_transform", "cnnmem_pool_out_dims", "cnnmem_pool", "cnnmem_softmax",
                      "cnnmem_version"):
             getattr(lib, name).restype = i
-        lib.cnnmem_debug_fastdiv.argtypes = [ctypes.c_uint, ctypes.c_uint]
-        lib.cnnmem_debug_fastdiv.restype = ctypes.c_uint
-        lib.cnnmem_debug_xcd_tile.argtypes = [ctypes.c_uint, ctypes.c_uint]
-        lib.cnnmem_debug_xcd_tile.restype = ctypes.c_uint
         _lib = lib
     return _lib
 
 
-def _ptr(t, dtype: int = F32) -> Optional[int]:
-    """Device address of a torch tensor (or a raw integer address / None)."""
+_HOOKS_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcnnmem_testhooks.so")
+_hooks = None
+
+
+def test_hooks() -> ctypes.CDLL:
+    """The host-only hooks of the CPU test-suite (include/cnnmem_debug.h), a library of their own."""
+    global _hooks
+    if _hooks is None:
+        if not os.path.exists(_HOOKS_PATH):
+            raise RuntimeError(f"{_HOOKS_PATH} is missing: build it with `python -m paper_1610_03618_amd.build`")
+        lib = ctypes.CDLL(_HOOKS_PATH)
+        i = ctypes.c_int
+        lib.cnnmem_debug_canonical_permutation.argtypes = [ctypes.POINTER(i), ctypes.POINTER(i), ctypes.POINTER(i),
+                                                           ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(i)]
+        lib.cnnmem_debug_canonical_permutation.restype = i
+        lib.cnnmem_debug_fastdiv.argtypes = [ctypes.c_uint, ctypes.c_uint]
+        lib.cnnmem_debug_fastdiv.restype = ctypes.c_uint
+        lib.cnnmem_debug_xcd_tile.argtypes = [ctypes.c_uint, ctypes.c_uint]
+        lib.cnnmem_debug_xcd_tile.restype = ctypes.c_uint
+        _hooks = lib
+    return _hooks
+
+
+def _ptr(t, dtype: int = F32, numel: Optional[int] = None) -> Optional[int]:
+    """Device address of a torch tensor (or a raw integer address / None).
+
+    ``numel``: the elements the call will read or write there.  The C ABI takes bare pointers and cannot know
+    a buffer's size, so this is the one place a tensor that is too small can be refused before a kernel runs
+    past its end."""
     if t is None or isinstance(t, int):
         return t
     if not isinstance(t, torch.Tensor):
         raise TypeError("expected a torch tensor or an integer address")
+    if numel is not None and t.numel() < numel:
+        raise ValueError(f"tensor of {t.numel()} elements where the call needs {numel}")
     if t.device.type != "cuda":
         raise ValueError("cnnmem works on GPU memory only (got a CPU tensor)")
     if _DTYPE_OF.get(t.dtype) != dtype or not t.is_contiguous():
         raise ValueError("cnnmem takes contiguous tensors of the stated storage format "
                          "(float32 unless a dtype is given)")
     return t.data_ptr()
+
+
+def _prod(*extents) -> Optional[int]:
+    """Element count of a tensor with these extents; None when an extent is not positive (the library then
+    rejects the call itself)."""
+    n = 1
+    for e in extents:
+        if e <= 0:
+            return None
+        n *= e
+    return n
+
+
+def _pooled(N, C, H, W, kh, kw, sh, sw, ph, pw) -> Optional[int]:
+    if min(N, C, H, W, kh, kw, sh, sw) <= 0 or ph < 0 or pw < 0 or H + 2 * ph < kh or W + 2 * pw < kw:
+        return None
+    return N * C * ((H + 2 * ph - kh) // sh + 1) * ((W + 2 * pw - kw) // sw + 1)
 
 
 def dtype_of(t: torch.Tensor) -> int:
@@ -131,27 +170,32 @@ def _stream(stream) -> Optional[int]:
 # ---- one-to-one mirrors of the C entry points (return the status code) ----
 
 def cnnmem_transform(src, dst, N, C, H, W, src_layout, dst_layout, stream=None) -> int:
-    return library().cnnmem_transform(_ptr(src), _ptr(dst), N, C, H, W, src_layout, dst_layout,
+    n = _prod(N, C, H, W)
+    return library().cnnmem_transform(_ptr(src, F32, n), _ptr(dst, F32, n), N, C, H, W, src_layout, dst_layout,
                                       _stream(stream))
 
 
 def cnnmem_permute(src, dst, dims, perm, stream=None) -> int:
-    return library().cnnmem_permute(_ptr(src), _ptr(dst), (ctypes.c_int * 4)(*dims), (ctypes.c_int * 4)(*perm),
-                                    _stream(stream))
+    n = _prod(*dims)
+    return library().cnnmem_permute(_ptr(src, F32, n), _ptr(dst, F32, n), (ctypes.c_int * 4)(*dims),
+                                    (ctypes.c_int * 4)(*perm), _stream(stream))
 
 
 def cnnmem_relayout(src, dst, N, C, H, W, src_layout: str, dst_layout: str, stream=None) -> int:
-    return library().cnnmem_relayout(_ptr(src), _ptr(dst), N, C, H, W, src_layout.encode(), dst_layout.encode(),
-                                     _stream(stream))
+    n = _prod(N, C, H, W)
+    return library().cnnmem_relayout(_ptr(src, F32, n), _ptr(dst, F32, n), N, C, H, W, src_layout.encode(),
+                                     dst_layout.encode(), _stream(stream))
 
 
 def cnnmem_permute_dtype(src, dst, dims, perm, dtype, stream=None) -> int:
-    return library().cnnmem_permute_dtype(_ptr(src, dtype), _ptr(dst, dtype), (ctypes.c_int * 4)(*dims),
+    n = _prod(*dims)
+    return library().cnnmem_permute_dtype(_ptr(src, dtype, n), _ptr(dst, dtype, n), (ctypes.c_int * 4)(*dims),
                                           (ctypes.c_int * 4)(*perm), dtype, _stream(stream))
 
 
 def cnnmem_relayout_dtype(src, dst, N, C, H, W, src_layout: str, dst_layout: str, dtype, stream=None) -> int:
-    return library().cnnmem_relayout_dtype(_ptr(src, dtype), _ptr(dst, dtype), N, C, H, W, src_layout.encode(),
+    n = _prod(N, C, H, W)
+    return library().cnnmem_relayout_dtype(_ptr(src, dtype, n), _ptr(dst, dtype, n), N, C, H, W, src_layout.encode(),
                                            dst_layout.encode(), dtype, _stream(stream))
 
 
@@ -159,32 +203,39 @@ def cnnmem_debug_canonical_permutation(dims, perm):
     """(status, rank, merged source extents, permutation over them): host-only debug hook."""
     rank = ctypes.c_int(0)
     cd, cp = (ctypes.c_longlong * 4)(), (ctypes.c_int * 4)()
-    st = library().cnnmem_debug_canonical_permutation((ctypes.c_int * 4)(*dims), (ctypes.c_int * 4)(*perm),
+    st = test_hooks().cnnmem_debug_canonical_permutation((ctypes.c_int * 4)(*dims), (ctypes.c_int * 4)(*perm),
                                                       ctypes.byref(rank), cd, cp)
     return st, rank.value, list(cd)[:rank.value], list(cp)[:rank.value]
 
 
 def cnnmem_pool_backward(src, ddst, dsrc, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, stream=None) -> int:
-    return library().cnnmem_pool_backward(_ptr(src), _ptr(ddst), _ptr(dsrc), N, C, H, W, layout, mode, kh, kw, sh, sw,
-                                          ph, pw, _stream(stream))
+    n, no = _prod(N, C, H, W), _pooled(N, C, H, W, kh, kw, sh, sw, ph, pw)
+    return library().cnnmem_pool_backward(_ptr(src, F32, n), _ptr(ddst, F32, no), _ptr(dsrc, F32, n), N, C, H, W, layout,
+                                          mode, kh, kw, sh, sw, ph, pw, _stream(stream))
 
 
 def cnnmem_softmax_backward(probs, dprobs, dlogits, N, classes, stream=None) -> int:
-    return library().cnnmem_softmax_backward(_ptr(probs), _ptr(dprobs), _ptr(dlogits), N, classes, _stream(stream))
+    n = _prod(N, classes)
+    return library().cnnmem_softmax_backward(_ptr(probs, F32, n), _ptr(dprobs, F32, n), _ptr(dlogits, F32, n), N, classes,
+                                             _stream(stream))
 
 
 def cnnmem_transform_dtype(src, dst, N, C, H, W, src_layout, dst_layout, dtype, stream=None) -> int:
-    return library().cnnmem_transform_dtype(_ptr(src, dtype), _ptr(dst, dtype), N, C, H, W, src_layout, dst_layout,
+    n = _prod(N, C, H, W)
+    return library().cnnmem_transform_dtype(_ptr(src, dtype, n), _ptr(dst, dtype, n), N, C, H, W, src_layout, dst_layout,
                                             dtype, _stream(stream))
 
 
 def cnnmem_pool_dtype(src, dst, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, dtype, stream=None) -> int:
-    return library().cnnmem_pool_dtype(_ptr(src, dtype), _ptr(dst, dtype), N, C, H, W, layout, mode, kh, kw, sh, sw,
+    n, no = _prod(N, C, H, W), _pooled(N, C, H, W, kh, kw, sh, sw, ph, pw)
+    return library().cnnmem_pool_dtype(_ptr(src, dtype, n), _ptr(dst, dtype, no), N, C, H, W, layout, mode, kh, kw, sh, sw,
                                        ph, pw, dtype, _stream(stream))
 
 
 def cnnmem_softmax_dtype(logits, probs, N, classes, dtype, stream=None) -> int:
-    return library().cnnmem_softmax_dtype(_ptr(logits, dtype), _ptr(probs, dtype), N, classes, dtype, _stream(stream))
+    n = _prod(N, classes)
+    return library().cnnmem_softmax_dtype(_ptr(logits, dtype, n), _ptr(probs, dtype, n), N, classes, dtype,
+                                          _stream(stream))
 
 
 def cnnmem_pool_out_dims(H, W, kh, kw, sh, sw, ph, pw) -> Tuple[int, int, int]:
@@ -194,7 +245,8 @@ def cnnmem_pool_out_dims(H, W, kh, kw, sh, sw, ph, pw) -> Tuple[int, int, int]:
 
 
 def cnnmem_pool(src, dst, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, stream=None) -> int:
-    return library().cnnmem_pool(_ptr(src), _ptr(dst), N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw,
+    n, no = _prod(N, C, H, W), _pooled(N, C, H, W, kh, kw, sh, sw, ph, pw)
+    return library().cnnmem_pool(_ptr(src, F32, n), _ptr(dst, F32, no), N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw,
                                  _stream(stream))
 
 
@@ -207,12 +259,14 @@ def _tuning(tuning):
 def cnnmem_pool_tuned(src, dst, N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw, tuning=None, stream=None) -> int:
     """``tuning``: a :class:`PoolTuning`, a dict of its fields, or None."""
     t = _tuning(tuning)
-    return library().cnnmem_pool_tuned(_ptr(src), _ptr(dst), N, C, H, W, layout, mode, kh, kw, sh, sw, ph, pw,
-                                       ctypes.byref(t) if t is not None else None, _stream(stream))
+    n, no = _prod(N, C, H, W), _pooled(N, C, H, W, kh, kw, sh, sw, ph, pw)
+    return library().cnnmem_pool_tuned(_ptr(src, F32, n), _ptr(dst, F32, no), N, C, H, W, layout, mode, kh, kw, sh, sw,
+                                       ph, pw, ctypes.byref(t) if t is not None else None, _stream(stream))
 
 
 def cnnmem_softmax(logits, probs, N, classes, stream=None) -> int:
-    return library().cnnmem_softmax(_ptr(logits), _ptr(probs), N, classes, _stream(stream))
+    n = _prod(N, classes)
+    return library().cnnmem_softmax(_ptr(logits, F32, n), _ptr(probs, F32, n), N, classes, _stream(stream))
 
 
 def cnnmem_choose_layout(kind: int, N: int, C: int, Ct: int, Nt: int, default: int = NCHW) -> Tuple[int, int]:

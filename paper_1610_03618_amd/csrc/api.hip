@@ -2,7 +2,6 @@
 // before the arguments of a call have been found valid, and none at load time,
 // so the library loads (and rejects bad calls) on a machine without a GPU.
 #include "cnnmem.h"
-#include "cnnmem_debug.h"
 #include "common.hpp"
 
 using namespace cnnmem;
@@ -287,25 +286,5 @@ const char* cnnmem_status_string(int status) {
 }
 
 int cnnmem_version(void) { return 200; }   // 0.2.0: storage orders, 16-bit storage, backward passes
-
-unsigned cnnmem_debug_fastdiv(unsigned n, unsigned d) {
-    return fd_div(n, make_fastdiv(d));
-}
-
-int cnnmem_debug_canonical_permutation(const int* dims, const int* perm, int* rank, long long* canonical_dims,
-                                       int* canonical_perm) {
-    if (!dims || !perm || !rank || !canonical_dims || !canonical_perm) return 1;
-    bool seen[4] = {false, false, false, false};
-    for (int i = 0; i < 4; ++i) {
-        if (dims[i] <= 0 || perm[i] < 0 || perm[i] > 3 || seen[perm[i]]) return 1;
-        seen[perm[i]] = true;
-    }
-    canonical_permutation(dims, perm, rank, canonical_dims, canonical_perm);
-    return 0;
-}
-
-unsigned cnnmem_debug_xcd_tile(unsigned block, unsigned nblocks) {
-    return xcd_contiguous_tile(block, nblocks);
-}
 
 }  // extern "C"

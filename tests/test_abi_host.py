@@ -15,24 +15,33 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 INVALID = 1
 
 
-def _declared_symbols():
-    names = set()
-    for fn in sorted(os.listdir(os.path.join(ROOT, "include"))):
-        if fn.endswith(".h"):
-            text = open(os.path.join(ROOT, "include", fn)).read()
-            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-            names.update(re.findall(r"\b(cnnmem_\w+)\s*\(", text))
-    return names
+def _declared_symbols(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return set(re.findall(r"\b(cnnmem_\w+)\s*\(", text))
 
 
 def test_library_is_built_and_exports_every_declared_symbol():
+    assert sorted(f for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h")) == \
+        ["cnnmem.h", "cnnmem_debug.h"]
     assert os.path.exists(hip_build.LIB_PATH)
     lib = ctypes.CDLL(hip_build.LIB_PATH)
-    declared = _declared_symbols()
+    declared = _declared_symbols("cnnmem.h")
     assert {"cnnmem_transform", "cnnmem_pool", "cnnmem_softmax", "cnnmem_pool_out_dims",
             "cnnmem_status_string", "cnnmem_version"} <= declared
     for name in declared:
         assert hasattr(lib, name), name
+
+
+def test_test_hooks_live_in_a_library_of_their_own():
+    hooks = ctypes.CDLL(hip_build.HOOKS_LIB_PATH)
+    product = ctypes.CDLL(hip_build.LIB_PATH)
+    declared = _declared_symbols("cnnmem_debug.h")
+    assert declared == {"cnnmem_debug_fastdiv", "cnnmem_debug_xcd_tile", "cnnmem_debug_canonical_permutation"}
+    for name in declared:
+        assert hasattr(hooks, name), name
+        assert not hasattr(product, name), f"{name} is exported by the product library"
+    assert cm.test_hooks().cnnmem_debug_fastdiv(17, 0) == 0xFFFFFFFF      # no quotient, no SIGFPE
 
 
 def test_version_and_status_strings():
@@ -108,7 +117,7 @@ def test_binding_refuses_cpu_tensors():
 
 
 def test_fastdiv_is_exact():
-    lib = cm.library()
+    lib = cm.test_hooks()
     rng = np.random.default_rng(5)
     divisors = [1, 2, 3, 4, 5, 7, 13, 27, 28, 32, 55, 112, 729, 3025, 21841, 65536, 65537,
                 (1 << 31) - 1] + rng.integers(1, 1 << 31, size=40).tolist()
@@ -122,7 +131,7 @@ def test_fastdiv_is_exact():
 
 @pytest.mark.parametrize("nblocks", [1, 2, 7, 8, 9, 15, 16, 17, 63, 64, 100, 1001, 4096, 12289])
 def test_xcd_tile_order_is_a_bijection_and_groups_by_xcd(nblocks):
-    lib = cm.library()
+    lib = cm.test_hooks()
     tiles = [lib.cnnmem_debug_xcd_tile(b, nblocks) for b in range(nblocks)]
     assert sorted(tiles) == list(range(nblocks))
     # blocks dealt to one XCD (same id mod 8) get consecutive tiles
@@ -163,3 +172,30 @@ def test_headers_compile_as_plain_c(tmp_path):
     include = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", include, "-c", str(src),
                     "-o", str(tmp_path / "use_headers.o")], check=True)
+
+
+def test_binding_refuses_tensors_smaller_than_the_call_needs():
+    """A bare pointer carries no size, so the binding is where an undersized tensor is caught, before any launch
+    (the size is looked at first, so the check can be exercised here without a GPU)."""
+    import torch
+    from paper_1610_03618_amd import binding
+
+    assert binding._prod(2, 3, 4, 5) == 120 and binding._prod(2, 0, 4, 5) is None
+    assert binding._pooled(16, 64, 32, 32, 3, 3, 2, 2, 0, 0) == 16 * 64 * 15 * 15
+    assert binding._pooled(1, 1, 2, 2, 3, 3, 1, 1, 0, 0) is None        # window larger than the image
+    small, enough = torch.zeros(10), torch.zeros(16)
+    with pytest.raises(ValueError, match="needs 16"):
+        cm.cnnmem_transform(enough, small, 2, 2, 2, 2, cm.NCHW, cm.CHWN, stream=0)
+    with pytest.raises(ValueError, match="needs 16"):
+        cm.cnnmem_pool(small, enough, 1, 1, 4, 4, cm.NCHW, cm.POOL_MAX, 2, 2, 2, 2, 0, 0, stream=0)
+    with pytest.raises(ValueError, match="needs 4"):
+        cm.cnnmem_pool(enough, torch.zeros(3), 1, 1, 4, 4, cm.NCHW, cm.POOL_MAX, 2, 2, 2, 2, 0, 0, stream=0)
+    with pytest.raises(ValueError, match="needs 12"):
+        cm.cnnmem_softmax(small, small, 3, 4, stream=0)
+    with pytest.raises(ValueError, match="needs 24"):
+        cm.cnnmem_permute(enough, enough, (1, 2, 3, 4), (3, 2, 1, 0), stream=0)
+    with pytest.raises(ValueError, match="needs 16"):
+        cm.cnnmem_pool_backward(enough, torch.zeros(4), small, 1, 1, 4, 4, cm.NCHW, cm.POOL_MAX, 2, 2, 2, 2, 0, 0, stream=0)
+    # large enough: the next check (CPU memory is refused) is reached
+    with pytest.raises(ValueError, match="GPU memory"):
+        cm.cnnmem_transform(enough, enough, 2, 2, 2, 2, cm.NCHW, cm.CHWN, stream=0)

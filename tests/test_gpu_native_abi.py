@@ -19,3 +19,18 @@ def test_native_program_matches_the_oracle():
     print(run.stderr)
     assert run.returncode == 0, run.stdout[-2000:] + run.stderr[-2000:]
     assert "all checks passed" in run.stdout
+
+
+def test_native_launch_cost_program_runs():
+    """Host cost per call and eager steps against graph replays (measurement; the bound here is only a guard
+    against a launch path that regresses to many times the cost of a replay)."""
+    binary = os.path.join(HERE, "native", "launch_cost.bin")
+    assert os.path.exists(binary), f"{binary} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`"
+    run = subprocess.run([binary], capture_output=True, text=True, timeout=300)
+    print(run.stdout)
+    print(run.stderr)
+    assert run.returncode == 0, run.stdout[-2000:] + run.stderr[-2000:]
+    last = run.stdout.strip().splitlines()[-1]
+    assert last.startswith("eager / graph:")
+    ratios = [float(t) for t in last.replace("eager / graph:", "").replace("and", " ").split()]
+    assert all(r < 3.0 for r in ratios), last
