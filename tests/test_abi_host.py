@@ -185,17 +185,17 @@ def test_binding_refuses_tensors_smaller_than_the_call_needs():
     assert binding._pooled(1, 1, 2, 2, 3, 3, 1, 1, 0, 0) is None        # window larger than the image
     small, enough = torch.zeros(10), torch.zeros(16)
     with pytest.raises(ValueError, match="needs 16"):
-        cm.cnnmem_transform(enough, small, 2, 2, 2, 2, cm.NCHW, cm.CHWN, stream=0)
+        cm.cnnmem_transform(FAKE, small, 2, 2, 2, 2, cm.NCHW, cm.CHWN, stream=0)
     with pytest.raises(ValueError, match="needs 16"):
         cm.cnnmem_pool(small, enough, 1, 1, 4, 4, cm.NCHW, cm.POOL_MAX, 2, 2, 2, 2, 0, 0, stream=0)
     with pytest.raises(ValueError, match="needs 4"):
-        cm.cnnmem_pool(enough, torch.zeros(3), 1, 1, 4, 4, cm.NCHW, cm.POOL_MAX, 2, 2, 2, 2, 0, 0, stream=0)
+        cm.cnnmem_pool(FAKE, torch.zeros(3), 1, 1, 4, 4, cm.NCHW, cm.POOL_MAX, 2, 2, 2, 2, 0, 0, stream=0)
     with pytest.raises(ValueError, match="needs 12"):
         cm.cnnmem_softmax(small, small, 3, 4, stream=0)
     with pytest.raises(ValueError, match="needs 24"):
         cm.cnnmem_permute(enough, enough, (1, 2, 3, 4), (3, 2, 1, 0), stream=0)
     with pytest.raises(ValueError, match="needs 16"):
-        cm.cnnmem_pool_backward(enough, torch.zeros(4), small, 1, 1, 4, 4, cm.NCHW, cm.POOL_MAX, 2, 2, 2, 2, 0, 0, stream=0)
+        cm.cnnmem_pool_backward(FAKE, FAKE, small, 1, 1, 4, 4, cm.NCHW, cm.POOL_MAX, 2, 2, 2, 2, 0, 0, stream=0)
     # large enough: the next check (CPU memory is refused) is reached
     with pytest.raises(ValueError, match="GPU memory"):
         cm.cnnmem_transform(enough, enough, 2, 2, 2, 2, cm.NCHW, cm.CHWN, stream=0)
