@@ -82,62 +82,6 @@ def parse_args():
     return ap.parse_args()
 
 
-class TimingEvents:
-    """HIP events made for timing: created with hipEventDisableSystemFence, which drops the system-scope
-    fence (and the cache write-back that comes with it) that a default event performs when it completes.
-    HIP documents the flag for events that only measure time.  Measured on MI355X with a 46 us copy kernel:
-    an event after every launch adds 2.8 us per launch with default events (torch.cuda.Event) and 1.0 us
-    with these.  They are recorded on torch's current stream, the stream the library launches on."""
-
-    DISABLE_SYSTEM_FENCE = 0x20000000
-
-    def __init__(self, torch):
-        import ctypes
-        self._ct = ctypes
-        path = None
-        with open("/proc/self/maps") as f:                      # the HIP runtime this process already uses
-            for line in f:
-                if "libamdhip64.so" in line:
-                    path = line.split()[-1]
-                    break
-        if path is None:
-            raise RuntimeError("the HIP runtime is not loaded in this process")
-        self._hip = ctypes.CDLL(path)
-        self._hip.hipEventCreateWithFlags.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint]
-        self._hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
-        self._hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
-        self._hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
-        self._torch = torch
-        self._made = []
-
-    def _check(self, status, what):
-        if status != 0:
-            raise RuntimeError(f"{what} failed with HIP status {status}")
-
-    def create(self, n):
-        out = []
-        for _ in range(n):
-            ev = self._ct.c_void_p()
-            self._check(self._hip.hipEventCreateWithFlags(self._ct.byref(ev), self.DISABLE_SYSTEM_FENCE),
-                        "hipEventCreateWithFlags")
-            out.append(ev)
-        self._made += out
-        return out
-
-    def record(self, ev):
-        stream = self._ct.c_void_p(self._torch.cuda.current_stream().cuda_stream)
-        self._check(self._hip.hipEventRecord(ev, stream), "hipEventRecord")
-
-    def elapsed_ms(self, a, b):
-        ms = self._ct.c_float()
-        self._check(self._hip.hipEventElapsedTime(self._ct.byref(ms), a, b), "hipEventElapsedTime")
-        return ms.value
-
-    def destroy_all(self):
-        for ev in self._made:
-            self._hip.hipEventDestroy(ev)
-        self._made = []
-
 
 class Op:
     """One launch of the hot path with its rotating buffer sets."""
@@ -653,26 +597,11 @@ def measure_configs(torch, cm, wl, rl, tev, iters=20):
     three untimed launches.  Several of these tensors take a few microseconds, less than the host needs to
     issue a launch from Python, hence the graph.  Nothing here is checked against the oracle (the parity tests
     run the same tensors through it)."""
+    from paper_1610_03618_amd.timing import graph_train_ms
     ops, _ = build_config_ops(torch, cm, wl, rl, set())
     out = []
     for op in ops:
-        for i in range(3):
-            op.launch(i % op.nsets)
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            for i in range(iters):
-                op.launch(i % op.nsets)
-        graph.replay()
-        a, b = tev.create(2)
-        torch.cuda.synchronize()
-        tev.record(a)
-        graph.replay()
-        tev.record(b)
-        torch.cuda.synchronize()
-        ms = tev.elapsed_ms(a, b) / iters
-        tev.destroy_all()
-        del graph
+        ms = graph_train_ms(torch, tev, op.launch, op.nsets, iters, replays=1)
         gbps = op.alg_bytes / (ms * 1e-3) / 1e9
         out.append({"config": op.config, "name": op.name, "alg_bytes": op.alg_bytes, "back_to_back_ms": round(ms, 5),
                     "achieved": round(gbps, 1), "frac": round(gbps / rl.PEAK_HBM_GBPS, 4)})
@@ -752,6 +681,7 @@ def main():
     import torch
     import paper_1610_03618_amd as cm
     from paper_1610_03618_amd import counters
+    from paper_1610_03618_amd.timing import TimingEvents
     from paper_1610_03618_amd import roofline as rl
     from paper_1610_03618_amd import workloads as wl
 
