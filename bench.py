@@ -41,6 +41,9 @@ WORKLOADS = {
                 "avg), softmax on 4096x21841",
     "shapes": "layer shapes beyond the paper's networks: small and awkward batches, padded / stride-1 / 5x5 / global "
               "pooling, very short and very long softmax rows; with --compare-torch also PyTorch's own kernel per launch",
+    "access_patterns": "what the memory system makes of the transform's access order: pattern-only kernels (the "
+                       "addresses of a tiled transpose without LDS, barrier or transposition) and copies in scattered "
+                       "chunk order, beside the library's transform and copy on the config 2 tensor",
     "configs": "every tensor of the five benchmark configurations, one launch each (the default run reports the "
                "same launches, timed back to back, under per_config)",
     "layout_policy": "the three AlexNet pooling layers of config 3 under both layout policies: pool where the "
@@ -53,6 +56,7 @@ WORKLOAD_TEXT = {
     "softmax_sweep": "softmax, batch 32..256 x categories 10..10000 (the range of Fig. 13)",
     "layouts": "storage-order changes among NCHW / NHWC / CHWN / HWCN on 128x96x55x55, 64x64x112x112 and 64x3x224x224",
     "backward": "backward of max/avg pooling (64x64x224x224 2x2/s2, 128x96x55x55 3x3/s2; NCHW and CHWN) and of softmax (4096x21841)",
+    "access_patterns": "transform 128x96x55x55 both ways, a copy of the same bytes, pattern-only kernels and scattered-chunk copies",
     "configs": "all five configurations: pooling in NCHW and CHWN, transforms both ways, softmax, on every tensor they name",
     "layout_policy": "config 3 (AlexNet, N=128) max-pool 3x3/s2 x3: NCHW in place vs NCHW->CHWN + pool + CHWN->NCHW",
     "shapes": "general shapes: transform at batches 1..100, pooling 3x3/s2/p1, 3x3/s1/p1, 5x5/s3/p2, global 7x7 (NCHW and "
@@ -496,6 +500,54 @@ def measure_extras(torch, cm, ops, tev, iters=20):
     return out
 
 
+def build_access_pattern_ops(torch, cm, wl, rl, only):
+    """Section IV.C's transform beside kernels that only reproduce its memory accesses (no LDS, no barrier, data
+    not transposed) and beside copies whose chunks are read or written in a scattered order."""
+    import ctypes
+    from paper_1610_03618_amd import build as hip_build
+    probes = ctypes.CDLL(hip_build.PROBES_LIB_PATH)
+    p, i, ll = ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong
+    probes.cnnmem_probe_tile_pattern.argtypes = [p, p, ll, ll, i, i, i, i, p]
+    probes.cnnmem_probe_chunk_copy.argtypes = [p, p, ll, i, i, p]
+    dev = torch.device("cuda:0")
+    t = wl.config(2).transforms[0]
+    N, C, H, W = t.N, t.C, t.H, t.W
+    M, n = C * H * W, t.numel
+    ns = 4
+    a = [torch.randn(n, device=dev) for _ in range(ns)]
+    b = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(ns)]
+    ops = []
+
+    def stream():
+        return torch.cuda.current_stream().cuda_stream or None
+
+    def add(name, nbytes, fn):
+        if not only or name in only:
+            ops.append(Op(name, "transform", nbytes, n, "elements", fn, ns))
+
+    full = rl.transform_bytes(N, C, H, W)
+    add("copy", full, lambda k: cm.cnnmem_transform(a[k], b[k], 1, 1, 1, n, cm.NCHW, cm.NCHW))
+    add("transform_nchw_to_chwn", full, lambda k: cm.cnnmem_transform(a[k], b[k], N, C, H, W, cm.NCHW, cm.CHWN))
+    add("transform_chwn_to_nchw", full, lambda k: cm.cnnmem_transform(a[k], b[k], N, C, H, W, cm.CHWN, cm.NCHW))
+    for (TR, NS, r_fastest) in ((32, 128, 0), (128, 32, 0), (128, 32, 1), (256, 32, 1), (512, 32, 1)):
+        covered = 2 * 4 * (M // TR) * TR * N
+        tag = f"{TR}x{NS}" + ("_image_groups_slowest" if r_fastest else "")
+        add(f"pattern_chwn_to_nchw_{tag}", covered,
+            lambda k, TR=TR, NS=NS, rf=r_fastest: probes.cnnmem_probe_tile_pattern(
+                a[k].data_ptr(), b[k].data_ptr(), M, N, TR, NS, 1, rf, stream()))
+        add(f"pattern_nchw_to_chwn_{tag}", covered,
+            lambda k, TR=TR, NS=NS, rf=r_fastest: probes.cnnmem_probe_tile_pattern(
+                a[k].data_ptr(), b[k].data_ptr(), M, N, TR, NS, 0, rf, stream()))
+    for chunk in (128, 4096, 65536, 1048576):
+        whole = (4 * n // chunk) * chunk // 4
+        for scatter, sname in ((1, "reads"), (2, "writes"), (3, "both")):
+            add(f"copy_chunks_{chunk}B_scattered_{sname}", 2 * 4 * whole,
+                lambda k, chunk=chunk, scatter=scatter, whole=whole: probes.cnnmem_probe_chunk_copy(
+                    a[k].data_ptr(), b[k].data_ptr(), whole, chunk, scatter, stream()))
+    torch.cuda.synchronize()
+    return ops, {}
+
+
 def build_config_ops(torch, cm, wl, rl, only):
     """Every tensor the five benchmark configurations name, one launch each: the pooling layers in both layouts
     (config 4: max and avg), the transforms in both directions (config 3: on the pooled shapes too), the
@@ -693,7 +745,8 @@ def main():
     only = set(filter(None, args.only.split(",")))
     builders = {"largest": build_ops, "table1": build_table1_ops, "softmax_sweep": build_softmax_sweep_ops,
                 "layout_policy": build_layout_policy_ops, "layouts": build_layouts_ops,
-                "backward": build_backward_ops, "shapes": build_shapes_ops, "configs": build_config_ops}
+                "backward": build_backward_ops, "shapes": build_shapes_ops, "configs": build_config_ops,
+                "access_patterns": build_access_pattern_ops}
     if args.workload == "largest":
         ops, host_inputs = build_ops(torch, cm, wl, rl, only, args.dtype)
     else:

@@ -16,6 +16,9 @@ SOURCES = ["api.hip", "transform.hip", "permute.hip", "pool.hip", "softmax.hip",
 HOOKS_LIB_PATH = os.path.join(HERE, "libcnnmem_testhooks.so")
 HOOKS_SOURCES = ["testhooks.hip"]
 HOOKS_NEEDS = ["permute.hip", "transform.hip"]
+# memory-system probes of `bench.py --workload access_patterns` (measurement support, a library of their own)
+PROBES_LIB_PATH = os.path.join(HERE, "libcnnmem_probes.so")
+PROBES_SOURCES = ["probes.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -46,7 +49,7 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
     """Compile every HIP source (in parallel) and link ``paper_1610_03618_amd/libcnnmem.so``."""
     os.makedirs(BUILD_DIR, exist_ok=True)
     pending = []
-    for name in SOURCES + HOOKS_SOURCES:
+    for name in SOURCES + HOOKS_SOURCES + PROBES_SOURCES:
         obj = os.path.join(BUILD_DIR, os.path.splitext(name)[0] + ".o")
         cmd = [HIPCC] + FLAGS + ["-I", INCLUDE, "-I", CSRC, "-c", os.path.join(CSRC, name), "-o", obj]
         pending.append((cmd, obj))
@@ -66,7 +69,8 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
     def obj_of(name):
         return os.path.join(BUILD_DIR, os.path.splitext(name)[0] + ".o")
 
-    for sources, path in ((SOURCES, LIB_PATH), (HOOKS_SOURCES + HOOKS_NEEDS, HOOKS_LIB_PATH)):
+    for sources, path in ((SOURCES, LIB_PATH), (HOOKS_SOURCES + HOOKS_NEEDS, HOOKS_LIB_PATH),
+                          (PROBES_SOURCES, PROBES_LIB_PATH)):
         link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", "-Wl,--no-undefined"] + \
             [obj_of(n) for n in sources] + ["-o", path]
         if verbose:
