@@ -455,55 +455,89 @@ __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
     // store starts on a 128-byte line of dst (no line is written in two pieces).
     if constexpr (OY > 1 && KH != 0) {
         constexpr int ROWS = (OY - 1) * SH + KH;
+        constexpr int MAXIT = 4;                     // blocks of OY outputs a lane may hold in registers
         const int nblk = (int)div_blk.d;             // row blocks per plane
         const int n_items = planes * nblk * g.Wo;
         const int r_last = r_hi - 1;                 // rows of the slab: [r_lo, r_hi)
-        for (int it = (int)threadIdx.x; it < n_items; it += kSlabThreads) {
-            const int pb = (int)fd_div((uint32_t)it, div_wo);      // plane * nblk + block
-            const int j = it - pb * g.Wo;
-            const int pl = (int)fd_div((uint32_t)pb, div_blk);
-            const int blk = pb - pl * nblk;
-            const int il0 = blk * OY;                               // first output row of the lane, strip-local
-            const int rb = (i0 + il0) * SH - g.ph;
-            const int qb = j * SW - g.pw;
-            const int base = lds0 + pl * plane_in;
-            // Rows and columns are clamped into the slab: a clamped tap of a real output lies in the same
-            // window (so the maximum is unchanged; the average drops it by a select), and the rows of outputs
-            // past the strip's end only feed results that are never stored.
-            int qc[KW];
-            bool q_in[KW];
+        // Results stay in registers until every lane has finished reading the slab, are then parked in the slab
+        // in output order, and leave as one contiguous run of line-aligned wavefront stores.  Stored straight
+        // from the lanes, OY row pieces per wavefront, the outputs cost 1.15x their bytes in write traffic
+        // (counters, 3x3/s1/p1 on 64x256x56x56) and the kernel 57 % of peak (68 % staged; the average 56 -> 62 %).
+        // Stride 1 only: with two rows per lane at stride 2 the staging costs more than the 9 % of extra write
+        // traffic it removes (3x3/s2/p1 average on 256x64x112x112: 71 % of peak direct, 68 % staged).
+        const bool staged = SH == 1 && n_items <= MAXIT * kSlabThreads && n_out <= kSlabFloats;
+        float res[MAXIT][OY];
 #pragma unroll
-            for (int x = 0; x < KW; ++x) {
-                const int q = qb + x;
-                q_in[x] = !PADDED || (q >= 0 && q < g.W);
-                qc[x] = !PADDED ? q : (q < 0 ? 0 : (q < g.W ? q : g.W - 1));
-            }
-            float hr[ROWS];
-#pragma unroll
-            for (int y = 0; y < ROWS; ++y) {
-                const int r = rb + y;
-                int rc = r < r_last ? r : r_last;
-                if (PADDED) rc = rc > r_lo ? rc : r_lo;
-                const float* row = slab + base + rc * g.W;
-                float acc = Acc<MODE>::identity();
+        for (int round = 0; round < MAXIT; ++round) {
+            for (int it = (int)threadIdx.x + round * kSlabThreads; it < n_items;
+                 it += staged ? n_items : kSlabThreads) {          // staged: one block per round
+                const int pb = (int)fd_div((uint32_t)it, div_wo);      // plane * nblk + block
+                const int j = it - pb * g.Wo;
+                const int pl = (int)fd_div((uint32_t)pb, div_blk);
+                const int blk = pb - pl * nblk;
+                const int il0 = blk * OY;                               // first output row of the lane, strip-local
+                const int rb = (i0 + il0) * SH - g.ph;
+                const int qb = j * SW - g.pw;
+                const int base = lds0 + pl * plane_in;
+                // Rows and columns are clamped into the slab: a clamped tap of a real output lies in the same
+                // window (so the maximum is unchanged; the average drops it by a select), and the rows of outputs
+                // past the strip's end only feed results that are never stored.
+                int qc[KW];
+                bool q_in[KW];
 #pragma unroll
                 for (int x = 0; x < KW; ++x) {
-                    const float v = row[qc[x]];
-                    if (MODE == CNNMEM_POOL_MAX) acc = fmaxf(acc, v);
-                    else acc += q_in[x] ? v : 0.f;
+                    const int q = qb + x;
+                    q_in[x] = !PADDED || (q >= 0 && q < g.W);
+                    qc[x] = !PADDED ? q : (q < 0 ? 0 : (q < g.W ? q : g.W - 1));
                 }
-                if (MODE != CNNMEM_POOL_MAX && PADDED && (r < 0 || r >= g.H)) acc = 0.f;
-                hr[y] = acc;
+                float hr[ROWS];
+#pragma unroll
+                for (int y = 0; y < ROWS; ++y) {
+                    const int r = rb + y;
+                    int rc = r < r_last ? r : r_last;
+                    if (PADDED) rc = rc > r_lo ? rc : r_lo;
+                    const float* row = slab + base + rc * g.W;
+                    float acc = Acc<MODE>::identity();
+#pragma unroll
+                    for (int x = 0; x < KW; ++x) {
+                        const float v = row[qc[x]];
+                        if (MODE == CNNMEM_POOL_MAX) acc = fmaxf(acc, v);
+                        else acc += q_in[x] ? v : 0.f;
+                    }
+                    if (MODE != CNNMEM_POOL_MAX && PADDED && (r < 0 || r >= g.H)) acc = 0.f;
+                    hr[y] = acc;
+                }
+                float* out = dst + out0 + (size_t)(pl * rows_out + il0) * g.Wo + j;
+#pragma unroll
+                for (int k = 0; k < OY; ++k) {
+                    float acc = hr[k * SH];
+#pragma unroll
+                    for (int y = 1; y < KH; ++y) acc = Acc<MODE>::op(acc, hr[k * SH + y]);
+                    acc = Acc<MODE>::finish(acc, (float)(KH * KW));
+                    if (staged) res[round][k] = acc;
+                    else if (il0 + k < rows_out) st1_stream(out + (size_t)k * g.Wo, acc);
+                }
             }
-            float* out = dst + out0 + (size_t)(pl * rows_out + il0) * g.Wo + j;
+            if (!staged) return;                     // the unstaged walk did every block in its first round
+        }
+        __syncthreads();                             // every tap has been read: the slab can take the results
 #pragma unroll
-            for (int k = 0; k < OY; ++k) {
-                float acc = hr[k * SH];
+        for (int round = 0; round < MAXIT; ++round) {
+            const int it = (int)threadIdx.x + round * kSlabThreads;
+            if (it < n_items) {
+                const int pb = (int)fd_div((uint32_t)it, div_wo);
+                const int j = it - pb * g.Wo;
+                const int pl = (int)fd_div((uint32_t)pb, div_blk);
+                const int il0 = (pb - pl * nblk) * OY;
 #pragma unroll
-                for (int y = 1; y < KH; ++y) acc = Acc<MODE>::op(acc, hr[k * SH + y]);
-                if (il0 + k < rows_out) st1_stream(out + (size_t)k * g.Wo, Acc<MODE>::finish(acc, (float)(KH * KW)));
+                for (int k = 0; k < OY; ++k)
+                    if (il0 + k < rows_out) slab[(pl * rows_out + il0 + k) * g.Wo + j] = res[round][k];
             }
         }
+        __syncthreads();
+        const int lead_s = (int)(((reinterpret_cast<uintptr_t>(dst) >> 2) + out0) & 31);
+        for (int o = (int)threadIdx.x - lead_s; o < n_out; o += kSlabThreads)
+            if (o >= 0) st1_stream(dst + out0 + o, slab[o]);
         return;
     }
     const int lead = (int)(((reinterpret_cast<uintptr_t>(dst) >> 2) + out0) & 31);
