@@ -69,3 +69,63 @@ def test_bench_has_no_cpu_fallback():
     assert r.returncode == 2
     assert "no CPU fallback" in r.stderr
     assert r.stdout.strip() == ""
+
+
+# ---- HBM traffic tables under profiles/ -------------------------------------------------------------------
+
+def _traffic_tables():
+    import glob
+    return sorted(glob.glob(os.path.join(ROOT, "profiles", "hbm_traffic_*.json")))
+
+
+def test_traffic_tables_are_consistent_with_their_counters():
+    """Every `traffic` figure that bench.py may print equals FETCH_SIZE / factor + WRITE_SIZE / factor (KiB -> bytes)
+    of the same table, and the factors are the calibration copy's counters over its known size."""
+    import json
+    tables = _traffic_tables()
+    assert tables, "profiles/ holds no counter summary"
+    for path in tables:
+        t = json.load(open(path))
+        cal = t["calibration"]
+        assert abs(cal["fetch_kib"] / cal["copy_kib_each_way"] - cal["fetch_factor"]) < 1e-5
+        assert abs(cal["write_kib"] / cal["copy_kib_each_way"] - cal["write_factor"]) < 1e-5
+        assert t["ops"], path
+        for name, op in t["ops"].items():
+            want = (op["fetch_kib"] / cal["fetch_factor"] + op["write_kib"] / cal["write_factor"]) * 1024
+            assert abs(op["traffic"] - want) <= 1e-3 * want, (path, name)
+            assert abs(op["traffic"] - (op["read_bytes"] + op["write_bytes"])) <= 2, (path, name)
+            assert abs(op["traffic_over_algorithmic"] - op["traffic"] / op["alg_bytes"]) < 1e-3, (path, name)
+
+
+def test_headline_traffic_table_matches_the_markdown_summary_and_the_byte_model():
+    import json
+    t = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic_largest_configs.json")))
+    assert set(t["ops"]) == {"transform_nchw_to_chwn", "transform_chwn_to_nchw", "pool_max_nchw", "pool_max_chwn",
+                             "pool_avg_nchw", "pool_avg_chwn", "softmax"}
+    assert t["ops"]["transform_nchw_to_chwn"]["alg_bytes"] == rl.transform_bytes(128, 96, 55, 55)
+    assert t["ops"]["pool_max_chwn"]["alg_bytes"] == rl.pool_bytes(64, 64, 224, 224, 2, 2, 2, 2)
+    assert t["ops"]["softmax"]["alg_bytes"] == rl.softmax_bytes(4096, 21841)
+    md = open(os.path.join(ROOT, "profiles", "bench_largest_configs_hbm_traffic.md")).read()
+    rows = {}
+    for line in md.splitlines():
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) == 9 and cells[0] in t["ops"]:
+            rows[cells[0]] = cells
+    assert set(rows) == set(t["ops"])
+    for name, cells in rows.items():
+        op = t["ops"][name]
+        assert abs(float(cells[2]) - op["fetch_kib"]) < 0.06 and abs(float(cells[3]) - op["write_kib"]) < 0.06
+        assert abs(float(cells[6]) - op["traffic"] / 1e6) < 0.006
+        assert abs(float(cells[8]) - op["traffic_over_algorithmic"]) < 1e-4
+    assert t["sources_digest"] in md
+
+
+def test_traffic_is_only_reported_for_the_sources_it_was_measured_on(tmp_path):
+    import json
+    from paper_1610_03618_amd import counters
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_largest_configs.json")
+    t = json.load(open(path))
+    assert counters.load_for(path, t["sources_digest"])["ops"] == t["ops"]
+    assert counters.load_for(path, "0" * 16) is None
+    assert counters.load_for(str(tmp_path / "missing.json"), t["sources_digest"]) is None
+    assert len(counters.sources_digest()) == 16
