@@ -28,8 +28,6 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
 ]
-# extra compiler options for A/B builds, e.g. CNNMEM_EXTRA_FLAGS="-DCNNMEM_STORE_SC1=0"
-FLAGS += os.environ.get("CNNMEM_EXTRA_FLAGS", "").split()
 BUILD_DIR = os.path.join(HERE, "_build")
 
 

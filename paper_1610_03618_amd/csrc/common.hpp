@@ -96,11 +96,7 @@ __host__ __device__ __forceinline__ uint32_t xcd_contiguous_tile(uint32_t block,
 // Every tensor here is read once and written once, so loads and stores carry the
 // non-temporal hint (the `nt` bit of global_load/global_store): lines are not kept
 // in L2 / the memory-side cache at the expense of data that will be reused.  On
-// MI355X a plain float4 copy gains 6-8 % from it.  CNNMEM_STREAM_NT=0 builds
-// without the hint (A/B measurements).
-#ifndef CNNMEM_STREAM_NT
-#define CNNMEM_STREAM_NT 1
-#endif
+// MI355X a plain float4 copy gains 6-8 % from it.
 typedef float v4f_t __attribute__((ext_vector_type(4)));
 typedef float v2f_t __attribute__((ext_vector_type(2)));
 
@@ -119,95 +115,51 @@ typedef float v2f_t __attribute__((ext_vector_type(2)));
 // of more than 64 bits must be followed by two wait states before a vector ALU instruction overwrites
 // its data registers (the compiler inserts them for its own stores); without them a few lanes stored
 // the next loop index instead of their result.  The address form `off` reads no scalar registers, and
-// stores of up to 64 bits have no such hazard.  CNNMEM_STORE_SC1=0 builds with the compiler's own
-// non-temporal stores everywhere (A/B measurements).
-#ifndef CNNMEM_STORE_SC1
-#define CNNMEM_STORE_SC1 1
-#endif
+// stores of up to 64 bits have no such hazard.
 
 __device__ __forceinline__ float4 ld4_stream(const float* p) {
-#if CNNMEM_STREAM_NT
     const v4f_t v = __builtin_nontemporal_load(reinterpret_cast<const v4f_t*>(p));
-#else
-    const v4f_t v = *reinterpret_cast<const v4f_t*>(p);
-#endif
     return make_float4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ void st4_stream(float* p, const float4& a) {
     const v4f_t v = {a.x, a.y, a.z, a.w};
-#if CNNMEM_STREAM_NT
     __builtin_nontemporal_store(v, reinterpret_cast<v4f_t*>(p));
-#else
-    *reinterpret_cast<v4f_t*>(p) = v;
-#endif
 }
 // 128-bit accesses at any 4-byte aligned address (gfx950 global memory accepts dword-aligned
 // multi-dword accesses; the type's alignment tells the compiler, which picks the instruction).
 typedef v4f_t v4f_unaligned_t __attribute__((aligned(4)));
 __device__ __forceinline__ float4 ld4u_stream(const float* p) {
-#if CNNMEM_STREAM_NT
     const v4f_unaligned_t v = __builtin_nontemporal_load(reinterpret_cast<const v4f_unaligned_t*>(p));
-#else
-    const v4f_unaligned_t v = *reinterpret_cast<const v4f_unaligned_t*>(p);
-#endif
     return make_float4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ void st4u_stream(float* p, const float4& a) {
     const v4f_unaligned_t v = {a.x, a.y, a.z, a.w};
-#if CNNMEM_STREAM_NT
     __builtin_nontemporal_store(v, reinterpret_cast<v4f_unaligned_t*>(p));
-#else
-    *reinterpret_cast<v4f_unaligned_t*>(p) = v;
-#endif
 }
 __device__ __forceinline__ void st2_stream(float* p, float a, float b) {
     const v2f_t v = {a, b};
-#if CNNMEM_STREAM_NT
     __builtin_nontemporal_store(v, reinterpret_cast<v2f_t*>(p));
-#else
-    *reinterpret_cast<v2f_t*>(p) = v;
-#endif
 }
 __device__ __forceinline__ float ld1_stream(const float* p) {
-#if CNNMEM_STREAM_NT
     return __builtin_nontemporal_load(p);
-#else
-    return *p;
-#endif
 }
 __device__ __forceinline__ void st1_stream(float* p, float a) {
-#if CNNMEM_STREAM_NT
     __builtin_nontemporal_store(a, p);
-#else
-    *p = a;
-#endif
 }
 
 // 128-bit (16-byte aligned) and 64-bit write-through stores, see above
 __device__ __forceinline__ void st4_through(float* p, const float4& a) {
-#if CNNMEM_STORE_SC1 && CNNMEM_STREAM_NT
     const v4f_t v = {a.x, a.y, a.z, a.w};
     asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v));
-#else
-    st4_stream(p, a);
-#endif
 }
 // the same at any 4-byte aligned address
 __device__ __forceinline__ void st4u_through(float* p, const float4& a) {
-#if CNNMEM_STORE_SC1 && CNNMEM_STREAM_NT
     const v4f_t v = {a.x, a.y, a.z, a.w};
     asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v));
-#else
-    st4u_stream(p, a);
-#endif
 }
 __device__ __forceinline__ void st2_through(float* p, float a, float b) {
-#if CNNMEM_STORE_SC1 && CNNMEM_STREAM_NT
     const v2f_t v = {a, b};
     asm volatile("global_store_dwordx2 %0, %1, off sc1 nt" : : "v"(p), "v"(v));
-#else
-    st2_stream(p, a, b);
-#endif
 }
 
 // Occupancy throttle.  On tensors of hundreds of MB, HBM throughput on MI355X is

@@ -41,11 +41,7 @@ __device__ __forceinline__ void st16_stream(uint16_t* p, u32x4 v) {
 }
 // write-through 128-bit store (device scope on top of the non-temporal hint; see st4_through)
 __device__ __forceinline__ void st16_through(uint16_t* p, u32x4 v) {
-#if CNNMEM_STORE_SC1 && CNNMEM_STREAM_NT
     asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v));
-#else
-    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
-#endif
 }
 __device__ __forceinline__ void st16u_stream(uint16_t* p, u32x4 v) {
     const u32x4_unaligned w = v;
