@@ -199,3 +199,25 @@ def test_binding_refuses_tensors_smaller_than_the_call_needs():
     # large enough: the next check (CPU memory is refused) is reached
     with pytest.raises(ValueError, match="GPU memory"):
         cm.cnnmem_transform(enough, enough, 2, 2, 2, 2, cm.NCHW, cm.CHWN, stream=0)
+
+
+def test_probe_library_is_separate_and_validates_on_the_host():
+    """The memory-system probes of `bench.py --workload access_patterns` live in a library of their own and
+    refuse arguments that would address past the buffers before they launch anything."""
+    probes = ctypes.CDLL(hip_build.PROBES_LIB_PATH)
+    product = ctypes.CDLL(hip_build.LIB_PATH)
+    p, i, ll = ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong
+    probes.cnnmem_probe_tile_pattern.argtypes = [p, p, ll, ll, i, i, i, i, p]
+    probes.cnnmem_probe_chunk_copy.argtypes = [p, p, ll, i, i, p]
+    for name in ("cnnmem_probe_tile_pattern", "cnnmem_probe_chunk_copy"):
+        assert not hasattr(product, name)
+    tile = probes.cnnmem_probe_tile_pattern
+    assert tile(None, FAKE, 1024, 128, 32, 128, 1, 0, None) == INVALID            # null pointer
+    assert tile(FAKE, FAKE + 4096, 1024, 128, 32, 64, 1, 0, None) == INVALID      # tile of 2048 floats: no kernel
+    assert tile(FAKE, FAKE + 4096, 1024, 100, 32, 128, 1, 0, None) == INVALID     # images not a multiple of the tile
+    assert tile(FAKE, FAKE + 4096, 16, 128, 32, 128, 1, 0, None) == INVALID       # fewer rows than one tile
+    assert tile(FAKE + 4, FAKE + 4096, 1024, 128, 32, 128, 1, 0, None) == INVALID  # misaligned
+    chunk = probes.cnnmem_probe_chunk_copy
+    assert chunk(FAKE, FAKE + 4096, 1000, 4096, 3, None) == INVALID               # not whole chunks
+    assert chunk(FAKE, FAKE + 4096, 1024, 24, 3, None) == INVALID                 # chunk not a multiple of 16 bytes
+    assert chunk(FAKE, None, 1024, 4096, 3, None) == INVALID
