@@ -198,7 +198,8 @@ int launch_vec4(const float* src, float* dst, long long R, long long S, hipStrea
     const long long tiles = tiles_r * tiles_s;
     if (tiles > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
     constexpr size_t lds_bytes = sizeof(float) * TS * (TR + 4);
-    static_assert(lds_bytes <= 65536, "fits the default per-workgroup LDS limit");
+    // above the default per-workgroup limit (gfx950 has 160 KB): opt in, once per device
+    if (lds_bytes > 65536 && !allow_large_lds<&transpose_vec4_kernel<TR, TS, THREADS>>(lds_bytes)) return CNNMEM_ERR_RUNTIME;
     hipLaunchKernelGGL((transpose_vec4_kernel<TR, TS, THREADS>), dim3((unsigned)tiles), dim3(THREADS), lds_bytes, st,
                        src, dst, R, S, (uint32_t)tiles_s);
     return launch_status();
@@ -210,7 +211,7 @@ int launch_swz(const float* src, float* dst, long long R, long long S, hipStream
     const long long tiles = tiles_r * tiles_s;
     if (tiles > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
     constexpr size_t lds_bytes = sizeof(float) * TS * TR;
-    static_assert(lds_bytes <= 65536, "fits the default per-workgroup LDS limit");
+    if (lds_bytes > 65536 && !allow_large_lds<&transpose_swz_kernel<TR, TS, THREADS>>(lds_bytes)) return CNNMEM_ERR_RUNTIME;
     hipLaunchKernelGGL((transpose_swz_kernel<TR, TS, THREADS>), dim3((unsigned)tiles), dim3(THREADS), lds_bytes, st,
                        src, dst, R, S, (uint32_t)tiles_r, (uint32_t)tiles_s, order);
     return launch_status();
@@ -232,8 +233,16 @@ enum Shape {
     kShortRows256,  // swz 128 x 32, r-tiles fastest: CHWN -> NCHW from 256 images on (256x512x14x14: 72.0 %)
     kLongRowsRagged,   // vec4 128 x 64, 512 lanes: NCHW -> CHWN, 65..127 images that are not a multiple of 32
     kShortRowsRagged,  // swz 32 x 128: CHWN -> NCHW, the same batches (one tile spans every image)
+    kLongRowsSmall,    // vec4 128 x 256, 1024 lanes, 135 KB of LDS: NCHW -> CHWN, 65..128 images, at most 24 MB
+    kShortRowsSmall,   // swz 256 x 128, 1024 lanes, 128 KB of LDS: CHWN -> NCHW, the same tensors
     kNumShapes
 };
+
+// tiles of 256 along the long side (the short side fits one tile): between 128 and 256 of them
+bool fat_tiles_fill_one_round(long long long_side) {
+    const long long tiles = ceil_div64(long_side, 256);
+    return tiles >= 128 && tiles <= 256;
+}
 
 Shape choose_shape(long long R, long long S) {
     if (R <= 16) return kRows16;
@@ -246,11 +255,20 @@ Shape choose_shape(long long R, long long S) {
         // group of a few images that walks the whole tensor for them, and the more CHWN rows a tile holds, the
         // fewer lines it shares with its neighbours (100x64x57x57: 55.8 % with 128 x 32 tiles, 65 % with 128 x 64)
         if (R > 64 && R < 128 && R % 32 != 0) return kLongRowsRagged;
+        // Small tensors: when fat tiles (128 KB in flight each) make exactly one round of workgroups that keeps at
+        // least half of the 256 CUs busy, they beat many small ones (128x256x13x13, 22 MB, 169 tiles: 57 -> 69 % of
+        // peak back to back, level with a copy of the same bytes; 36 MB and more: no gain; 5 MB, 36 tiles: slower)
+        if (R > 64 && R <= 128 && fat_tiles_fill_one_round(S)) return kLongRowsSmall;
+        // NCHW rows whose pitch is a multiple of 8 cache lines start on the same few memory channels: 128 of them
+        // read at one column offset collide, 32 rows x 512 B spread (128x256x27x27: 64.7 -> 70.5 % of peak;
+        // 128x96x55x55, pitch 9075 lines, prefers the 128-row tile: 75.6 % against 74.1 %)
+        if (R > 64 && S % 256 == 0) return kLongRows256;
         if (R > 64) return kLongRows128;
         if (R == 64) return kLongRows64;
     } else if (R >= 4 * S) {                        // many short source rows: CHWN -> NCHW with S images
         if (S >= 256) return kShortRows256;
         if (S > 64 && S < 128 && S % 32 != 0) return kShortRowsRagged;   // 100x64x57x57: 46 % -> 63 %
+        if (S > 64 && S <= 128 && fat_tiles_fill_one_round(R)) return kShortRowsSmall;   // 128x256x13x13: 58.6 -> 69 %
         if (S > 64) return kShortRows128;
         if (S >= 48) return kShortRows64;
     }
@@ -283,6 +301,8 @@ int launch_transpose2d(const float* src, float* dst, long long R, long long S, h
         case kShortRows256: return launch_swz<128, 32, 1024>(src, dst, R, S, st, 2);
         case kLongRowsRagged: return launch_vec4<128, 64, 512>(src, dst, R, S, st);
         case kShortRowsRagged: return launch_swz<32, 128, 1024>(src, dst, R, S, st, 0);
+        case kLongRowsSmall: return launch_vec4<128, 256, 1024>(src, dst, R, S, st);
+        case kShortRowsSmall: return launch_swz<256, 128, 1024>(src, dst, R, S, st, 0);
         default: return launch_vec4<64, 64>(src, dst, R, S, st);
     }
 }

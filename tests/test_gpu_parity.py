@@ -70,7 +70,7 @@ def test_transform_matches_oracle_bit_for_bit(shape):
     assert same_bits(host(same), x)
 
 
-@pytest.mark.parametrize("tile", list(range(13)))
+@pytest.mark.parametrize("tile", list(range(15)))
 def test_transform_every_tile_shape(tile, monkeypatch):
     monkeypatch.setenv("CNNMEM_TRANSFORM_TILE", str(tile))
     for (N, C, H, W) in [(128, 3, 9, 12), (20, 5, 7, 4), (260, 1, 33, 4)]:
