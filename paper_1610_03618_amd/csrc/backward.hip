@@ -478,14 +478,14 @@ struct BwdSlabPlan {
 
 // streams floats [lo, hi) of `p` (16-byte aligned base, `total` floats long) into dst_lds so that
 // element e sits at dst_lds[e - a_lo]; returns a_lo, the aligned start.  All loads unconditional.
-template <int VEC>
+template <int VEC, int THREADS = kBwdThreads>
 __device__ __forceinline__ size_t stream_to_lds(const float* __restrict__ p, size_t lo, size_t hi, size_t total,
                                                 float* dst_lds) {
     const size_t mask = (reinterpret_cast<uintptr_t>(p) & 127u) == 0 ? 31 : 3;
     const size_t a_lo = lo & ~mask;
     const int nvec = (int)((hi - a_lo + 3) >> 2);
     const size_t a_last = (total - 4) & ~(size_t)3;            // total >= 4 (dispatch)
-    // rounds of kBwdThreads vectors; a round past the end of the part is skipped by the whole
+    // rounds of THREADS vectors; a round past the end of the part is skipped by the whole
     // workgroup (uniform), inside a round every load is unconditional
     float4 v[VEC];
     if (a_lo + 4 * (size_t)(nvec - 1) <= a_last) {
@@ -494,29 +494,29 @@ __device__ __forceinline__ size_t stream_to_lds(const float* __restrict__ p, siz
         const float* base = p + a_lo;
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
-            if (k * kBwdThreads >= nvec) break;
-            const uint32_t q = threadIdx.x + k * kBwdThreads;
+            if (k * THREADS >= nvec) break;
+            const uint32_t q = threadIdx.x + k * THREADS;
             v[k] = ld4_stream(base + 4u * (q < (uint32_t)nvec ? q : 0u));
         }
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
-            if (k * kBwdThreads >= nvec) break;
-            const uint32_t q = threadIdx.x + k * kBwdThreads;
+            if (k * THREADS >= nvec) break;
+            const uint32_t q = threadIdx.x + k * THREADS;
             if (q < (uint32_t)nvec) *reinterpret_cast<float4*>(dst_lds + 4 * q) = v[k];
         }
         return a_lo;
     }
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
-        if (k * kBwdThreads >= nvec) break;
-        const int q = threadIdx.x + k * kBwdThreads;
+        if (k * THREADS >= nvec) break;
+        const int q = threadIdx.x + k * THREADS;
         size_t a = a_lo + 4 * (size_t)(q < nvec ? q : 0);
         a = a <= a_last ? a : a_last;
         v[k] = ld4_stream(p + a);
     }
     for (int k = 0; k < VEC; ++k) {
-        if (k * kBwdThreads >= nvec) break;
-        const int q = threadIdx.x + k * kBwdThreads;
+        if (k * THREADS >= nvec) break;
+        const int q = threadIdx.x + k * THREADS;
         const size_t a = a_lo + 4 * (size_t)q;
         if (q < nvec && a <= a_last) *reinterpret_cast<float4*>(dst_lds + 4 * q) = v[k];
         if (q < nvec && a > a_last)
@@ -729,6 +729,154 @@ __global__ __launch_bounds__(kBwdThreads) void pool_bwd_nchw_slab_kernel(
     }
 }
 
+// ---- NCHW average, 3x3 / stride 2 without padding (the overlapped pooling of the paper's networks) -------
+// The slab kernel above is bound by instruction issue, not by memory: a division and a dozen clamps per element
+// on the vector side, and as much loop and address arithmetic on the scalar side.  Here
+//   * the lanes of a wavefront are the columns of one row (of 64 / LW rows for planes narrower than 33 columns,
+//     LW the next power of two), so what depends on the column is computed once per lane;
+//   * what depends on the row is computed once per workgroup, 64 rows per instruction, and left in LDS as a
+//     table of descriptors (LDS indices): the inner loop reads a descriptor, adds the lane's column and goes.
+//     Window rows that do not exist point at a row of zeros, results that must not be kept at a trash row: the
+//     loop has no conditions (14 vector, 5 scalar and 5 LDS instructions per pair of rows);
+//   * a lane gathers one pair of input rows (2u, 2u+1) of its column: both rows lie in window row u, the even one
+//     also in u-1, so four gradients serve two elements.
+// The same structure for the maximum (a lane per window, first maximum of nine taps in LDS, gradient added to
+// that element of the staged result, even window rows and columns before odd ones) measured level with the slab
+// kernel (65 us on 128x96x55x55) and was not kept.
+constexpr int kRowThreads = 256;
+constexpr int kRowGyVecs = 3;               // float4 per lane a workgroup's gradient rows may take
+struct RowsLds {                // LDS layout in floats; the staged result starts at 0
+    int gy_at;                  // gradient rows
+    int zero_at, trash_at;      // a row of zeros (Wo + 35 floats), a row nobody reads (W + 4 floats)
+    int desc_at;                // descriptors, four ints each
+    int ntab;                   // descriptors: row pairs, whole rounds of the workgroup
+    int lanes_per_row;          // LW
+};
+
+__global__ __launch_bounds__(kRowThreads) void pool_bwd_avg_nchw_k3s2_kernel(
+    const float* __restrict__ ddst, float* __restrict__ dsrc, PoolGeom g, BwdSlabPlan plan, RowsLds at, FastDiv div_pairs,
+    FastDiv div_strips) {
+    constexpr int kWaves = kRowThreads / 64;
+    float* slab = reinterpret_cast<float*>(bwd_dyn_lds);
+    const int H = g.H, W = g.W, Ho = g.Ho, Wo = g.Wo;
+    const int plane_in = H * W, plane_out = Ho * Wo;
+    const uint32_t total_planes = (uint32_t)plan.total_planes;         // the tensors have fewer than 2^31 elements (launcher)
+    // strips of one plane share gradient rows: neighbours on one XCD
+    const uint32_t tile = plan.strips == 1 ? blockIdx.x : xcd_contiguous_tile(blockIdx.x, gridDim.x);
+    uint32_t p0;
+    int planes, h0, rows;
+    if (plan.strips == 1) {
+        p0 = tile * (uint32_t)plan.planes_per_wg;
+        const uint32_t left = total_planes - p0;
+        planes = left < (uint32_t)plan.planes_per_wg ? (int)left : plan.planes_per_wg;
+        h0 = 0;
+        rows = H;
+    } else {
+        p0 = fd_div(tile, div_strips);
+        planes = 1;
+        h0 = (int)(tile - p0 * (uint32_t)plan.strips) * plan.rows_per_wg;        // even (launcher)
+        rows = H - h0 < plan.rows_per_wg ? H - h0 : plan.rows_per_wg;
+    }
+    // window rows that touch input rows [h0, h0 + rows): at least one (H >= 3, h0 even)
+    const int i_lo = h0 >= 2 ? (h0 >> 1) - 1 : 0;
+    const int i_hi = ((h0 + rows - 1) >> 1) < Ho - 1 ? (h0 + rows - 1) >> 1 : Ho - 1;
+    const int n_elems = planes * rows * W;
+    const uint32_t out0 = p0 * (uint32_t)plane_in + (uint32_t)(h0 * W);
+    // element o of the workgroup's run sits at stage[o], placed so that the float4 a lane stores at the end
+    // (o = 4*lane - lead) is one aligned 128-bit LDS read
+    const int lead = (int)((((uint32_t)reinterpret_cast<uintptr_t>(dsrc) >> 2) + out0) & 31u);
+    const int stage_at = lead & 3;
+    int4* desc = reinterpret_cast<int4*>(slab + at.desc_at);
+
+    // ---- gradient rows on their way: floats [lo, hi) of ddst land so that element e sits at slab[gy_at + e - a_lo],
+    // a_lo the 128-byte (else 16-byte) aligned start at or below lo; up to kRowGyVecs float4 per lane ----
+    const uint32_t total_out = total_planes * (uint32_t)plane_out;
+    const uint32_t lo = p0 * (uint32_t)plane_out + (uint32_t)(i_lo * Wo);
+    const uint32_t hi = (p0 + planes - 1) * (uint32_t)plane_out + (uint32_t)((i_hi + 1) * Wo);
+    const uint32_t a_lo = lo & ~((reinterpret_cast<uintptr_t>(ddst) & 127u) == 0 ? 31u : 3u);
+    const uint32_t nvec = (hi - a_lo + 3) >> 2;                    // <= kRowGyVecs * kRowThreads (launcher)
+    const uint32_t a_last = (total_out - 4) & ~3u;                 // the last float4 that ends inside the tensor
+    float4 v[kRowGyVecs];
+#pragma unroll
+    for (int k = 0; k < kRowGyVecs; ++k) {
+        if ((uint32_t)(k * kRowThreads) >= nvec) break;             // uniform
+        const uint32_t q = threadIdx.x + k * kRowThreads;
+        const uint32_t a = a_lo + 4 * (q < nvec ? q : nvec - 1);
+        v[k] = ld4_stream(ddst + (a <= a_last ? a : a_last));
+    }
+
+    // ---- descriptors and the row of zeros while the loads are in flight ----
+    // slab index of element (plane p0, window row 0, column 0) of ddst
+    const int gy_base = at.gy_at + (int)(p0 * (uint32_t)plane_out - a_lo);
+    const int pairs = (rows + 1) >> 1, n_pairs = planes * pairs, u0 = h0 >> 1;
+    for (int t = threadIdx.x; t < at.ntab; t += kRowThreads) {
+        const bool valid = t < n_pairs;
+        const int tv = valid ? t : 0;
+        const int pl = planes > 1 ? (int)fd_div((uint32_t)tv, div_pairs) : 0;
+        const int ul = tv - pl * pairs, u = u0 + ul;
+        const int rows_at = gy_base + pl * plane_out;
+        int4 d;
+        d.x = u >= 1 ? rows_at + (u - 1) * Wo : at.zero_at + 1;         // window row u-1 (u-1 < Ho always)
+        d.y = u < Ho ? rows_at + u * Wo : at.zero_at + 1;               // window row u
+        d.z = valid ? stage_at + (pl * rows + 2 * ul) * W : at.trash_at;
+        d.w = valid && 2 * ul + 1 < rows ? d.z + W : at.trash_at;
+        desc[t] = d;
+    }
+    for (int q = threadIdx.x; q < Wo + 3; q += kRowThreads) slab[at.zero_at + q] = 0.f;
+#pragma unroll
+    for (int k = 0; k < kRowGyVecs; ++k) {
+        if ((uint32_t)(k * kRowThreads) >= nvec) break;
+        const uint32_t q = threadIdx.x + k * kRowThreads;
+        const uint32_t a = a_lo + 4 * q;
+        if (q < nvec) {
+            if (a <= a_last) {
+                *reinterpret_cast<float4*>(slab + at.gy_at + 4 * q) = v[k];
+            } else {                                                // the float4 that crosses the end of the tensor
+                for (uint32_t e = 0; e < 4; ++e)
+                    if (a + e < total_out) slab[at.gy_at + 4 * q + e] = ddst[a + e];
+            }
+        }
+    }
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int LW = at.lanes_per_row;
+    const int SUB = 64 / LW, sub = lane / LW, step = kWaves * SUB;
+    const float inv = 1.0f / 9.0f;
+    for (int w = lane & (LW - 1); w < ((W + 63) & ~63); w += 64) {
+        // column w lies in window column (w-1)>>1 and, when even, in the next one; both are read whatever they
+        // are (the float before a row and the one after it are inside the LDS allocation)
+        const int jb = (w - 1) >> 1;
+        const bool j0_ok = jb >= 0 && jb < Wo, j1_ok = (w & 1) == 0 && jb + 1 < Wo;
+        if (w < W) {
+            for (int base = wave * SUB; base < at.ntab; base += step) {
+                const int4 d = desc[base + sub];
+                const float* pa = slab + d.x + jb;
+                const float* pb = slab + d.y + jb;
+                const float a0 = pa[0], a1 = pa[1], b0 = pb[0], b1 = pb[1];
+                const float ta = (j0_ok ? a0 : 0.f) + (j1_ok ? a1 : 0.f);
+                const float tb = (j0_ok ? b0 : 0.f) + (j1_ok ? b1 : 0.f);
+                slab[d.z + w] = (ta + tb) * inv;
+                slab[d.w + w] = tb * inv;
+            }
+        }
+    }
+    __syncthreads();
+    // the workgroup's gradients leave as one contiguous run, 128 bits per lane, each wavefront's 1 KB starting
+    // on a line of dsrc
+    const float* stage = slab + stage_at;
+    for (int o = 4 * (int)threadIdx.x - lead; o < n_elems; o += 4 * kRowThreads) {
+        float* q = dsrc + out0 + o;
+        if (o >= 0 && o + 4 <= n_elems) {
+            st4_stream(q, *reinterpret_cast<const float4*>(stage + o));
+        } else {
+            for (int e = 0; e < 4; ++e)
+                if (o + e >= 0 && o + e < n_elems) q[e] = stage[o + e];
+        }
+    }
+}
+
 // ---- NCHW, 2x2 / stride 2, no padding, even H, W a multiple of 4 ------------------------
 // Rows pair up across the whole tensor, every input belongs to exactly one window: a lane
 // takes one float4 of both rows of a pair (two windows) and the two gradients above them.
@@ -841,6 +989,84 @@ int launch_bwd_slab(const float* src, const float* ddst, float* dsrc, const Pool
     return launch_status();
 }
 
+// average, 3x3 / stride 2 without padding in NCHW: whole planes per workgroup, or strips of an even number of rows
+int launch_bwd_avg_k3s2(const float* ddst, float* dsrc, const PoolGeom& g, hipStream_t st) {
+    constexpr int kWaves = kRowThreads / 64;
+    const long long planes = (long long)g.N * g.C;
+    const long long plane_in = (long long)g.H * g.W, plane_out = (long long)g.Ho * g.Wo;
+    // the streamed and the staged part may start up to 31 floats before their first element and are padded to float4
+    auto part = [](long long floats) { return (long long)((floats + 32 + 3) / 4 * 4); };
+    auto round_up = [](long long v, long long m) { return (v + m - 1) / m * m; };
+    int lanes_per_row = 64;
+    while (lanes_per_row / 2 >= g.W) lanes_per_row /= 2;
+    const long long step = kWaves * (64 / lanes_per_row);          // row pairs per round of the workgroup
+    // LDS layout for a staged result of out_f floats, gy_f gradient floats and `tasks` row pairs; the floats needed
+    auto layout = [&](long long out_f, long long gy_f, long long tasks, RowsLds& at) {
+        long long o = part(out_f);
+        at.gy_at = (int)o; o += part(gy_f);
+        at.zero_at = (int)o; o += round_up(g.Wo + 3, 4);
+        at.trash_at = (int)o; o += round_up(g.W + 4, 4);
+        at.desc_at = (int)o;
+        at.ntab = (int)round_up(tasks, step);
+        at.lanes_per_row = lanes_per_row;
+        if (part(gy_f) > 4LL * kRowThreads * kRowGyVecs) return 1LL << 40;        // more than the lanes' registers take
+        return o + 4LL * at.ntab;
+    };
+    auto planes_need = [&](long long q, RowsLds& at) {
+        return layout(q * plane_in, q * plane_out, q * ((g.H + 1) / 2), at);
+    };
+    // a strip of r input rows (r even): its windows span at most r / 2 + 2 gradient rows
+    auto strip_need = [&](long long r, RowsLds& at) {
+        const long long gr = r / 2 + 2 < g.Ho ? r / 2 + 2 : g.Ho;
+        return layout(r * g.W, gr * g.Wo, (r + 1) / 2, at);
+    };
+    auto busy = [](long long work, long long slots) {
+        return (double)work / (double)(ceil_div64(work, slots) * slots);
+    };
+    BwdSlabPlan plan;
+    plan.total_planes = planes;
+    RowsLds at, probe;
+    long long blocks = 0, lds_floats = 0;
+    int preferred = env_int("CNNMEM_BWD_SLAB_FLOATS", 8192);
+    if (preferred < 1024 || preferred > kBwdSlabFloats) preferred = kBwdSlabFloats;
+    if (planes_need(1, probe) <= kBwdSlabFloats) {
+        // Planes per workgroup: among the counts that fit the preferred size (32 KB) and leave at least 2048
+        // workgroups, the one that keeps the lanes busiest over the passes (more LDS per workgroup means fewer
+        // wavefronts per CU: 128x96x55x55 runs in 39 us with one or two planes, in 46 us with three).
+        const long long budget = planes_need(1, probe) <= preferred ? preferred : kBwdSlabFloats;
+        long long p = 1;
+        double best = -1.0;
+        for (long long q = 1; q <= planes && planes_need(q, probe) <= budget; ++q) {
+            if (q > 1 && planes / q < 2048) break;
+            const double score = busy(q * plane_in / 4 + 1, kRowThreads) * busy(q * ((g.H + 1) / 2), step);
+            if (score > best + 0.02) { best = score; p = q; }         // prefer the smaller count on near ties
+        }
+        plan.planes_per_wg = (int)p;
+        plan.rows_per_wg = g.H;
+        plan.strips = 1;
+        blocks = ceil_div64(planes, p);
+        lds_floats = planes_need(p, at);
+    } else {
+        long long r = g.H / 2 * 2;
+        while (r > 2 && strip_need(r, probe) > preferred) r -= 2;
+        if (r < 8) {                                    // wide rows: take the large size
+            r = g.H / 2 * 2;
+            while (r > 2 && strip_need(r, probe) > kBwdSlabFloats) r -= 2;
+        }
+        if (r < 2 || strip_need(r, probe) > kBwdSlabFloats) return CNNMEM_ERR_UNSUPPORTED;
+        plan.planes_per_wg = 1;
+        plan.rows_per_wg = (int)r;
+        plan.strips = ceil_div(g.H, r);
+        blocks = planes * plan.strips;
+        lds_floats = strip_need(r, at);
+    }
+    if (blocks > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(pool_bwd_avg_nchw_k3s2_kernel, dim3((unsigned)blocks), dim3(kRowThreads),
+                       sizeof(float) * (size_t)lds_floats, st, ddst, dsrc, g, plan, at,
+                       make_fastdiv((uint32_t)((g.H + 1) / 2)), make_fastdiv((uint32_t)plan.strips));
+    return launch_status();
+}
+
 template <int MODE>
 int dispatch_pool_backward(const float* src, const float* ddst, float* dsrc, const PoolGeom& g, int layout,
                            hipStream_t st) {
@@ -879,8 +1105,13 @@ int dispatch_pool_backward(const float* src, const float* ddst, float* dsrc, con
             return launch_status();
         }
     }
-    // LDS slab: input rows, gradient rows and (maximum) one position per window share 60 KB
     const long long plane_in = (long long)g.H * g.W, plane_out = (long long)g.Ho * g.Wo;
+    if (MODE == CNNMEM_POOL_AVG && a16 && g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2 && g.ph == 0 && g.pw == 0 &&
+        plane_in * planes < (1LL << 31) && plane_out * planes >= 4 && env_int("CNNMEM_BWD_ROWS", 1) != 0) {
+        const int rc = launch_bwd_avg_k3s2(ddst, dsrc, g, st);
+        if (rc != CNNMEM_ERR_UNSUPPORTED) return rc;
+    }
+    // LDS slab: input rows, gradient rows and (maximum) one position per window share 60 KB
     if (a16 && plane_in * planes < (1LL << 40) && plane_in * planes >= 4 && plane_out * planes >= 4) {
         constexpr bool kMax = MODE == CNNMEM_POOL_MAX;
         // each streamed part may start up to 31 floats before its first element and is padded to float4
