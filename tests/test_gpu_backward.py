@@ -26,6 +26,8 @@ CASES = [  # N, C, H, W, k, s, p
     # batches that are multiples of 32: the CHWN patch kernel (ragged patches, one-cell images, several chunks)
     (32, 3, 27, 27, 3, 2, 0), (64, 2, 55, 55, 3, 2, 0), (32, 2, 13, 13, 3, 2, 0), (32, 1, 5, 5, 3, 2, 0),
     (32, 2, 64, 70, 3, 2, 0), (96, 1, 3, 3, 3, 2, 0), (32, 1, 9, 40, 3, 2, 0),
+    # thousands of small planes: several planes per workgroup in NCHW, several rows per wavefront
+    (64, 128, 13, 13, 3, 2, 0), (128, 96, 7, 7, 3, 2, 0), (64, 96, 8, 6, 3, 2, 0),
 ]
 
 
