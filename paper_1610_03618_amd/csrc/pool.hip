@@ -40,8 +40,18 @@ struct Acc {
     static __device__ __forceinline__ float4 op4(const float4& a, const float4& b) {
         return make_float4(op(a.x, b.x), op(a.y, b.y), op(a.z, b.z), op(a.w, b.w));
     }
+    // Equation 2's division by the window area.  The compiler's correctly rounded fp32 division is about ten
+    // instructions per output, which the padded NCHW kernels, bound by vector instruction issue, cannot afford.
+    // The reciprocal is formed once (loop invariant; at compile time for the fixed windows) and one residual step on
+    // the product gives the correctly rounded quotient again: q = a r, e = a - q d exactly by fma, q + e r.  The
+    // fix-up instruction restores the quotient of infinities and NaNs.
     static __device__ __forceinline__ float finish(float a, float divisor) {
-        return MODE == CNNMEM_POOL_MAX ? a : a / divisor;
+        if (MODE == CNNMEM_POOL_MAX) return a;
+        const float r = 1.0f / divisor;
+        float q = a * r;
+        const float e = __builtin_fmaf(-q, divisor, a);
+        q = __builtin_fmaf(e, r, q);
+        return __builtin_amdgcn_div_fixupf(q, divisor, a);
     }
     static __device__ __forceinline__ float4 finish4(const float4& a, float divisor) {
         return make_float4(finish(a.x, divisor), finish(a.y, divisor), finish(a.z, divisor),
