@@ -18,6 +18,11 @@ extern "C" {
  * decoding; exact for 0 <= n < 2^31, 1 <= d < 2^31; d = 0 returns 0xffffffff.  Host only. */
 CNNMEM_API unsigned cnnmem_debug_fastdiv(unsigned n, unsigned d);
 
+/* The three-instruction divider of indices inside a workgroup's LDS slab (exact for n < 2^20): the number of
+ * quotients that differ from n / d over every divisor in [1, max_d] and the numerators k*d - 1, k*d, k*d + 1
+ * below max_n; -1 when max_n > 2^20, max_d = 0 or max_d >= 2^20.  Host only. */
+CNNMEM_API long long cnnmem_debug_smalldiv_mismatches(unsigned max_n, unsigned max_d);
+
 /* Logical tile that hardware workgroup `block` of an `nblocks`-wide launch
  * processes under the XCD-contiguous ordering (a bijection on [0, nblocks)).
  * Host only. */

@@ -108,6 +108,8 @@ def test_hooks() -> ctypes.CDLL:
         lib.cnnmem_debug_canonical_permutation.restype = i
         lib.cnnmem_debug_fastdiv.argtypes = [ctypes.c_uint, ctypes.c_uint]
         lib.cnnmem_debug_fastdiv.restype = ctypes.c_uint
+        lib.cnnmem_debug_smalldiv_mismatches.argtypes = [ctypes.c_uint, ctypes.c_uint]
+        lib.cnnmem_debug_smalldiv_mismatches.restype = ctypes.c_longlong
         lib.cnnmem_debug_xcd_tile.argtypes = [ctypes.c_uint, ctypes.c_uint]
         lib.cnnmem_debug_xcd_tile.restype = ctypes.c_uint
         _hooks = lib

@@ -80,6 +80,24 @@ __host__ __device__ __forceinline__ uint32_t fd_div(uint32_t n, const FastDiv& f
     return (uint32_t)(((uint64_t)n * f.magic) >> f.shift);
 }
 
+// Exact unsigned division of a small n (n < 2^20: indices inside a workgroup's LDS slab) by a fixed d in [1, 2^20) in
+// three full-rate vector instructions; the 64-bit multiply and shift of fd_div cost about ten issue slots.
+// (n + 1/2) / d is at least 1/(2d) away from the next integer, which the two roundings (n/d * 2^-23 at most) cannot
+// bridge while n < 2^21.
+struct SmallDiv {
+    float inv;
+    uint32_t d;
+};
+__host__ __device__ __forceinline__ SmallDiv make_smalldiv(uint32_t d) {
+    SmallDiv s;
+    s.inv = 1.0f / (float)d;
+    s.d = d;
+    return s;
+}
+__host__ __device__ __forceinline__ uint32_t sd_div(uint32_t n, const SmallDiv& s) {
+    return (uint32_t)(((float)n + 0.5f) * s.inv);
+}
+
 // Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has
 // its own L2.  This maps the hardware block id to a logical tile id such that
 // consecutive logical tiles run on the same XCD (tiles that share halo rows then

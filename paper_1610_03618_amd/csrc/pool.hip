@@ -457,6 +457,11 @@ __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
     __syncthreads();
 
     // ---- pool from LDS; outputs of the workgroup are contiguous in dst ----
+    // Everything below indexes the workgroup's own slab and outputs: numbers below 2^20, divided in three
+    // instructions (sd_div) and multiplied at full rate (24-bit multiply); the padded kernels are bound by the
+    // issue of vector instructions, and 32-bit multiplies issue at a quarter of the rate.
+    const SmallDiv sd_wo = make_smalldiv(div_wo.d), sd_plane_out = make_smalldiv(div_plane_out.d),
+                   sd_blk = make_smalldiv(div_blk.d);
     const int n_out = planes * rows_out * g.Wo;     // planes > 1 implies rows_out == Ho
     const size_t out0 = (size_t)p0 * plane_out + (size_t)i0 * g.Wo;
     // LDS index of element (plane p0, row 0, col 0); may be negative when r_lo > 0
@@ -481,14 +486,14 @@ __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
         for (int round = 0; round < MAXIT; ++round) {
             for (int it = (int)threadIdx.x + round * kSlabThreads; it < n_items;
                  it += staged ? n_items : kSlabThreads) {          // staged: one block per round
-                const int pb = (int)fd_div((uint32_t)it, div_wo);      // plane * nblk + block
-                const int j = it - pb * g.Wo;
-                const int pl = (int)fd_div((uint32_t)pb, div_blk);
-                const int blk = pb - pl * nblk;
+                const int pb = (int)sd_div((uint32_t)it, sd_wo);      // plane * nblk + block
+                const int j = it - __mul24(pb, g.Wo);
+                const int pl = (int)sd_div((uint32_t)pb, sd_blk);
+                const int blk = pb - __mul24(pl, nblk);
                 const int il0 = blk * OY;                               // first output row of the lane, strip-local
                 const int rb = (i0 + il0) * SH - g.ph;
                 const int qb = j * SW - g.pw;
-                const int base = lds0 + pl * plane_in;
+                const int base = lds0 + __mul24(pl, plane_in);
                 // Rows and columns are clamped into the slab: a clamped tap of a real output lies in the same
                 // window (so the maximum is unchanged; the average drops it by a select), and the rows of outputs
                 // past the strip's end only feed results that are never stored.
@@ -506,7 +511,7 @@ __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
                     const int r = rb + y;
                     int rc = r < r_last ? r : r_last;
                     if (PADDED) rc = rc > r_lo ? rc : r_lo;
-                    const float* row = slab + base + rc * g.W;
+                    const float* row = slab + base + __mul24(rc, g.W);
                     float acc = Acc<MODE>::identity();
 #pragma unroll
                     for (int x = 0; x < KW; ++x) {
@@ -517,15 +522,18 @@ __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
                     if (MODE != CNNMEM_POOL_MAX && PADDED && (r < 0 || r >= g.H)) acc = 0.f;
                     hr[y] = acc;
                 }
-                float* out = dst + out0 + (size_t)(pl * rows_out + il0) * g.Wo + j;
 #pragma unroll
                 for (int k = 0; k < OY; ++k) {
                     float acc = hr[k * SH];
 #pragma unroll
                     for (int y = 1; y < KH; ++y) acc = Acc<MODE>::op(acc, hr[k * SH + y]);
-                    acc = Acc<MODE>::finish(acc, (float)(KH * KW));
-                    if (staged) res[round][k] = acc;
-                    else if (il0 + k < rows_out) st1_stream(out + (size_t)k * g.Wo, acc);
+                    res[round][k] = Acc<MODE>::finish(acc, (float)(KH * KW));
+                }
+                if (!staged) {
+                    float* out = dst + out0 + (size_t)(__mul24(__mul24(pl, rows_out) + il0, g.Wo) + j);
+#pragma unroll
+                    for (int k = 0; k < OY; ++k)
+                        if (il0 + k < rows_out) st1_stream(out + __mul24(k, g.Wo), res[round][k]);
                 }
             }
             if (!staged) return;                     // the unstaged walk did every block in its first round
@@ -535,13 +543,13 @@ __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
         for (int round = 0; round < MAXIT; ++round) {
             const int it = (int)threadIdx.x + round * kSlabThreads;
             if (it < n_items) {
-                const int pb = (int)fd_div((uint32_t)it, div_wo);
-                const int j = it - pb * g.Wo;
-                const int pl = (int)fd_div((uint32_t)pb, div_blk);
-                const int il0 = (pb - pl * nblk) * OY;
+                const int pb = (int)sd_div((uint32_t)it, sd_wo);
+                const int j = it - __mul24(pb, g.Wo);
+                const int pl = (int)sd_div((uint32_t)pb, sd_blk);
+                const int il0 = (pb - __mul24(pl, nblk)) * OY;
 #pragma unroll
                 for (int k = 0; k < OY; ++k)
-                    if (il0 + k < rows_out) slab[(pl * rows_out + il0 + k) * g.Wo + j] = res[round][k];
+                    if (il0 + k < rows_out) slab[__mul24(__mul24(pl, rows_out) + il0 + k, g.Wo) + j] = res[round][k];
             }
         }
         __syncthreads();
@@ -555,14 +563,14 @@ __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
         if (o < 0) continue;
         int pl = 0, rem = o;
         if (planes > 1) {
-            pl = (int)fd_div((uint32_t)o, div_plane_out);
-            rem = o - pl * plane_out;
+            pl = (int)sd_div((uint32_t)o, sd_plane_out);
+            rem = o - __mul24(pl, plane_out);
         }
-        const int il = (int)fd_div((uint32_t)rem, div_wo);
-        const int j = rem - il * g.Wo;
+        const int il = (int)sd_div((uint32_t)rem, sd_wo);
+        const int j = rem - __mul24(il, g.Wo);
         const int rb = (i0 + il) * sh - g.ph;
         const int qb = j * sw - g.pw;
-        const int base = lds0 + pl * plane_in;      // LDS index of this plane's element (0, 0)
+        const int base = lds0 + __mul24(pl, plane_in);     // LDS index of this plane's element (0, 0)
         float acc = Acc<MODE>::identity();
         if (KH != 0) {
             // With padding, a tap outside the image is read from the nearest in-image position, which
@@ -578,7 +586,7 @@ __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
                     const int q = qb + x;
                     const bool in = r_in && (!PADDED || (q >= 0 && q < g.W));
                     const int qc = !PADDED ? q : (q < 0 ? 0 : (q < g.W ? q : g.W - 1));
-                    const float v = slab[base + rc * g.W + qc];
+                    const float v = slab[base + __mul24(rc, g.W) + qc];
                     if (MODE == CNNMEM_POOL_MAX) acc = fmaxf(acc, v);
                     else acc += in ? v : 0.f;
                 }
@@ -590,7 +598,7 @@ __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
             const int r_lo = rb < 0 ? 0 : rb, r_hi = rb + kh < g.H ? rb + kh : g.H;
             const int q_lo = qb < 0 ? 0 : qb, q_hi = qb + kw < g.W ? qb + kw : g.W;
             for (int r = r_lo; r < r_hi; ++r) {
-                const int row = base + r * g.W;
+                const int row = base + __mul24(r, g.W);
 #pragma unroll 4
                 for (int q = q_lo; q < q_hi; ++q) acc = Acc<MODE>::op(acc, slab[row + q]);
             }

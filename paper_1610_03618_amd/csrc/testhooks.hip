@@ -12,6 +12,23 @@ unsigned cnnmem_debug_fastdiv(unsigned n, unsigned d) {
     return fd_div(n, make_fastdiv(d));
 }
 
+// quotients of the small-number division that differ from n / d, over every divisor in [1, max_d] and the
+// numerators k*d - 1, k*d, k*d + 1 below max_n (where a quotient can go wrong first); -1 for arguments out of range
+long long cnnmem_debug_smalldiv_mismatches(unsigned max_n, unsigned max_d) {
+    if (max_n > (1u << 20) || max_d == 0 || max_d >= (1u << 20)) return -1;
+    long long bad = 0;
+    for (unsigned d = 1; d <= max_d; ++d) {
+        const SmallDiv s = make_smalldiv(d);
+        for (unsigned m = 0; m < max_n; m += d)
+            for (int e = -1; e <= 1; ++e) {
+                const long long n = (long long)m + e;
+                if (n < 0 || n >= (long long)max_n) continue;
+                if (sd_div((unsigned)n, s) != (unsigned)n / d) ++bad;
+            }
+    }
+    return bad;
+}
+
 int cnnmem_debug_canonical_permutation(const int* dims, const int* perm, int* rank, long long* canonical_dims,
                                        int* canonical_perm) {
     if (!dims || !perm || !rank || !canonical_dims || !canonical_perm) return 1;

@@ -37,7 +37,8 @@ def test_test_hooks_live_in_a_library_of_their_own():
     hooks = ctypes.CDLL(hip_build.HOOKS_LIB_PATH)
     product = ctypes.CDLL(hip_build.LIB_PATH)
     declared = _declared_symbols("cnnmem_debug.h")
-    assert declared == {"cnnmem_debug_fastdiv", "cnnmem_debug_xcd_tile", "cnnmem_debug_canonical_permutation"}
+    assert declared == {"cnnmem_debug_fastdiv", "cnnmem_debug_smalldiv_mismatches", "cnnmem_debug_xcd_tile",
+                        "cnnmem_debug_canonical_permutation"}
     for name in declared:
         assert hasattr(hooks, name), name
         assert not hasattr(product, name), f"{name} is exported by the product library"
@@ -127,6 +128,15 @@ def test_fastdiv_is_exact():
         for n in ns:
             if 0 <= n < (1 << 31):
                 assert lib.cnnmem_debug_fastdiv(n, d) == n // d, (n, d)
+
+
+def test_small_number_divider_is_exact_where_a_quotient_can_first_go_wrong():
+    lib = cm.test_hooks()
+    # every divisor up to 4096 against every multiple of it below 2^20 and its two neighbours
+    assert lib.cnnmem_debug_smalldiv_mismatches(1 << 20, 4096) == 0
+    assert lib.cnnmem_debug_smalldiv_mismatches(1 << 16, 65535) == 0
+    assert lib.cnnmem_debug_smalldiv_mismatches((1 << 20) + 1, 4) == -1       # beyond what the divider promises
+    assert lib.cnnmem_debug_smalldiv_mismatches(16, 0) == -1
 
 
 @pytest.mark.parametrize("nblocks", [1, 2, 7, 8, 9, 15, 16, 17, 63, 64, 100, 1001, 4096, 12289])
