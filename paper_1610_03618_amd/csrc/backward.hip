@@ -581,13 +581,9 @@ __global__ __launch_bounds__(kBwdThreads) void pool_bwd_nchw_slab_kernel(
         }
     }
     __syncthreads();
-    // the phases below index the workgroup's own slab: numbers below 2^20, divided in three instructions
-    const SmallDiv sd_w = make_smalldiv(div_w.d), sd_plane_in = make_smalldiv(div_plane_in.d),
-                   sd_wo = make_smalldiv(div_wo.d), sd_plane_out = make_smalldiv(div_plane_out.d),
-                   sd_cells_w = make_smalldiv(div_cells_w.d), sd_cells_plane = make_smalldiv(div_cells_plane.d);
     // LDS index of element (plane p0, row 0, col 0) of x and of ddst
-    const int x_base = (int)((long long)((size_t)p0 * plane_in) - (long long)x_a_lo);      // small numbers
-    const int gy_base = (int)((long long)((size_t)p0 * plane_out) - (long long)gy_a_lo);
+    const long long x_base = (long long)((size_t)p0 * plane_in) - (long long)x_a_lo;
+    const long long gy_base = (long long)((size_t)p0 * plane_out) - (long long)gy_a_lo;
 
     if (MODE == CNNMEM_POOL_MAX && have_windows) {
         // phase A: window (pl, i, j), i in [i_lo, i_hi], flattened like its place in ddst
@@ -596,18 +592,18 @@ __global__ __launch_bounds__(kBwdThreads) void pool_bwd_nchw_slab_kernel(
         for (int v = threadIdx.x; v < n_win; v += kBwdThreads) {
             int pl = 0, rem = v;
             if (planes > 1) {
-                pl = (int)sd_div((uint32_t)v, sd_plane_out);
-                rem = v - __mul24(pl, plane_out);
+                pl = (int)fd_div((uint32_t)v, div_plane_out);
+                rem = v - pl * plane_out;
             }
-            const int il = (int)sd_div((uint32_t)rem, sd_wo);
-            const int j = rem - __mul24(il, g.Wo);
+            const int il = (int)fd_div((uint32_t)rem, div_wo);
+            const int j = rem - il * g.Wo;
             const int i = i_lo + il;
-            const float* xs = slab + (x_base + __mul24(pl, plane_in));
+            const float* xs = slab + (x_base + (long long)pl * plane_in);
             float best = kNegInf;
             int where = -1;
             if (KH != 0 && g.ph == 0 && g.pw == 0) {
                 // compile-time window without padding: every tap is inside the image
-                const int base = __mul24(i * sh, g.W) + j * sw;
+                const int base = (i * sh) * g.W + j * sw;
                 best = xs[base];
                 where = base;
 #pragma unroll
@@ -629,7 +625,7 @@ __global__ __launch_bounds__(kBwdThreads) void pool_bwd_nchw_slab_kernel(
                     if (where < 0 || val > best) { best = val; where = r * g.W + q; }
                 }
             }
-            amax_lds[gy_base + __mul24(pl, plane_out) + __mul24(i, g.Wo) + j] = where;
+            amax_lds[gy_base + (long long)pl * plane_out + i * g.Wo + j] = where;
         }
         __syncthreads();
     }
@@ -650,12 +646,12 @@ __global__ __launch_bounds__(kBwdThreads) void pool_bwd_nchw_slab_kernel(
         const int ci0 = h0 / S;
         for (int v = threadIdx.x; v < n_cells; v += kBwdThreads) {
             // per_plane = cells of a whole plane (planes > 1 implies whole planes)
-            const int pl = planes > 1 ? (int)sd_div((uint32_t)v, sd_cells_plane) : 0;
-            const int rem = v - __mul24(pl, (int)div_cells_plane.d);
-            const int cil = (int)sd_div((uint32_t)rem, sd_cells_w);
-            const int cj = rem - __mul24(cil, cells_w);
+            const int pl = planes > 1 ? (int)fd_div((uint32_t)v, div_cells_plane) : 0;
+            const int rem = v - pl * (int)div_cells_plane.d;
+            const int cil = (int)fd_div((uint32_t)rem, div_cells_w);
+            const int cj = rem - cil * cells_w;
             const int ci = ci0 + cil;
-            const int gofs = gy_base + __mul24(pl, plane_out);
+            const long long gofs = gy_base + (long long)pl * plane_out;
             float gyv[NW][NW];
             int own[NW][NW];
 #pragma unroll
@@ -664,10 +660,10 @@ __global__ __launch_bounds__(kBwdThreads) void pool_bwd_nchw_slab_kernel(
                 for (int b = 0; b < NW; ++b) {
                     const int i = ci - (NW - 1) + a, j = cj - (NW - 1) + b;
                     const bool ok = i >= 0 && i < g.Ho && j >= 0 && j < g.Wo;
-                    gyv[a][b] = ok ? gy_lds[gofs + __mul24(i, g.Wo) + j] : 0.f;
-                    own[a][b] = (ok && MODE == CNNMEM_POOL_MAX) ? amax_lds[gofs + __mul24(i, g.Wo) + j] : -1;
+                    gyv[a][b] = ok ? gy_lds[gofs + i * g.Wo + j] : 0.f;
+                    own[a][b] = (ok && MODE == CNNMEM_POOL_MAX) ? amax_lds[gofs + i * g.Wo + j] : -1;
                 }
-            float* oplane = stage + (__mul24(pl, plane_in) - __mul24(h0, g.W));
+            float* oplane = stage + (long long)pl * plane_in - (long long)h0 * g.W;
 #pragma unroll
             for (int ey = 0; ey < S; ++ey) {
                 const int h = S * ci + ey;
@@ -676,7 +672,7 @@ __global__ __launch_bounds__(kBwdThreads) void pool_bwd_nchw_slab_kernel(
                 for (int ex = 0; ex < S; ++ex) {
                     const int w = S * cj + ex;
                     if (w >= g.W) continue;
-                    const int me = __mul24(h, g.W) + w;
+                    const int me = h * g.W + w;
                     float acc = 0.f;
 #pragma unroll
                     for (int a = 0; a < NW; ++a)
@@ -697,23 +693,23 @@ __global__ __launch_bounds__(kBwdThreads) void pool_bwd_nchw_slab_kernel(
         for (int o = threadIdx.x; o < n_elems; o += kBwdThreads) {
             int pl = 0, rem = o;
             if (planes > 1) {
-                pl = (int)sd_div((uint32_t)o, sd_plane_in);
-                rem = o - __mul24(pl, plane_in);
+                pl = (int)fd_div((uint32_t)o, div_plane_in);
+                rem = o - pl * plane_in;
             }
-            const int hl = (int)sd_div((uint32_t)rem, sd_w);
-            const int w = rem - __mul24(hl, g.W);
+            const int hl = (int)fd_div((uint32_t)rem, div_w);
+            const int w = rem - hl * g.W;
             const int h = h0 + hl;
             int a_lo, a_hi, b_lo, b_hi;
             window_range(h, kh, sh, g.ph, g.Ho, a_lo, a_hi);
             window_range(w, kw, sw, g.pw, g.Wo, b_lo, b_hi);
-            const int gofs = gy_base + __mul24(pl, plane_out);
-            const int me = __mul24(h, g.W) + w;
+            const long long gofs = gy_base + (long long)pl * plane_out;
+            const int me = h * g.W + w;
             float acc = 0.f;
             for (int i = a_lo; i <= a_hi; ++i)
                 for (int j = b_lo; j <= b_hi; ++j) {
-                    const float gyv = gy_lds[gofs + __mul24(i, g.Wo) + j];
+                    const float gyv = gy_lds[gofs + i * g.Wo + j];
                     if (MODE == CNNMEM_POOL_AVG) acc += gyv;
-                    else if (amax_lds[gofs + __mul24(i, g.Wo) + j] == me) acc += gyv;
+                    else if (amax_lds[gofs + i * g.Wo + j] == me) acc += gyv;
                 }
             stage[o] = MODE == CNNMEM_POOL_AVG ? acc / (float)(kh * kw) : acc;
         }
@@ -765,8 +761,8 @@ __global__ __launch_bounds__(kRowThreads) void pool_bwd_avg_nchw_k3s2_kernel(
     const int H = g.H, W = g.W, Ho = g.Ho, Wo = g.Wo;
     const int plane_in = H * W, plane_out = Ho * Wo;
     const uint32_t total_planes = (uint32_t)plan.total_planes;         // the tensors have fewer than 2^31 elements (launcher)
-    // strips of one plane share gradient rows: neighbours on one XCD
-    const uint32_t tile = plan.strips == 1 ? blockIdx.x : xcd_contiguous_tile(blockIdx.x, gridDim.x);
+    // neighbours share cache lines of the gradients (planes are not whole lines, strips share rows): one XCD
+    const uint32_t tile = xcd_contiguous_tile(blockIdx.x, gridDim.x);
     uint32_t p0;
     int planes, h0, rows;
     if (plan.strips == 1) {
