@@ -793,7 +793,7 @@ int dispatch_nchw(const float* src, float* dst, const PoolGeom& g, const PoolTun
             // round for a handful of lanes each: PL2 8.9 -> 6.8 us, PL4 9.1 -> 7.0, PL10 9.5 -> 7.5, PL7 10.7 -> 9.4.
             const long long min_blocks = 1024;
             if (planes / p < min_blocks) p = planes / min_blocks > 0 ? planes / min_blocks : 1;
-            if (p * (long long)g.Ho * g.Wo < (1 << 30)) {
+            if (p * (long long)g.Ho * g.Wo < (1 << 20)) {         // the kernel's small-number divider
                 plan.planes_per_wg = (int)p;
                 plan.rows_per_wg = g.Ho;
                 plan.strips = 1;
@@ -804,7 +804,7 @@ int dispatch_nchw(const float* src, float* dst, const PoolGeom& g, const PoolTun
             // rows_out output rows need (rows_out-1)*sh + kh input rows
             const long long max_in_rows = budget / g.W;
             long long rows_out = (max_in_rows - g.kh) / g.sh + 1;
-            if (max_in_rows >= g.kh && rows_out >= 1) {
+            if (max_in_rows >= g.kh && rows_out >= 1 && rows_out * g.Wo < (1 << 20)) {
                 if (rows_out > g.Ho) rows_out = g.Ho;
                 plan.planes_per_wg = 1;
                 plan.rows_per_wg = (int)rows_out;
