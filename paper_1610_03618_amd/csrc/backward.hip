@@ -740,11 +740,9 @@ __global__ __launch_bounds__(kBwdThreads) void pool_bwd_nchw_slab_kernel(
 //     loop has no conditions (14 vector, 5 scalar and 5 LDS instructions per pair of rows);
 //   * a lane gathers one pair of input rows (2u, 2u+1) of its column: both rows lie in window row u, the even one
 //     also in u-1, so four gradients serve two elements.
-// The same structure for the maximum (a lane per window, first maximum of nine taps in LDS, gradient added to
-// that element of the staged result, even window rows and columns before odd ones) measured level with the slab
-// kernel (65 us on 128x96x55x55) and was not kept.
+// The maximum takes the same structure with a lane per window (pool_bwd_max_nchw_k3s2_kernel below).
 constexpr int kRowThreads = 256;
-constexpr int kRowGyVecs = 3;               // float4 per lane a workgroup's gradient rows may take
+constexpr int kRowGyVecs = 3, kRowXVecs = 8;      // float4 per lane a workgroup's gradient rows / input rows may take
 struct RowsLds {                // LDS layout in floats; the staged result starts at 0
     int gy_at;                  // gradient rows
     int zero_at, trash_at;      // a row of zeros (Wo + 35 floats), a row nobody reads (W + 4 floats)
@@ -867,6 +865,183 @@ __global__ __launch_bounds__(kRowThreads) void pool_bwd_avg_nchw_k3s2_kernel(
     // on a line of dsrc
     const float* stage = slab + stage_at;
     for (int o = 4 * (int)threadIdx.x - lead; o < n_elems; o += 4 * kRowThreads) {
+        float* q = dsrc + out0 + o;
+        if (o >= 0 && o + 4 <= n_elems) {
+            st4_stream(q, *reinterpret_cast<const float4*>(stage + o));
+        } else {
+            for (int e = 0; e < 4; ++e)
+                if (o + e >= 0 && o + e < n_elems) q[e] = stage[o + e];
+        }
+    }
+}
+
+// ---- NCHW maximum, 3x3 / stride 2 without padding: the same shape of kernel -----------------------------
+// A lane owns a window: it finds the window's first maximum among the nine taps in LDS and adds the window's
+// gradient to that element of the staged result.  Windows two rows (or two columns) apart share no input, so even
+// window rows go first, a barrier, then odd ones; inside a row the even columns go first, then the odd ones (same
+// wavefront, program order): no atomics, and the order of the at most four additions of an element is fixed.
+// Both streams (input rows, gradient rows) are requested before the table is built.  128x96x55x55: 65-69 us in the
+// slab kernel, 61 us here (256 lanes, one plane per workgroup; 512 lanes 63 us; strips of 28 rows 64 us, of 14 rows
+// 98 us: a workgroup's piece must not get small).
+// LDS: [ input rows | gradient rows | staged result | descriptors ]
+struct MaxRowsLds {
+    int gy_at, stage_at, desc_at;
+    int ntab0, ntab1;           // descriptors of the even and of the odd window rows, whole rounds of the workgroup
+    int lanes_per_row;          // LW, for window rows
+};
+
+__global__ __launch_bounds__(kRowThreads) void pool_bwd_max_nchw_k3s2_kernel(
+    const float* __restrict__ src, const float* __restrict__ ddst, float* __restrict__ dsrc, PoolGeom g, BwdSlabPlan plan,
+    MaxRowsLds at, FastDiv div_even, FastDiv div_odd, FastDiv div_strips) {
+    constexpr int THREADS = kRowThreads, kWaves = THREADS / 64;
+    constexpr int GV = kRowGyVecs, XV = kRowXVecs;                // float4 per lane that a workgroup's streams may take
+    float* slab = reinterpret_cast<float*>(bwd_dyn_lds);
+    const int H = g.H, W = g.W, Ho = g.Ho, Wo = g.Wo;
+    const int plane_in = H * W, plane_out = Ho * Wo;
+    const uint32_t total_planes = (uint32_t)plan.total_planes;         // the tensors have fewer than 2^31 elements (launcher)
+    const uint32_t tile = xcd_contiguous_tile(blockIdx.x, gridDim.x);
+    uint32_t p0;
+    int planes, h0, rows;
+    if (plan.strips == 1) {
+        p0 = tile * (uint32_t)plan.planes_per_wg;
+        const uint32_t left = total_planes - p0;
+        planes = left < (uint32_t)plan.planes_per_wg ? (int)left : plan.planes_per_wg;
+        h0 = 0;
+        rows = H;
+    } else {
+        p0 = fd_div(tile, div_strips);
+        planes = 1;
+        h0 = (int)(tile - p0 * (uint32_t)plan.strips) * plan.rows_per_wg;        // even (launcher)
+        rows = H - h0 < plan.rows_per_wg ? H - h0 : plan.rows_per_wg;
+    }
+    // window rows that touch input rows [h0, h0 + rows): at least one (H >= 3, h0 even)
+    const int i_lo = h0 >= 2 ? (h0 >> 1) - 1 : 0;
+    const int i_hi = ((h0 + rows - 1) >> 1) < Ho - 1 ? (h0 + rows - 1) >> 1 : Ho - 1;
+    const int xr_lo = planes > 1 ? 0 : 2 * i_lo, xr_hi = planes > 1 ? H : 2 * i_hi + 3;         // inside the image
+    const int n_elems = planes * rows * W;
+    const uint32_t out0 = p0 * (uint32_t)plane_in + (uint32_t)(h0 * W);
+    const int lead = (int)((((uint32_t)reinterpret_cast<uintptr_t>(dsrc) >> 2) + out0) & 31u);
+    const int stage_at = at.stage_at + (lead & 3);
+    int4* desc = reinterpret_cast<int4*>(slab + at.desc_at);
+
+    // ---- both streams on their way (element e of a stream lands at its part's start + e - a_lo) ----
+    const uint32_t total_out = total_planes * (uint32_t)plane_out, total_in = total_planes * (uint32_t)plane_in;
+    const uint32_t g_lo = p0 * (uint32_t)plane_out + (uint32_t)(i_lo * Wo);
+    const uint32_t g_hi = (p0 + planes - 1) * (uint32_t)plane_out + (uint32_t)((i_hi + 1) * Wo);
+    const uint32_t g_alo = g_lo & ~((reinterpret_cast<uintptr_t>(ddst) & 127u) == 0 ? 31u : 3u);
+    const uint32_t g_nvec = (g_hi - g_alo + 3) >> 2, g_alast = (total_out - 4) & ~3u;
+    const uint32_t x_lo = p0 * (uint32_t)plane_in + (uint32_t)(xr_lo * W);
+    const uint32_t x_hi = (p0 + planes - 1) * (uint32_t)plane_in + (uint32_t)(xr_hi * W);
+    const uint32_t x_alo = x_lo & ~((reinterpret_cast<uintptr_t>(src) & 127u) == 0 ? 31u : 3u);
+    const uint32_t x_nvec = (x_hi - x_alo + 3) >> 2, x_alast = (total_in - 4) & ~3u;
+    float4 gv[GV], xv[XV];
+#pragma unroll
+    for (int k = 0; k < GV; ++k) {
+        if ((uint32_t)(k * THREADS) >= g_nvec) break;             // uniform
+        const uint32_t q = threadIdx.x + k * THREADS;
+        const uint32_t a = g_alo + 4 * (q < g_nvec ? q : g_nvec - 1);
+        gv[k] = ld4_stream(ddst + (a <= g_alast ? a : g_alast));
+    }
+#pragma unroll
+    for (int k = 0; k < XV; ++k) {
+        if ((uint32_t)(k * THREADS) >= x_nvec) break;
+        const uint32_t q = threadIdx.x + k * THREADS;
+        const uint32_t a = x_alo + 4 * (q < x_nvec ? q : x_nvec - 1);
+        xv[k] = ld4_stream(src + (a <= x_alast ? a : x_alast));
+    }
+
+    // ---- descriptors and the cleared stage while the loads are in flight ----
+    const int gy_base = at.gy_at + (int)(p0 * (uint32_t)plane_out - g_alo);       // slab index of (plane p0, window row 0, col 0)
+    const int x_base = (int)(p0 * (uint32_t)plane_in - x_alo);
+    for (int t = threadIdx.x; t < at.ntab0 + at.ntab1; t += THREADS) {
+        const int parity = t >= at.ntab0 ? 1 : 0;
+        const int k_flat = t - (parity ? at.ntab0 : 0);
+        // window rows i_lo <= i <= i_hi with i % 2 == parity, of every plane
+        const int first = i_lo + (((i_lo & 1) != parity) ? 1 : 0);
+        const int count = first <= i_hi ? (i_hi - first) / 2 + 1 : 0;
+        const bool valid = k_flat < planes * count;
+        const int kv = valid ? k_flat : 0;
+        const int pl = planes > 1 ? (int)fd_div((uint32_t)kv, parity ? div_odd : div_even) : 0;
+        const int i = (count > 0 ? first : i_lo) + 2 * (kv - pl * count);
+        int4 d;
+        d.x = x_base + pl * plane_in + 2 * i * W;                       // first tap row of the window row
+        d.y = gy_base + pl * plane_out + i * Wo;
+        d.z = stage_at + (pl * rows - h0 + 2 * i) * W;                  // that tap row in the staged result
+        d.w = valid ? (2 * i - h0) * W : -(1 << 30);                    // ... and inside the plane's part of the run
+        desc[t] = d;
+    }
+    {
+        const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int q = threadIdx.x; q < (n_elems + 6) / 4; q += THREADS) reinterpret_cast<float4*>(slab + at.stage_at)[q] = zero;
+    }
+#pragma unroll
+    for (int k = 0; k < GV; ++k) {
+        if ((uint32_t)(k * THREADS) >= g_nvec) break;
+        const uint32_t q = threadIdx.x + k * THREADS;
+        const uint32_t a = g_alo + 4 * q;
+        if (q < g_nvec) {
+            if (a <= g_alast) *reinterpret_cast<float4*>(slab + at.gy_at + 4 * q) = gv[k];
+            else
+                for (uint32_t e = 0; e < 4; ++e)
+                    if (a + e < total_out) slab[at.gy_at + 4 * q + e] = ddst[a + e];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < XV; ++k) {
+        if ((uint32_t)(k * THREADS) >= x_nvec) break;
+        const uint32_t q = threadIdx.x + k * THREADS;
+        const uint32_t a = x_alo + 4 * q;
+        if (q < x_nvec) {
+            if (a <= x_alast) *reinterpret_cast<float4*>(slab + 4 * q) = xv[k];
+            else
+                for (uint32_t e = 0; e < 4; ++e)
+                    if (a + e < total_in) slab[4 * q + e] = src[a + e];
+        }
+    }
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int LW = at.lanes_per_row;
+    const int SUB = 64 / LW, sub = lane / LW, step = kWaves * SUB;
+    const unsigned run_of_plane = (unsigned)(rows * W);
+    for (int parity = 0; parity < 2; ++parity) {
+        const int tab = parity ? at.ntab0 : 0, ntab = parity ? at.ntab1 : at.ntab0;
+        for (int j = lane & (LW - 1); j < ((Wo + 63) & ~63); j += 64) {
+            const bool col_ok = j < Wo;
+            const int jc = col_ok ? j : Wo - 1;
+            const bool even_col = (j & 1) == 0;
+            for (int base = wave * SUB; base < ntab; base += step) {
+                const int4 d = desc[tab + base + sub];
+                const float* xp = slab + d.x + 2 * jc;
+                float best = xp[0];
+                int off = 0;
+#pragma unroll
+                for (int y = 0; y < 3; ++y)
+#pragma unroll
+                    for (int x = 0; x < 3; ++x) {
+                        if (y == 0 && x == 0) continue;
+                        const float val = xp[y * W + x];
+                        if (val > best) { best = val; off = y * W + x; }
+                    }
+                const float gyv = slab[d.y + jc];
+                const int t = 2 * jc + off;
+                const bool ok = col_ok && (unsigned)(d.w + t) < run_of_plane;
+                // neighbouring lanes may name the same element: even columns first, then odd ones, as two separate
+                // LDS read-modify-writes of the wavefront (the fences keep the compiler from merging them or moving
+                // the second read above the first write)
+                float* out = slab + d.z + t;
+                if (ok && even_col) *out += gyv;
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_wave_barrier();
+                asm volatile("" ::: "memory");
+                if (ok && !even_col) *out += gyv;
+            }
+        }
+        __syncthreads();
+    }
+    const float* stage = slab + stage_at;
+    for (int o = 4 * (int)threadIdx.x - lead; o < n_elems; o += 4 * THREADS) {
         float* q = dsrc + out0 + o;
         if (o >= 0 && o + 4 <= n_elems) {
             st4_stream(q, *reinterpret_cast<const float4*>(stage + o));
@@ -1068,6 +1243,65 @@ int launch_bwd_avg_k3s2(const float* ddst, float* dsrc, const PoolGeom& g, hipSt
     return launch_status();
 }
 
+// maximum, 3x3 / stride 2 without padding in NCHW: whole planes per workgroup, or strips of an even number of rows
+int launch_bwd_max_k3s2(const float* src, const float* ddst, float* dsrc, const PoolGeom& g, hipStream_t st) {
+    constexpr int THREADS = kRowThreads, kWaves = THREADS / 64;
+    const long long planes = (long long)g.N * g.C;
+    const long long plane_in = (long long)g.H * g.W, plane_out = (long long)g.Ho * g.Wo;
+    auto part = [](long long floats) { return (long long)((floats + 32 + 3) / 4 * 4); };
+    auto round_up = [](long long v, long long m) { return (v + m - 1) / m * m; };
+    int lanes_per_row = 64;
+    while (lanes_per_row / 2 >= g.Wo) lanes_per_row /= 2;
+    const long long step = kWaves * (64 / lanes_per_row);          // window rows per round of the workgroup
+    auto layout = [&](long long out_f, long long gy_f, long long x_f, long long tasks0, long long tasks1, MaxRowsLds& at) {
+        long long o = part(x_f);
+        at.gy_at = (int)o; o += part(gy_f);
+        at.stage_at = (int)o; o += part(out_f);
+        at.desc_at = (int)o;
+        at.ntab0 = (int)round_up(tasks0, step);
+        at.ntab1 = (int)round_up(tasks1, step);
+        at.lanes_per_row = lanes_per_row;
+        // more than the lanes' registers take
+        if (part(gy_f) > 4LL * THREADS * kRowGyVecs || part(x_f) > 4LL * THREADS * kRowXVecs) return 1LL << 40;
+        return o + 4LL * (at.ntab0 + at.ntab1);
+    };
+    auto planes_need = [&](long long q, MaxRowsLds& at) {
+        return layout(q * plane_in, q * plane_out, q * plane_in, q * ((g.Ho + 1) / 2), q * (g.Ho / 2), at);
+    };
+    // a strip of r input rows (r even): its windows span at most r + 4 input rows and r / 2 + 2 gradient rows, at most
+    // r / 4 + 1 of them of one parity
+    auto strip_need = [&](long long r, MaxRowsLds& at) {
+        const long long xr = r + 4 < g.H ? r + 4 : g.H, gr = r / 2 + 2 < g.Ho ? r / 2 + 2 : g.Ho;
+        return layout(r * g.W, gr * g.Wo, xr * g.W, r / 4 + 1, r / 4 + 1, at);
+    };
+    BwdSlabPlan plan;
+    plan.total_planes = planes;
+    MaxRowsLds at, probe;
+    long long blocks = 0, lds_floats = 0;
+    if (planes_need(1, probe) <= kBwdSlabFloats) {
+        plan.planes_per_wg = 1;
+        plan.rows_per_wg = g.H;
+        plan.strips = 1;
+        blocks = planes;
+        lds_floats = planes_need(1, at);
+    } else {
+        long long r = g.H / 2 * 2;
+        while (r > 2 && strip_need(r, probe) > kBwdSlabFloats) r -= 2;
+        if (r < 2 || strip_need(r, probe) > kBwdSlabFloats) return CNNMEM_ERR_UNSUPPORTED;
+        plan.planes_per_wg = 1;
+        plan.rows_per_wg = (int)r;
+        plan.strips = ceil_div(g.H, r);
+        blocks = planes * plan.strips;
+        lds_floats = strip_need(r, at);
+    }
+    if (blocks > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(pool_bwd_max_nchw_k3s2_kernel, dim3((unsigned)blocks), dim3(THREADS),
+                       sizeof(float) * (size_t)lds_floats, st, src, ddst, dsrc, g, plan, at,
+                       make_fastdiv((uint32_t)((g.Ho + 1) / 2)), make_fastdiv((uint32_t)(g.Ho / 2 > 0 ? g.Ho / 2 : 1)),
+                       make_fastdiv((uint32_t)plan.strips));
+    return launch_status();
+}
+
 template <int MODE>
 int dispatch_pool_backward(const float* src, const float* ddst, float* dsrc, const PoolGeom& g, int layout,
                            hipStream_t st) {
@@ -1107,9 +1341,10 @@ int dispatch_pool_backward(const float* src, const float* ddst, float* dsrc, con
         }
     }
     const long long plane_in = (long long)g.H * g.W, plane_out = (long long)g.Ho * g.Wo;
-    if (MODE == CNNMEM_POOL_AVG && a16 && g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2 && g.ph == 0 && g.pw == 0 &&
+    if (a16 && g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2 && g.ph == 0 && g.pw == 0 &&
         plane_in * planes < (1LL << 31) && plane_out * planes >= 4 && env_int("CNNMEM_BWD_ROWS", 1) != 0) {
-        const int rc = launch_bwd_avg_k3s2(ddst, dsrc, g, st);
+        const int rc = MODE == CNNMEM_POOL_AVG ? launch_bwd_avg_k3s2(ddst, dsrc, g, st)
+                                               : launch_bwd_max_k3s2(src, ddst, dsrc, g, st);
         if (rc != CNNMEM_ERR_UNSUPPORTED) return rc;
     }
     // LDS slab: input rows, gradient rows and (maximum) one position per window share 60 KB
