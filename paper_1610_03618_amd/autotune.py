@@ -110,9 +110,8 @@ def tune_pool(N: int, C: int, H: int, W: int, layout: int, mode: int, k: int, s:
         cols, _ = hill_climb(lambda f: timed({**best, "cols_per_lane": f}), 1, 2, margin=NOISE)
         best["cols_per_lane"] = cols
     else:
-        candidates = [dict(nchw_kernel=2, slab_lanes=lanes) for lanes in (512, 256, 1024)]   # the default first
-        if k == 2 and s == 2 and p == 0 and H % 2 == 0 and W % 4 == 0:
-            candidates.insert(0, dict(nchw_kernel=1))
+        # the library's own choice first (row pairs, the rows kernel or the slab kernel), then the slab kernel by size
+        candidates = [dict()] + [dict(nchw_kernel=2, slab_lanes=lanes) for lanes in (512, 256, 1024)]
         times = [(timed(c), c) for c in candidates]
         # the library's default kernel (first candidate) stays unless another beats it by more than the noise
         first_ms = times[0][0]

@@ -607,6 +607,184 @@ __global__ __launch_bounds__(THREADS) void pool_nchw_slab_kernel(
     }
 }
 
+// ---- NCHW, 3x3 / stride 2 without padding (the overlapped pooling of the paper's networks): rows kernel -----
+// The lanes of a wavefront are the output columns of one output row (of 64 / LW rows for planes of fewer than 33
+// output columns, LW the next power of two); what depends on the row - where its three input rows and its
+// result sit in LDS - is computed once per workgroup into a table of descriptors, so the inner loop is a
+// descriptor read, nine taps and eight operations.  The input rows are requested before the table is built;
+// results are staged in LDS and leave as one line-aligned run.
+// LDS: [ input rows | staged outputs | trash row | descriptors ]
+constexpr int kRowThreads = 256;
+constexpr int kRowXVecs = 8;                        // float4 per lane a workgroup's input rows may take
+constexpr int kRowLdsFloats = 15360;
+struct PoolRowsLds {
+    int stage_at, trash_at, desc_at;
+    int ntab;                   // descriptors: output rows, whole rounds of the workgroup
+    int lanes_per_row;          // LW
+};
+extern __shared__ float4 pool_dyn_lds[];
+
+template <int MODE>
+__global__ __launch_bounds__(kRowThreads) void pool_nchw_k3s2_rows_kernel(
+    const float* __restrict__ src, float* __restrict__ dst, PoolGeom g, SlabPlan plan, PoolRowsLds at, FastDiv div_ho,
+    FastDiv div_strips) {
+    constexpr int THREADS = kRowThreads, kWaves = THREADS / 64, XV = kRowXVecs;
+    float* slab = reinterpret_cast<float*>(pool_dyn_lds);
+    const int H = g.H, W = g.W, Ho = g.Ho, Wo = g.Wo;
+    const int plane_in = H * W, plane_out = Ho * Wo;
+    const uint32_t total_planes = (uint32_t)plan.total_planes;         // the tensors have fewer than 2^31 elements (launcher)
+    const uint32_t tile = xcd_contiguous_tile(blockIdx.x, gridDim.x);
+    uint32_t p0;
+    int planes, i0, rows_out;
+    if (plan.strips == 1) {
+        p0 = tile * (uint32_t)plan.planes_per_wg;
+        const uint32_t left = total_planes - p0;
+        planes = left < (uint32_t)plan.planes_per_wg ? (int)left : plan.planes_per_wg;
+        i0 = 0;
+        rows_out = Ho;
+    } else {
+        p0 = fd_div(tile, div_strips);
+        planes = 1;
+        i0 = (int)(tile - p0 * (uint32_t)plan.strips) * plan.rows_per_wg;
+        rows_out = Ho - i0 < plan.rows_per_wg ? Ho - i0 : plan.rows_per_wg;
+    }
+    // input rows [r_lo, r_hi) of the first ... last plane
+    const int r_lo = planes > 1 ? 0 : 2 * i0, r_hi = planes > 1 ? H : 2 * (i0 + rows_out - 1) + 3;
+    const int n_out = planes * rows_out * Wo;
+    const uint32_t out0 = p0 * (uint32_t)plane_out + (uint32_t)(i0 * Wo);
+    const int lead = (int)((((uint32_t)reinterpret_cast<uintptr_t>(dst) >> 2) + out0) & 31u);
+    const int stage_at = at.stage_at + (lead & 3);
+    int4* desc = reinterpret_cast<int4*>(slab + at.desc_at);
+
+    // ---- input rows on their way (element e lands at slab[e - a_lo], a_lo the line-aligned start) ----
+    const uint32_t total_in = total_planes * (uint32_t)plane_in;
+    const uint32_t x_lo = p0 * (uint32_t)plane_in + (uint32_t)(r_lo * W);
+    const uint32_t x_hi = (p0 + planes - 1) * (uint32_t)plane_in + (uint32_t)(r_hi * W);
+    const uint32_t a_lo = x_lo & ~((reinterpret_cast<uintptr_t>(src) & 127u) == 0 ? 31u : 3u);
+    const uint32_t nvec = (x_hi - a_lo + 3) >> 2, a_last = (total_in - 4) & ~3u;
+    float4 xv[XV];
+#pragma unroll
+    for (int k = 0; k < XV; ++k) {
+        if ((uint32_t)(k * THREADS) >= nvec) break;              // uniform
+        const uint32_t q = threadIdx.x + k * THREADS;
+        const uint32_t a = a_lo + 4 * (q < nvec ? q : nvec - 1);
+        xv[k] = ld4_stream(src + (a <= a_last ? a : a_last));
+    }
+    // ---- descriptors while the loads are in flight: { first input row of the window row, staged output row } ----
+    const int x_base = (int)(p0 * (uint32_t)plane_in - a_lo);                  // slab index of (plane p0, row 0, col 0)
+    const int n_rows = planes * rows_out;
+    for (int t = threadIdx.x; t < at.ntab; t += THREADS) {
+        const bool valid = t < n_rows;
+        const int tv = valid ? t : 0;
+        const int pl = planes > 1 ? (int)fd_div((uint32_t)tv, div_ho) : 0;
+        const int il = tv - pl * rows_out;
+        int4 d;
+        d.x = x_base + pl * plane_in + 2 * (i0 + il) * W;
+        d.y = valid ? stage_at + tv * Wo : at.trash_at;
+        d.z = 0; d.w = 0;
+        desc[t] = d;
+    }
+#pragma unroll
+    for (int k = 0; k < XV; ++k) {
+        if ((uint32_t)(k * THREADS) >= nvec) break;
+        const uint32_t q = threadIdx.x + k * THREADS;
+        const uint32_t a = a_lo + 4 * q;
+        if (q < nvec) {
+            if (a <= a_last) *reinterpret_cast<float4*>(slab + 4 * q) = xv[k];
+            else
+                for (uint32_t e = 0; e < 4; ++e)
+                    if (a + e < total_in) slab[4 * q + e] = src[a + e];
+        }
+    }
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int LW = at.lanes_per_row;
+    const int SUB = 64 / LW, sub = lane / LW, step = kWaves * SUB;
+    for (int j = lane & (LW - 1); j < ((Wo + 63) & ~63); j += 64) {
+        if (j < Wo) {
+            for (int base = wave * SUB; base < at.ntab; base += step) {
+                const int4 d = desc[base + sub];
+                const float* xp = slab + d.x + 2 * j;
+                float acc = Acc<MODE>::identity();
+#pragma unroll
+                for (int y = 0; y < 3; ++y)
+#pragma unroll
+                    for (int x = 0; x < 3; ++x) acc = Acc<MODE>::op(acc, xp[y * W + x]);
+                slab[d.y + j] = Acc<MODE>::finish(acc, 9.0f);
+            }
+        }
+    }
+    __syncthreads();
+    // the workgroup's outputs leave as one contiguous run, 128 bits per lane, each wavefront's 1 KB starting on a
+    // line of dst
+    const float* stage = slab + stage_at;
+    for (int o = 4 * (int)threadIdx.x - lead; o < n_out; o += 4 * THREADS) {
+        float* q = dst + out0 + o;
+        if (o >= 0 && o + 4 <= n_out) {
+            st4_stream(q, *reinterpret_cast<const float4*>(stage + o));
+        } else {
+            for (int e = 0; e < 4; ++e)
+                if (o + e >= 0 && o + e < n_out) q[e] = stage[o + e];
+        }
+    }
+}
+
+template <int MODE>
+int launch_nchw_k3s2_rows(const float* src, float* dst, const PoolGeom& g, hipStream_t st) {
+    constexpr int kWaves = kRowThreads / 64;
+    const long long planes = (long long)g.N * g.C;
+    const long long plane_in = (long long)g.H * g.W, plane_out = (long long)g.Ho * g.Wo;
+    auto part = [](long long floats) { return (long long)((floats + 32 + 3) / 4 * 4); };
+    auto round_up = [](long long v, long long m) { return (v + m - 1) / m * m; };
+    int lanes_per_row = 64;
+    while (lanes_per_row / 2 >= g.Wo) lanes_per_row /= 2;
+    const long long step = kWaves * (64 / lanes_per_row);          // output rows per round of the workgroup
+    auto layout = [&](long long x_f, long long out_f, long long tasks, PoolRowsLds& at) {
+        long long o = part(x_f);
+        at.stage_at = (int)o; o += part(out_f);
+        at.trash_at = (int)o; o += round_up(g.Wo + 4, 4);
+        at.desc_at = (int)o;
+        at.ntab = (int)round_up(tasks, step);
+        at.lanes_per_row = lanes_per_row;
+        if (part(x_f) > 4LL * kRowThreads * kRowXVecs) return 1LL << 40;          // more than the lanes' registers take
+        return o + 4LL * at.ntab;
+    };
+    auto planes_need = [&](long long q, PoolRowsLds& at) { return layout(q * plane_in, q * plane_out, q * g.Ho, at); };
+    auto strip_need = [&](long long r, PoolRowsLds& at) { return layout((2 * r + 1) * g.W, r * g.Wo, r, at); };
+    SlabPlan plan;
+    plan.total_planes = planes;
+    PoolRowsLds at, probe;
+    long long blocks = 0, lds_floats = 0;
+    // 16 KB: eight 256-lane workgroups per CU with room to spare (20 KB measured level, 32 KB and 60 KB 3-10 % slower)
+    int budget = env_int("CNNMEM_POOL_ROWS_FLOATS", 4096);
+    if (budget < 1024 || budget > kRowLdsFloats) budget = kRowLdsFloats;
+    if (planes_need(1, probe) <= kRowLdsFloats) {
+        long long p = 1;
+        while (p + 1 <= planes && planes_need(p + 1, probe) <= budget && planes / (p + 1) >= 1024) ++p;
+        plan.planes_per_wg = (int)p;
+        plan.rows_per_wg = g.Ho;
+        plan.strips = 1;
+        blocks = ceil_div64(planes, p);
+        lds_floats = planes_need(p, at);
+    } else {
+        long long r = g.Ho;
+        while (r > 1 && strip_need(r, probe) > kRowLdsFloats) --r;
+        if (strip_need(r, probe) > kRowLdsFloats) return CNNMEM_ERR_UNSUPPORTED;
+        plan.planes_per_wg = 1;
+        plan.rows_per_wg = (int)r;
+        plan.strips = ceil_div(g.Ho, r);
+        blocks = planes * plan.strips;
+        lds_floats = strip_need(r, at);
+    }
+    if (blocks > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((pool_nchw_k3s2_rows_kernel<MODE>), dim3((unsigned)blocks), dim3(kRowThreads),
+                       sizeof(float) * (size_t)lds_floats, st, src, dst, g, plan, at, make_fastdiv((uint32_t)g.Ho),
+                       make_fastdiv((uint32_t)plan.strips));
+    return launch_status();
+}
+
 // ---- host-side dispatch ------------------------------------------------------
 
 template <int MODE>
@@ -778,8 +956,17 @@ int dispatch_nchw(const float* src, float* dst, const PoolGeom& g, const PoolTun
         }
     }
 
-    // (2) LDS slab: whole planes when they fit, else strips of output rows
     const long long plane_in = (long long)g.H * g.W;
+    // (2a) 3x3 / stride 2 without padding on planes of 100 outputs and more: the rows kernel (128x96x55x55 33.0 -> 32.7 us,
+    // 128x256x27x27 23.7 -> 22.9 us, back to back 31.5 -> 30.8 and 22.3 -> 21.3 us; 13x13 planes are better off in the
+    // slab kernel's 48 planes per workgroup: 7.2 against 8.0 us)
+    if (a16 && g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2 && g.ph == 0 && g.pw == 0 && g.Ho * (long long)g.Wo >= 100 &&
+        plane_in * planes < (1LL << 31) && plane_in * planes >= 4 && tune.nchw_kernel == 0 &&
+        env_int("CNNMEM_POOL_ROWS", 1) != 0) {
+        const int rc = launch_nchw_k3s2_rows<MODE>(src, dst, g, st);
+        if (rc != CNNMEM_ERR_UNSUPPORTED) return rc;
+    }
+    // (2) LDS slab: whole planes when they fit, else strips of output rows
     if (aligned16(src) && plane_in * planes < (1LL << 40) && plane_in * planes >= 4) {
         SlabPlan plan;
         plan.total_planes = planes;
