@@ -626,40 +626,28 @@ extern __shared__ float4 pool_dyn_lds[];
 
 template <int MODE>
 __global__ __launch_bounds__(kRowThreads) void pool_nchw_k3s2_rows_kernel(
-    const float* __restrict__ src, float* __restrict__ dst, PoolGeom g, SlabPlan plan, PoolRowsLds at, FastDiv div_ho,
-    FastDiv div_strips) {
+    const float* __restrict__ src, float* __restrict__ dst, PoolGeom g, SlabPlan plan, PoolRowsLds at, FastDiv div_ho) {
     constexpr int THREADS = kRowThreads, kWaves = THREADS / 64, XV = kRowXVecs;
     float* slab = reinterpret_cast<float*>(pool_dyn_lds);
-    const int H = g.H, W = g.W, Ho = g.Ho, Wo = g.Wo;
-    const int plane_in = H * W, plane_out = Ho * Wo;
+    const int W = g.W, Ho = g.Ho, Wo = g.Wo;
+    const int plane_in = g.H * W, plane_out = Ho * Wo;
     const uint32_t total_planes = (uint32_t)plan.total_planes;         // the tensors have fewer than 2^31 elements (launcher)
     const uint32_t tile = xcd_contiguous_tile(blockIdx.x, gridDim.x);
-    uint32_t p0;
-    int planes, i0, rows_out;
-    if (plan.strips == 1) {
-        p0 = tile * (uint32_t)plan.planes_per_wg;
-        const uint32_t left = total_planes - p0;
-        planes = left < (uint32_t)plan.planes_per_wg ? (int)left : plan.planes_per_wg;
-        i0 = 0;
-        rows_out = Ho;
-    } else {
-        p0 = fd_div(tile, div_strips);
-        planes = 1;
-        i0 = (int)(tile - p0 * (uint32_t)plan.strips) * plan.rows_per_wg;
-        rows_out = Ho - i0 < plan.rows_per_wg ? Ho - i0 : plan.rows_per_wg;
-    }
-    // input rows [r_lo, r_hi) of the first ... last plane
-    const int r_lo = planes > 1 ? 0 : 2 * i0, r_hi = planes > 1 ? H : 2 * (i0 + rows_out - 1) + 3;
-    const int n_out = planes * rows_out * Wo;
-    const uint32_t out0 = p0 * (uint32_t)plane_out + (uint32_t)(i0 * Wo);
+    // whole planes per workgroup (planes that do not fit stay with the slab kernel, whose strips of output rows
+    // measured 15 % faster than strips here: 64x96x110x110 60.7 against 71.5 us)
+    const uint32_t p0 = tile * (uint32_t)plan.planes_per_wg;
+    const uint32_t left = total_planes - p0;
+    const int planes = left < (uint32_t)plan.planes_per_wg ? (int)left : plan.planes_per_wg;
+    const int n_out = planes * plane_out;
+    const uint32_t out0 = p0 * (uint32_t)plane_out;
     const int lead = (int)((((uint32_t)reinterpret_cast<uintptr_t>(dst) >> 2) + out0) & 31u);
     const int stage_at = at.stage_at + (lead & 3);
     int4* desc = reinterpret_cast<int4*>(slab + at.desc_at);
 
     // ---- input rows on their way (element e lands at slab[e - a_lo], a_lo the line-aligned start) ----
     const uint32_t total_in = total_planes * (uint32_t)plane_in;
-    const uint32_t x_lo = p0 * (uint32_t)plane_in + (uint32_t)(r_lo * W);
-    const uint32_t x_hi = (p0 + planes - 1) * (uint32_t)plane_in + (uint32_t)(r_hi * W);
+    const uint32_t x_lo = p0 * (uint32_t)plane_in;
+    const uint32_t x_hi = (p0 + planes) * (uint32_t)plane_in;
     const uint32_t a_lo = x_lo & ~((reinterpret_cast<uintptr_t>(src) & 127u) == 0 ? 31u : 3u);
     const uint32_t nvec = (x_hi - a_lo + 3) >> 2, a_last = (total_in - 4) & ~3u;
     float4 xv[XV];
@@ -672,14 +660,14 @@ __global__ __launch_bounds__(kRowThreads) void pool_nchw_k3s2_rows_kernel(
     }
     // ---- descriptors while the loads are in flight: { first input row of the window row, staged output row } ----
     const int x_base = (int)(p0 * (uint32_t)plane_in - a_lo);                  // slab index of (plane p0, row 0, col 0)
-    const int n_rows = planes * rows_out;
+    const int n_rows = planes * Ho;
     for (int t = threadIdx.x; t < at.ntab; t += THREADS) {
         const bool valid = t < n_rows;
         const int tv = valid ? t : 0;
-        const int pl = planes > 1 ? (int)fd_div((uint32_t)tv, div_ho) : 0;
-        const int il = tv - pl * rows_out;
+        const int pl = (int)fd_div((uint32_t)tv, div_ho);
+        const int i = tv - pl * Ho;
         int4 d;
-        d.x = x_base + pl * plane_in + 2 * (i0 + il) * W;
+        d.x = x_base + pl * plane_in + 2 * i * W;
         d.y = valid ? stage_at + tv * Wo : at.trash_at;
         d.z = 0; d.w = 0;
         desc[t] = d;
@@ -752,7 +740,6 @@ int launch_nchw_k3s2_rows(const float* src, float* dst, const PoolGeom& g, hipSt
         return o + 4LL * at.ntab;
     };
     auto planes_need = [&](long long q, PoolRowsLds& at) { return layout(q * plane_in, q * plane_out, q * g.Ho, at); };
-    auto strip_need = [&](long long r, PoolRowsLds& at) { return layout((2 * r + 1) * g.W, r * g.Wo, r, at); };
     SlabPlan plan;
     plan.total_planes = planes;
     PoolRowsLds at, probe;
@@ -760,28 +747,17 @@ int launch_nchw_k3s2_rows(const float* src, float* dst, const PoolGeom& g, hipSt
     // 16 KB: eight 256-lane workgroups per CU with room to spare (20 KB measured level, 32 KB and 60 KB 3-10 % slower)
     int budget = env_int("CNNMEM_POOL_ROWS_FLOATS", 4096);
     if (budget < 1024 || budget > kRowLdsFloats) budget = kRowLdsFloats;
-    if (planes_need(1, probe) <= kRowLdsFloats) {
-        long long p = 1;
-        while (p + 1 <= planes && planes_need(p + 1, probe) <= budget && planes / (p + 1) >= 1024) ++p;
-        plan.planes_per_wg = (int)p;
-        plan.rows_per_wg = g.Ho;
-        plan.strips = 1;
-        blocks = ceil_div64(planes, p);
-        lds_floats = planes_need(p, at);
-    } else {
-        long long r = g.Ho;
-        while (r > 1 && strip_need(r, probe) > kRowLdsFloats) --r;
-        if (strip_need(r, probe) > kRowLdsFloats) return CNNMEM_ERR_UNSUPPORTED;
-        plan.planes_per_wg = 1;
-        plan.rows_per_wg = (int)r;
-        plan.strips = ceil_div(g.Ho, r);
-        blocks = planes * plan.strips;
-        lds_floats = strip_need(r, at);
-    }
+    if (planes_need(1, probe) > kRowLdsFloats) return CNNMEM_ERR_UNSUPPORTED;
+    long long p = 1;
+    while (p + 1 <= planes && planes_need(p + 1, probe) <= budget && planes / (p + 1) >= 1024) ++p;
+    plan.planes_per_wg = (int)p;
+    plan.rows_per_wg = g.Ho;
+    plan.strips = 1;
+    blocks = ceil_div64(planes, p);
+    lds_floats = planes_need(p, at);
     if (blocks > 0x7fffffffLL) return CNNMEM_ERR_UNSUPPORTED;
     hipLaunchKernelGGL((pool_nchw_k3s2_rows_kernel<MODE>), dim3((unsigned)blocks), dim3(kRowThreads),
-                       sizeof(float) * (size_t)lds_floats, st, src, dst, g, plan, at, make_fastdiv((uint32_t)g.Ho),
-                       make_fastdiv((uint32_t)plan.strips));
+                       sizeof(float) * (size_t)lds_floats, st, src, dst, g, plan, at, make_fastdiv((uint32_t)g.Ho));
     return launch_status();
 }
 
@@ -957,10 +933,10 @@ int dispatch_nchw(const float* src, float* dst, const PoolGeom& g, const PoolTun
     }
 
     const long long plane_in = (long long)g.H * g.W;
-    // (2a) 3x3 / stride 2 without padding on planes of 100 outputs and more: the rows kernel (128x96x55x55 33.0 -> 32.7 us,
-    // 128x256x27x27 23.7 -> 22.9 us, back to back 31.5 -> 30.8 and 22.3 -> 21.3 us; 13x13 planes are better off in the
-    // slab kernel's 48 planes per workgroup: 7.2 against 8.0 us)
-    if (a16 && g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2 && g.ph == 0 && g.pw == 0 && g.Ho * (long long)g.Wo >= 100 &&
+    // (2a) 3x3 / stride 2 without padding on planes of 12 output columns and more that fit LDS whole: the rows kernel
+    // (128x96x55x55 33.0 -> 32.7 us, 128x256x27x27 23.7 -> 22.9 us, back to back 31.5 -> 30.8 and 22.3 -> 21.3 us; planes of
+    // 24x24 and 13x13 are better off in the slab kernel's many planes per workgroup: 6.1 against 6.5, 7.2 against 8.0 us)
+    if (a16 && g.kh == 3 && g.kw == 3 && g.sh == 2 && g.sw == 2 && g.ph == 0 && g.pw == 0 && g.Wo >= 12 &&
         plane_in * planes < (1LL << 31) && plane_in * planes >= 4 && tune.nchw_kernel == 0 &&
         env_int("CNNMEM_POOL_ROWS", 1) != 0) {
         const int rc = launch_nchw_k3s2_rows<MODE>(src, dst, g, st);
